@@ -1,0 +1,136 @@
+/*
+ * CPU oracle for early-exit decoding with KV recomputation -- C API.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the plain, slow reference that the HIP
+ * library is checked against.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may load it; the product path never does.  It shares no
+ * code, header, table or helper with the HIP library.
+ *
+ * What it computes (paper Section 4 "KV recomputation", Section 5.2 exit rule,
+ * Appendix D.3 forced full pass, Appendix B.1 "both methods generate the same
+ * output"):
+ *   - G0: the plain definition.  Every new token is produced by a cache-free
+ *     causal forward of the whole sequence so far; the exit rule is applied to
+ *     the last position at each exit in depth order.
+ *   - G1: the paper's mechanism.  A per-layer KV cache, a list of the most
+ *     recent early-exited tokens whose deep KV is missing, and in every step
+ *     those tokens are fed again with the current token (from layer 1) so that
+ *     their KV is recomputed; a full-depth pass is forced when the list
+ *     reaches max_pending.
+ * Arithmetic: storage fp32; every reduction (dot product, mean square,
+ * softmax sum) is accumulated in fp64 and rounded once to fp32.  With
+ * dtype = EO_BF16 values are additionally rounded to bf16 (round to nearest
+ * even) at the points where the bf16 model stores bf16: matrix inputs
+ * (x*g before the RMS scale, attention output, SwiGLU product), q/k after
+ * RoPE, v, and therefore the cached K,V.  The residual stream, softmax,
+ * logits and confidences stay fp32.
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_*.py
+ * against closed forms, invariants, numpy/scipy fp64 routines and the G0
+ * brute force (no "parity unpinned" function).
+ */
+#ifndef EE_ORACLE_H
+#define EE_ORACLE_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { EO_F32 = 0, EO_BF16 = 1 };
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
+    int32_t n_exits, exit_layers[8]; /* 1-based "after layer e", ascending, < n_layers */
+    int32_t dtype;                   /* EO_F32 | EO_BF16: storage of matrices and the embedding */
+    float rms_eps, rope_base;
+} eo_config;
+
+/* tensor kinds, same numbering as the workload generator's TensorKind */
+enum { EO_EMBED = 0, EO_ATTN_NORM = 1, EO_WQ = 2, EO_WK = 3, EO_WV = 4, EO_WO = 5, EO_MLP_NORM = 6,
+       EO_WG = 7, EO_WU = 8, EO_WD = 9, EO_EXIT_NORM = 10, EO_EXIT_HEAD = 11, EO_FINAL_NORM = 12,
+       EO_FINAL_HEAD = 13 };
+
+typedef struct eo_model eo_model;
+typedef struct eo_state eo_state;
+
+/* what one head evaluation saw (one row) */
+typedef struct {
+    int32_t layer;    /* depth of the head: exit layer e_i, or n_layers for the final head */
+    int32_t argmax;   /* lowest index among maximal logits */
+    int32_t arg2;     /* index of the runner-up logit */
+    float conf;       /* max softmax probability = 1 / sum_i exp(z_i - z_max) */
+    float top1, top2; /* the two largest logits */
+} eo_diag;
+
+void eo_set_threads(int n); /* row-parallel matvec threads (results do not depend on it); default 1 */
+int eo_get_threads(void);
+
+/* model: pointers are borrowed (the caller keeps the arrays alive).  Matrices/embedding: float* for
+ * EO_F32, uint16_t* (bf16 bit patterns) for EO_BF16, row-major [out][in].  Norm gains: float*. */
+eo_model* eo_model_create(const eo_config* cfg);
+int eo_model_set_tensor(eo_model*, int kind, int index, const void* data);
+void eo_model_free(eo_model*);
+
+/* ---- G0: plain definition (cache-free) ---- */
+/* Generates n_new tokens after the prompt; exit_layer_out[j] in {e_1.., n_layers}. */
+int eo_generate_g0(const eo_model*, const int32_t* prompt, int n_prompt, int n_new, float threshold,
+                   int32_t* tokens_out, int32_t* exit_layer_out);
+/* Same, with the forced full-depth rule (Appendix D.3) derived from the exit history alone. */
+int eo_generate_g0_capped(const eo_model*, const int32_t* prompt, int n_prompt, int n_new, float threshold,
+                          int max_pending, int32_t* tokens_out, int32_t* exit_layer_out);
+/* Exit-free greedy loop (a standard LLM): a third generator, used to pin threshold 1. */
+int eo_generate_plain(const eo_model*, const int32_t* prompt, int n_prompt, int n_new, int32_t* tokens_out);
+/* Cache-free forward of a whole sequence (layer-major).  Any output may be NULL.
+ * hidden_out: [n_layers+1][n][d] residual stream after the embedding and after each layer.
+ * k_out / v_out: [n_layers][n][d] keys (after RoPE) and values. */
+int eo_forward_sequence(const eo_model*, const int32_t* tokens, int n, float* hidden_out, float* k_out,
+                        float* v_out);
+
+/* ---- G1: KV cache + pending list + recomputation ---- */
+eo_state* eo_state_create(const eo_model*, int max_positions, int max_pending);
+void eo_state_free(eo_state*);
+/* Full-depth forward of the prompt, all KV filled.  Every head is evaluated on the last position:
+ * diag_out[0..n_exits-1] for the exits, diag_out[n_exits] for the final head. */
+int eo_prefill(eo_state*, const int32_t* tokens, int n, eo_diag* diag_out);
+/* One decode step in three parts, so that a test can drive the decision itself:
+ *   begin   - takes the current token (the one emitted last); returns 1 if this step is forced full
+ *             depth because the pending count has reached max_pending, else 0;
+ *   advance - runs the next segment of layers over the pending rows and the current row; if the
+ *             segment ends at an exit and eval_head != 0, or it ends at the last layer, evaluates
+ *             that head on the current row into *diag.  Returns the depth reached;
+ *   commit  - ends the step at the depth reached, emitting `token`. */
+int eo_step_begin(eo_state*, int32_t token);
+int eo_step_advance(eo_state*, int eval_head, eo_diag* diag);
+int eo_step_commit(eo_state*, int32_t token);
+/* The paper's rule on top of the three parts: exit at the first exit whose confidence >= threshold
+ * (exits are not evaluated when threshold >= 1 or the step is forced). */
+int eo_decode_step(eo_state*, int32_t token, float threshold, int32_t* next_token, int32_t* exit_layer,
+                   float* conf);
+/* Runs pending rows through their missing layers; no token is emitted. */
+int eo_flush(eo_state*);
+int eo_filled(const eo_state*, int segment); /* positions whose KV is present in every layer of the segment */
+int eo_n_pending(const eo_state*);
+int eo_kv_read(const eo_state*, int layer, int pos0, int n, float* k_out, float* v_out); /* [n][d] */
+int eo_last_hidden(const eo_state*, float* x_out); /* current row's residual stream at the depth reached */
+int eo_last_logits(const eo_state*, float* z_out); /* logits of the last head evaluated, [vocab] */
+
+/* ---- single operations, exported for pins and real-shape spot checks ---- */
+float eo_bf16_round(float v);
+/* y[n] = r * sum_k W[n][k] * rnd(x[k]*g[k]),  r = 1/sqrt(mean(x^2)+eps); g == NULL: no norm (r = 1, g = 1) */
+void eo_norm_matvec(int dtype, const void* W, int N, int K, const float* x, const float* g, float eps,
+                    float* y);
+void eo_rope(int dtype, float* vec, int n_heads, int head_dim, int pos, float base);
+/* one query row over n_ctx cached positions; q,out: [H*hd]; K,V: [n_ctx][H*hd] */
+void eo_attention_row(int dtype, const float* q, const float* K, const float* V, int n_ctx, int n_heads,
+                      int head_dim, float* out);
+void eo_swiglu(int dtype, const float* gate, const float* up, int n, float* out);
+void eo_softmax_max(const float* z, int n, eo_diag* out);
+/* one layer on one row: x in/out [d]; K,V: [>=pos+1][d], row `pos` is written, rows 0..pos are read */
+int eo_layer_row(const eo_model*, int layer, float* x, int pos, float* K, float* V);
+/* head i (0..n_exits-1 exits, n_exits = final) on one row; z_out may be NULL */
+int eo_head_row(const eo_model*, int head, const float* x, float* z_out, eo_diag* diag);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
