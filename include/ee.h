@@ -1,0 +1,179 @@
+/*
+ * ee.h -- C ABI of the early-exit decode library for MI355X (gfx950).
+ *
+ * One autoregressive decode step through a decoder-only transformer with early-exit heads, using
+ * KV recomputation (paper: Section 4, paragraph "KV recomputation"; Appendix D.3 "Inference
+ * service").  Tokens that leave at an early exit are kept on a per-sequence list of recent tokens
+ * whose deep-layer KV is missing; every later step that goes deeper carries them along, so that
+ * their KV entries are filled.  A full-depth step is forced when the list reaches max_pending
+ * (Appendix D.3, last sentence).  The exit rule is the confidence rule of Section 5.2: at each
+ * exit, in depth order, leave if the largest next-token probability reaches the threshold; a
+ * threshold of 1 disables the exits.
+ *
+ * Conventions
+ *   - Plain C.  Every call returns 0 (EE_OK) or a negative error code; ee_strerror() names it and
+ *     ee_last_hip_error() returns the HIP status behind the last EE_ERR_HIP.
+ *   - The library allocates NO device memory.  The caller passes device buffers (sizes come from
+ *     the *_bytes queries; every buffer must be 256-byte aligned) and a HIP stream as `void*`
+ *     (NULL = the default stream).  Small pinned host buffers are allocated at create time.
+ *   - "dev_" arguments are device pointers, everything else is host memory, read or written only
+ *     during the call.
+ *   - A model is immutable once its tensors are set and may serve several caches.  A cache handle,
+ *     and a model while a call is running on it, must not be used from two threads at once.
+ *   - All work is enqueued on the given stream; calls that return tokens synchronise that stream
+ *     before returning (the host needs the exit decision to know which layers to launch next).
+ */
+#ifndef EE_H
+#define EE_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { EE_F32 = 0, EE_BF16 = 1 };
+
+enum {
+    EE_OK = 0,
+    EE_ERR_CONFIG = -1, /* bad shapes, exits not ascending, unsupported sizes */
+    EE_ERR_NOMEM = -2,  /* a caller buffer is too small, or the KV block pool is exhausted */
+    EE_ERR_RANGE = -3,  /* token >= vocab, bad sequence id, position beyond max_positions */
+    EE_ERR_STATE = -4,  /* tokens / pending_mask disagree with the cache state; missing tensors */
+    EE_ERR_IO = -5,     /* weight file unreadable or malformed */
+    EE_ERR_HIP = -6,    /* a HIP call failed; see ee_last_hip_error() */
+    EE_ERR_ARG = -7     /* NULL or misaligned pointer, bad count */
+};
+
+/* Compile-time limits of one launch */
+#define EE_MAX_ROWS 256 /* rows (current + deferred tokens of all sequences) in one step */
+#define EE_MAX_SEQS 64  /* sequences in one step */
+#define EE_MAX_EXITS 8
+
+/*
+ * Model: pre-RMSNorm decoder, rotary position embedding (half-split pairs, angle
+ * pos * rope_base^(-2i/head_dim)), SwiGLU MLP, no biases, untied heads.  Exit i sits after layer
+ * exit_layers[i] (1-based) and is an RMSNorm gain plus its own d_model x vocab matrix
+ * (Section 2: minimalistic exit = optional norm + output embedding).
+ * Supported: d_model = n_heads*head_dim; head_dim in {32, 64, 128}; d_model, d_ff multiples of 32;
+ * vocab a multiple of 32.
+ */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
+    int32_t n_exits, exit_layers[EE_MAX_EXITS]; /* ascending, each in [1, n_layers-1] */
+    int32_t dtype;                              /* EE_F32 | EE_BF16: storage of matrices, embedding, KV */
+    int32_t max_positions;                      /* longest sequence (prompt + generated) */
+    float rms_eps, rope_base;
+} ee_config;
+
+/* Tensor kinds for ee_model_set_tensor (index = layer for per-layer kinds, exit number for EXIT_*). */
+enum {
+    EE_T_EMBED = 0,      /* [vocab][d_model]                                        */
+    EE_T_ATTN_NORM = 1,  /* [d_model] fp32 gain, per layer                          */
+    EE_T_WQ = 2,         /* [d_model][d_model], row = output feature (y = W x)      */
+    EE_T_WK = 3,
+    EE_T_WV = 4,
+    EE_T_WO = 5,
+    EE_T_MLP_NORM = 6,   /* [d_model] fp32 gain                                     */
+    EE_T_WG = 7,         /* [d_ff][d_model]                                         */
+    EE_T_WU = 8,         /* [d_ff][d_model]                                         */
+    EE_T_WD = 9,         /* [d_model][d_ff]                                         */
+    EE_T_EXIT_NORM = 10, /* [d_model] fp32 gain, per exit                           */
+    EE_T_EXIT_HEAD = 11, /* [vocab][d_model], per exit                              */
+    EE_T_FINAL_NORM = 12,
+    EE_T_FINAL_HEAD = 13,
+    EE_T_KINDS = 14
+};
+
+typedef struct ee_model ee_model;
+typedef struct ee_kv_cache ee_kv_cache;
+
+const char* ee_strerror(int code);
+int ee_last_hip_error(void);
+
+/* ---------------------------------------------------------------- model */
+
+/* Sizes of the two device buffers a model needs.  weight_bytes holds the packed weights and the
+ * rotary table; workspace_bytes holds per-step activations for up to max_rows rows
+ * (1 <= max_rows <= EE_MAX_ROWS) and max_seqs sequences per step (1 <= max_seqs <= EE_MAX_SEQS). */
+int ee_model_bytes(const ee_config* cfg, int max_rows, int max_seqs, size_t* weight_bytes,
+                   size_t* workspace_bytes);
+
+/* Creates a model over the caller's device buffers; no tensor is set yet.  Enqueues the rotary table
+ * initialisation on `stream`. */
+int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes, void* dev_workspace,
+                    size_t workspace_bytes, int max_rows, int max_seqs, void* stream, ee_model** out);
+
+/* Sets one tensor from a DEVICE array in the plain row-major layout given above (matrices and the
+ * embedding in the model's dtype, gains fp32).  The library repacks it into its own layout inside
+ * dev_weights (enqueued on `stream`; dev_src may be reused once the stream has passed this point).
+ * n_elems must equal the tensor's element count. */
+int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, size_t n_elems, void* stream);
+
+/* Reads a weight file and sets every tensor.  File: the 8 bytes "EEWT0001", the ee_config struct,
+ * then every tensor in the order EMBED, per layer {ATTN_NORM, WQ, WK, WV, WO, MLP_NORM, WG, WU, WD},
+ * per exit {EXIT_NORM, EXIT_HEAD}, FINAL_NORM, FINAL_HEAD, each as raw little-endian elements.
+ * dev_staging is a device scratch buffer of at least staging_bytes = the largest tensor. */
+int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weights, size_t weight_bytes,
+                  void* dev_workspace, size_t workspace_bytes, int max_rows, int max_seqs, void* dev_staging,
+                  size_t staging_bytes, void* stream, ee_model** out);
+
+int ee_model_free(ee_model* m);
+
+/* Test hook: if dev_logits != NULL, every head evaluation also stores its fp32 logits there,
+ * [row][vocab] for the rows it evaluates (capacity_rows rows).  NULL switches it off. */
+int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);
+
+/* ---------------------------------------------------------------- KV cache */
+
+/* The cache is paged: a pool of blocks of block_tokens positions (a multiple of 32), shared by up to
+ * max_seqs sequences, max_tokens_total positions in all.  Besides K and V it holds, per sequence, the
+ * residual rows of the deferred tokens (max_pending + 1 rows) so that a deferred token resumes above
+ * the depth it reached instead of starting again from layer 1 -- the KV entries it produces are the
+ * same.  max_pending in [0, 63]: the forced-full-depth limit (0: every step runs full depth). */
+int ee_kv_cache_bytes(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens,
+                      int max_pending, size_t* bytes);
+int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens,
+                       int max_pending, void* dev_pool, size_t pool_bytes, ee_kv_cache** out);
+int ee_kv_cache_reset(ee_kv_cache* c, int seq); /* frees the sequence's blocks, clears its pending list */
+/* Number of positions whose K,V are present in `layer` (0-based). */
+int ee_kv_cache_filled(const ee_kv_cache* c, int seq, int layer, int32_t* n_positions);
+int ee_kv_cache_pending(const ee_kv_cache* c, int seq, int32_t* n_pending);
+/* Copies K and V of positions [pos0, pos0+n) of one layer to host arrays [n][d_model] fp32. */
+int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int pos0, int n, float* k_host,
+                     float* v_host, void* stream);
+/* Runs every deferred token of the given sequences through its missing layers; emits nothing. */
+int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, void* stream);
+int ee_kv_cache_free(ee_kv_cache* c);
+/* Test hook: residual stream (fp32 [d_model]) of the sequence's newest processed position, at the
+ * depth it reached. */
+int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_host, void* stream);
+
+/* ---------------------------------------------------------------- prefill and decode */
+
+/* Full-depth causal forward of a prompt into an empty sequence; all KV filled (the first token comes
+ * from the prefill phase, Section 4).  The exit rule is then applied to the last position to choose
+ * the first generated token: next_token / exit_layer follow the rule, conf[i] is the confidence at
+ * exit i (i < n_exits) and conf[n_exits] at the final head; with threshold >= 1 the exits are not
+ * evaluated and their conf entries are -1. */
+int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
+               int32_t* next_token, int32_t* exit_layer, float* conf, void* stream);
+
+/* One decode step for n_seqs sequences.
+ *   seq_ids      [n_seqs]   distinct sequence ids
+ *   row_offsets  [n_seqs+1] rows of sequence i are tokens[row_offsets[i] .. row_offsets[i+1])
+ *   tokens       per sequence: the ids of its deferred tokens, oldest first, then the current token
+ *                (the one emitted by the previous call)
+ *   pending_mask 1 = deferred row (KV fill only), 0 = current token; exactly the last row of each
+ *                sequence is 0.  The library keeps the list itself and checks the caller's against
+ *                it (EE_ERR_STATE on mismatch).
+ *   threshold    exit iff confidence >= threshold and threshold < 1
+ * Outputs, [n_seqs] each: next_token, exit_layer (an exit layer, or n_layers for a full or forced
+ * step) and conf (confidence at the head that emitted). */
+int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
+                   const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
+                   int32_t* exit_layer, float* conf, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,891 @@
+// Host side of the C ABI declared in ee.h: buffer layout, weight packing, the paged KV cache with its
+// per-sequence fill watermarks and list of deferred tokens, and the step scheduler that launches one
+// segment of layers at a time and reads the exit decision back before launching the next
+// (Section 4 "KV recomputation", Section 5.2 exit rule, Appendix D.3 forced full pass).
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ee_internal.h"
+
+using namespace ee;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIPCHK(expr)                          \
+    do {                                      \
+        hipError_t _e = (expr);               \
+        if (_e != hipSuccess) {               \
+            g_last_hip = (int)_e;             \
+            return EE_ERR_HIP;                \
+        }                                     \
+    } while (0)
+
+#define EECHK(expr)              \
+    do {                         \
+        int _r = (expr);         \
+        if (_r != EE_OK) return _r; \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline size_t esize(int dtype) { return dtype == EE_BF16 ? 2 : 4; }
+
+int check_config(const ee_config& c) {
+    if (c.n_layers < 1 || c.n_heads < 1 || c.d_model != c.n_heads * c.head_dim) return EE_ERR_CONFIG;
+    if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return EE_ERR_CONFIG;
+    if (c.d_model % 32 || c.d_ff % 32 || c.d_ff < 32 || c.vocab % 32 || c.vocab < 32) return EE_ERR_CONFIG;
+    if (c.dtype != EE_F32 && c.dtype != EE_BF16) return EE_ERR_CONFIG;
+    if (c.n_exits < 0 || c.n_exits > EE_MAX_EXITS) return EE_ERR_CONFIG;
+    for (int i = 0; i < c.n_exits; ++i) {
+        if (c.exit_layers[i] < 1 || c.exit_layers[i] >= c.n_layers) return EE_ERR_CONFIG;
+        if (i && c.exit_layers[i] <= c.exit_layers[i - 1]) return EE_ERR_CONFIG;
+    }
+    if (c.max_positions < 1 || c.max_positions > (1 << 20)) return EE_ERR_CONFIG;
+    if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return EE_ERR_CONFIG;
+    return EE_OK;
+}
+
+struct WeightLayout {
+    size_t embed, rope, gf, wf, total;
+    std::vector<size_t> g1, qkv, wo, g2, gu, wd, ge, we;
+};
+
+WeightLayout weight_layout(const ee_config& c) {
+    WeightLayout w;
+    size_t es = esize(c.dtype), d = c.d_model, F = c.d_ff, V = c.vocab, off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes);
+        return o;
+    };
+    w.embed = take(V * d * es);
+    for (int l = 0; l < c.n_layers; ++l) {
+        w.g1.push_back(take(d * 4));
+        w.qkv.push_back(take(3 * d * d * es));
+        w.wo.push_back(take(d * d * es));
+        w.g2.push_back(take(d * 4));
+        w.gu.push_back(take(2 * F * d * es));
+        w.wd.push_back(take(d * F * es));
+    }
+    for (int i = 0; i < c.n_exits; ++i) {
+        w.ge.push_back(take(d * 4));
+        w.we.push_back(take(V * d * es));
+    }
+    w.gf = take(d * 4);
+    w.wf = take(V * d * es);
+    w.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 8);
+    w.total = off;
+    return w;
+}
+
+struct WorkspaceLayout {
+    size_t upload, upload_bytes;  // [descs][btab][tokens], one host-to-device copy per step
+    size_t descs, btab, tokens;
+    size_t q, attn, act, partials, counters, attn_part, stage, total;
+    int max_blocks_per_seq;
+};
+
+WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs) {
+    WorkspaceLayout w;
+    size_t es = esize(c.dtype), d = c.d_model, off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes);
+        return o;
+    };
+    w.max_blocks_per_seq = c.max_positions / 32 + 1;
+    w.upload = off;
+    w.descs = take(sizeof(SegDesc) * (EE_MAX_EXITS + 1));
+    w.btab = take((size_t)max_seqs * w.max_blocks_per_seq * 4);
+    w.tokens = take(EE_MAX_ROWS * 4);
+    w.upload_bytes = off - w.upload;
+    w.q = take((size_t)max_rows * d * es);
+    w.attn = take((size_t)max_rows * d * es);
+    w.act = take((size_t)max_rows * c.d_ff * es);
+    w.partials = take((size_t)(c.vocab / 32) * EE_MAX_SEQS * sizeof(HeadPartial));
+    w.counters = take(256 * 4);
+    w.attn_part = take(attention_part_floats(max_rows, c.n_heads, c.head_dim) * 4);
+    w.stage = take(2 * (size_t)max_rows * d * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+struct ee_model {
+    ee_config cfg;
+    int max_rows, max_seqs;
+    char* wbase;
+    char* ws;
+    WeightLayout wl;
+    WorkspaceLayout wsl;
+    std::vector<uint8_t> have;  // per tensor: set?
+    int n_missing;
+    char* pinned;            // host staging for the upload region, then the head results
+    HeadResult* results;     // host view
+    HeadResult* results_dev; // device view of the same memory
+    float* dbg_logits;
+    int dbg_rows;
+    int n_seg() const { return cfg.n_exits + 1; }
+    int seg_begin(int s) const { return s == 0 ? 0 : cfg.exit_layers[s - 1]; }
+    int seg_end(int s) const { return s < cfg.n_exits ? cfg.exit_layers[s] : cfg.n_layers; }
+    int seg_of_layer(int l) const {
+        for (int s = 0; s < n_seg(); ++s)
+            if (l < seg_end(s)) return s;
+        return n_seg() - 1;
+    }
+    SegDesc* host_desc(int i) const { return (SegDesc*)(pinned + (wsl.descs - wsl.upload)) + i; }
+    int32_t* host_btab() const { return (int32_t*)(pinned + (wsl.btab - wsl.upload)); }
+    int32_t* host_tokens() const { return (int32_t*)(pinned + (wsl.tokens - wsl.upload)); }
+    SegDesc* dev_desc(int i) const { return (SegDesc*)(ws + wsl.descs) + i; }
+    int32_t* dev_btab() const { return (int32_t*)(ws + wsl.btab); }
+    int32_t* dev_tokens() const { return (int32_t*)(ws + wsl.tokens); }
+    const float* gain(size_t off) const { return (const float*)(wbase + off); }
+    int tensor_slot(int kind, int index) const {
+        int L = cfg.n_layers, E = cfg.n_exits;
+        switch (kind) {
+            case EE_T_EMBED: return index == 0 ? 0 : -1;
+            case EE_T_FINAL_NORM: return index == 0 ? 1 : -1;
+            case EE_T_FINAL_HEAD: return index == 0 ? 2 : -1;
+            case EE_T_EXIT_NORM: return index >= 0 && index < E ? 3 + index : -1;
+            case EE_T_EXIT_HEAD: return index >= 0 && index < E ? 3 + E + index : -1;
+            default: break;
+        }
+        static const int per_layer[] = {EE_T_ATTN_NORM, EE_T_WQ, EE_T_WK, EE_T_WV, EE_T_WO, EE_T_MLP_NORM, EE_T_WG, EE_T_WU, EE_T_WD};
+        for (int j = 0; j < 9; ++j)
+            if (per_layer[j] == kind) return index >= 0 && index < L ? 3 + 2 * E + index * 9 + j : -1;
+        return -1;
+    }
+    int n_tensors() const { return 3 + 2 * cfg.n_exits + 9 * cfg.n_layers; }
+};
+
+struct SeqState {
+    std::vector<int32_t> filled;   // per segment: positions whose KV is present in all its layers
+    std::vector<int32_t> blocks;   // logical block -> physical block
+    std::vector<int32_t> tokring;  // token id of position p at p % S
+};
+
+struct ee_kv_cache {
+    const ee_model* m;
+    int max_seqs, BT, S, max_pending, n_blocks;
+    char* pool;
+    size_t off_x, off_xg, off_xgh, off_ssq;
+    int ssq_stride;  // partial sums per row
+    KvGeom geom;
+    std::vector<int32_t> free_blocks;
+    std::vector<SeqState> seqs;
+    float* x() const { return (float*)(pool + off_x); }
+    void* xg() const { return pool + off_xg; }
+    void* xgh() const { return pool + off_xgh; }
+    float* ssq() const { return (float*)(pool + off_ssq); }
+    int slot_of(int seq, int pos) const { return seq * S + pos % S; }
+    int transient_slot(int r) const { return max_seqs * S + r; }
+    int n_pending(const SeqState& s) const { return s.filled.front() - s.filled.back(); }
+};
+
+namespace {
+
+size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending, int* n_blocks,
+                      size_t* off_x, size_t* off_xg, size_t* off_xgh, size_t* off_ssq) {
+    const ee_config& c = m->cfg;
+    size_t es = esize(c.dtype), d = c.d_model;
+    int nb = (int)((max_tokens_total + BT - 1) / BT) + max_seqs;
+    size_t blk = 2 * (size_t)c.n_heads * BT * c.head_dim;
+    size_t off = align_up((size_t)c.n_layers * nb * blk * es);
+    size_t slots = (size_t)max_seqs * (max_pending + 1) + m->max_rows;
+    size_t P = d / (16 * gemm_resid_tiles_per_wg());
+    if (n_blocks) *n_blocks = nb;
+    if (off_x) *off_x = off;
+    off += align_up(slots * d * 4);
+    if (off_xg) *off_xg = off;
+    off += align_up(slots * d * es);
+    if (off_xgh) *off_xgh = off;
+    off += align_up(slots * d * es);
+    if (off_ssq) *off_ssq = off;
+    off += align_up(slots * P * 4);
+    return off;
+}
+
+int check_cache_args(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending) {
+    if (!m) return EE_ERR_ARG;
+    if (max_seqs < 1 || max_seqs > 4096 || max_tokens_total < 1 || BT < 32 || BT % 32 || BT > 1024) return EE_ERR_CONFIG;
+    if (max_pending < 0 || max_pending > 63) return EE_ERR_CONFIG;
+    return EE_OK;
+}
+
+// ---- the per-layer launch sequence over the rows described by dev_desc(di)
+int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    const int d = cf.d_model, F = cf.d_ff, dt = cf.dtype;
+    SegDesc* dd = m->dev_desc(di);
+    const int32_t* xrow = (const int32_t*)((char*)dd + offsetof(SegDesc, xrow));
+    for (int l = l0; l < l1; ++l) {
+        GemmCommon g{};
+        g.dtype = dt;
+        g.T = T;
+        g.desc = dd;
+        g.inv_d = 1.0f / (float)d;
+        g.eps = cf.rms_eps;
+        g.ssq_stride = c->ssq_stride;
+        g.ssq_n = c->ssq_stride;
+        // q,k,v = W_qkv rmsnorm(x; g1); rotary; KV write
+        g.W = m->wbase + m->wl.qkv[l];
+        g.N = 3 * d;
+        g.K = d;
+        g.A = c->xg();
+        g.lda = d;
+        g.arow = xrow;
+        g.ssq = c->ssq();
+        HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
+        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, dd, T, n_qt, m->dev_btab(), c->geom, l, d,
+                                (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx, st));
+        // x += W_o a ; operand for the MLP norm
+        g.W = m->wbase + m->wl.wo[l];
+        g.N = d;
+        g.K = d;
+        g.A = m->ws + m->wsl.attn;
+        g.arow = nullptr;
+        g.ssq = nullptr;
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
+        // act = silu(W_g h) * (W_u h)
+        g.W = m->wbase + m->wl.gu[l];
+        g.N = 2 * F;
+        g.K = d;
+        g.A = c->xg();
+        g.arow = xrow;
+        g.ssq = c->ssq();
+        HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, F, st));
+        // x += W_d act ; operand for the next layer (or the final head), and for an exit head after this layer
+        g.W = m->wbase + m->wl.wd[l];
+        g.N = d;
+        g.K = F;
+        g.A = m->ws + m->wsl.act;
+        g.lda = F;
+        g.arow = nullptr;
+        g.ssq = nullptr;
+        const float* g_next = (l + 1 < cf.n_layers) ? m->gain(m->wl.g1[l + 1]) : m->gain(m->wl.gf);
+        const float* g_head = nullptr;
+        for (int i = 0; i < cf.n_exits; ++i)
+            if (cf.exit_layers[i] == l + 1) g_head = m->gain(m->wl.ge[i]);
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->ssq(), g_next, g_head, d, st));
+    }
+    return EE_OK;
+}
+
+// head `hi` (exit number, or n_exits for the final head) on the rows listed in dev_desc(di).head_*
+int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, float threshold, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    bool fin = hi >= cf.n_exits;
+    SegDesc* dd = m->dev_desc(di);
+    GemmCommon g{};
+    g.dtype = cf.dtype;
+    g.W = m->wbase + (fin ? m->wl.wf : m->wl.we[hi]);
+    g.N = cf.vocab;
+    g.K = cf.d_model;
+    g.A = fin ? c->xg() : c->xgh();
+    g.lda = cf.d_model;
+    g.arow = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
+    g.ssq = c->ssq();
+    g.ssq_stride = c->ssq_stride;
+    g.ssq_n = c->ssq_stride;
+    g.inv_d = 1.0f / (float)cf.d_model;
+    g.eps = cf.rms_eps;
+    g.T = n_head;
+    g.desc = dd;
+    float* logits = (m->dbg_logits && n_head <= m->dbg_rows) ? m->dbg_logits : nullptr;
+    HIPCHK(launch_gemm_head(g, (HeadPartial*)(m->ws + m->wsl.partials), (int32_t*)(m->ws + m->wsl.counters), logits, mode,
+                            threshold, m->results_dev, st));
+    return EE_OK;
+}
+
+int ensure_blocks(ee_kv_cache* c, SeqState& s, int n_positions) {
+    int need = (n_positions + c->BT - 1) / c->BT;
+    if (need > c->geom.max_blocks_per_seq) return EE_ERR_RANGE;
+    while ((int)s.blocks.size() < need) {
+        if (c->free_blocks.empty()) return EE_ERR_NOMEM;
+        s.blocks.push_back(c->free_blocks.back());
+        c->free_blocks.pop_back();
+    }
+    return EE_OK;
+}
+
+void put_btab(const ee_model* m, const ee_kv_cache* c, int row, const SeqState& s) {
+    int32_t* bt = m->host_btab() + (size_t)row * c->geom.max_blocks_per_seq;
+    std::copy(s.blocks.begin(), s.blocks.end(), bt);
+}
+
+int upload(ee_model* m, hipStream_t st) {
+    HIPCHK(hipMemcpyAsync(m->ws + m->wsl.upload, m->pinned, m->wsl.upload_bytes, hipMemcpyHostToDevice, st));
+    return EE_OK;
+}
+
+struct StepSeq {
+    int seq, p;     // sequence id, position of the current token (or -1 for a flush)
+    bool forced, active;
+};
+
+// rows of the active sequences for segment `seg`: positions [filled[seg], last] of each
+void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::vector<StepSeq>& ss, int seg, bool with_head,
+                float threshold, int* rows_out) {
+    int T = 0, nqt = 0, nh = 0;
+    for (size_t b = 0; b < ss.size(); ++b) {
+        if (!ss[b].active) continue;
+        const SeqState& s = c->seqs[ss[b].seq];
+        int lo = s.filled[seg];
+        int hi = ss[b].p >= 0 ? ss[b].p : s.filled[0] - 1;  // inclusive
+        int first = T;
+        for (int pos = lo; pos <= hi; ++pos, ++T) {
+            if (T >= EE_MAX_ROWS) { *rows_out = EE_MAX_ROWS + 1; return; }
+            d->xrow[T] = c->slot_of(ss[b].seq, pos);
+            d->pos[T] = pos;
+            d->kvblk[T] = s.blocks[pos / c->BT];
+            d->rseq[T] = (int)b;
+        }
+        for (int r = first; r < T; r += 16) {
+            d->qt_row0[nqt] = r;
+            d->qt_nq[nqt] = std::min(16, T - r);
+            ++nqt;
+        }
+        bool is_final = seg == m->n_seg() - 1;
+        if (with_head && ss[b].p >= 0 && T > first && (is_final || (!ss[b].forced && threshold < 1.0f))) {
+            d->head_xrow[nh] = c->slot_of(ss[b].seq, ss[b].p);
+            d->head_slot[nh] = seg * EE_MAX_SEQS + (int)b;
+            ++nh;
+        }
+    }
+    d->T = T;
+    d->n_qt = nqt;
+    d->n_head = nh;
+    d->pad = 0;
+    *rows_out = T;
+}
+
+int max_ctx_of(const ee_kv_cache* c, const std::vector<StepSeq>& ss) {
+    int mx = 1;
+    for (auto& q : ss) mx = std::max(mx, (q.p >= 0 ? q.p : c->seqs[q.seq].filled[0] - 1) + 1);
+    return mx;
+}
+
+// Common engine of decode and flush.  For a flush p = -1 everywhere and no head runs.
+int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float threshold, bool decode, int32_t* next_token,
+             int32_t* exit_layer, float* conf, hipStream_t st) {
+    const int n_seg = m->n_seg();
+    for (size_t b = 0; b < ss.size(); ++b) put_btab(m, c, (int)b, c->seqs[ss[b].seq]);
+    int max_ctx = max_ctx_of(c, ss);
+    std::vector<int> rows(n_seg, 0);
+    auto rebuild = [&](int from) -> int {
+        for (int s = from; s < n_seg; ++s) {
+            build_desc(m, c, m->host_desc(s), ss, s, decode, threshold, &rows[s]);
+            if (rows[s] > m->max_rows || rows[s] > 64) return EE_ERR_NOMEM;
+        }
+        return upload(m, st);
+    };
+    EECHK(rebuild(0));
+    int n_active = (int)ss.size();
+    for (int s = 0; s < n_seg && n_active > 0; ++s) {
+        const SegDesc* hd = m->host_desc(s);
+        if (hd->T > 0) {
+            if (s == 0 && decode)
+                HIPCHK(launch_embed(m->cfg.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), hd->T, m->cfg.d_model,
+                                    m->gain(m->wl.g1[0]), c->x(), c->xg(), c->ssq(), c->ssq_stride, st));
+            EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
+        }
+        bool is_final = s == n_seg - 1;
+        if (decode && hd->n_head > 0) {
+            EECHK(run_head(m, c, s, s, hd->n_head, is_final ? HEAD_EMIT : HEAD_RULE, threshold, st));
+            HIPCHK(hipStreamSynchronize(st));
+            int fired_now = 0;
+            for (int i = 0; i < hd->n_head; ++i) {
+                int slot = hd->head_slot[i];
+                int b = slot - s * EE_MAX_SEQS;
+                const HeadResult& r = m->results[slot];
+                if (r.fired) {
+                    next_token[b] = r.token;
+                    exit_layer[b] = m->seg_end(s);
+                    if (conf) conf[b] = r.conf;
+                    ss[b].active = false;
+                    SeqState& sq = c->seqs[ss[b].seq];
+                    for (int k = 0; k <= s; ++k) sq.filled[k] = ss[b].p + 1;
+                    ++fired_now;
+                }
+            }
+            n_active -= fired_now;
+            if (fired_now && n_active > 0 && !is_final) EECHK(rebuild(s + 1));
+        }
+        if (is_final) {
+            if (!decode) {
+                for (auto& q : ss) {
+                    SeqState& sq = c->seqs[q.seq];
+                    for (int k = 1; k < n_seg; ++k) sq.filled[k] = sq.filled[0];
+                }
+                HIPCHK(hipStreamSynchronize(st));
+            }
+        }
+    }
+    return EE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ee_strerror(int code) {
+    switch (code) {
+        case EE_OK: return "ok";
+        case EE_ERR_CONFIG: return "bad or unsupported configuration";
+        case EE_ERR_NOMEM: return "buffer too small or KV block pool exhausted";
+        case EE_ERR_RANGE: return "token, sequence id or position out of range";
+        case EE_ERR_STATE: return "arguments disagree with the cache state, or tensors missing";
+        case EE_ERR_IO: return "weight file unreadable or malformed";
+        case EE_ERR_HIP: return "HIP call failed";
+        case EE_ERR_ARG: return "null or misaligned pointer, or bad count";
+    }
+    return "unknown error";
+}
+
+int ee_last_hip_error(void) { return g_last_hip; }
+
+int ee_model_bytes(const ee_config* cfg, int max_rows, int max_seqs, size_t* weight_bytes, size_t* workspace_bytes) {
+    if (!cfg) return EE_ERR_ARG;
+    EECHK(check_config(*cfg));
+    if (max_rows < 1 || max_rows > EE_MAX_ROWS || max_seqs < 1 || max_seqs > EE_MAX_SEQS) return EE_ERR_CONFIG;
+    if (weight_bytes) *weight_bytes = weight_layout(*cfg).total;
+    if (workspace_bytes) *workspace_bytes = workspace_layout(*cfg, max_rows, max_seqs).total;
+    return EE_OK;
+}
+
+int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes, void* dev_workspace,
+                    size_t workspace_bytes, int max_rows, int max_seqs, void* stream, ee_model** out) {
+    if (!cfg || !dev_weights || !dev_workspace || !out) return EE_ERR_ARG;
+    if (((uintptr_t)dev_weights | (uintptr_t)dev_workspace) & 255) return EE_ERR_ARG;
+    size_t wb, sb;
+    EECHK(ee_model_bytes(cfg, max_rows, max_seqs, &wb, &sb));
+    if (weight_bytes < wb || workspace_bytes < sb) return EE_ERR_NOMEM;
+    ee_model* m = new (std::nothrow) ee_model();
+    if (!m) return EE_ERR_NOMEM;
+    m->cfg = *cfg;
+    m->max_rows = max_rows;
+    m->max_seqs = max_seqs;
+    m->wbase = (char*)dev_weights;
+    m->ws = (char*)dev_workspace;
+    m->wl = weight_layout(*cfg);
+    m->wsl = workspace_layout(*cfg, max_rows, max_seqs);
+    m->have.assign(m->n_tensors(), 0);
+    m->n_missing = m->n_tensors();
+    m->dbg_logits = nullptr;
+    m->dbg_rows = 0;
+    size_t res_bytes = sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1);
+    hipError_t e = hipHostMalloc((void**)&m->pinned, align_up(m->wsl.upload_bytes) + res_bytes, hipHostMallocMapped);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        delete m;
+        return EE_ERR_HIP;
+    }
+    std::memset(m->pinned, 0, align_up(m->wsl.upload_bytes) + res_bytes);
+    m->results = (HeadResult*)(m->pinned + align_up(m->wsl.upload_bytes));
+    hipStream_t st = (hipStream_t)stream;
+    int rc = EE_OK;
+    do {
+        if ((e = hipHostGetDevicePointer((void**)&m->results_dev, m->results, 0)) != hipSuccess) break;
+        if ((e = hipMemsetAsync(m->ws + m->wsl.counters, 0, 256 * 4, st)) != hipSuccess) break;
+        e = launch_rope_table((float*)(m->wbase + m->wl.rope), cfg->max_positions, cfg->head_dim, cfg->rope_base, st);
+    } while (0);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        rc = EE_ERR_HIP;
+        (void)hipHostFree(m->pinned);
+        delete m;
+        return rc;
+    }
+    *out = m;
+    return EE_OK;
+}
+
+int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, size_t n_elems, void* stream) {
+    if (!m || !dev_src) return EE_ERR_ARG;
+    int slot = m->tensor_slot(kind, index);
+    if (slot < 0) return EE_ERR_RANGE;
+    const ee_config& c = m->cfg;
+    const size_t d = c.d_model, F = c.d_ff, V = c.vocab, es = esize(c.dtype);
+    const int dt = c.dtype, hd = c.head_dim;
+    hipStream_t st = (hipStream_t)stream;
+    auto gain = [&](size_t off) -> int {
+        if (n_elems != d) return EE_ERR_ARG;
+        HIPCHK(hipMemcpyAsync(m->wbase + off, dev_src, d * 4, hipMemcpyDeviceToDevice, st));
+        return EE_OK;
+    };
+    auto mat = [&](size_t off, size_t rows, size_t K, int mode, int mul, int toff) -> int {
+        if (n_elems != rows * K) return EE_ERR_ARG;
+        HIPCHK(launch_pack(dt, dev_src, m->wbase + off, (int)rows, (int)K, mode, hd, mul, toff, st));
+        return EE_OK;
+    };
+    int rc;
+    switch (kind) {
+        case EE_T_EMBED:
+            if (n_elems != V * d) return EE_ERR_ARG;
+            HIPCHK(hipMemcpyAsync(m->wbase + m->wl.embed, dev_src, V * d * es, hipMemcpyDeviceToDevice, st));
+            rc = EE_OK;
+            break;
+        case EE_T_ATTN_NORM: rc = gain(m->wl.g1[index]); break;
+        case EE_T_MLP_NORM: rc = gain(m->wl.g2[index]); break;
+        case EE_T_EXIT_NORM: rc = gain(m->wl.ge[index]); break;
+        case EE_T_FINAL_NORM: rc = gain(m->wl.gf); break;
+        case EE_T_WQ: rc = mat(m->wl.qkv[index], d, d, 1, 1, 0); break;
+        case EE_T_WK: rc = mat(m->wl.qkv[index] + d * d * es, d, d, 1, 1, 0); break;
+        case EE_T_WV: rc = mat(m->wl.qkv[index] + 2 * d * d * es, d, d, 1, 1, 0); break;
+        case EE_T_WO: rc = mat(m->wl.wo[index], d, d, 0, 1, 0); break;
+        case EE_T_WG: rc = mat(m->wl.gu[index], F, d, 0, 2, 0); break;
+        case EE_T_WU: rc = mat(m->wl.gu[index], F, d, 0, 2, 1); break;
+        case EE_T_WD: rc = mat(m->wl.wd[index], d, F, 0, 1, 0); break;
+        case EE_T_EXIT_HEAD: rc = mat(m->wl.we[index], V, d, 0, 1, 0); break;
+        case EE_T_FINAL_HEAD: rc = mat(m->wl.wf, V, d, 0, 1, 0); break;
+        default: return EE_ERR_RANGE;
+    }
+    if (rc != EE_OK) return rc;
+    if (!m->have[slot]) {
+        m->have[slot] = 1;
+        --m->n_missing;
+    }
+    return EE_OK;
+}
+
+int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weights, size_t weight_bytes,
+                  void* dev_workspace, size_t workspace_bytes, int max_rows, int max_seqs, void* dev_staging,
+                  size_t staging_bytes, void* stream, ee_model** out) {
+    if (!cfg || !weights_path || !dev_staging || !out) return EE_ERR_ARG;
+    FILE* f = std::fopen(weights_path, "rb");
+    if (!f) return EE_ERR_IO;
+    char magic[8];
+    ee_config fc;
+    if (std::fread(magic, 1, 8, f) != 8 || std::memcmp(magic, "EEWT0001", 8) != 0 || std::fread(&fc, sizeof fc, 1, f) != 1) {
+        std::fclose(f);
+        return EE_ERR_IO;
+    }
+    if (fc.n_layers != cfg->n_layers || fc.d_model != cfg->d_model || fc.n_heads != cfg->n_heads || fc.d_ff != cfg->d_ff ||
+        fc.vocab != cfg->vocab || fc.dtype != cfg->dtype || fc.n_exits != cfg->n_exits) {
+        std::fclose(f);
+        return EE_ERR_IO;
+    }
+    ee_model* m = nullptr;
+    int rc = ee_model_create(cfg, dev_weights, weight_bytes, dev_workspace, workspace_bytes, max_rows, max_seqs, stream, &m);
+    if (rc != EE_OK) {
+        std::fclose(f);
+        return rc;
+    }
+    const size_t d = cfg->d_model, F = cfg->d_ff, V = cfg->vocab, es = esize(cfg->dtype);
+    const size_t chunk = 32u << 20;
+    char* host = nullptr;
+    hipError_t e = hipHostMalloc((void**)&host, chunk, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        std::fclose(f);
+        ee_model_free(m);
+        return EE_ERR_HIP;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    auto one = [&](int kind, int index, size_t n, size_t esz) -> int {
+        size_t bytes = n * esz;
+        if (bytes > staging_bytes) return EE_ERR_NOMEM;
+        for (size_t o = 0; o < bytes; o += chunk) {
+            size_t nb = std::min(chunk, bytes - o);
+            if (std::fread(host, 1, nb, f) != nb) return EE_ERR_IO;
+            HIPCHK(hipMemcpyAsync((char*)dev_staging + o, host, nb, hipMemcpyHostToDevice, st));
+            HIPCHK(hipStreamSynchronize(st));
+        }
+        EECHK(ee_model_set_tensor(m, kind, index, dev_staging, n, stream));
+        HIPCHK(hipStreamSynchronize(st));
+        return EE_OK;
+    };
+    rc = one(EE_T_EMBED, 0, V * d, es);
+    for (int l = 0; rc == EE_OK && l < cfg->n_layers; ++l) {
+        const int kinds[] = {EE_T_ATTN_NORM, EE_T_WQ, EE_T_WK, EE_T_WV, EE_T_WO, EE_T_MLP_NORM, EE_T_WG, EE_T_WU, EE_T_WD};
+        const size_t ns[] = {d, d * d, d * d, d * d, d * d, d, F * d, F * d, d * F};
+        for (int j = 0; rc == EE_OK && j < 9; ++j)
+            rc = one(kinds[j], l, ns[j], (kinds[j] == EE_T_ATTN_NORM || kinds[j] == EE_T_MLP_NORM) ? 4 : es);
+    }
+    for (int i = 0; rc == EE_OK && i < cfg->n_exits; ++i) {
+        rc = one(EE_T_EXIT_NORM, i, d, 4);
+        if (rc == EE_OK) rc = one(EE_T_EXIT_HEAD, i, V * d, es);
+    }
+    if (rc == EE_OK) rc = one(EE_T_FINAL_NORM, 0, d, 4);
+    if (rc == EE_OK) rc = one(EE_T_FINAL_HEAD, 0, V * d, es);
+    std::fclose(f);
+    (void)hipHostFree(host);
+    if (rc != EE_OK) {
+        ee_model_free(m);
+        return rc;
+    }
+    *out = m;
+    return EE_OK;
+}
+
+int ee_model_free(ee_model* m) {
+    if (!m) return EE_ERR_ARG;
+    if (m->pinned) (void)hipHostFree(m->pinned);
+    delete m;
+    return EE_OK;
+}
+
+int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows) {
+    if (!m) return EE_ERR_ARG;
+    m->dbg_logits = (float*)dev_logits;
+    m->dbg_rows = dev_logits ? capacity_rows : 0;
+    return EE_OK;
+}
+
+/* ------------------------------------------------------------------ KV cache */
+
+int ee_kv_cache_bytes(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens, int max_pending,
+                      size_t* bytes) {
+    EECHK(check_cache_args(m, max_seqs, max_tokens_total, block_tokens, max_pending));
+    if (bytes) *bytes = kv_pool_layout(m, max_seqs, max_tokens_total, block_tokens, max_pending, 0, 0, 0, 0, 0);
+    return EE_OK;
+}
+
+int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens, int max_pending,
+                       void* dev_pool, size_t pool_bytes, ee_kv_cache** out) {
+    EECHK(check_cache_args(m, max_seqs, max_tokens_total, block_tokens, max_pending));
+    if (!dev_pool || !out || ((uintptr_t)dev_pool & 255)) return EE_ERR_ARG;
+    ee_kv_cache* c = new (std::nothrow) ee_kv_cache();
+    if (!c) return EE_ERR_NOMEM;
+    size_t need = kv_pool_layout(m, max_seqs, max_tokens_total, block_tokens, max_pending, &c->n_blocks, &c->off_x, &c->off_xg,
+                                 &c->off_xgh, &c->off_ssq);
+    if (pool_bytes < need) {
+        delete c;
+        return EE_ERR_NOMEM;
+    }
+    const ee_config& cf = m->cfg;
+    c->m = m;
+    c->max_seqs = max_seqs;
+    c->BT = block_tokens;
+    c->S = max_pending + 1;
+    c->max_pending = max_pending;
+    c->pool = (char*)dev_pool;
+    c->ssq_stride = cf.d_model / (16 * gemm_resid_tiles_per_wg());
+    c->geom.pool = dev_pool;
+    c->geom.blk_stride = 2 * (size_t)cf.n_heads * block_tokens * cf.head_dim;
+    c->geom.layer_stride = (size_t)c->n_blocks * c->geom.blk_stride;
+    c->geom.H = cf.n_heads;
+    c->geom.hd = cf.head_dim;
+    c->geom.BT = block_tokens;
+    c->geom.max_blocks_per_seq = m->wsl.max_blocks_per_seq;
+    for (int b = c->n_blocks - 1; b >= 0; --b) c->free_blocks.push_back(b);
+    c->seqs.resize(max_seqs);
+    for (auto& s : c->seqs) {
+        s.filled.assign(m->n_seg(), 0);
+        s.tokring.assign(c->S, -1);
+    }
+    *out = c;
+    return EE_OK;
+}
+
+int ee_kv_cache_reset(ee_kv_cache* c, int seq) {
+    if (!c) return EE_ERR_ARG;
+    if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
+    SeqState& s = c->seqs[seq];
+    for (int32_t b : s.blocks) c->free_blocks.push_back(b);
+    s.blocks.clear();
+    std::fill(s.filled.begin(), s.filled.end(), 0);
+    std::fill(s.tokring.begin(), s.tokring.end(), -1);
+    return EE_OK;
+}
+
+int ee_kv_cache_filled(const ee_kv_cache* c, int seq, int layer, int32_t* n_positions) {
+    if (!c || !n_positions) return EE_ERR_ARG;
+    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= c->m->cfg.n_layers) return EE_ERR_RANGE;
+    *n_positions = c->seqs[seq].filled[c->m->seg_of_layer(layer)];
+    return EE_OK;
+}
+
+int ee_kv_cache_pending(const ee_kv_cache* c, int seq, int32_t* n_pending) {
+    if (!c || !n_pending) return EE_ERR_ARG;
+    if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
+    *n_pending = c->n_pending(c->seqs[seq]);
+    return EE_OK;
+}
+
+int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int pos0, int n, float* k_host, float* v_host,
+                     void* stream) {
+    if (!m || !c || !k_host || !v_host || c->m != m) return EE_ERR_ARG;
+    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= m->cfg.n_layers || pos0 < 0 || n < 0) return EE_ERR_RANGE;
+    const SeqState& s = c->seqs[seq];
+    if (pos0 + n > (int)s.blocks.size() * c->BT) return EE_ERR_RANGE;
+    if (n == 0) return EE_OK;
+    hipStream_t st = (hipStream_t)stream;
+    put_btab(m, c, 0, s);
+    EECHK(upload(m, st));
+    const size_t d = m->cfg.d_model;
+    float* ks = (float*)(m->ws + m->wsl.stage);
+    float* vs = ks + (size_t)m->max_rows * d;
+    for (int o = 0; o < n; o += m->max_rows) {
+        int nn = std::min(m->max_rows, n - o);
+        HIPCHK(launch_kv_gather(m->cfg.dtype, c->geom, layer, m->dev_btab(), pos0 + o, nn, ks, vs, st));
+        HIPCHK(hipMemcpyAsync(k_host + (size_t)o * d, ks, nn * d * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipMemcpyAsync(v_host + (size_t)o * d, vs, nn * d * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+    }
+    return EE_OK;
+}
+
+int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_host, void* stream) {
+    if (!m || !c || !x_host) return EE_ERR_ARG;
+    if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
+    const SeqState& s = c->seqs[seq];
+    if (s.filled[0] < 1) return EE_ERR_STATE;
+    hipStream_t st = (hipStream_t)stream;
+    size_t d = m->cfg.d_model;
+    HIPCHK(hipMemcpyAsync(x_host, c->x() + (size_t)c->slot_of(seq, s.filled[0] - 1) * d, d * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    return EE_OK;
+}
+
+int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, void* stream) {
+    if (!m || !c || !seq_ids || c->m != m) return EE_ERR_ARG;
+    if (n_seqs < 1 || n_seqs > m->max_seqs) return EE_ERR_ARG;
+    if (m->n_missing) return EE_ERR_STATE;
+    std::vector<StepSeq> ss;
+    for (int b = 0; b < n_seqs; ++b) {
+        int sid = seq_ids[b];
+        if (sid < 0 || sid >= c->max_seqs) return EE_ERR_RANGE;
+        for (auto& q : ss)
+            if (q.seq == sid) return EE_ERR_ARG;
+        if (c->seqs[sid].filled[0] < 1) return EE_ERR_STATE;
+        ss.push_back(StepSeq{sid, -1, true, true});
+    }
+    return run_step(m, c, ss, 1.0f, false, nullptr, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int ee_kv_cache_free(ee_kv_cache* c) {
+    if (!c) return EE_ERR_ARG;
+    delete c;
+    return EE_OK;
+}
+
+/* ------------------------------------------------------------------ prefill */
+
+int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
+               int32_t* next_token, int32_t* exit_layer, float* conf, void* stream) {
+    if (!m || !c || !tokens || !next_token || !exit_layer || c->m != m) return EE_ERR_ARG;
+    if (m->n_missing) return EE_ERR_STATE;
+    if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
+    if (n_tokens < 1 || n_tokens > m->cfg.max_positions) return EE_ERR_RANGE;
+    for (int i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) return EE_ERR_RANGE;
+    SeqState& s = c->seqs[seq];
+    if (s.filled[0] != 0) return EE_ERR_STATE;
+    EECHK(ensure_blocks(c, s, n_tokens));
+    hipStream_t st = (hipStream_t)stream;
+    const ee_config& cf = m->cfg;
+    const int n_seg = m->n_seg();
+    const int CH = std::min(m->max_rows, 64);
+    put_btab(m, c, 0, s);
+    for (int p0 = 0; p0 < n_tokens; p0 += CH) {
+        int n = std::min(CH, n_tokens - p0);
+        bool last = p0 + n == n_tokens;
+        SegDesc* d = m->host_desc(0);
+        d->T = n;
+        d->n_qt = 0;
+        for (int r = 0; r < n; ++r) {
+            d->xrow[r] = c->transient_slot(r);
+            d->pos[r] = p0 + r;
+            d->kvblk[r] = s.blocks[(p0 + r) / c->BT];
+            d->rseq[r] = 0;
+            m->host_tokens()[r] = tokens[p0 + r];
+        }
+        for (int r = 0; r < n; r += 16) {
+            d->qt_row0[d->n_qt] = r;
+            d->qt_nq[d->n_qt] = std::min(16, n - r);
+            ++d->n_qt;
+        }
+        if (last) d->xrow[n - 1] = c->slot_of(seq, n_tokens - 1);  // so that the newest hidden state can be read back
+        d->n_head = 1;
+        d->head_xrow[0] = d->xrow[n - 1];
+        d->head_slot[0] = 0;
+        // one descriptor per head so that each writes its own result slot
+        for (int i = 1; i < n_seg; ++i) {
+            SegDesc* di = m->host_desc(i);
+            di->T = 0;
+            di->n_head = 1;
+            di->head_xrow[0] = d->head_xrow[0];
+            di->head_slot[0] = i * EE_MAX_SEQS;
+        }
+        EECHK(upload(m, st));
+        HIPCHK(launch_embed(cf.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), n, cf.d_model, m->gain(m->wl.g1[0]),
+                            c->x(), c->xg(), c->ssq(), c->ssq_stride, st));
+        for (int sgi = 0; sgi < n_seg; ++sgi) {
+            EECHK(run_layers(m, c, 0, n, d->n_qt, m->seg_begin(sgi), m->seg_end(sgi), p0 + n, st));
+            bool fin = sgi == n_seg - 1;
+            if (last && (fin || threshold < 1.0f)) EECHK(run_head(m, c, sgi, sgi, 1, fin ? HEAD_EMIT : HEAD_RULE, threshold, st));
+        }
+        HIPCHK(hipStreamSynchronize(st));  // the pinned staging is rewritten by the next chunk
+    }
+    int chosen = n_seg - 1;
+    for (int i = 0; i < n_seg; ++i) {
+        bool fin = i == n_seg - 1;
+        if (!fin && !(threshold < 1.0f)) {
+            if (conf) conf[i] = -1.f;
+            continue;
+        }
+        const HeadResult& r = m->results[i * EE_MAX_SEQS];
+        if (conf) conf[i] = r.conf;
+        if (!fin && r.fired && chosen == n_seg - 1) chosen = i;
+    }
+    *next_token = m->results[chosen * EE_MAX_SEQS].token;
+    *exit_layer = m->seg_end(chosen);
+    for (auto& f : s.filled) f = n_tokens;
+    return EE_OK;
+}
+
+/* ------------------------------------------------------------------ decode */
+
+int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
+                   const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
+                   int32_t* exit_layer, float* conf, void* stream) {
+    if (!m || !c || !seq_ids || !row_offsets || !tokens || !pending_mask || !next_token || !exit_layer || c->m != m)
+        return EE_ERR_ARG;
+    if (n_seqs < 1 || n_seqs > m->max_seqs) return EE_ERR_ARG;
+    if (m->n_missing) return EE_ERR_STATE;
+    if (!(threshold >= 0.f)) return EE_ERR_ARG;
+    std::vector<StepSeq> ss;
+    size_t blocks_needed = 0;
+    // pass 1: validate everything before touching any state
+    for (int b = 0; b < n_seqs; ++b) {
+        int sid = seq_ids[b];
+        if (sid < 0 || sid >= c->max_seqs) return EE_ERR_RANGE;
+        for (auto& q : ss)
+            if (q.seq == sid) return EE_ERR_ARG;
+        const SeqState& s = c->seqs[sid];
+        if (s.filled[0] < 1) return EE_ERR_STATE;  // not prefilled
+        int r0 = row_offsets[b], r1 = row_offsets[b + 1];
+        int pend = c->n_pending(s);
+        if (r1 - r0 != pend + 1) return EE_ERR_STATE;
+        for (int i = 0; i < pend; ++i) {
+            if (pending_mask[r0 + i] != 1) return EE_ERR_STATE;
+            if (tokens[r0 + i] != s.tokring[(s.filled.back() + i) % c->S]) return EE_ERR_STATE;
+        }
+        if (pending_mask[r1 - 1] != 0) return EE_ERR_STATE;
+        int tok = tokens[r1 - 1];
+        if (tok < 0 || tok >= m->cfg.vocab) return EE_ERR_RANGE;
+        int p = s.filled[0];
+        if (p >= m->cfg.max_positions) return EE_ERR_RANGE;
+        if ((p + c->BT) / c->BT > c->geom.max_blocks_per_seq) return EE_ERR_RANGE;
+        if ((p + c->BT) / c->BT > (int)s.blocks.size()) ++blocks_needed;
+        if (blocks_needed > c->free_blocks.size()) return EE_ERR_NOMEM;
+        ss.push_back(StepSeq{sid, p, pend >= c->max_pending, true});
+    }
+    // pass 2: commit the current tokens
+    for (int b = 0; b < n_seqs; ++b) {
+        SeqState& s = c->seqs[ss[b].seq];
+        EECHK(ensure_blocks(c, s, ss[b].p + 1));
+        int tok = tokens[row_offsets[b + 1] - 1];
+        s.tokring[ss[b].p % c->S] = tok;
+        m->host_tokens()[b] = tok;  // segment 0 has exactly one row per sequence, in step order
+    }
+    return run_step(m, c, ss, threshold, true, next_token, exit_layer, conf, (hipStream_t)stream);
+}
+
+}  // extern "C"

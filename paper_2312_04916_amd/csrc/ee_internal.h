@@ -1,0 +1,93 @@
+// Internal declarations shared by the host logic (ee_api.cpp) and the kernels (ee_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ee.h"
+
+namespace ee {
+
+// Per-launch row description, built on the host, copied to the device once per step.
+struct SegDesc {
+    int32_t T;       // rows in this launch
+    int32_t n_qt;    // attention query tiles
+    int32_t n_head;  // rows the head is evaluated on
+    int32_t pad;
+    int32_t xrow[EE_MAX_ROWS];   // residual-store slot of row r
+    int32_t pos[EE_MAX_ROWS];    // position of row r in its sequence
+    int32_t kvblk[EE_MAX_ROWS];  // physical KV block that holds pos[r]
+    int32_t rseq[EE_MAX_ROWS];   // index of the row's sequence in this step's block-table array
+    int32_t qt_row0[EE_MAX_ROWS];  // query tile: first row, number of rows (<= 16, one sequence,
+    int32_t qt_nq[EE_MAX_ROWS];    //   consecutive positions)
+    int32_t head_xrow[EE_MAX_SEQS];  // residual-store slot of each head row
+    int32_t head_slot[EE_MAX_SEQS];  // result slot of each head row
+};
+
+// What a head evaluation reports per row (lives in pinned host memory, written by the kernel).
+struct HeadResult {
+    int32_t token;
+    float conf;
+    int32_t fired;
+    int32_t pad;
+};
+
+struct HeadPartial {
+    float max, sum;
+    int32_t idx, pad;
+};
+
+// Geometry of the paged cache as the kernels see it.
+struct KvGeom {
+    void* pool;           // [L][n_blocks][2][H][BT][hd]
+    size_t layer_stride;  // elements
+    size_t blk_stride;    // elements: 2*H*BT*hd
+    int32_t H, hd, BT, max_blocks_per_seq;
+};
+
+enum HeadMode { HEAD_RULE = 0, HEAD_EMIT = 1 };
+
+// ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
+
+hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);
+
+// mode 0: destination tile = src_tile*tile_mul + tile_off; mode 1: rotary pairing inside each head
+hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, int tile_mul,
+                       int tile_off, hipStream_t s);
+
+hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
+                        const float* g_next, float* x, void* xg, float* ssq, int ssq_stride, hipStream_t s);
+
+struct GemmCommon {
+    int dtype;
+    const void* W;     // packed weights of this matrix
+    int N, K;          // output features (packed rows), reduction length
+    const void* A;     // activations, [rows][lda]
+    int lda;
+    const int32_t* arow;  // row indirection into A (and into ssq), or NULL
+    const float* ssq;     // partial sums of squares [slot][ssq_stride], or NULL (no RMS scale)
+    int ssq_stride, ssq_n;
+    float inv_d, eps;
+    int T;  // rows
+    const SegDesc* desc;
+};
+
+hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, const float* rope_cs, const KvGeom& kv, int layer,
+                           hipStream_t s);
+hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, float* ssq_out, const float* g_next,
+                             const float* g_head, int d, hipStream_t s);
+hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, int F, hipStream_t s);
+hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
+                            float threshold, HeadResult* results, hipStream_t s);
+
+hipError_t launch_attention(int dtype, const void* q, void* out, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
+                            hipStream_t s);
+
+hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_t* btab_seq, int pos0, int n,
+                            float* k_out, float* v_out, hipStream_t s);
+
+int gemm_resid_tiles_per_wg();  // G of the residual epilogue: ssq partials per row = d / (16*G)
+size_t attention_part_floats(int max_rows, int H, int hd);  // scratch the attention kernel needs
+
+}  // namespace ee

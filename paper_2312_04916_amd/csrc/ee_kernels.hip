@@ -1,0 +1,694 @@
+// HIP kernels (gfx950) for one early-exit decode step with KV recomputation.
+//
+// Every decode GEMM has at most a few dozen rows (the current token plus the deferred tokens that are
+// carried along, Section 4 "KV recomputation"), so it is a weight-streaming problem bound by HBM
+// bandwidth: weights are stored pre-shuffled so that one wave load instruction fetches 1 KB of
+// contiguous memory that is already a 16x32 bf16 MFMA operand, a workgroup owns a few 16-column
+// tiles and splits the reduction dimension over its waves, and everything that follows the product
+// (rotary embedding and the KV-cache write, residual add, the next layer's normalised input,
+// SwiGLU, the soft-max max/arg-max over the vocabulary and the exit decision) runs in the epilogue
+// of the kernel that produced it.  No float atomics: every reduction has a fixed order.
+#include "ee_internal.h"
+
+namespace ee {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename ST> __device__ __forceinline__ ST cvt_st(float v);
+template <> __device__ __forceinline__ float cvt_st<float>(float v) { return v; }
+template <> __device__ __forceinline__ __bf16 cvt_st<__bf16>(float v) { return (__bf16)v; }  // round to nearest even
+
+template <typename ST> __device__ __forceinline__ float ld_f(const ST* p) { return (float)*p; }
+
+// ------------------------------------------------------------------------------------------------
+// rotary table: cs[pos][i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
+// ------------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(float2* cs, int max_pos, int half, int hd, float base) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= max_pos * half) return;
+    int pos = idx / half, i = idx % half;
+    double ang = (double)pos * pow((double)base, -2.0 * (double)i / (double)hd);
+    cs[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s) {
+    int n = max_pos * (hd / 2);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (float2*)cs, max_pos, hd / 2, hd, base);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// weight packing.  Source: row-major [n_rows][K].  Destination rows are grouped in tiles of 16.
+//   bf16: [tile][K/32][lane 0..63][8]  with lane = (k_group << 4) | row_in_tile, k = kt*32 + k_group*8 + j
+//   fp32: [tile][16][K] (row permutation only)
+// mode 1 reorders the 16-row tiles inside every head so that the two halves of a rotary pair
+// (feature i and i + hd/2) sit in neighbouring tiles: tile (h, c, s) = features h*hd + s*hd/2 + c*16 ..
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int dst_tile_of(int src_tile, int mode, int hd, int tile_mul, int tile_off) {
+    if (mode == 0) return src_tile * tile_mul + tile_off;
+    int row = src_tile * 16;
+    int h = row / hd, o = row % hd;
+    int s = o >= hd / 2;
+    int c = (o % (hd / 2)) / 16;
+    return (h * (hd / 32) + c) * 2 + s;
+}
+
+__global__ void pack_bf16_kernel(const __bf16* __restrict__ src, uint4* __restrict__ dst, int n_tiles, int K, int mode,
+                                 int hd, int tile_mul, int tile_off) {
+    int KT = K / 32;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;  // (src_tile, kt, lane)
+    long total = (long)n_tiles * KT * 64;
+    if (idx >= total) return;
+    int lane = idx & 63;
+    long r = idx >> 6;
+    int kt = r % KT;
+    int st = r / KT;
+    int dt = dst_tile_of(st, mode, hd, tile_mul, tile_off);
+    const uint4* sp = (const uint4*)(src + ((size_t)(st * 16 + (lane & 15)) * K + kt * 32 + (lane >> 4) * 8));
+    dst[((size_t)dt * KT + kt) * 64 + lane] = *sp;
+}
+
+__global__ void pack_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int n_rows, int K, int mode, int hd,
+                                int tile_mul, int tile_off) {
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)n_rows * K) return;
+    int row = idx / K, k = idx % K;
+    int dt = dst_tile_of(row / 16, mode, hd, tile_mul, tile_off);
+    dst[((size_t)dt * 16 + (row & 15)) * K + k] = src[idx];
+}
+
+hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, int tile_mul,
+                       int tile_off, hipStream_t s) {
+    if (dtype == EE_BF16) {
+        long total = (long)(n_rows / 16) * (K / 32) * 64;
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const __bf16*)src,
+                           (uint4*)dst, n_rows / 16, K, mode, hd, tile_mul, tile_off);
+    } else {
+        long total = (long)n_rows * K;
+        hipLaunchKernelGGL(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float*)src,
+                           (float*)dst, n_rows, K, mode, hd, tile_mul, tile_off);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// embedding gather: x = E[token]; xg = st(x * g_next); ssq[slot][0] = sum x^2, ssq[slot][1..] = 0
+// one workgroup per row
+// ------------------------------------------------------------------------------------------------
+template <typename ST>
+__global__ void embed_kernel(const ST* __restrict__ embed, const int32_t* __restrict__ tokens, const SegDesc* __restrict__ desc,
+                             int d, const float* __restrict__ g_next, float* __restrict__ x, ST* __restrict__ xg,
+                             float* __restrict__ ssq, int ssq_stride) {
+    __shared__ float red[256];
+    int r = blockIdx.x;
+    int slot = desc->xrow[r];
+    int tok = tokens[r];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        float v = (float)embed[(size_t)tok * d + i];
+        x[(size_t)slot * d + i] = v;
+        xg[(size_t)slot * d + i] = cvt_st<ST>(v * g_next[i]);
+        s += v * v;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    for (int i = threadIdx.x; i < ssq_stride; i += blockDim.x) ssq[(size_t)slot * ssq_stride + i] = (i == 0) ? red[0] : 0.f;
+}
+
+hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
+                        const float* g_next, float* x, void* xg, float* ssq, int ssq_stride, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    if (dtype == EE_BF16)
+        hipLaunchKernelGGL(embed_kernel<__bf16>, dim3(T), dim3(256), 0, s, (const __bf16*)embed, dev_tokens, desc, d, g_next, x,
+                           (__bf16*)xg, ssq, ssq_stride);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)embed, dev_tokens, desc, d, g_next, x,
+                           (float*)xg, ssq, ssq_stride);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// skinny GEMM: out[m][n] = r[m] * sum_k A[m][k] * W[n][k],  m < T <= MT*16
+// A workgroup owns G consecutive 16-column tiles; its G*KS waves split K in KS parts.
+// The result lands in LDS as out[MT*16][G*16] fp32 and is handed to the epilogue.
+// ------------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const void* W;
+    int KT;  // K / 32 (bf16) ; K (fp32 path uses K directly)
+    int K;
+    const void* A;
+    int lda;
+    const int32_t* arow;
+    const float* ssq;
+    int ssq_stride, ssq_n;
+    float inv_d, eps;
+    int T;
+};
+
+template <int G, int KS, int MT>
+struct GemmSmem {
+    float red[KS][G][MT][256];
+    float out[MT * 16][G * 16];
+    float rs[MT * 16];
+};
+
+template <int MT>
+__device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
+    // r[m] = 1/sqrt(mean(x^2)+eps); the sum of squares arrives as ssq_n partial sums, added in order
+    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+        float r = 1.f;
+        if (a.ssq != nullptr && m < a.T) {
+            int slot = a.arow ? a.arow[m] : m;
+            const float* p = a.ssq + (size_t)slot * a.ssq_stride;
+            float s = 0.f;
+            for (int i = 0; i < a.ssq_n; ++i) s += p[i];
+            r = 1.0f / sqrtf(s * a.inv_d + a.eps);
+        }
+        rs[m] = r;
+    }
+}
+
+template <int G, int KS, int MT>
+__device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = wave / KS, ks = wave % KS;
+    const int li = lane & 15, lg = lane >> 4;
+    const int KT = a.KT;
+    const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
+    const u32x4* wp = (const u32x4*)a.W + ((size_t)(tile0 + g) * KT + kt0) * 64 + lane;
+    const __bf16* ap[MT];
+    bool av[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int row = mt * 16 + li;
+        av[mt] = row < a.T;
+        int idx = av[mt] ? (a.arow ? a.arow[row] : row) : 0;
+        ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + lg * 8;
+    }
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    int kt = kt0;
+    constexpr int C = 8;
+    for (; kt + C <= kt1; kt += C) {
+        u32x4 w[C];
+#pragma unroll
+        for (int u = 0; u < C; ++u) w[u] = __builtin_nontemporal_load(wp + u * 64);
+        wp += C * 64;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            u32x4 av4[C];
+#pragma unroll
+            for (int u = 0; u < C; ++u) av4[u] = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)(kt + u) * 32) : zero;
+#pragma unroll
+            for (int u = 0; u < C; ++u)
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av4[u]),
+                                                                  __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
+        }
+    }
+    for (; kt < kt1; ++kt) {
+        u32x4 w = __builtin_nontemporal_load(wp);
+        wp += 64;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            u32x4 a4 = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)kt * 32) : zero;
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, w),
+                                                              acc[mt], 0, 0, 0);
+        }
+    }
+    // accumulator layout: lane (lg, li) holds D[row = lg*4 + r][col = li]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm.red[ks][g][mt][(lg * 4 + r) * 16 + li] = acc[mt][r];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * MT * 256; idx += blockDim.x) {
+        int e = idx & 255, mt = (idx >> 8) % MT, gg = idx / (256 * MT);
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) s += sm.red[k][gg][mt][e];
+        int m = mt * 16 + (e >> 4);
+        sm.out[m][gg * 16 + (e & 15)] = s * sm.rs[m];
+    }
+    __syncthreads();
+}
+
+// fp32 path (tiny model, parity only): plain FMA loop, weights row-major [tile][16][K]
+template <int G, int KS, int MT>
+__device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < MT * 16 * G * 16; idx += blockDim.x) {
+        int m = idx / (G * 16), c = idx % (G * 16);
+        float s = 0.f;
+        if (m < a.T) {
+            int slot = a.arow ? a.arow[m] : m;
+            const float* ar = (const float*)a.A + (size_t)slot * a.lda;
+            const float* wr = (const float*)a.W + ((size_t)tile0 * 16 + c) * a.K;
+            for (int k = 0; k < a.K; ++k) s = fmaf(ar[k], wr[k], s);
+        }
+        sm.out[m][c] = s * sm.rs[m];
+    }
+    __syncthreads();
+}
+
+template <typename ST, int G, int KS, int MT>
+__device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
+    rms_scales<MT>(a, sm.rs);
+    if constexpr (sizeof(ST) == 2)
+        gemm_mainloop_bf16<G, KS, MT>(a, tile0, sm);  // (its first __syncthreads orders rs before use)
+    else
+        gemm_mainloop_f32<G, KS, MT>(a, tile0, sm);
+}
+
+// ---- epilogue 1: rotary embedding, q to the workspace, k and v into the paged cache
+template <typename ST>
+struct QkvArgs {
+    ST* q;
+    int d;
+    const float2* rope_cs;
+    ST* kv_layer;  // pool + layer * layer_stride
+    size_t blk_stride;
+    int H, hd, BT;
+    const SegDesc* desc;
+};
+
+template <typename ST, int KS, int MT>
+__global__ __launch_bounds__(2 * KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
+    __shared__ GemmSmem<2, KS, MT> sm;
+    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
+    const int per_part = e.H * (e.hd / 32);
+    const int part = blockIdx.x / per_part;  // 0 q, 1 k, 2 v
+    const int rem = blockIdx.x % per_part;
+    const int h = rem / (e.hd / 32), c = rem % (e.hd / 32);
+    const int half = e.hd / 2;
+    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+        int m = idx >> 4, i = idx & 15;
+        if (m >= a.T) continue;
+        float lo = sm.out[m][i], hi = sm.out[m][16 + i];
+        int pos = e.desc->pos[m];
+        if (part < 2) {
+            float2 cs = e.rope_cs[(size_t)pos * half + c * 16 + i];
+            float nlo = lo * cs.x - hi * cs.y;
+            float nhi = hi * cs.x + lo * cs.y;
+            lo = nlo;
+            hi = nhi;
+        }
+        if (part == 0) {
+            ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 16 + i;
+            qp[0] = cvt_st<ST>(lo);
+            qp[half] = cvt_st<ST>(hi);
+        } else {
+            ST* kp = e.kv_layer + (size_t)e.desc->kvblk[m] * e.blk_stride + (part == 2 ? (size_t)e.H * e.BT * e.hd : 0) +
+                     ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 16 + i;
+            kp[0] = cvt_st<ST>(lo);
+            kp[half] = cvt_st<ST>(hi);
+        }
+    }
+}
+
+// ---- epilogue 2: residual add; normalised-input operand(s) for what follows; sum-of-squares partial
+template <typename ST>
+struct ResidArgs {
+    float* x;
+    ST* xg;
+    ST* xgh;
+    float* ssq_out;
+    int ssq_stride;
+    const float* g_next;
+    const float* g_head;
+    int d;
+    const SegDesc* desc;
+};
+
+template <typename ST, int KS, int MT>
+__global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
+    __shared__ GemmSmem<1, KS, MT> sm;
+    gemm_mainloop<ST, 1, KS, MT>(a, blockIdx.x, sm);
+    const int n0 = blockIdx.x * 16;
+    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+        int m = idx >> 4, i = idx & 15;
+        if (m >= a.T) continue;
+        size_t o = (size_t)e.desc->xrow[m] * e.d + n0 + i;
+        float v = e.x[o] + sm.out[m][i];
+        e.x[o] = v;
+        sm.out[m][i] = v;
+        e.xg[o] = cvt_st<ST>(v * e.g_next[n0 + i]);
+        if (e.xgh) e.xgh[o] = cvt_st<ST>(v * e.g_head[n0 + i]);
+    }
+    __syncthreads();
+    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+        if (m >= a.T) continue;
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += sm.out[m][i] * sm.out[m][i];
+        e.ssq_out[(size_t)e.desc->xrow[m] * e.ssq_stride + blockIdx.x] = s;
+    }
+}
+
+// ---- epilogue 3: SwiGLU.  tile 2j holds gate features 16j.., tile 2j+1 the matching up features
+template <typename ST, int KS, int MT>
+__global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, int F) {
+    __shared__ GemmSmem<2, KS, MT> sm;
+    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
+    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+        int m = idx >> 4, i = idx & 15;
+        if (m >= a.T) continue;
+        float gt = sm.out[m][i], up = sm.out[m][16 + i];
+        float sl = gt / (1.0f + expf(-gt));
+        act[(size_t)m * F + blockIdx.x * 16 + i] = cvt_st<ST>(sl * up);
+    }
+}
+
+// ---- epilogue 4: exit / final head.  Per workgroup: (max, arg max, sum exp) of its 32 logits per row;
+// the workgroup that finishes last merges all partials in a fixed order and takes the exit decision.
+struct HeadArgs {
+    HeadPartial* partials;  // [n_wg][EE_MAX_SEQS]
+    int32_t* counter;
+    float* logits;  // optional [row][V]
+    int V;
+    int mode;
+    float threshold;
+    HeadResult* results;
+    const SegDesc* desc;
+};
+
+__device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float m2, float s2, int i2) {
+    if (m2 > m || (m2 == m && i2 < i)) {
+        s = s * expf(m - m2) + s2;
+        m = m2;
+        i = i2;
+    } else {
+        s = s + s2 * expf(m2 - m);
+    }
+}
+
+template <typename ST, int KS, int MT>
+__global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
+    __shared__ GemmSmem<2, KS, MT> sm;
+    __shared__ int s_last;
+    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
+    const int n0 = blockIdx.x * 32;
+    if (e.logits) {
+        for (int idx = threadIdx.x; idx < MT * 16 * 32; idx += blockDim.x) {
+            int m = idx >> 5, c = idx & 31;
+            if (m < a.T) e.logits[(size_t)m * e.V + n0 + c] = sm.out[m][c];
+        }
+    }
+    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+        if (m >= a.T) continue;
+        float mx = sm.out[m][0];
+        int ix = 0;
+        for (int c = 1; c < 32; ++c)
+            if (sm.out[m][c] > mx) {
+                mx = sm.out[m][c];
+                ix = c;
+            }
+        float s = 0.f;
+        for (int c = 0; c < 32; ++c) s += expf(sm.out[m][c] - mx);
+        HeadPartial p;
+        p.max = mx;
+        p.sum = s;
+        p.idx = n0 + ix;
+        p.pad = 0;
+        e.partials[(size_t)blockIdx.x * EE_MAX_SEQS + m] = p;
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = (atomicAdd(e.counter, 1) == (int)gridDim.x - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // merge: thread t folds workgroups t, t+nthr, ... in ascending order, then a fixed tree over threads
+    float* redm = &sm.red[0][0][0][0];
+    float* reds = redm + 512;
+    int* redi = (int*)(reds + 512);
+    const int nthr = blockDim.x;  // 2*KS*64 <= 512
+    for (int m = 0; m < a.T; ++m) {
+        float mx = -INFINITY, s = 0.f;
+        int ix = 0x7fffffff;
+        for (int w = threadIdx.x; w < (int)gridDim.x; w += nthr) {
+            HeadPartial p = e.partials[(size_t)w * EE_MAX_SEQS + m];
+            merge_partial(mx, s, ix, p.max, p.sum, p.idx);
+        }
+        redm[threadIdx.x] = mx;
+        reds[threadIdx.x] = s;
+        redi[threadIdx.x] = ix;
+        __syncthreads();
+        for (int o = nthr >> 1; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) {
+                float m1 = redm[threadIdx.x], s1 = reds[threadIdx.x];
+                int i1 = redi[threadIdx.x];
+                float m2 = redm[threadIdx.x + o], s2 = reds[threadIdx.x + o];
+                int i2 = redi[threadIdx.x + o];
+                if (s2 > 0.f || m2 > -INFINITY) merge_partial(m1, s1, i1, m2, s2, i2);
+                redm[threadIdx.x] = m1;
+                reds[threadIdx.x] = s1;
+                redi[threadIdx.x] = i1;
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            float conf = 1.0f / reds[0];
+            HeadResult r;
+            r.token = redi[0];
+            r.conf = conf;
+            r.fired = (e.mode == HEAD_EMIT) || (conf >= e.threshold);
+            r.pad = 0;
+            e.results[e.desc->head_slot[m]] = r;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *e.counter = 0;
+}
+
+// ---- host-side dispatch
+static GemmArgs make_args(const GemmCommon& c) {
+    GemmArgs a;
+    a.W = c.W;
+    a.K = c.K;
+    a.KT = c.K / 32;
+    a.A = c.A;
+    a.lda = c.lda;
+    a.arow = c.arow;
+    a.ssq = c.ssq;
+    a.ssq_stride = c.ssq_stride;
+    a.ssq_n = c.ssq_n;
+    a.inv_d = c.inv_d;
+    a.eps = c.eps;
+    a.T = c.T;
+    return a;
+}
+
+static int mt_of(int T) { return T <= 16 ? 1 : (T <= 32 ? 2 : 4); }
+
+#define EE_DISPATCH_MT(T, CALL)              \
+    switch (mt_of(T)) {                      \
+        case 1: { constexpr int MT = 1; CALL; } break; \
+        case 2: { constexpr int MT = 2; CALL; } break; \
+        default: { constexpr int MT = 4; CALL; } break; \
+    }
+
+constexpr int KS_QKV = 4, KS_RES = 8, KS_SWI = 4, KS_HEAD = 4;
+
+int gemm_resid_tiles_per_wg() { return 1; }
+
+hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, const float* rope_cs, const KvGeom& kv, int layer,
+                           hipStream_t s) {
+    if (c.T <= 0) return hipSuccess;
+    if (c.T > 64) return hipErrorInvalidValue;
+    GemmArgs a = make_args(c);
+    dim3 grid(c.N / 32), block(2 * KS_QKV * 64);
+    if (c.dtype == EE_BF16) {
+        QkvArgs<__bf16> e{(__bf16*)q, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
+                          kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<__bf16, KS_QKV, MT>), grid, block, 0, s, a, e));
+    } else {
+        QkvArgs<float> e{(float*)q, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
+                         kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<float, KS_QKV, MT>), grid, block, 0, s, a, e));
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, float* ssq_out, const float* g_next,
+                             const float* g_head, int d, hipStream_t s) {
+    if (c.T <= 0) return hipSuccess;
+    if (c.T > 64) return hipErrorInvalidValue;
+    GemmArgs a = make_args(c);
+    dim3 grid(c.N / 16), block(KS_RES * 64);
+    if (c.dtype == EE_BF16) {
+        ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<__bf16, KS_RES, MT>), grid, block, 0, s, a, e));
+    } else {
+        ResidArgs<float> e{x, (float*)xg, (float*)xgh, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<float, KS_RES, MT>), grid, block, 0, s, a, e));
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, int F, hipStream_t s) {
+    if (c.T <= 0) return hipSuccess;
+    if (c.T > 64) return hipErrorInvalidValue;
+    GemmArgs a = make_args(c);
+    dim3 grid(c.N / 32), block(2 * KS_SWI * 64);
+    if (c.dtype == EE_BF16) {
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, 0, s, a, (__bf16*)act, F));
+    } else {
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, 0, s, a, (float*)act, F));
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
+                            float threshold, HeadResult* results, hipStream_t s) {
+    if (c.T <= 0) return hipSuccess;
+    if (c.T > 64) return hipErrorInvalidValue;
+    GemmArgs a = make_args(c);
+    HeadArgs e{partials, counter, logits, c.N, mode, threshold, results, c.desc};
+    dim3 grid(c.N / 32), block(2 * KS_HEAD * 64);
+    if (c.dtype == EE_BF16) {
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_head_kernel<__bf16, KS_HEAD, MT>), grid, block, 0, s, a, e));
+    } else {
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_head_kernel<float, KS_HEAD, MT>), grid, block, 0, s, a, e));
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// attention, reference-grade kernel: one workgroup per (row, head); the row at position p attends to
+// cache positions 0..p of its sequence (which includes the rows before it in this launch: their K,V
+// were written by the QKV kernel).  Online soft-max over chunks of 1024 positions.
+// ------------------------------------------------------------------------------------------------
+template <typename ST>
+__device__ __forceinline__ const ST* kv_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int which, int h,
+                                             int pos) {
+    int blk = bt[pos / kv.BT];
+    return layer_base + (size_t)blk * kv.blk_stride + (which ? (size_t)kv.H * kv.BT * kv.hd : 0) +
+           ((size_t)h * kv.BT + (pos % kv.BT)) * kv.hd;
+}
+
+__device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            float b = red[threadIdx.x + o];
+            red[threadIdx.x] = is_max ? fmaxf(red[threadIdx.x], b) : red[threadIdx.x] + b;
+        }
+        __syncthreads();
+    }
+    float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+template <typename ST>
+__global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__ q, ST* __restrict__ out,
+                                                          const SegDesc* __restrict__ desc, const int32_t* __restrict__ btab,
+                                                          KvGeom kv, const ST* __restrict__ layer_base, int d) {
+    __shared__ float qs[128];
+    __shared__ float sc[1024];
+    __shared__ float red[256];
+    const int r = blockIdx.x, h = blockIdx.y, hd = kv.hd;
+    const int pos = desc->pos[r];
+    const int32_t* bt = btab + (size_t)desc->rseq[r] * kv.max_blocks_per_seq;
+    const float scale = 1.0f / sqrtf((float)hd);
+    for (int i = threadIdx.x; i < hd; i += 256) qs[i] = (float)q[(size_t)r * d + h * hd + i];
+    __syncthreads();
+    float m = -INFINITY, l = 0.f, acc = 0.f;
+    const int n_ctx = pos + 1;
+    for (int j0 = 0; j0 < n_ctx; j0 += 1024) {
+        int nj = min(1024, n_ctx - j0);
+        float cmax = -INFINITY;
+        for (int jj = threadIdx.x; jj < nj; jj += 256) {
+            const ST* kp = kv_ptr(layer_base, kv, bt, 0, h, j0 + jj);
+            float s = 0.f;
+            for (int c = 0; c < hd; ++c) s = fmaf(qs[c], (float)kp[c], s);
+            s *= scale;
+            sc[jj] = s;
+            cmax = fmaxf(cmax, s);
+        }
+        cmax = block_reduce(cmax, red, true);
+        float m_new = fmaxf(m, cmax);
+        float psum = 0.f;
+        for (int jj = threadIdx.x; jj < nj; jj += 256) {
+            float p = expf(sc[jj] - m_new);
+            sc[jj] = p;
+            psum += p;
+        }
+        psum = block_reduce(psum, red, false);
+        float corr = expf(m - m_new);  // exp(-inf) = 0 on the first chunk
+        l = l * corr + psum;
+        if ((int)threadIdx.x < hd) {
+            float a2 = 0.f;
+            for (int jj = 0; jj < nj; ++jj) a2 = fmaf(sc[jj], (float)kv_ptr(layer_base, kv, bt, 1, h, j0 + jj)[threadIdx.x], a2);
+            acc = acc * corr + a2;
+        }
+        m = m_new;
+        __syncthreads();
+    }
+    if ((int)threadIdx.x < hd) out[(size_t)r * d + h * hd + threadIdx.x] = cvt_st<ST>(acc / l);
+}
+
+size_t attention_part_floats(int max_rows, int H, int hd) {
+    (void)max_rows;
+    (void)H;
+    (void)hd;
+    return 64;
+}
+
+hipError_t launch_attention(int dtype, const void* q, void* out, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
+                            hipStream_t s) {
+    (void)n_qt;
+    (void)part;
+    (void)counters;
+    (void)max_ctx;
+    if (T <= 0) return hipSuccess;
+    dim3 grid(T, kv.H), block(256);
+    if (dtype == EE_BF16)
+        hipLaunchKernelGGL(attn_simple_kernel<__bf16>, grid, block, 0, s, (const __bf16*)q, (__bf16*)out, desc, btab, kv,
+                           (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride, d);
+    else
+        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, block, 0, s, (const float*)q, (float*)out, desc, btab, kv,
+                           (const float*)kv.pool + (size_t)layer * kv.layer_stride, d);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// cache export (tests): K,V of positions [pos0, pos0+n) of one layer as fp32 [n][d]
+// ------------------------------------------------------------------------------------------------
+template <typename ST>
+__global__ void kv_gather_kernel(KvGeom kv, const ST* __restrict__ layer_base, const int32_t* __restrict__ bt, int pos0, int n,
+                                 float* __restrict__ k_out, float* __restrict__ v_out) {
+    int d = kv.H * kv.hd;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)n * d) return;
+    int t = idx / d, c = idx % d;
+    int h = c / kv.hd, i = c % kv.hd;
+    k_out[idx] = (float)kv_ptr(layer_base, kv, bt, 0, h, pos0 + t)[i];
+    v_out[idx] = (float)kv_ptr(layer_base, kv, bt, 1, h, pos0 + t)[i];
+}
+
+hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_t* btab_seq, int pos0, int n,
+                            float* k_out, float* v_out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    long total = (long)n * kv.H * kv.hd;
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (dtype == EE_BF16)
+        hipLaunchKernelGGL(kv_gather_kernel<__bf16>, grid, block, 0, s, kv, (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride,
+                           btab_seq, pos0, n, k_out, v_out);
+    else
+        hipLaunchKernelGGL(kv_gather_kernel<float>, grid, block, 0, s, kv, (const float*)kv.pool + (size_t)layer * kv.layer_stride,
+                           btab_seq, pos0, n, k_out, v_out);
+    return hipGetLastError();
+}
+
+}  // namespace ee

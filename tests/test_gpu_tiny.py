@@ -1,0 +1,199 @@
+"""GPU parity on the tiny workload (C1, fp32) and on a tiny bf16 model, through the C ABI, against the
+CPU oracle: tokens and exit layers exact outside the guard band, hidden states / logits / cached KV
+within the stated relative error (1e-4 for fp32, 2e-2 for bf16)."""
+import os
+import tempfile
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_04916_amd as ee
+from oracle import oracle as O
+from oracle.from_workload import build_model
+from workload import CONFIGS, ModelShape, prompt_tokens, write_weight_file
+
+from common import ee_config_of, load_gpu_model, lockstep, rel_err
+
+pytestmark = pytest.mark.gpu
+
+C1 = CONFIGS["C1"]
+TINY_BF16 = ModelShape(4, 128, 4, 32, 352, 1024, (1, 2), "bf16", 0.02, 0.3)
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module", params=["f32", "bf16"])
+def pair(request):
+    shape = C1.shape if request.param == "f32" else TINY_BF16
+    om = build_model(shape, 0, gain_jitter=0.1)
+    gm = load_gpu_model(shape, 0, gain_jitter=0.1, max_positions=256, max_rows=64, max_seqs=2)
+    yield shape, om, gm
+    gm.close()
+
+
+@pytest.fixture(scope="module")
+def prompt():
+    return prompt_tokens(C1.shape.vocab, C1.prompt_len[0], C1.prompt_seed).numpy()
+
+
+def new_cache(gm, max_pending=40, block_tokens=32, max_seqs=2):
+    return ee.KvCache(gm, max_seqs, 512, block_tokens, max_pending)
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.2, 0.35, 0.5, 0.8, 1.0])
+def test_lockstep_generation(pair, prompt, tau):
+    shape, om, gm = pair
+    print(f"case: lockstep {shape.dtype} tau={tau}", flush=True)
+    cache = new_cache(gm)
+    logits = gm.enable_logits(1)
+    rep = lockstep(gm, cache, om, prompt, C1.new_tokens, tau, max_pending=40, logits=logits)
+    assert not rep.mismatches, rep.mismatches[:5]
+    tol = TOL[shape.dtype]
+    assert rep.max_hidden_err <= tol, rep.max_hidden_err
+    assert rep.max_logit_err <= tol, rep.max_logit_err
+    assert rep.max_conf_err <= (1e-4 if shape.dtype == "f32" else 2e-2)
+    if tau == 0.0:
+        assert set(rep.exit_layers) == {shape.exit_layers[0]}
+    if tau == 1.0:
+        assert set(rep.exit_layers) == {shape.n_layers}
+        if rep.teacher_forced == 0:
+            assert rep.tokens == om.generate_plain(prompt, C1.new_tokens).tolist()
+    if shape.dtype == "f32":
+        assert rep.teacher_forced == 0
+        toks, exits = om.generate_g0(prompt, C1.new_tokens, tau)
+        assert rep.tokens == toks.tolist() and rep.exit_layers == exits.tolist()
+    # KV recomputation: after a flush the cache equals the oracle's (which equals a full-depth forward)
+    n_pos = len(prompt) + C1.new_tokens - 1
+    st = rep.state
+    cache.flush([0])
+    st.flush()
+    assert cache.pending(0) == 0
+    for l in range(shape.n_layers):
+        assert cache.filled(0, l) == n_pos
+        k, v = cache.read(0, l, 0, n_pos)
+        ko, vo = st.kv_read(l, 0, n_pos)
+        assert rel_err(k, ko) <= tol and rel_err(v, vo) <= tol, (l, rel_err(k, ko), rel_err(v, vo))
+    gm.enable_logits(1)
+    cache.close()
+
+
+def test_kv_is_incomplete_before_flush_and_watermarks(pair, prompt):
+    shape, om, gm = pair
+    print(f"case: watermarks {shape.dtype}", flush=True)
+    cache = new_cache(gm)
+    rep = lockstep(gm, cache, om, prompt, 9, 0.0, max_pending=40, check_hidden=False)
+    P = len(prompt)
+    assert cache.pending(0) == 8
+    assert cache.filled(0, 0) == P + 8 and cache.filled(0, 1) == P and cache.filled(0, 3) == P
+    cache.close()
+
+
+@pytest.mark.parametrize("cap", [1, 3])
+def test_forced_full_depth(pair, prompt, cap):
+    shape, om, gm = pair
+    print(f"case: cap {shape.dtype} cap={cap}", flush=True)
+    cache = new_cache(gm, max_pending=cap)
+    rep = lockstep(gm, cache, om, prompt, 14, 0.0, max_pending=cap)
+    assert not rep.mismatches, rep.mismatches[:5]
+    L, e1 = shape.n_layers, shape.exit_layers[0]
+    for j in range(1, 14):
+        assert rep.exit_layers[j] == (L if j % (cap + 1) == 0 else e1)
+    assert rep.forced_full == (14 - 1) // (cap + 1)
+    cache.close()
+
+
+def test_two_sequences_equal_each_alone(pair, prompt):
+    """Sequences are independent: a batch of two ragged sequences gives what each gives alone."""
+    shape, om, gm = pair
+    print(f"case: batch2 {shape.dtype}", flush=True)
+    tau, n_new = 0.35, 20
+    p2 = prompt_tokens(shape.vocab, 23, 7).numpy()
+    alone = []
+    for p in (prompt, p2):
+        cache = new_cache(gm)
+        rep = lockstep(gm, cache, om, p, n_new, tau, max_pending=40, check_hidden=False)
+        alone.append((rep.tokens, rep.exit_layers))
+        cache.close()
+    cache = new_cache(gm)
+    seqs = ee.Sequences(shape.n_layers)
+    out = {0: ([], []), 1: ([], [])}
+    for s, p in ((0, prompt), (1, p2)):
+        tok, ex, _ = ee.prefill(gm, cache, s, p, tau)
+        seqs.start(s, tok)
+        out[s][0].append(tok)
+        out[s][1].append(ex)
+    for _ in range(n_new - 1):
+        ro, tk, pm = seqs.rows([0, 1])
+        nt, exl, _ = ee.decode_step(gm, cache, [0, 1], ro, tk, pm, tau)
+        seqs.update([0, 1], nt, exl)
+        for s in (0, 1):
+            out[s][0].append(int(nt[s]))
+            out[s][1].append(int(exl[s]))
+    for s in (0, 1):
+        assert out[s][0] == alone[s][0] and out[s][1] == alone[s][1]
+    cache.close()
+
+
+def test_long_prompt_spans_chunks_and_blocks(pair):
+    """Prompt longer than one prefill chunk (64 rows) and several cache blocks, ragged tail."""
+    shape, om, gm = pair
+    print(f"case: long prompt {shape.dtype}", flush=True)
+    p = prompt_tokens(shape.vocab, 150, 11).numpy()
+    cache = new_cache(gm, max_pending=5)
+    rep = lockstep(gm, cache, om, p, 12, 0.35, max_pending=5)
+    assert not rep.mismatches, rep.mismatches[:5]
+    assert rep.max_hidden_err <= TOL[shape.dtype]
+    k, v = cache.read(0, shape.n_layers - 1, 0, 150)
+    ko, vo = rep.state.kv_read(shape.n_layers - 1, 0, 150)
+    assert rel_err(k, ko) <= TOL[shape.dtype] and rel_err(v, vo) <= TOL[shape.dtype]
+    cache.close()
+
+
+def test_model_load_from_file_matches_set_tensor(prompt):
+    print("case: model_load file", flush=True)
+    shape = C1.shape
+    om = build_model(shape, 0)
+    with tempfile.TemporaryDirectory() as td:
+        path = os.path.join(td, "c1.eewt")
+        write_weight_file(path, shape, 0, max_positions=256)
+        gm = ee.model_load(ee_config_of(shape, 256), path, 64, 1)
+    cache = ee.KvCache(gm, 1, 256, 32, 40)
+    rep = lockstep(gm, cache, om, prompt, 12, 0.5, max_pending=40)
+    assert not rep.mismatches and rep.max_hidden_err <= 1e-4
+    cache.close()
+    gm.close()
+
+
+def test_error_codes(pair, prompt):
+    shape, om, gm = pair
+    print(f"case: errors {shape.dtype}", flush=True)
+    cache = new_cache(gm, max_pending=4)
+
+    def code(fn):
+        with pytest.raises(ee.EeError) as e:
+            fn()
+        return e.value.code
+
+    # decode before prefill; bad token; bad sequence id
+    assert code(lambda: ee.decode_step(gm, cache, [0], [0, 1], [5], [0], 0.5)) == -4
+    assert code(lambda: ee.prefill(gm, cache, 0, [shape.vocab], 0.5)) == -3
+    assert code(lambda: ee.prefill(gm, cache, 9, [1, 2], 0.5)) == -3
+    tok, ex, _ = ee.prefill(gm, cache, 0, prompt, 0.0)
+    assert code(lambda: ee.prefill(gm, cache, 0, prompt, 0.0)) == -4          # sequence not empty
+    nt, exl, _ = ee.decode_step(gm, cache, [0], [0, 1], [tok], [0], 0.0)      # exits early -> one pending
+    assert cache.pending(0) == 1
+    assert code(lambda: ee.decode_step(gm, cache, [0], [0, 1], [int(nt[0])], [0], 0.0)) == -4   # pending row missing
+    assert code(lambda: ee.decode_step(gm, cache, [0], [0, 2], [tok + 1, int(nt[0])], [1, 0], 0.0)) == -4  # wrong id
+    assert code(lambda: ee.decode_step(gm, cache, [0], [0, 2], [tok, int(nt[0])], [0, 0], 0.0)) == -4      # wrong mask
+    assert code(lambda: ee.decode_step(gm, cache, [0, 0], [0, 2, 4], [tok, int(nt[0])] * 2, [1, 0, 1, 0], 0.0)) == -7
+    assert code(lambda: ee.decode_step(gm, cache, [0], [0, 2], [tok, shape.vocab], [1, 0], 0.0)) == -3
+    ee.decode_step(gm, cache, [0], [0, 2], [tok, int(nt[0])], [1, 0], 0.0)    # the right call still works
+    assert cache.pending(0) == 2
+    cache.reset(0)
+    assert cache.pending(0) == 0 and cache.filled(0, 0) == 0
+    # pool exhaustion: 2 sequences * 32-token blocks, 40 tokens in all -> 2 + 2 blocks
+    small = ee.KvCache(gm, 2, 40, 32, 4)
+    ee.prefill(gm, small, 0, prompt_tokens(shape.vocab, 100, 3).numpy(), 1.0)
+    assert code(lambda: ee.prefill(gm, small, 1, prompt_tokens(shape.vocab, 40, 3).numpy(), 1.0)) == -2
+    small.close()
+    cache.close()

@@ -13,4 +13,5 @@ from .gen import (  # noqa: F401
     model_tensor_list,
     prompt_tokens,
     prompt_lengths,
+    write_weight_file,
 )

@@ -232,3 +232,25 @@ def prompt_tokens(vocab: int, n: int, seed: int = 1, device="cpu") -> torch.Tens
 def prompt_lengths(n_seqs: int, lo: int, hi: int, seed: int = 2) -> List[int]:
     """Prompt lengths uniform in [lo, hi] (inclusive)."""
     return [int(v) for v in uniform_ints(seed, 1001, n_seqs, lo, hi + 1)]
+
+
+def write_weight_file(path: str, shape: ModelShape, seed: int = 0, max_positions: int = 4096,
+                      gain_jitter: float = 0.0) -> None:
+    """Writes the seeded model in the library's weight-file format: the 8 bytes "EEWT0001", the config
+    (19 little-endian 32-bit fields: n_layers, d_model, n_heads, head_dim, d_ff, vocab, n_exits,
+    exit_layers[8], dtype, max_positions, rms_eps, rope_base), then every tensor in canonical order as
+    raw elements (matrices in the storage dtype, gains fp32)."""
+    import struct
+
+    ex = list(shape.exit_layers) + [0] * (8 - len(shape.exit_layers))
+    hdr = struct.pack("<7i8i2i2f", shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff,
+                      shape.vocab, len(shape.exit_layers), *ex, 1 if shape.dtype == "bf16" else 0, max_positions,
+                      shape.rms_eps, shape.rope_base)
+    with open(path, "wb") as f:
+        f.write(b"EEWT0001")
+        f.write(hdr)
+        for kind, idx in model_tensor_list(shape):
+            t = model_tensor(shape, kind, idx, seed, "cpu", gain_jitter).contiguous()
+            if t.dtype == torch.bfloat16:
+                t = t.view(torch.int16)
+            f.write(t.numpy().tobytes())
