@@ -78,18 +78,18 @@ void matvec(int dtype, const void* W, int N, int K, const float* h, double r, fl
         matvec_t((const float*)W, N, K, h, r, y);
 }
 
-// r = 1/sqrt(mean(x^2)+eps);  h[k] = rnd(x[k]*g[k]).  rmsnorm(x;g) = r*h (the scale r is applied to
-// the matrix product, which is the same number up to the last rounding).
-double norm_input(int dtype, const float* x, const float* g, int K, float eps, float* h) {
+// r = 1/sqrt(mean(x^2)+eps);  h[k] = x[k]*g[k].  rmsnorm(x;g) = r*h (the scale r is applied to the
+// matrix product, which is the same number up to the last rounding).
+double norm_input(const float* x, const float* g, int K, float eps, float* h) {
     double ss = 0;
     for (int k = 0; k < K; ++k) ss += (double)x[k] * (double)x[k];
-    for (int k = 0; k < K; ++k) h[k] = rnd(dtype, x[k] * g[k]);
+    for (int k = 0; k < K; ++k) h[k] = x[k] * g[k];
     float r = (float)(1.0 / std::sqrt(ss / K + (double)eps));
     return (double)r;
 }
 
 // RoPE, half-split pairing: (i, i+hd/2), angle pos * base^(-2i/hd), positions from 0.
-void rope(int dtype, float* vec, int H, int hd, int pos, float base) {
+void rope(float* vec, int H, int hd, int pos, float base) {
     int half = hd / 2;
     for (int h = 0; h < H; ++h) {
         float* p = vec + (size_t)h * hd;
@@ -97,13 +97,13 @@ void rope(int dtype, float* vec, int H, int hd, int pos, float base) {
             double ang = (double)pos * std::pow((double)base, -2.0 * i / hd);
             double c = std::cos(ang), s = std::sin(ang);
             double a = p[i], b = p[i + half];
-            p[i] = rnd(dtype, (float)(a * c - b * s));
-            p[i + half] = rnd(dtype, (float)(b * c + a * s));
+            p[i] = (float)(a * c - b * s);
+            p[i + half] = (float)(b * c + a * s);
         }
     }
 }
 
-void attention_row(int dtype, const float* q, const float* K, const float* V, int n_ctx, int H, int hd,
+void attention_row(const float* q, const float* K, const float* V, int n_ctx, int H, int hd,
                    float* out) {
     int d = H * hd;
     double scale = 1.0 / std::sqrt((double)hd);
@@ -124,16 +124,16 @@ void attention_row(int dtype, const float* q, const float* K, const float* V, in
         for (int c = 0; c < hd; ++c) {
             double acc = 0;
             for (int j = 0; j < n_ctx; ++j) acc += p[j] * (double)V[(size_t)j * d + (size_t)h * hd + c];
-            out[(size_t)h * hd + c] = rnd(dtype, (float)(acc / den));
+            out[(size_t)h * hd + c] = (float)(acc / den);
         }
     }
 }
 
-void swiglu(int dtype, const float* gate, const float* up, int n, float* out) {
+void swiglu(const float* gate, const float* up, int n, float* out) {
     for (int i = 0; i < n; ++i) {
         double t = gate[i];
         double sl = t / (1.0 + std::exp(-t));
-        out[i] = rnd(dtype, (float)(sl * (double)up[i]));
+        out[i] = (float)(sl * (double)up[i]);
     }
 }
 
@@ -188,20 +188,23 @@ void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) 
     std::vector<float> h(d > F ? d : F), q(d), a(d), gate(F), up(F), y(d);
     float* k = K + (size_t)pos * d;
     float* v = V + (size_t)pos * d;
-    double r = norm_input(dt, x, m->g1[l], d, c.rms_eps, h.data());
+    double r = norm_input(x, m->g1[l], d, c.rms_eps, h.data());
     matvec(dt, m->wq[l], d, d, h.data(), r, q.data());
     matvec(dt, m->wk[l], d, d, h.data(), r, k);
     matvec(dt, m->wv[l], d, d, h.data(), r, v);
-    rope(dt, q.data(), c.n_heads, c.head_dim, pos, c.rope_base);
-    rope(dt, k, c.n_heads, c.head_dim, pos, c.rope_base);
-    for (int i = 0; i < d; ++i) v[i] = rnd(dt, v[i]);
-    attention_row(dt, q.data(), K, V, pos + 1, c.n_heads, c.head_dim, a.data());
+    rope(q.data(), c.n_heads, c.head_dim, pos, c.rope_base);
+    rope(k, c.n_heads, c.head_dim, pos, c.rope_base);
+    for (int i = 0; i < d; ++i) {  // the cache stores K and V in the model's storage type
+        k[i] = rnd(dt, k[i]);
+        v[i] = rnd(dt, v[i]);
+    }
+    attention_row(q.data(), K, V, pos + 1, c.n_heads, c.head_dim, a.data());
     matvec(dt, m->wo[l], d, d, a.data(), 1.0, y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
-    r = norm_input(dt, x, m->g2[l], d, c.rms_eps, h.data());
+    r = norm_input(x, m->g2[l], d, c.rms_eps, h.data());
     matvec(dt, m->wg[l], F, d, h.data(), r, gate.data());
     matvec(dt, m->wu[l], F, d, h.data(), r, up.data());
-    swiglu(dt, gate.data(), up.data(), F, h.data());
+    swiglu(gate.data(), up.data(), F, h.data());
     matvec(dt, m->wd[l], d, F, h.data(), 1.0, y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
 }
@@ -212,7 +215,7 @@ void head_row(const eo_model* m, int head, const float* x, float* z, eo_diag* di
     const float* g = fin ? m->gf : m->ge[head];
     const void* W = fin ? m->wf : m->we[head];
     std::vector<float> h(c.d_model);
-    double r = norm_input(c.dtype, x, g, c.d_model, c.rms_eps, h.data());
+    double r = norm_input(x, g, c.d_model, c.rms_eps, h.data());
     matvec(c.dtype, W, c.vocab, c.d_model, h.data(), r, z);
     if (diag) {
         softmax_max(z, c.vocab, diag);
@@ -538,23 +541,23 @@ void eo_norm_matvec(int dtype, const void* W, int N, int K, const float* x, cons
     std::vector<float> h(K);
     double r = 1.0;
     if (g)
-        r = norm_input(dtype, x, g, K, eps, h.data());
+        r = norm_input(x, g, K, eps, h.data());
     else
-        for (int k = 0; k < K; ++k) h[k] = rnd(dtype, x[k]);
+        for (int k = 0; k < K; ++k) h[k] = x[k];
     matvec(dtype, W, N, K, h.data(), r, y);
 }
 
-void eo_rope(int dtype, float* vec, int n_heads, int head_dim, int pos, float base) {
-    rope(dtype, vec, n_heads, head_dim, pos, base);
+void eo_rope(float* vec, int n_heads, int head_dim, int pos, float base) {
+    rope(vec, n_heads, head_dim, pos, base);
 }
 
-void eo_attention_row(int dtype, const float* q, const float* K, const float* V, int n_ctx, int n_heads,
+void eo_attention_row(const float* q, const float* K, const float* V, int n_ctx, int n_heads,
                       int head_dim, float* out) {
-    attention_row(dtype, q, K, V, n_ctx, n_heads, head_dim, out);
+    attention_row(q, K, V, n_ctx, n_heads, head_dim, out);
 }
 
-void eo_swiglu(int dtype, const float* gate, const float* up, int n, float* out) {
-    swiglu(dtype, gate, up, n, out);
+void eo_swiglu(const float* gate, const float* up, int n, float* out) {
+    swiglu(gate, up, n, out);
 }
 
 void eo_softmax_max(const float* z, int n, eo_diag* out) {

@@ -17,13 +17,13 @@
  *     those tokens are fed again with the current token (from layer 1) so that
  *     their KV is recomputed; a full-depth pass is forced when the list
  *     reaches max_pending.
- * Arithmetic: storage fp32; every reduction (dot product, mean square,
+ * Arithmetic: values are fp32; every reduction (dot product, mean square,
  * softmax sum) is accumulated in fp64 and rounded once to fp32.  With
- * dtype = EO_BF16 values are additionally rounded to bf16 (round to nearest
- * even) at the points where the bf16 model stores bf16: matrix inputs
- * (x*g before the RMS scale, attention output, SwiGLU product), q/k after
- * RoPE, v, and therefore the cached K,V.  The residual stream, softmax,
- * logits and confidences stay fp32.
+ * dtype = EO_BF16 the stored tensors are bf16: the weight matrices and the
+ * embedding (given as bf16 bit patterns) and the cached K (after RoPE) and V,
+ * which are rounded to bf16 (nearest even) when written.  Nothing else is
+ * rounded: activations, the residual stream, q, softmax, logits and
+ * confidences stay fp32.
  *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py
  * against closed forms, invariants, numpy/scipy fp64 routines and the G0
@@ -116,14 +116,14 @@ int eo_last_logits(const eo_state*, float* z_out); /* logits of the last head ev
 
 /* ---- single operations, exported for pins and real-shape spot checks ---- */
 float eo_bf16_round(float v);
-/* y[n] = r * sum_k W[n][k] * rnd(x[k]*g[k]),  r = 1/sqrt(mean(x^2)+eps); g == NULL: no norm (r = 1, g = 1) */
+/* y[n] = r * sum_k W[n][k] * (x[k]*g[k]),  r = 1/sqrt(mean(x^2)+eps); g == NULL: no norm (r = 1, g = 1) */
 void eo_norm_matvec(int dtype, const void* W, int N, int K, const float* x, const float* g, float eps,
                     float* y);
-void eo_rope(int dtype, float* vec, int n_heads, int head_dim, int pos, float base);
+void eo_rope(float* vec, int n_heads, int head_dim, int pos, float base);
 /* one query row over n_ctx cached positions; q,out: [H*hd]; K,V: [n_ctx][H*hd] */
-void eo_attention_row(int dtype, const float* q, const float* K, const float* V, int n_ctx, int n_heads,
+void eo_attention_row(const float* q, const float* K, const float* V, int n_ctx, int n_heads,
                       int head_dim, float* out);
-void eo_swiglu(int dtype, const float* gate, const float* up, int n, float* out);
+void eo_swiglu(const float* gate, const float* up, int n, float* out);
 void eo_softmax_max(const float* z, int n, eo_diag* out);
 /* one layer on one row: x in/out [d]; K,V: [>=pos+1][d], row `pos` is written, rows 0..pos are read */
 int eo_layer_row(const eo_model*, int layer, float* x, int pos, float* K, float* V);

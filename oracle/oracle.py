@@ -67,11 +67,11 @@ def lib():
         L.eo_norm_matvec.restype = None
         L.eo_norm_matvec.argtypes = [C.c_int, vp, C.c_int, C.c_int, fp, fp, C.c_float, fp]
         L.eo_rope.restype = None
-        L.eo_rope.argtypes = [C.c_int, fp, C.c_int, C.c_int, C.c_int, C.c_float]
+        L.eo_rope.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_float]
         L.eo_attention_row.restype = None
-        L.eo_attention_row.argtypes = [C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_int, fp]
+        L.eo_attention_row.argtypes = [fp, fp, fp, C.c_int, C.c_int, C.c_int, fp]
         L.eo_swiglu.restype = None
-        L.eo_swiglu.argtypes = [C.c_int, fp, fp, C.c_int, fp]
+        L.eo_swiglu.argtypes = [fp, fp, C.c_int, fp]
         L.eo_softmax_max.restype = None
         L.eo_softmax_max.argtypes = [fp, C.c_int, C.POINTER(EoDiag)]
         L.eo_layer_row.argtypes = [vp, C.c_int, fp, C.c_int, fp, fp]
@@ -276,21 +276,21 @@ def norm_matvec(dtype: int, W: np.ndarray, x: np.ndarray, g: Optional[np.ndarray
     return y
 
 
-def rope(dtype: int, vec: np.ndarray, n_heads: int, head_dim: int, pos: int, base: float) -> np.ndarray:
+def rope(vec: np.ndarray, n_heads: int, head_dim: int, pos: int, base: float) -> np.ndarray:
     out = np.ascontiguousarray(vec, dtype=np.float32).copy()
-    lib().eo_rope(dtype, _fp(out), n_heads, head_dim, pos, base)
+    lib().eo_rope(_fp(out), n_heads, head_dim, pos, base)
     return out
 
 
-def attention_row(dtype: int, q: np.ndarray, K: np.ndarray, V: np.ndarray, n_heads: int, head_dim: int):
+def attention_row(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_heads: int, head_dim: int):
     out = np.zeros(n_heads * head_dim, np.float32)
-    lib().eo_attention_row(dtype, _fp(q), _fp(K), _fp(V), K.shape[0], n_heads, head_dim, _fp(out))
+    lib().eo_attention_row(_fp(q), _fp(K), _fp(V), K.shape[0], n_heads, head_dim, _fp(out))
     return out
 
 
-def swiglu(dtype: int, gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
     out = np.zeros_like(gate)
-    lib().eo_swiglu(dtype, _fp(gate), _fp(up), len(gate), _fp(out))
+    lib().eo_swiglu(_fp(gate), _fp(up), len(gate), _fp(out))
     return out
 
 

@@ -103,9 +103,10 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     w.btab = take((size_t)max_seqs * w.max_blocks_per_seq * 4);
     w.tokens = take(EE_MAX_ROWS * 4);
     w.upload_bytes = off - w.upload;
-    w.q = take((size_t)max_rows * d * es);
-    w.attn = take((size_t)max_rows * d * es);
-    w.act = take((size_t)max_rows * c.d_ff * es);
+    size_t terms = c.dtype == EE_BF16 ? 2 : 1;  // bf16 activations are stored as hi and lo terms
+    w.q = take(terms * max_rows * d * es);
+    w.attn = take(terms * max_rows * d * es);
+    w.act = take(terms * max_rows * c.d_ff * es);
     w.partials = take((size_t)(c.vocab / 32) * EE_MAX_SEQS * sizeof(HeadPartial));
     w.counters = take(256 * 4);
     w.attn_part = take(attention_part_floats(max_rows, c.n_heads, c.head_dim) * 4);
@@ -130,6 +131,7 @@ struct ee_model {
     HeadResult* results_dev; // device view of the same memory
     float* dbg_logits;
     int dbg_rows;
+    size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? (size_t)max_rows * ld : 0; }  // hi -> lo distance
     int n_seg() const { return cfg.n_exits + 1; }
     int seg_begin(int s) const { return s == 0 ? 0 : cfg.exit_layers[s - 1]; }
     int seg_end(int s) const { return s < cfg.n_exits ? cfg.exit_layers[s] : cfg.n_layers; }
@@ -174,6 +176,7 @@ struct ee_kv_cache {
     int max_seqs, BT, S, max_pending, n_blocks;
     char* pool;
     size_t off_x, off_xg, off_xgh, off_ssq;
+    size_t xs_lo;    // element distance from the hi to the lo term in xg / xgh (0 for fp32)
     int ssq_stride;  // partial sums per row
     KvGeom geom;
     std::vector<int32_t> free_blocks;
@@ -201,10 +204,11 @@ size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total,
     if (n_blocks) *n_blocks = nb;
     if (off_x) *off_x = off;
     off += align_up(slots * d * 4);
+    size_t terms = c.dtype == EE_BF16 ? 2 : 1;
     if (off_xg) *off_xg = off;
-    off += align_up(slots * d * es);
+    off += align_up(terms * slots * d * es);
     if (off_xgh) *off_xgh = off;
-    off += align_up(slots * d * es);
+    off += align_up(terms * slots * d * es);
     if (off_ssq) *off_ssq = off;
     off += align_up(slots * P * 4);
     return off;
@@ -237,33 +241,37 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.N = 3 * d;
         g.K = d;
         g.A = c->xg();
+        g.a_lo = c->xs_lo;
         g.lda = d;
         g.arow = xrow;
         g.ssq = c->ssq();
-        HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
-        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, dd, T, n_qt, m->dev_btab(), c->geom, l, d,
+        HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
+        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
                                 (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx, st));
         // x += W_o a ; operand for the MLP norm
         g.W = m->wbase + m->wl.wo[l];
         g.N = d;
         g.K = d;
         g.A = m->ws + m->wsl.attn;
+        g.a_lo = m->lo_rows(d);
         g.arow = nullptr;
         g.ssq = nullptr;
-        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
         // act = silu(W_g h) * (W_u h)
         g.W = m->wbase + m->wl.gu[l];
         g.N = 2 * F;
         g.K = d;
         g.A = c->xg();
+        g.a_lo = c->xs_lo;
         g.arow = xrow;
         g.ssq = c->ssq();
-        HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, F, st));
+        HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, st));
         // x += W_d act ; operand for the next layer (or the final head), and for an exit head after this layer
         g.W = m->wbase + m->wl.wd[l];
         g.N = d;
         g.K = F;
         g.A = m->ws + m->wsl.act;
+        g.a_lo = m->lo_rows(F);
         g.lda = F;
         g.arow = nullptr;
         g.ssq = nullptr;
@@ -271,7 +279,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         const float* g_head = nullptr;
         for (int i = 0; i < cf.n_exits; ++i)
             if (cf.exit_layers[i] == l + 1) g_head = m->gain(m->wl.ge[i]);
-        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->ssq(), g_next, g_head, d, st));
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d, st));
     }
     return EE_OK;
 }
@@ -287,6 +295,7 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.N = cf.vocab;
     g.K = cf.d_model;
     g.A = fin ? c->xg() : c->xgh();
+    g.a_lo = c->xs_lo;
     g.lda = cf.d_model;
     g.arow = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
     g.ssq = c->ssq();
@@ -391,7 +400,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
         if (hd->T > 0) {
             if (s == 0 && decode)
                 HIPCHK(launch_embed(m->cfg.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), hd->T, m->cfg.d_model,
-                                    m->gain(m->wl.g1[0]), c->x(), c->xg(), c->ssq(), c->ssq_stride, st));
+                                    m->gain(m->wl.g1[0]), c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
             EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
         }
         bool is_final = s == n_seg - 1;
@@ -666,6 +675,7 @@ int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total
     c->max_pending = max_pending;
     c->pool = (char*)dev_pool;
     c->ssq_stride = cf.d_model / (16 * gemm_resid_tiles_per_wg());
+    c->xs_lo = cf.dtype == EE_BF16 ? ((size_t)max_seqs * (max_pending + 1) + m->max_rows) * cf.d_model : 0;
     c->geom.pool = dev_pool;
     c->geom.blk_stride = 2 * (size_t)cf.n_heads * block_tokens * cf.head_dim;
     c->geom.layer_stride = (size_t)c->n_blocks * c->geom.blk_stride;
@@ -815,7 +825,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
         }
         EECHK(upload(m, st));
         HIPCHK(launch_embed(cf.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), n, cf.d_model, m->gain(m->wl.g1[0]),
-                            c->x(), c->xg(), c->ssq(), c->ssq_stride, st));
+                            c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
         for (int sgi = 0; sgi < n_seg; ++sgi) {
             EECHK(run_layers(m, c, 0, n, d->n_qt, m->seg_begin(sgi), m->seg_end(sgi), p0 + n, st));
             bool fin = sgi == n_seg - 1;

@@ -56,13 +56,14 @@ hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K,
                        int tile_off, hipStream_t s);
 
 hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
-                        const float* g_next, float* x, void* xg, float* ssq, int ssq_stride, hipStream_t s);
+                        const float* g_next, float* x, void* xg, size_t xg_lo, float* ssq, int ssq_stride, hipStream_t s);
 
 struct GemmCommon {
     int dtype;
     const void* W;     // packed weights of this matrix
     int N, K;          // output features (packed rows), reduction length
     const void* A;     // activations, [rows][lda]
+    size_t a_lo;       // element offset from the hi term of A to its lo term (bf16 model), else 0
     int lda;
     const int32_t* arow;  // row indirection into A (and into ssq), or NULL
     const float* ssq;     // partial sums of squares [slot][ssq_stride], or NULL (no RMS scale)
@@ -72,15 +73,15 @@ struct GemmCommon {
     const SegDesc* desc;
 };
 
-hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, const float* rope_cs, const KvGeom& kv, int layer,
+hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
                            hipStream_t s);
-hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, float* ssq_out, const float* g_next,
-                             const float* g_head, int d, hipStream_t s);
-hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, int F, hipStream_t s);
+hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
+                             const float* g_next, const float* g_head, int d, hipStream_t s);
+hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int F, hipStream_t s);
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
                             float threshold, HeadResult* results, hipStream_t s);
 
-hipError_t launch_attention(int dtype, const void* q, void* out, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
                             hipStream_t s);
 

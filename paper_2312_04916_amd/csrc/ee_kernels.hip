@@ -20,7 +20,22 @@ template <typename ST> __device__ __forceinline__ ST cvt_st(float v);
 template <> __device__ __forceinline__ float cvt_st<float>(float v) { return v; }
 template <> __device__ __forceinline__ __bf16 cvt_st<__bf16>(float v) { return (__bf16)v; }  // round to nearest even
 
-template <typename ST> __device__ __forceinline__ float ld_f(const ST* p) { return (float)*p; }
+// Activations of the bf16 model are carried as two bf16 terms, hi = bf16(v) and lo = bf16(v - hi), so
+// that a matrix input keeps about 16 mantissa bits while still being an MFMA bf16 operand (two MFMAs
+// per tile; the matrix cores idle anyway in this bandwidth-bound regime).  `lo_off` is the element
+// distance from the hi array to the lo array.  The fp32 model has a single term.
+template <typename ST> __device__ __forceinline__ void store_split(ST* p, size_t lo_off, float v);
+template <> __device__ __forceinline__ void store_split<float>(float* p, size_t, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_split<__bf16>(__bf16* p, size_t lo_off, float v) {
+    __bf16 hi = (__bf16)v;
+    p[0] = hi;
+    p[lo_off] = (__bf16)(v - (float)hi);
+}
+template <typename ST> __device__ __forceinline__ float load_split(const ST* p, size_t lo_off);
+template <> __device__ __forceinline__ float load_split<float>(const float* p, size_t) { return *p; }
+template <> __device__ __forceinline__ float load_split<__bf16>(const __bf16* p, size_t lo_off) {
+    return (float)p[0] + (float)p[lo_off];
+}
 
 // ------------------------------------------------------------------------------------------------
 // rotary table: cs[pos][i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
@@ -100,7 +115,7 @@ hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K,
 template <typename ST>
 __global__ void embed_kernel(const ST* __restrict__ embed, const int32_t* __restrict__ tokens, const SegDesc* __restrict__ desc,
                              int d, const float* __restrict__ g_next, float* __restrict__ x, ST* __restrict__ xg,
-                             float* __restrict__ ssq, int ssq_stride) {
+                             size_t xg_lo, float* __restrict__ ssq, int ssq_stride) {
     __shared__ float red[256];
     int r = blockIdx.x;
     int slot = desc->xrow[r];
@@ -109,7 +124,7 @@ __global__ void embed_kernel(const ST* __restrict__ embed, const int32_t* __rest
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
         float v = (float)embed[(size_t)tok * d + i];
         x[(size_t)slot * d + i] = v;
-        xg[(size_t)slot * d + i] = cvt_st<ST>(v * g_next[i]);
+        store_split<ST>(xg + (size_t)slot * d + i, xg_lo, v * g_next[i]);
         s += v * v;
     }
     red[threadIdx.x] = s;
@@ -122,14 +137,14 @@ __global__ void embed_kernel(const ST* __restrict__ embed, const int32_t* __rest
 }
 
 hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
-                        const float* g_next, float* x, void* xg, float* ssq, int ssq_stride, hipStream_t s) {
+                        const float* g_next, float* x, void* xg, size_t xg_lo, float* ssq, int ssq_stride, hipStream_t s) {
     if (T <= 0) return hipSuccess;
     if (dtype == EE_BF16)
         hipLaunchKernelGGL(embed_kernel<__bf16>, dim3(T), dim3(256), 0, s, (const __bf16*)embed, dev_tokens, desc, d, g_next, x,
-                           (__bf16*)xg, ssq, ssq_stride);
+                           (__bf16*)xg, xg_lo, ssq, ssq_stride);
     else
         hipLaunchKernelGGL(embed_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)embed, dev_tokens, desc, d, g_next, x,
-                           (float*)xg, ssq, ssq_stride);
+                           (float*)xg, xg_lo, ssq, ssq_stride);
     return hipGetLastError();
 }
 
@@ -143,6 +158,7 @@ struct GemmArgs {
     int KT;  // K / 32 (bf16) ; K (fp32 path uses K directly)
     int K;
     const void* A;
+    size_t a_lo;  // element offset of the lo term of A (bf16 only)
     int lda;
     const int32_t* arow;
     const float* ssq;
@@ -204,13 +220,19 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
         wp += C * 64;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            u32x4 av4[C];
+            u32x4 ah[C], al[C];
 #pragma unroll
-            for (int u = 0; u < C; ++u) av4[u] = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)(kt + u) * 32) : zero;
+            for (int u = 0; u < C; ++u) {
+                ah[u] = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)(kt + u) * 32) : zero;
+                al[u] = av[mt] ? *(const u32x4*)(ap[mt] + a.a_lo + (size_t)(kt + u) * 32) : zero;
+            }
 #pragma unroll
-            for (int u = 0; u < C; ++u)
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av4[u]),
+            for (int u = 0; u < C; ++u) {
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, al[u]),
                                                                   __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ah[u]),
+                                                                  __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
+            }
         }
     }
     for (; kt < kt1; ++kt) {
@@ -219,6 +241,9 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             u32x4 a4 = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)kt * 32) : zero;
+            u32x4 l4 = av[mt] ? *(const u32x4*)(ap[mt] + a.a_lo + (size_t)kt * 32) : zero;
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, l4), __builtin_bit_cast(bf16x8, w),
+                                                              acc[mt], 0, 0, 0);
             acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, w),
                                                               acc[mt], 0, 0, 0);
         }
@@ -271,6 +296,7 @@ __device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, Gemm
 template <typename ST>
 struct QkvArgs {
     ST* q;
+    size_t q_lo;
     int d;
     const float2* rope_cs;
     ST* kv_layer;  // pool + layer * layer_stride
@@ -302,8 +328,8 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvAr
         }
         if (part == 0) {
             ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 16 + i;
-            qp[0] = cvt_st<ST>(lo);
-            qp[half] = cvt_st<ST>(hi);
+            store_split<ST>(qp, e.q_lo, lo);
+            store_split<ST>(qp + half, e.q_lo, hi);
         } else {
             ST* kp = e.kv_layer + (size_t)e.desc->kvblk[m] * e.blk_stride + (part == 2 ? (size_t)e.H * e.BT * e.hd : 0) +
                      ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 16 + i;
@@ -319,6 +345,7 @@ struct ResidArgs {
     float* x;
     ST* xg;
     ST* xgh;
+    size_t xs_lo;  // lo offset of xg and xgh
     float* ssq_out;
     int ssq_stride;
     const float* g_next;
@@ -339,8 +366,8 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
         float v = e.x[o] + sm.out[m][i];
         e.x[o] = v;
         sm.out[m][i] = v;
-        e.xg[o] = cvt_st<ST>(v * e.g_next[n0 + i]);
-        if (e.xgh) e.xgh[o] = cvt_st<ST>(v * e.g_head[n0 + i]);
+        store_split<ST>(e.xg + o, e.xs_lo, v * e.g_next[n0 + i]);
+        if (e.xgh) store_split<ST>(e.xgh + o, e.xs_lo, v * e.g_head[n0 + i]);
     }
     __syncthreads();
     for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
@@ -354,7 +381,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
 
 // ---- epilogue 3: SwiGLU.  tile 2j holds gate features 16j.., tile 2j+1 the matching up features
 template <typename ST, int KS, int MT>
-__global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, int F) {
+__global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F) {
     __shared__ GemmSmem<2, KS, MT> sm;
     gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
     for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
@@ -362,7 +389,7 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST
         if (m >= a.T) continue;
         float gt = sm.out[m][i], up = sm.out[m][16 + i];
         float sl = gt / (1.0f + expf(-gt));
-        act[(size_t)m * F + blockIdx.x * 16 + i] = cvt_st<ST>(sl * up);
+        store_split<ST>(act + (size_t)m * F + blockIdx.x * 16 + i, act_lo, sl * up);
     }
 }
 
@@ -475,6 +502,7 @@ static GemmArgs make_args(const GemmCommon& c) {
     a.K = c.K;
     a.KT = c.K / 32;
     a.A = c.A;
+    a.a_lo = c.a_lo;
     a.lda = c.lda;
     a.arow = c.arow;
     a.ssq = c.ssq;
@@ -499,49 +527,49 @@ constexpr int KS_QKV = 4, KS_RES = 8, KS_SWI = 4, KS_HEAD = 4;
 
 int gemm_resid_tiles_per_wg() { return 1; }
 
-hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, const float* rope_cs, const KvGeom& kv, int layer,
+hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
                            hipStream_t s) {
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
     dim3 grid(c.N / 32), block(2 * KS_QKV * 64);
     if (c.dtype == EE_BF16) {
-        QkvArgs<__bf16> e{(__bf16*)q, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
+        QkvArgs<__bf16> e{(__bf16*)q, q_lo, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
                           kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
         EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<__bf16, KS_QKV, MT>), grid, block, 0, s, a, e));
     } else {
-        QkvArgs<float> e{(float*)q, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
+        QkvArgs<float> e{(float*)q, q_lo, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
                          kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
         EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<float, KS_QKV, MT>), grid, block, 0, s, a, e));
     }
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, float* ssq_out, const float* g_next,
-                             const float* g_head, int d, hipStream_t s) {
+hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
+                             const float* g_next, const float* g_head, int d, hipStream_t s) {
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
     dim3 grid(c.N / 16), block(KS_RES * 64);
     if (c.dtype == EE_BF16) {
-        ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
+        ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
         EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<__bf16, KS_RES, MT>), grid, block, 0, s, a, e));
     } else {
-        ResidArgs<float> e{x, (float*)xg, (float*)xgh, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
+        ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
         EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<float, KS_RES, MT>), grid, block, 0, s, a, e));
     }
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, int F, hipStream_t s) {
+hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int F, hipStream_t s) {
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
     dim3 grid(c.N / 32), block(2 * KS_SWI * 64);
     if (c.dtype == EE_BF16) {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, 0, s, a, (__bf16*)act, F));
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, 0, s, a, (__bf16*)act, act_lo, F));
     } else {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, 0, s, a, (float*)act, F));
+        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, 0, s, a, (float*)act, act_lo, F));
     }
     return hipGetLastError();
 }
@@ -591,8 +619,9 @@ __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) 
 
 template <typename ST>
 __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__ q, ST* __restrict__ out,
-                                                          const SegDesc* __restrict__ desc, const int32_t* __restrict__ btab,
-                                                          KvGeom kv, const ST* __restrict__ layer_base, int d) {
+                                                          size_t io_lo, const SegDesc* __restrict__ desc,
+                                                          const int32_t* __restrict__ btab, KvGeom kv,
+                                                          const ST* __restrict__ layer_base, int d) {
     __shared__ float qs[128];
     __shared__ float sc[1024];
     __shared__ float red[256];
@@ -600,7 +629,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
     const int pos = desc->pos[r];
     const int32_t* bt = btab + (size_t)desc->rseq[r] * kv.max_blocks_per_seq;
     const float scale = 1.0f / sqrtf((float)hd);
-    for (int i = threadIdx.x; i < hd; i += 256) qs[i] = (float)q[(size_t)r * d + h * hd + i];
+    for (int i = threadIdx.x; i < hd; i += 256) qs[i] = load_split<ST>(q + (size_t)r * d + h * hd + i, io_lo);
     __syncthreads();
     float m = -INFINITY, l = 0.f, acc = 0.f;
     const int n_ctx = pos + 1;
@@ -634,7 +663,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
         m = m_new;
         __syncthreads();
     }
-    if ((int)threadIdx.x < hd) out[(size_t)r * d + h * hd + threadIdx.x] = cvt_st<ST>(acc / l);
+    if ((int)threadIdx.x < hd) store_split<ST>(out + (size_t)r * d + h * hd + threadIdx.x, io_lo, acc / l);
 }
 
 size_t attention_part_floats(int max_rows, int H, int hd) {
@@ -644,7 +673,7 @@ size_t attention_part_floats(int max_rows, int H, int hd) {
     return 64;
 }
 
-hipError_t launch_attention(int dtype, const void* q, void* out, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
                             hipStream_t s) {
     (void)n_qt;
@@ -654,10 +683,10 @@ hipError_t launch_attention(int dtype, const void* q, void* out, const SegDesc* 
     if (T <= 0) return hipSuccess;
     dim3 grid(T, kv.H), block(256);
     if (dtype == EE_BF16)
-        hipLaunchKernelGGL(attn_simple_kernel<__bf16>, grid, block, 0, s, (const __bf16*)q, (__bf16*)out, desc, btab, kv,
+        hipLaunchKernelGGL(attn_simple_kernel<__bf16>, grid, block, 0, s, (const __bf16*)q, (__bf16*)out, io_lo, desc, btab, kv,
                            (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride, d);
     else
-        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, block, 0, s, (const float*)q, (float*)out, desc, btab, kv,
+        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, block, 0, s, (const float*)q, (float*)out, io_lo, desc, btab, kv,
                            (const float*)kv.pool + (size_t)layer * kv.layer_stride, d);
     return hipGetLastError();
 }

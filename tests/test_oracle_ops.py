@@ -87,14 +87,14 @@ def test_rmsnorm_scale_invariance():
 
 
 def test_norm_matvec_bf16_contract():
-    """bf16 storage: weights are bf16 bit patterns; the input is rounded as bf16(x*g), the RMS scale stays fp32."""
+    """bf16 storage: weights are bf16 bit patterns; the input x*g and the RMS scale stay fp32."""
     N, K, eps = 48, 128, 1e-5
     W32 = f32(RNG.standard_normal((N, K)) * 0.05)
     Wb = bf16_bits(W32)
     x = f32(RNG.standard_normal(K))
     g = f32(1.0 + 0.1 * RNG.standard_normal(K))
     y = O.norm_matvec(O.EO_BF16, Wb, x, g, eps)
-    h = bf16_vals(f32(x * g)).astype(np.float64)
+    h = f32(x * g).astype(np.float64)
     r = np.float32(1.0 / np.sqrt(np.mean(x.astype(np.float64) ** 2) + eps))
     ref = float(r) * (bf16_vals(W32).astype(np.float64) @ h)
     assert np.max(np.abs(y - ref)) <= 1e-6 * np.max(np.abs(ref))
@@ -107,19 +107,19 @@ def test_norm_matvec_bf16_contract():
 
 def test_rope_position_zero_is_identity():
     v = f32(RNG.standard_normal(4 * 32))
-    assert np.array_equal(O.rope(O.EO_F32, v, 4, 32, 0, 10000.0), v)
+    assert np.array_equal(O.rope(v, 4, 32, 0, 10000.0), v)
 
 
 def test_rope_textbook_rotation_and_pairing():
     # head_dim 4, half-split pairs (0,2) and (1,3); angles pos*base^0 and pos*base^(-2/4)
     base, pos = 10000.0, 3
     v = f32([1.0, 2.0, 0.0, 0.0])
-    out = O.rope(O.EO_F32, v, 1, 4, pos, base)
+    out = O.rope(v, 1, 4, pos, base)
     a0, a1 = pos * 1.0, pos * base ** (-0.5)
     ref = np.array([np.cos(a0), 2 * np.cos(a1), np.sin(a0), 2 * np.sin(a1)])
     assert np.allclose(out, ref, atol=1e-7)
     # a vector on the second element of a pair rotates the other way round the circle
-    out = O.rope(O.EO_F32, f32([0, 0, 1.0, 0]), 1, 4, pos, base)
+    out = O.rope(f32([0, 0, 1.0, 0]), 1, 4, pos, base)
     assert np.allclose(out, [-np.sin(a0), 0, np.cos(a0), 0], atol=1e-7)
 
 
@@ -129,11 +129,11 @@ def test_rope_preserves_norm_and_depends_on_relative_position():
     k = f32(RNG.standard_normal(H * hd))
     for h in range(H):
         sl = slice(h * hd, (h + 1) * hd)
-        assert np.isclose(np.linalg.norm(O.rope(O.EO_F32, q, H, hd, 77, 10000.0)[sl]), np.linalg.norm(q[sl]),
+        assert np.isclose(np.linalg.norm(O.rope(q, H, hd, 77, 10000.0)[sl]), np.linalg.norm(q[sl]),
                           rtol=1e-6)
-    s1 = O.rope(O.EO_F32, q, H, hd, 9, 10000.0)[:hd] @ O.rope(O.EO_F32, k, H, hd, 4, 10000.0)[:hd]
-    s2 = O.rope(O.EO_F32, q, H, hd, 109, 10000.0)[:hd] @ O.rope(O.EO_F32, k, H, hd, 104, 10000.0)[:hd]
-    s3 = O.rope(O.EO_F32, q, H, hd, 9, 10000.0)[:hd] @ O.rope(O.EO_F32, k, H, hd, 5, 10000.0)[:hd]
+    s1 = O.rope(q, H, hd, 9, 10000.0)[:hd] @ O.rope(k, H, hd, 4, 10000.0)[:hd]
+    s2 = O.rope(q, H, hd, 109, 10000.0)[:hd] @ O.rope(k, H, hd, 104, 10000.0)[:hd]
+    s3 = O.rope(q, H, hd, 9, 10000.0)[:hd] @ O.rope(k, H, hd, 5, 10000.0)[:hd]
     assert np.isclose(s1, s2, rtol=1e-4, atol=1e-5)
     assert not np.isclose(s1, s3, rtol=1e-3)
 
@@ -142,7 +142,7 @@ def test_rope_heads_use_the_same_angles():
     hd = 8
     one = f32(RNG.standard_normal(hd))
     two = np.concatenate([one, one])
-    out = O.rope(O.EO_F32, two, 2, hd, 5, 10000.0)
+    out = O.rope(two, 2, hd, 5, 10000.0)
     assert np.array_equal(out[:hd], out[hd:])
 
 
@@ -153,7 +153,7 @@ def test_attention_single_position_returns_v():
     q = f32(RNG.standard_normal(H * hd))
     K = f32(RNG.standard_normal((1, H * hd)))
     V = f32(RNG.standard_normal((1, H * hd)))
-    assert np.allclose(O.attention_row(O.EO_F32, q, K, V, H, hd), V[0], rtol=1e-7)
+    assert np.allclose(O.attention_row(q, K, V, H, hd), V[0], rtol=1e-7)
 
 
 def test_attention_uniform_keys_gives_mean_of_values():
@@ -161,7 +161,7 @@ def test_attention_uniform_keys_gives_mean_of_values():
     q = f32(RNG.standard_normal(H * hd))
     K = f32(np.tile(RNG.standard_normal(H * hd), (n, 1)))
     V = f32(RNG.standard_normal((n, H * hd)))
-    assert np.allclose(O.attention_row(O.EO_F32, q, K, V, H, hd), V.mean(0), rtol=1e-5, atol=1e-6)
+    assert np.allclose(O.attention_row(q, K, V, H, hd), V.mean(0), rtol=1e-5, atol=1e-6)
 
 
 def test_attention_matches_scipy_softmax_fp64_per_head():
@@ -169,7 +169,7 @@ def test_attention_matches_scipy_softmax_fp64_per_head():
     q = f32(RNG.standard_normal(H * hd))
     K = f32(RNG.standard_normal((n, H * hd)))
     V = f32(RNG.standard_normal((n, H * hd)))
-    out = O.attention_row(O.EO_F32, q, K, V, H, hd)
+    out = O.attention_row(q, K, V, H, hd)
     Kd = K.astype(np.float64).reshape(n, H, hd)
     Vd = V.astype(np.float64).reshape(n, H, hd)
     qd = q.astype(np.float64).reshape(H, hd)
@@ -184,11 +184,11 @@ def test_attention_heads_do_not_mix():
     q = f32(RNG.standard_normal(H * hd))
     K = f32(RNG.standard_normal((n, H * hd)))
     V = f32(RNG.standard_normal((n, H * hd)))
-    a = O.attention_row(O.EO_F32, q, K, V, H, hd)
+    a = O.attention_row(q, K, V, H, hd)
     K2, V2 = K.copy(), V.copy()
     K2[:, hd:] += 1.0
     V2[:, hd:] *= 2.0
-    b = O.attention_row(O.EO_F32, q, K2, V2, H, hd)
+    b = O.attention_row(q, K2, V2, H, hd)
     assert np.array_equal(a[:hd], b[:hd])
     assert not np.allclose(a[hd:], b[hd:])
 
@@ -198,13 +198,13 @@ def test_attention_heads_do_not_mix():
 def test_swiglu_zero_gate_and_fp64_formula():
     n = 257
     up = f32(RNG.standard_normal(n))
-    assert np.array_equal(O.swiglu(O.EO_F32, f32(np.zeros(n)), up), np.zeros(n, np.float32))
+    assert np.array_equal(O.swiglu(f32(np.zeros(n)), up), np.zeros(n, np.float32))
     gate = f32(RNG.standard_normal(n) * 4)
     ref = gate.astype(np.float64) * scipy.special.expit(gate.astype(np.float64)) * up.astype(np.float64)
-    assert np.allclose(O.swiglu(O.EO_F32, gate, up), ref, rtol=1e-6, atol=1e-9)
+    assert np.allclose(O.swiglu(gate, up), ref, rtol=1e-6, atol=1e-9)
     # large negative gate: silu -> 0-, large positive: silu -> t
-    assert abs(O.swiglu(O.EO_F32, f32([-60.0]), f32([1.0]))[0]) < 1e-20
-    assert O.swiglu(O.EO_F32, f32([60.0]), f32([1.0]))[0] == 60.0
+    assert abs(O.swiglu(f32([-60.0]), f32([1.0]))[0]) < 1e-20
+    assert O.swiglu(f32([60.0]), f32([1.0]))[0] == 60.0
 
 
 # ---------------------------------------------------------------- softmax max
