@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark: generated tokens/s of early-exit decode with KV recomputation at the 7B shape
+(threshold 0.8) against full-depth decode (threshold 1.0) on the same kernels, one MI355X.
+
+A "step" is one ee_decode_step: the whole hot path (embedding, the layers up to the exit taken, exit
+heads with the fused soft-max/decision, KV writes for the current and the deferred tokens) for one
+batch.  Inputs are seeded and synthetic (workload/gen.py): the 7B-shaped model of the C3 workload,
+a 1024-token uniform-random prompt, greedy decoding.  Weights and the KV cache are resident in HBM
+before the timed region starts.
+
+Prints ONE JSON line (see the design doc for every field).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=15)
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C5"])
+    ap.add_argument("--threshold", type=float, default=0.8)
+    ap.add_argument("--max-pending", type=int, default=15)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every kernel family (extra passes, stderr)")
+    ap.add_argument("--cpu-threads", type=int, default=0)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
+    return ap.parse_args()
+
+
+def step_bytes(shape, es, ctx, exit_layer, heads_tested, rows_per_layer):
+    """Algorithmic HBM bytes of one decode step of one sequence: weights of the layers run, the heads
+    evaluated, K and V of the context read once per layer, K and V of the active rows written, one
+    embedding row."""
+    d, F, V = shape.d_model, shape.d_ff, shape.vocab
+    w_layer = (4 * d * d + 3 * d * F) * es
+    w_head = d * V * es
+    b = exit_layer * w_layer + heads_tested * w_head + d * es
+    b += exit_layer * 2 * d * es * ctx
+    b += sum(rows_per_layer[:exit_layer]) * 2 * d * es
+    return b
+
+
+def generate(ee, gm, cache, prompt, tau, warmup, steps, shape, es, max_pending, profile_kernel=None):
+    """Prefill + (warmup + steps) decode steps; returns timing of the last `steps` and the bytes model."""
+    import torch
+
+    cache.reset(0)
+    tok, ex, _ = ee.prefill(gm, cache, 0, prompt, tau)
+    seqs = ee.Sequences(shape.n_layers)
+    seqs.start(0, tok)
+    exits, nbytes, forced = [], 0, 0
+    seg_ends = list(shape.exit_layers) + [shape.n_layers]
+    seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(shape.n_layers)]
+    fl = [len(prompt)] * len(seg_ends)  # host mirror of the fill watermarks, for the bytes model only
+    prof = None
+    t0 = None
+    for i in range(warmup + steps):
+        if i == warmup:
+            torch.cuda.synchronize()
+            if profile_kernel is not None:
+                gm.profile_begin(profile_kernel)
+            t0 = time.perf_counter()
+        ro, tk, pm = seqs.rows([0])
+        nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, tau)
+        seqs.update([0], nt, exl)
+        p, e = len(prompt) + i, int(exl[0])
+        if i >= warmup:
+            was_forced = len(tk) - 1 >= max_pending
+            rows = [p - fl[seg_of_layer[l]] + 1 for l in range(shape.n_layers)]
+            tested = 0 if (tau >= 1.0 or was_forced) else sum(1 for x in shape.exit_layers if x <= e)
+            tested += 1 if e == shape.n_layers else 0
+            nbytes += step_bytes(shape, es, p + 1, e, tested, rows)
+            exits.append(e)
+            forced += int(was_forced)
+        for k, se in enumerate(seg_ends):
+            if se <= e:
+                fl[k] = p + 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if profile_kernel is not None:
+        prof = gm.profile_end()
+    return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof)
+
+
+def cpu_baseline(shape, tensors_host, prompt, tau, max_pending, threads):
+    """Times the CPU oracle (as it stands) on a bounded sample of the same workload."""
+    from oracle import oracle as O
+    from oracle.from_workload import config_of
+
+    om = O.Model(config_of(shape))
+    for (kind, idx), arr in tensors_host.items():
+        om.set_tensor(kind, idx, arr)
+    O.set_threads(threads)
+    big = shape.d_model >= 2048
+    n_prompt, n_new = (8, 10) if big else (len(prompt), 32)
+    st = O.State(om, n_prompt + n_new + 1, max_pending)
+    dg = st.prefill(prompt[:n_prompt])
+    tok = dg[-1]["argmax"]
+    for d in dg[:-1]:
+        if tau < 1.0 and d["conf"] >= tau:
+            tok = d["argmax"]
+            break
+    t0 = time.perf_counter()
+    for _ in range(n_new):
+        tok, _, _ = st.decode_step(tok, tau)
+    dt = time.perf_counter() - t0
+    return {"value": n_new / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"same model and threshold; prompt cut to {n_prompt} tokens, {n_new} decode steps "
+                      f"({dt:.1f} s of CPU work)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2312_04916_amd as ee
+    from common import ee_config_of
+    from oracle.from_workload import to_numpy
+    from workload import CONFIGS, model_tensor, model_tensor_list, prompt_tokens
+
+    wl = CONFIGS[args.workload]
+    shape = wl.shape
+    es = 2 if shape.dtype == "bf16" else 4
+    n_prompt = wl.prompt_len[0]
+    max_pos = n_prompt + args.warmup + args.steps + 8
+    t_setup = time.perf_counter()
+    gm = ee.Model(ee_config_of(shape, max_pos), max_rows=64, max_seqs=1)
+    keep_host = not args.no_cpu_baseline
+    tensors_host = {}
+    for kind, idx in model_tensor_list(shape):
+        t = model_tensor(shape, kind, idx, wl.weight_seed, "cuda:0").contiguous()
+        gm.set_tensor(int(kind), idx, t)
+        if keep_host:
+            tensors_host[(int(kind), idx)] = to_numpy(t)
+        torch.cuda.synchronize()
+        del t
+    cache = ee.KvCache(gm, 1, max_pos, 64, args.max_pending)
+    prompt = prompt_tokens(shape.vocab, n_prompt, wl.prompt_seed).numpy()
+    print(f"[bench] model {args.workload} ready in {time.perf_counter() - t_setup:.1f}s "
+          f"({gm.weight_bytes / 1e9:.2f} GB weights)", file=sys.stderr, flush=True)
+
+    full = generate(ee, gm, cache, prompt, 1.0, args.warmup, args.steps, shape, es, args.max_pending)
+    early = generate(ee, gm, cache, prompt, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
+                     profile_kernel=ee.EE_K_SWIGLU)
+    tps_full = args.steps / full["seconds"]
+    tps = args.steps / early["seconds"]
+    n_l, ms_l = early["prof"]
+    w_swiglu = 2 * shape.d_ff * shape.d_model * es
+    achieved = w_swiglu / (ms_l / n_l * 1e-3) / 1e9 if n_l else 0.0
+    hist = {str(e): early["exits"].count(e) for e in sorted(set(early["exits"]))}
+    ideal_speedup = (full["bytes"] / args.steps) / (early["bytes"] / args.steps)
+
+    if args.breakdown:
+        for k, name in enumerate(ee.KERNEL_NAMES):
+            r = generate(ee, gm, cache, prompt, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
+                         profile_kernel=k)
+            n, ms = r["prof"]
+            print(f"[bench] {name:10s} launches {n:6d} avg {ms / max(n, 1) * 1e3:8.2f} us total {ms:9.2f} ms "
+                  f"of {r['seconds'] * 1e3:.1f} ms", file=sys.stderr, flush=True)
+
+    sweep = {}
+    if not args.no_sweep:
+        for tau in wl.thresholds:
+            if tau in (1.0, args.threshold):
+                continue
+            r = generate(ee, gm, cache, prompt, tau, args.warmup, args.steps, shape, es, args.max_pending)
+            sweep[str(tau)] = {"tokens_per_s": args.steps / r["seconds"], "speedup_vs_full_depth": full["seconds"] / r["seconds"],
+                               "bytes_model_speedup": full["bytes"] / r["bytes"], "forced_full_steps": r["forced"],
+                               "exit_histogram": {str(e): r["exits"].count(e) for e in sorted(set(r["exits"]))}}
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(f"swiglu_{args.workload}")
+
+    out = {
+        "metric": "generated tokens/s at 7B early-exit decode (thr 0.8) vs full-depth; HBM GB/s",
+        "value": tps, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": early["seconds"] / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {wl.note}, batch 1, prompt {n_prompt} random ids, greedy, "
+                               f"threshold {args.threshold}, max_pending {args.max_pending}",
+                   "threshold": args.threshold, "exit_layers": list(shape.exit_layers), "n_layers": shape.n_layers},
+        "full_depth_tokens_per_s": tps_full, "full_depth_ms_per_step": full["seconds"] / args.steps * 1e3,
+        "speedup_vs_full_depth": tps / tps_full, "bytes_model_speedup": ideal_speedup,
+        "exit_histogram": hist, "forced_full_steps": early["forced"], "threshold_sweep": sweep,
+        "hbm_gbps": early["bytes"] / early["seconds"] / 1e9, "hbm_frac": early["bytes"] / early["seconds"] / 1e9 / HBM_PEAK_GBPS,
+        "full_depth_hbm_gbps": full["bytes"] / full["seconds"] / 1e9,
+        "full_depth_hbm_frac": full["bytes"] / full["seconds"] / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "gemm_swiglu_kernel (gate|up projection + SwiGLU)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "launches": n_l, "avg_us": ms_l / max(n_l, 1) * 1e3, "bytes_per_launch": w_swiglu,
+                     "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        threads = args.cpu_threads or min(16, os.cpu_count() or 1)
+        cache.close()
+        out["cpu_baseline"] = cpu_baseline(shape, tensors_host, prompt, args.threshold, args.max_pending, threads)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

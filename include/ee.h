@@ -123,6 +123,15 @@ int ee_model_free(ee_model* m);
  * [row][vocab] for the rows it evaluates (capacity_rows rows).  NULL switches it off. */
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);
 
+/* Measurement hook (used by the benchmark's roofline figure): between begin and end, every launch of
+ * one kernel family carries a HIP event pair attached to the dispatch on the launch stream, so each
+ * pair measures that kernel's execution time.  end() waits for the recorded events and returns how
+ * many launches were timed and their summed duration.  At most max_launches are recorded; later
+ * ones run untimed.  (EE_K_ATTN times the main attention kernel, not the split merge after it.) */
+enum { EE_K_QKV = 0, EE_K_ATTN = 1, EE_K_OPROJ = 2, EE_K_SWIGLU = 3, EE_K_DOWN = 4, EE_K_HEAD = 5, EE_K_KINDS = 6 };
+int ee_profile_begin(ee_model* m, int kernel, int max_launches);
+int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms);
+
 /* ---------------------------------------------------------------- KV cache */
 
 /* The cache is paged: a pool of blocks of block_tokens positions (a multiple of 32), shared by up to

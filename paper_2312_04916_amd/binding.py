@@ -11,11 +11,13 @@ import torch
 
 EE_F32, EE_BF16 = 0, 1
 EE_MAX_ROWS, EE_MAX_SEQS, EE_MAX_EXITS = 256, 64, 8
+EE_K_QKV, EE_K_ATTN, EE_K_OPROJ, EE_K_SWIGLU, EE_K_DOWN, EE_K_HEAD = range(6)
+KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
 (EE_T_EMBED, EE_T_ATTN_NORM, EE_T_WQ, EE_T_WK, EE_T_WV, EE_T_WO, EE_T_MLP_NORM, EE_T_WG, EE_T_WU, EE_T_WD,
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_decode_step"]
 
@@ -61,6 +63,8 @@ def lib():
                                     C.POINTER(vp)]
         L.ee_model_free.argtypes = [vp]
         L.ee_debug_set_logits.argtypes = [vp, vp, C.c_int]
+        L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
+        L.ee_profile_end.argtypes = [vp, i32p, fp]
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
         L.ee_kv_cache_reset.argtypes = [vp, C.c_int]
@@ -138,6 +142,14 @@ class Model:
         self._logits = torch.zeros(rows, self.cfg.vocab, dtype=torch.float32, device=self.device)
         _chk(lib().ee_debug_set_logits(self.h, self._logits.data_ptr(), rows), "ee_debug_set_logits")
         return self._logits
+
+    def profile_begin(self, kernel: int, max_launches: int = 65536) -> None:
+        _chk(lib().ee_profile_begin(self.h, kernel, max_launches), "ee_profile_begin")
+
+    def profile_end(self) -> Tuple[int, float]:
+        n, ms = C.c_int32(), C.c_float()
+        _chk(lib().ee_profile_end(self.h, C.byref(n), C.byref(ms)), "ee_profile_end")
+        return n.value, ms.value
 
     def close(self):
         if self.h:

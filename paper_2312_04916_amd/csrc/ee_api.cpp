@@ -131,6 +131,9 @@ struct ee_model {
     HeadResult* results_dev; // device view of the same memory
     float* dbg_logits;
     int dbg_rows;
+    int prof_kernel = -1;               // kernel family being timed, or -1
+    std::vector<hipEvent_t> prof_ev;    // event pairs
+    size_t prof_used = 0;               // events recorded so far
     size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? (size_t)max_rows * ld : 0; }  // hi -> lo distance
     int n_seg() const { return cfg.n_exits + 1; }
     int seg_begin(int s) const { return s == 0 ? 0 : cfg.exit_layers[s - 1]; }
@@ -221,6 +224,16 @@ int check_cache_args(const ee_model* m, int max_seqs, int64_t max_tokens_total, 
     return EE_OK;
 }
 
+// Attaches an event pair to the next launch when its kernel family is being timed.
+struct Timed {
+    Timed(ee_model* m, int kernel, hipStream_t) {
+        if (m->prof_kernel == kernel && m->prof_used + 2 <= m->prof_ev.size()) {
+            set_launch_events(m->prof_ev[m->prof_used], m->prof_ev[m->prof_used + 1]);
+            m->prof_used += 2;
+        }
+    }
+};
+
 // ---- the per-layer launch sequence over the rows described by dev_desc(di)
 int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st) {
     const ee_config& cf = m->cfg;
@@ -245,9 +258,15 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.lda = d;
         g.arow = xrow;
         g.ssq = c->ssq();
-        HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
-        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
+        {
+            Timed t(m, EE_K_QKV, st);
+            HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
+        }
+        {
+            Timed t(m, EE_K_ATTN, st);
+            HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
                                 (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx, st));
+        }
         // x += W_o a ; operand for the MLP norm
         g.W = m->wbase + m->wl.wo[l];
         g.N = d;
@@ -256,7 +275,10 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.a_lo = m->lo_rows(d);
         g.arow = nullptr;
         g.ssq = nullptr;
-        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
+        {
+            Timed t(m, EE_K_OPROJ, st);
+            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
+        }
         // act = silu(W_g h) * (W_u h)
         g.W = m->wbase + m->wl.gu[l];
         g.N = 2 * F;
@@ -265,7 +287,10 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.a_lo = c->xs_lo;
         g.arow = xrow;
         g.ssq = c->ssq();
-        HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, st));
+        {
+            Timed t(m, EE_K_SWIGLU, st);
+            HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, st));
+        }
         // x += W_d act ; operand for the next layer (or the final head), and for an exit head after this layer
         g.W = m->wbase + m->wl.wd[l];
         g.N = d;
@@ -279,7 +304,10 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         const float* g_head = nullptr;
         for (int i = 0; i < cf.n_exits; ++i)
             if (cf.exit_layers[i] == l + 1) g_head = m->gain(m->wl.ge[i]);
-        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d, st));
+        {
+            Timed t(m, EE_K_DOWN, st);
+            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d, st));
+        }
     }
     return EE_OK;
 }
@@ -306,6 +334,7 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.T = n_head;
     g.desc = dd;
     float* logits = (m->dbg_logits && n_head <= m->dbg_rows) ? m->dbg_logits : nullptr;
+    Timed t(m, EE_K_HEAD, st);
     HIPCHK(launch_gemm_head(g, (HeadPartial*)(m->ws + m->wsl.partials), (int32_t*)(m->ws + m->wsl.counters), logits, mode,
                             threshold, m->results_dev, st));
     return EE_OK;
@@ -632,8 +661,37 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
     return EE_OK;
 }
 
+int ee_profile_begin(ee_model* m, int kernel, int max_launches) {
+    if (!m || kernel < 0 || kernel >= EE_K_KINDS || max_launches < 1 || max_launches > (1 << 20)) return EE_ERR_ARG;
+    while (m->prof_ev.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        HIPCHK(hipEventCreate(&e));
+        m->prof_ev.push_back(e);
+    }
+    m->prof_used = 0;
+    m->prof_kernel = kernel;
+    return EE_OK;
+}
+
+int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms) {
+    if (!m || !n_launches || !total_ms) return EE_ERR_ARG;
+    m->prof_kernel = -1;
+    float tot = 0.f;
+    for (size_t i = 0; i + 1 < m->prof_used; i += 2) {
+        HIPCHK(hipEventSynchronize(m->prof_ev[i + 1]));
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, m->prof_ev[i], m->prof_ev[i + 1]));
+        tot += ms;
+    }
+    *n_launches = (int32_t)(m->prof_used / 2);
+    *total_ms = tot;
+    m->prof_used = 0;
+    return EE_OK;
+}
+
 int ee_model_free(ee_model* m) {
     if (!m) return EE_ERR_ARG;
+    for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     if (m->pinned) (void)hipHostFree(m->pinned);
     delete m;
     return EE_OK;

@@ -47,6 +47,9 @@ struct KvGeom {
 
 enum HeadMode { HEAD_RULE = 0, HEAD_EMIT = 1 };
 
+// The next kernel launched by this thread reports its execution time through the event pair.
+void set_launch_events(hipEvent_t start, hipEvent_t stop);
+
 // ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);

@@ -10,7 +10,27 @@
 // of the kernel that produced it.  No float atomics: every reduction has a fixed order.
 #include "ee_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace ee {
+
+// Optional timing of the next launch: the event pair is attached to the dispatch itself, so the
+// elapsed time between the two events is the kernel's own execution time.
+static thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
+void set_launch_events(hipEvent_t start, hipEvent_t stop) {
+    t_ev0 = start;
+    t_ev1 = stop;
+}
+#define EE_LAUNCH(kernel, grid, block, stream, ...)                                            \
+    do {                                                                                       \
+        if (t_ev0) {                                                                           \
+            hipEvent_t _a = t_ev0, _b = t_ev1;                                                 \
+            t_ev0 = t_ev1 = nullptr;                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, _a, _b, 0, __VA_ARGS__);     \
+        } else {                                                                               \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                   \
+        }                                                                                      \
+    } while (0)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -50,7 +70,7 @@ __global__ void rope_table_kernel(float2* cs, int max_pos, int half, int hd, flo
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s) {
     int n = max_pos * (hd / 2);
-    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (float2*)cs, max_pos, hd / 2, hd, base);
+    EE_LAUNCH(rope_table_kernel, dim3((n + 255) / 256), dim3(256), s, (float2*)cs, max_pos, hd / 2, hd, base);
     return hipGetLastError();
 }
 
@@ -98,11 +118,11 @@ hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K,
                        int tile_off, hipStream_t s) {
     if (dtype == EE_BF16) {
         long total = (long)(n_rows / 16) * (K / 32) * 64;
-        hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const __bf16*)src,
+        EE_LAUNCH(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const __bf16*)src,
                            (uint4*)dst, n_rows / 16, K, mode, hd, tile_mul, tile_off);
     } else {
         long total = (long)n_rows * K;
-        hipLaunchKernelGGL(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float*)src,
+        EE_LAUNCH(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const float*)src,
                            (float*)dst, n_rows, K, mode, hd, tile_mul, tile_off);
     }
     return hipGetLastError();
@@ -140,10 +160,10 @@ hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens,
                         const float* g_next, float* x, void* xg, size_t xg_lo, float* ssq, int ssq_stride, hipStream_t s) {
     if (T <= 0) return hipSuccess;
     if (dtype == EE_BF16)
-        hipLaunchKernelGGL(embed_kernel<__bf16>, dim3(T), dim3(256), 0, s, (const __bf16*)embed, dev_tokens, desc, d, g_next, x,
+        EE_LAUNCH(embed_kernel<__bf16>, dim3(T), dim3(256), s, (const __bf16*)embed, dev_tokens, desc, d, g_next, x,
                            (__bf16*)xg, xg_lo, ssq, ssq_stride);
     else
-        hipLaunchKernelGGL(embed_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)embed, dev_tokens, desc, d, g_next, x,
+        EE_LAUNCH(embed_kernel<float>, dim3(T), dim3(256), s, (const float*)embed, dev_tokens, desc, d, g_next, x,
                            (float*)xg, xg_lo, ssq, ssq_stride);
     return hipGetLastError();
 }
@@ -176,17 +196,21 @@ struct GemmSmem {
 
 template <int MT>
 __device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
-    // r[m] = 1/sqrt(mean(x^2)+eps); the sum of squares arrives as ssq_n partial sums, added in order
-    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+    // r[m] = 1/sqrt(mean(x^2)+eps).  The sum of squares arrives as ssq_n partial sums (one per producing
+    // workgroup); one wave per row adds them: lane-strided in order, then a fixed butterfly.
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    for (int m = wave; m < MT * 16; m += nw) {
         float r = 1.f;
         if (a.ssq != nullptr && m < a.T) {
             int slot = a.arow ? a.arow[m] : m;
             const float* p = a.ssq + (size_t)slot * a.ssq_stride;
             float s = 0.f;
-            for (int i = 0; i < a.ssq_n; ++i) s += p[i];
+            for (int i = lane; i < a.ssq_n; i += 64) s += p[i];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
             r = 1.0f / sqrtf(s * a.inv_d + a.eps);
         }
-        rs[m] = r;
+        if (lane == 0) rs[m] = r;
     }
 }
 
@@ -198,56 +222,63 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
     const int KT = a.KT;
     const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
     const u32x4* wp = (const u32x4*)a.W + ((size_t)(tile0 + g) * KT + kt0) * 64 + lane;
+    // Rows beyond T read row 0 again (always a valid address): their products are never looked at,
+    // and an unpredicated load keeps the loop free of branches.
     const __bf16* ap[MT];
-    bool av[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         int row = mt * 16 + li;
-        av[mt] = row < a.T;
-        int idx = av[mt] ? (a.arow ? a.arow[row] : row) : 0;
-        ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + lg * 8;
+        if (row >= a.T) row = 0;
+        int idx = a.arow ? a.arow[row] : row;
+        ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + (size_t)kt0 * 32 + lg * 8;
     }
     f32x4 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    int kt = kt0;
-    constexpr int C = 8;
-    for (; kt + C <= kt1; kt += C) {
-        u32x4 w[C];
-#pragma unroll
-        for (int u = 0; u < C; ++u) w[u] = __builtin_nontemporal_load(wp + u * 64);
-        wp += C * 64;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            u32x4 ah[C], al[C];
-#pragma unroll
-            for (int u = 0; u < C; ++u) {
-                ah[u] = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)(kt + u) * 32) : zero;
-                al[u] = av[mt] ? *(const u32x4*)(ap[mt] + a.a_lo + (size_t)(kt + u) * 32) : zero;
-            }
-#pragma unroll
-            for (int u = 0; u < C; ++u) {
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, al[u]),
-                                                                  __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ah[u]),
-                                                                  __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
-            }
-        }
-    }
-    for (; kt < kt1; ++kt) {
-        u32x4 w = __builtin_nontemporal_load(wp);
-        wp += 64;
+    // Rolling pipeline of D tiles (1 KB of weights each) per wave: a slot is refilled with the tile D
+    // ahead as soon as its MFMAs are issued, so the wave always has about D KB of loads in flight.
+    constexpr int D = MT == 1 ? 8 : (MT == 2 ? 6 : 4);
+    u32x4 w[D], ah[MT][D], al[MT][D];
+    const int n = kt1 - kt0;
+    auto fill = [&](int u, int t) {  // slot u <- tile t (relative to kt0)
+        w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            u32x4 a4 = av[mt] ? *(const u32x4*)(ap[mt] + (size_t)kt * 32) : zero;
-            u32x4 l4 = av[mt] ? *(const u32x4*)(ap[mt] + a.a_lo + (size_t)kt * 32) : zero;
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, l4), __builtin_bit_cast(bf16x8, w),
-                                                              acc[mt], 0, 0, 0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, w),
-                                                              acc[mt], 0, 0, 0);
+            ah[mt][u] = *(const u32x4*)(ap[mt] + (size_t)t * 32);
+            al[mt][u] = *(const u32x4*)(ap[mt] + a.a_lo + (size_t)t * 32);
+        }
+    };
+    auto use = [&](int u) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, al[mt][u]),
+                                                              __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ah[mt][u]),
+                                                              __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
+        }
+    };
+    const int full = n / D, rem = n - full * D;
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n) fill(u, u);
+    for (int gI = 0; gI + 1 < full; ++gI) {  // steady state: every refill is in range
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u);
+            fill(u, (gI + 1) * D + u);
+            __builtin_amdgcn_sched_barrier(0);  // keep the slot order: the wait before use(u+1) then covers one slot only
         }
     }
+    if (full > 0) {  // last full group: refill only the slots the remainder needs
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u);
+            if (u < rem) fill(u, full * D + u);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < rem) use(u);
     // accumulator layout: lane (lg, li) holds D[row = lg*4 + r][col = li]
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -285,7 +316,11 @@ __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile0, 
 
 template <typename ST, int G, int KS, int MT>
 __device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
+#ifdef EE_EXP_NOSSQ
+    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) sm.rs[m] = 1.f;
+#else
     rms_scales<MT>(a, sm.rs);
+#endif
     if constexpr (sizeof(ST) == 2)
         gemm_mainloop_bf16<G, KS, MT>(a, tile0, sm);  // (its first __syncthreads orders rs before use)
     else
@@ -309,6 +344,9 @@ template <typename ST, int KS, int MT>
 __global__ __launch_bounds__(2 * KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
     __shared__ GemmSmem<2, KS, MT> sm;
     gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
+#ifdef EE_EXP_NOEPI
+    if (sm.out[0][0] != 12345.f) return;
+#endif
     const int per_part = e.H * (e.hd / 32);
     const int part = blockIdx.x / per_part;  // 0 q, 1 k, 2 v
     const int rem = blockIdx.x % per_part;
@@ -359,6 +397,9 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
     __shared__ GemmSmem<1, KS, MT> sm;
     gemm_mainloop<ST, 1, KS, MT>(a, blockIdx.x, sm);
     const int n0 = blockIdx.x * 16;
+#ifdef EE_EXP_NOEPI
+    if (sm.out[0][0] != 12345.f) return;
+#endif
     for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
         int m = idx >> 4, i = idx & 15;
         if (m >= a.T) continue;
@@ -393,17 +434,14 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST
     }
 }
 
-// ---- epilogue 4: exit / final head.  Per workgroup: (max, arg max, sum exp) of its 32 logits per row;
-// the workgroup that finishes last merges all partials in a fixed order and takes the exit decision.
+// ---- epilogue 4: exit / final head.  Per workgroup: (max, arg max, sum exp) of its 32 logits per row.
+// A one-workgroup kernel launched right after merges the partials in a fixed order and takes the exit
+// decision (an in-kernel "last workgroup merges" scheme needs a device-wide fence in every workgroup,
+// which costs more than the extra launch).
 struct HeadArgs {
     HeadPartial* partials;  // [n_wg][EE_MAX_SEQS]
-    int32_t* counter;
-    float* logits;  // optional [row][V]
+    float* logits;          // optional [row][V]
     int V;
-    int mode;
-    float threshold;
-    HeadResult* results;
-    const SegDesc* desc;
 };
 
 __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float m2, float s2, int i2) {
@@ -419,7 +457,6 @@ __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float 
 template <typename ST, int KS, int MT>
 __global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
     __shared__ GemmSmem<2, KS, MT> sm;
-    __shared__ int s_last;
     gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
     const int n0 = blockIdx.x * 32;
     if (e.logits) {
@@ -446,29 +483,27 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, Head
         p.pad = 0;
         e.partials[(size_t)blockIdx.x * EE_MAX_SEQS + m] = p;
     }
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = (atomicAdd(e.counter, 1) == (int)gridDim.x - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    // merge: thread t folds workgroups t, t+nthr, ... in ascending order, then a fixed tree over threads
-    float* redm = &sm.red[0][0][0][0];
-    float* reds = redm + 512;
-    int* redi = (int*)(reds + 512);
-    const int nthr = blockDim.x;  // 2*KS*64 <= 512
-    for (int m = 0; m < a.T; ++m) {
+}
+
+// confidence = 1 / sum_i exp(z_i - z_max); exit iff confidence >= threshold (or always, for the final head)
+__global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __restrict__ partials, int n_wg, int T, int mode,
+                                                         float threshold, HeadResult* results,
+                                                         const SegDesc* __restrict__ desc) {
+    __shared__ float redm[512], reds[512];
+    __shared__ int redi[512];
+    // thread t folds workgroups t, t+512, ... in ascending order, then a fixed tree over the threads
+    for (int m = 0; m < T; ++m) {
         float mx = -INFINITY, s = 0.f;
         int ix = 0x7fffffff;
-        for (int w = threadIdx.x; w < (int)gridDim.x; w += nthr) {
-            HeadPartial p = e.partials[(size_t)w * EE_MAX_SEQS + m];
+        for (int w = threadIdx.x; w < n_wg; w += 512) {
+            HeadPartial p = partials[(size_t)w * EE_MAX_SEQS + m];
             merge_partial(mx, s, ix, p.max, p.sum, p.idx);
         }
         redm[threadIdx.x] = mx;
         reds[threadIdx.x] = s;
         redi[threadIdx.x] = ix;
         __syncthreads();
-        for (int o = nthr >> 1; o > 0; o >>= 1) {
+        for (int o = 256; o > 0; o >>= 1) {
             if ((int)threadIdx.x < o) {
                 float m1 = redm[threadIdx.x], s1 = reds[threadIdx.x];
                 int i1 = redi[threadIdx.x];
@@ -486,13 +521,12 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, Head
             HeadResult r;
             r.token = redi[0];
             r.conf = conf;
-            r.fired = (e.mode == HEAD_EMIT) || (conf >= e.threshold);
+            r.fired = (mode == HEAD_EMIT) || (conf >= threshold);
             r.pad = 0;
-            e.results[e.desc->head_slot[m]] = r;
+            results[desc->head_slot[m]] = r;
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) *e.counter = 0;
 }
 
 // ---- host-side dispatch
@@ -536,11 +570,11 @@ hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const floa
     if (c.dtype == EE_BF16) {
         QkvArgs<__bf16> e{(__bf16*)q, q_lo, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
                           kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<__bf16, KS_QKV, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_qkv_kernel<__bf16, KS_QKV, MT>), grid, block, s, a, e));
     } else {
         QkvArgs<float> e{(float*)q, q_lo, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
                          kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_qkv_kernel<float, KS_QKV, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_qkv_kernel<float, KS_QKV, MT>), grid, block, s, a, e));
     }
     return hipGetLastError();
 }
@@ -553,10 +587,10 @@ hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh,
     dim3 grid(c.N / 16), block(KS_RES * 64);
     if (c.dtype == EE_BF16) {
         ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<__bf16, KS_RES, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_resid_kernel<__bf16, KS_RES, MT>), grid, block, s, a, e));
     } else {
         ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_resid_kernel<float, KS_RES, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_resid_kernel<float, KS_RES, MT>), grid, block, s, a, e));
     }
     return hipGetLastError();
 }
@@ -567,9 +601,9 @@ hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int
     GemmArgs a = make_args(c);
     dim3 grid(c.N / 32), block(2 * KS_SWI * 64);
     if (c.dtype == EE_BF16) {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, 0, s, a, (__bf16*)act, act_lo, F));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, s, a, (__bf16*)act, act_lo, F));
     } else {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, 0, s, a, (float*)act, act_lo, F));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, s, a, (float*)act, act_lo, F));
     }
     return hipGetLastError();
 }
@@ -579,13 +613,17 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
-    HeadArgs e{partials, counter, logits, c.N, mode, threshold, results, c.desc};
+    (void)counter;
+    HeadArgs e{partials, logits, c.N};
     dim3 grid(c.N / 32), block(2 * KS_HEAD * 64);
     if (c.dtype == EE_BF16) {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_head_kernel<__bf16, KS_HEAD, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_head_kernel<__bf16, KS_HEAD, MT>), grid, block, s, a, e));
     } else {
-        EE_DISPATCH_MT(c.T, hipLaunchKernelGGL((gemm_head_kernel<float, KS_HEAD, MT>), grid, block, 0, s, a, e));
+        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_head_kernel<float, KS_HEAD, MT>), grid, block, s, a, e));
     }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, partials, (int)grid.x, c.T, mode, threshold, results, c.desc);
     return hipGetLastError();
 }
 
@@ -666,28 +704,247 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
     if ((int)threadIdx.x < hd) store_split<ST>(out + (size_t)r * d + h * hd + threadIdx.x, io_lo, acc / l);
 }
 
+// ------------------------------------------------------------------------------------------------
+// attention, bf16 model: ragged multi-query decode attention over the paged cache with MFMA.
+// One workgroup = (query tile of <= 16 consecutive rows of one sequence, head, KV split); its 4 waves
+// take the split's 32-position tiles round-robin.  Per tile a wave computes S^T = K Q^T (K rows come
+// straight from the cache as MFMA A operands: 64 contiguous bytes per lane), applies the causal mask
+// (only the last rows of the context differ between the queries of a tile), keeps an online soft-max
+// per query, stages the V tile through LDS (coalesced 16-byte loads in, transposed 2-byte reads out)
+// and accumulates O^T += V^T P^T, where P^T is already in B-operand layout in the S^T registers.
+// q and P are fed as two bf16 terms each (hi + lo), so only K and V carry bf16 rounding.
+// Partials of the KV splits are merged by attn_merge_kernel in a fixed order.
+// ------------------------------------------------------------------------------------------------
+constexpr int ATT_MAX_SPLITS = 16;
+
+__host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
+                                                        size_t out_lo, const SegDesc* __restrict__ desc,
+                                                        const int32_t* __restrict__ btab, KvGeom kv,
+                                                        const __bf16* __restrict__ layer_base, int d, int NS,
+                                                        float* __restrict__ part) {
+    constexpr int KK = HD / 32, CG = HD / 16, VST = HD + 4;  // LDS row stride (elements): HD/2 + 2 dwords, conflict-free
+    constexpr int STAGE_BYTES = 4 * 32 * VST * 2;
+    constexpr int COMB_BYTES = (4 * 16 * (HD + 1) + 128) * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > COMB_BYTES ? STAGE_BYTES : COMB_BYTES];
+    const int qt = blockIdx.x / kv.H, h = blockIdx.x % kv.H, split = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
+    const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
+    const int pos0 = desc->pos[row0];
+    const int ctx = pos0 + nq;
+    const int32_t* bt = btab + (size_t)desc->rseq[row0] * kv.max_blocks_per_seq;
+    const int n_tiles = (ctx + 31) >> 5;
+    const int tps = (n_tiles + NS - 1) / NS;
+    const int t_lo = split * tps, t_hi = min(n_tiles, t_lo + tps);
+    const bool qvalid = li < nq;
+
+    bf16x8 qh[KK], ql[KK];
+    {
+        const __bf16* qp = q + (size_t)(row0 + (qvalid ? li : 0)) * d + h * HD + lg * (HD / 4);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            u32x4 a = qvalid ? *(const u32x4*)(qp + kk * 8) : zero;
+            u32x4 b = qvalid ? *(const u32x4*)(qp + q_lo + kk * 8) : zero;
+            qh[kk] = __builtin_bit_cast(bf16x8, a);
+            ql[kk] = __builtin_bit_cast(bf16x8, b);
+        }
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 o[CG];
+#pragma unroll
+    for (int c = 0; c < CG; ++c) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __bf16* vs = (__bf16*)smem + (size_t)wave * 32 * VST;
+
+    for (int t = t_lo + wave; t < t_hi; t += 4) {
+        const int tb = t << 5;
+        const int blk = bt[tb / kv.BT];
+        const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + (tb % kv.BT)) * HD;
+        const __bf16* vbase = kbase + (size_t)kv.H * kv.BT * HD;
+        // scores, transposed: rows = positions, columns = queries
+        f32x4 sacc[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            sacc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const __bf16* kp = kbase + (size_t)(sub * 16 + li) * HD + lg * (HD / 4);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                bf16x8 kf = __builtin_bit_cast(bf16x8, *(const u32x4*)(kp + kk * 8));
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, ql[kk], sacc[sub], 0, 0, 0);
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qh[kk], sacc[sub], 0, 0, 0);
+            }
+        }
+        // V tile -> LDS (rows beyond the context are zeroed: their probabilities are zero, their bits unknown)
+#pragma unroll
+        for (int ci = lane; ci < 32 * HD / 8; ci += 64) {
+            int p = ci / (HD / 8), c8 = ci % (HD / 8);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (tb + p < ctx) v = *(const u32x4*)(vbase + (size_t)p * HD + c8 * 8);
+            uint2* dst = (uint2*)(vs + p * VST + c8 * 8);
+            dst[0] = make_uint2(v.x, v.y);
+            dst[1] = make_uint2(v.z, v.w);
+        }
+        // causal mask + online soft-max per query (column li); this lane holds positions lg*4+r of each half
+        float pv[8];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int pa = tb + (e >> 2) * 16 + lg * 4 + (e & 3);
+            float val = (qvalid && pa <= pos0 + li) ? sacc[e >> 2][e & 3] * scale : -INFINITY;
+            pv[e] = val;
+            tmax = fmaxf(tmax, val);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        float corr = 1.f, psum = 0.f;
+        if (m_new == -INFINITY) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv[e] = 0.f;
+        } else {
+            corr = expf(m_run - m_new);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = expf(pv[e] - m_new);
+                psum += pv[e];
+            }
+        }
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+        bf16x8 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __bf16 hi = (__bf16)pv[e];
+            ph[e] = hi;
+            pl[e] = (__bf16)(pv[e] - (float)hi);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int c = 0; c < CG; ++c) {
+            bf16x8 vf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int pe = (e >> 2) * 16 + lg * 4 + (e & 3);
+                vf[e] = vs[pe * VST + c * 16 + li];
+            }
+            o[c] = o[c] * corr;
+            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
+            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // combine the 4 waves (fixed order)
+    __syncthreads();
+    float* wO = (float*)smem;  // [4][16][HD+1]
+    float* wm = wO + 4 * 16 * (HD + 1);
+    float* wl = wm + 64;
+#pragma unroll
+    for (int c = 0; c < CG; ++c)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) wO[(wave * 16 + li) * (HD + 1) + c * 16 + lg * 4 + r] = o[c][r];
+    if (lg == 0) {
+        wm[wave * 16 + li] = m_run;
+        wl[wave * 16 + li] = l_run;
+    }
+    __syncthreads();
+    float* pbase = part + ((size_t)(qt * kv.H + h) * NS + split) * att_part_stride(HD);
+    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+        int qq = idx / HD, cc = idx % HD;
+        if (qq >= nq) continue;
+        float M = fmaxf(fmaxf(wm[qq], wm[16 + qq]), fmaxf(wm[32 + qq], wm[48 + qq]));
+        float O = 0.f, L = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float f = expf(wm[w * 16 + qq] - M);
+                O += f * wO[(w * 16 + qq) * (HD + 1) + cc];
+                L += f * wl[w * 16 + qq];
+            }
+        }
+        if (NS == 1) {
+            store_split<__bf16>(out + (size_t)(row0 + qq) * d + h * HD + cc, out_lo, O / L);
+        } else {
+            pbase[32 + qq * HD + cc] = O;
+            if (cc == 0) {
+                pbase[qq] = M;
+                pbase[16 + qq] = L;
+            }
+        }
+    }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, int NS, __bf16* __restrict__ out,
+                                                         size_t out_lo, const SegDesc* __restrict__ desc, int H, int d) {
+    const int qt = blockIdx.x / H, h = blockIdx.x % H;
+    const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
+    const float* pb = part + (size_t)(qt * H + h) * NS * att_part_stride(HD);
+    for (int idx = threadIdx.x; idx < nq * HD; idx += 256) {
+        int qq = idx / HD, cc = idx % HD;
+        float M = -INFINITY;
+        for (int s = 0; s < NS; ++s) M = fmaxf(M, pb[(size_t)s * att_part_stride(HD) + qq]);
+        float O = 0.f, L = 0.f;
+        for (int s = 0; s < NS; ++s) {
+            const float* ps = pb + (size_t)s * att_part_stride(HD);
+            float ms = ps[qq];
+            if (ms == -INFINITY) continue;
+            float f = expf(ms - M);
+            O += f * ps[32 + qq * HD + cc];
+            L += f * ps[16 + qq];
+        }
+        store_split<__bf16>(out + (size_t)(row0 + qq) * d + h * HD + cc, out_lo, O / L);
+    }
+}
+
 size_t attention_part_floats(int max_rows, int H, int hd) {
-    (void)max_rows;
-    (void)H;
-    (void)hd;
-    return 64;
+    size_t entries = (size_t)max_rows * H;
+    if (entries < 1024) entries = 1024;
+    return entries * att_part_stride(hd);
+}
+
+template <int HD>
+static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, int n_qt, const int32_t* btab,
+                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, hipStream_t s) {
+    int wgs = n_qt * kv.H;
+    int NS = 1024 / wgs;
+    int by_len = ((max_ctx + 31) / 32 + 3) / 4;  // at least ~4 tiles (one per wave) per split
+    if (NS > by_len) NS = by_len;
+    if (NS > ATT_MAX_SPLITS) NS = ATT_MAX_SPLITS;
+    if (NS < 1) NS = 1;
+    const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
+    EE_LAUNCH(attn_mfma_kernel<HD>, dim3(wgs, NS), dim3(256), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, desc,
+                       btab, kv, lb, d, NS, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || NS == 1) return e;
+    EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, desc, kv.H, d);
+    return hipGetLastError();
 }
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
                             hipStream_t s) {
-    (void)n_qt;
-    (void)part;
     (void)counters;
-    (void)max_ctx;
     if (T <= 0) return hipSuccess;
+    if (dtype == EE_BF16) {
+        switch (kv.hd) {
+            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
+            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
+            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     dim3 grid(T, kv.H), block(256);
-    if (dtype == EE_BF16)
-        hipLaunchKernelGGL(attn_simple_kernel<__bf16>, grid, block, 0, s, (const __bf16*)q, (__bf16*)out, io_lo, desc, btab, kv,
-                           (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride, d);
-    else
-        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, block, 0, s, (const float*)q, (float*)out, io_lo, desc, btab, kv,
-                           (const float*)kv.pool + (size_t)layer * kv.layer_stride, d);
+    EE_LAUNCH(attn_simple_kernel<float>, grid, block, s, (const float*)q, (float*)out, io_lo, desc, btab, kv,
+                       (const float*)kv.pool + (size_t)layer * kv.layer_stride, d);
     return hipGetLastError();
 }
 
@@ -712,10 +969,10 @@ hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_
     long total = (long)n * kv.H * kv.hd;
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (dtype == EE_BF16)
-        hipLaunchKernelGGL(kv_gather_kernel<__bf16>, grid, block, 0, s, kv, (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride,
+        EE_LAUNCH(kv_gather_kernel<__bf16>, grid, block, s, kv, (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride,
                            btab_seq, pos0, n, k_out, v_out);
     else
-        hipLaunchKernelGGL(kv_gather_kernel<float>, grid, block, 0, s, kv, (const float*)kv.pool + (size_t)layer * kv.layer_stride,
+        EE_LAUNCH(kv_gather_kernel<float>, grid, block, s, kv, (const float*)kv.pool + (size_t)layer * kv.layer_stride,
                            btab_seq, pos0, n, k_out, v_out);
     return hipGetLastError();
 }

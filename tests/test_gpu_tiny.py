@@ -197,3 +197,30 @@ def test_error_codes(pair, prompt):
     assert code(lambda: ee.prefill(gm, small, 1, prompt_tokens(shape.vocab, 40, 3).numpy(), 1.0)) == -2
     small.close()
     cache.close()
+
+
+@pytest.mark.parametrize("hd,d,H", [(128, 256, 2), (64, 256, 4)])
+def test_other_head_dims_with_split_kv(hd, d, H):
+    """head_dim 128 / 64 models (MFMA attention with several KV splits and a ragged last tile)."""
+    print(f"case: head_dim {hd}", flush=True)
+    shape = ModelShape(3, d, H, hd, 512, 2048, (1, 2), "bf16", 0.02, 0.3 / (d / 128) ** 0.5)
+    om = build_model(shape, 3, gain_jitter=0.1)
+    gm = load_gpu_model(shape, 3, gain_jitter=0.1, max_positions=512, max_rows=64, max_seqs=1)
+    p = prompt_tokens(shape.vocab, 333, 5).numpy()
+    cache = ee.KvCache(gm, 1, 512, 64, 6)
+    logits = gm.enable_logits(1)
+    rep = lockstep(gm, cache, om, p, 24, 0.3, max_pending=6, logits=logits)
+    assert not rep.mismatches, rep.mismatches[:5]
+    assert rep.max_hidden_err <= 2e-2 and rep.max_logit_err <= 2e-2
+    assert len(set(rep.exit_layers)) >= 2
+    n_pos = len(p) + 23
+    cache.flush([0])
+    rep.state.flush()
+    for l in range(shape.n_layers):
+        k, v = cache.read(0, l, 0, n_pos)
+        ko, vo = rep.state.kv_read(l, 0, n_pos)
+        assert rel_err(k, ko) <= 2e-2 and rel_err(v, vo) <= 2e-2
+    print(f"head_dim {hd}: hidden err {rep.max_hidden_err:.2e} logit err {rep.max_logit_err:.2e} "
+          f"teacher-forced {rep.teacher_forced} exits {sorted(set(rep.exit_layers))}", flush=True)
+    cache.close()
+    gm.close()
