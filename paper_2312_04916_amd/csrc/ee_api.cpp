@@ -107,7 +107,7 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     w.q = take(terms * max_rows * d * es);
     w.attn = take(terms * max_rows * d * es);
     w.act = take(terms * max_rows * c.d_ff * es);
-    w.partials = take((size_t)(c.vocab / 32) * EE_MAX_SEQS * sizeof(HeadPartial));
+    w.partials = take((size_t)(c.vocab / 16) * EE_MAX_SEQS * sizeof(HeadPartial));
     w.counters = take(256 * 4);
     w.attn_part = take(attention_part_floats(max_rows, c.n_heads, c.head_dim) * 4);
     w.stage = take(2 * (size_t)max_rows * d * 4);
@@ -556,9 +556,9 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
         HIPCHK(hipMemcpyAsync(m->wbase + off, dev_src, d * 4, hipMemcpyDeviceToDevice, st));
         return EE_OK;
     };
-    auto mat = [&](size_t off, size_t rows, size_t K, int mode, int mul, int toff) -> int {
+    auto mat = [&](size_t off, size_t rows, size_t K, int mode) -> int {
         if (n_elems != rows * K) return EE_ERR_ARG;
-        HIPCHK(launch_pack(dt, dev_src, m->wbase + off, (int)rows, (int)K, mode, hd, mul, toff, st));
+        HIPCHK(launch_pack(dt, dev_src, m->wbase + off, (int)rows, (int)K, mode, hd, st));
         return EE_OK;
     };
     int rc;
@@ -572,15 +572,15 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
         case EE_T_MLP_NORM: rc = gain(m->wl.g2[index]); break;
         case EE_T_EXIT_NORM: rc = gain(m->wl.ge[index]); break;
         case EE_T_FINAL_NORM: rc = gain(m->wl.gf); break;
-        case EE_T_WQ: rc = mat(m->wl.qkv[index], d, d, 1, 1, 0); break;
-        case EE_T_WK: rc = mat(m->wl.qkv[index] + d * d * es, d, d, 1, 1, 0); break;
-        case EE_T_WV: rc = mat(m->wl.qkv[index] + 2 * d * d * es, d, d, 1, 1, 0); break;
-        case EE_T_WO: rc = mat(m->wl.wo[index], d, d, 0, 1, 0); break;
-        case EE_T_WG: rc = mat(m->wl.gu[index], F, d, 0, 2, 0); break;
-        case EE_T_WU: rc = mat(m->wl.gu[index], F, d, 0, 2, 1); break;
-        case EE_T_WD: rc = mat(m->wl.wd[index], d, F, 0, 1, 0); break;
-        case EE_T_EXIT_HEAD: rc = mat(m->wl.we[index], V, d, 0, 1, 0); break;
-        case EE_T_FINAL_HEAD: rc = mat(m->wl.wf, V, d, 0, 1, 0); break;
+        case EE_T_WQ: rc = mat(m->wl.qkv[index], d, d, PACK_ROTARY); break;
+        case EE_T_WK: rc = mat(m->wl.qkv[index] + d * d * es, d, d, PACK_ROTARY); break;
+        case EE_T_WV: rc = mat(m->wl.qkv[index] + 2 * d * d * es, d, d, PACK_ROTARY); break;
+        case EE_T_WO: rc = mat(m->wl.wo[index], d, d, PACK_PLAIN); break;
+        case EE_T_WG: rc = mat(m->wl.gu[index], F, d, PACK_GATE); break;
+        case EE_T_WU: rc = mat(m->wl.gu[index], F, d, PACK_UP); break;
+        case EE_T_WD: rc = mat(m->wl.wd[index], d, F, PACK_PLAIN); break;
+        case EE_T_EXIT_HEAD: rc = mat(m->wl.we[index], V, d, PACK_PLAIN); break;
+        case EE_T_FINAL_HEAD: rc = mat(m->wl.wf, V, d, PACK_PLAIN); break;
         default: return EE_ERR_RANGE;
     }
     if (rc != EE_OK) return rc;

@@ -54,9 +54,9 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);
 
-// mode 0: destination tile = src_tile*tile_mul + tile_off; mode 1: rotary pairing inside each head
-hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, int tile_mul,
-                       int tile_off, hipStream_t s);
+// Repacks one matrix into the tile layout of the GEMM kernels; `mode` places the rows (see ee_kernels.hip).
+enum PackMode { PACK_PLAIN = 0, PACK_ROTARY = 1, PACK_GATE = 2, PACK_UP = 3 };
+hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, hipStream_t s);
 
 hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
                         const float* g_next, float* x, void* xg, size_t xg_lo, float* ssq, int ssq_stride, hipStream_t s);

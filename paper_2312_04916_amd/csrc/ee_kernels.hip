@@ -21,16 +21,17 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop) {
     t_ev0 = start;
     t_ev1 = stop;
 }
-#define EE_LAUNCH(kernel, grid, block, stream, ...)                                            \
+#define EE_LAUNCH_SM(kernel, grid, block, shmem, stream, ...)                                  \
     do {                                                                                       \
         if (t_ev0) {                                                                           \
             hipEvent_t _a = t_ev0, _b = t_ev1;                                                 \
             t_ev0 = t_ev1 = nullptr;                                                           \
-            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, _a, _b, 0, __VA_ARGS__);     \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, _a, _b, 0, __VA_ARGS__); \
         } else {                                                                               \
-            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                   \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);               \
         }                                                                                      \
     } while (0)
+#define EE_LAUNCH(kernel, grid, block, stream, ...) EE_LAUNCH_SM(kernel, grid, block, 0, stream, __VA_ARGS__)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -75,55 +76,64 @@ hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStre
 }
 
 // ------------------------------------------------------------------------------------------------
-// weight packing.  Source: row-major [n_rows][K].  Destination rows are grouped in tiles of 16.
+// weight packing.  Source: row-major [n_rows][K].  Destination rows are grouped in tiles of 16, one
+// tile per workgroup of the GEMM kernels.
 //   bf16: [tile][K/32][lane 0..63][8]  with lane = (k_group << 4) | row_in_tile, k = kt*32 + k_group*8 + j
+//         (one wave load instruction = 1 KB of contiguous memory = one 16x32 MFMA operand)
 //   fp32: [tile][16][K] (row permutation only)
-// mode 1 reorders the 16-row tiles inside every head so that the two halves of a rotary pair
-// (feature i and i + hd/2) sit in neighbouring tiles: tile (h, c, s) = features h*hd + s*hd/2 + c*16 ..
+// Row placement (feature f -> tile, row in tile):
+//   PACK_PLAIN   tile f/16, row f%16
+//   PACK_ROTARY  both halves of a rotary pair in one tile: inside head h, feature o < hd/2 goes to
+//                tile h*hd/16 + o/8, row o%8; its partner o + hd/2 to the same tile, row 8 + o%8
+//   PACK_GATE / PACK_UP  gate feature f -> tile f/8, row f%8; up feature f -> tile f/8, row 8 + f%8
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int dst_tile_of(int src_tile, int mode, int hd, int tile_mul, int tile_off) {
-    if (mode == 0) return src_tile * tile_mul + tile_off;
-    int row = src_tile * 16;
-    int h = row / hd, o = row % hd;
-    int s = o >= hd / 2;
-    int c = (o % (hd / 2)) / 16;
-    return (h * (hd / 32) + c) * 2 + s;
+__device__ __forceinline__ void pack_place(int row, int mode, int hd, int& dt, int& dr) {
+    if (mode == PACK_PLAIN) {
+        dt = row >> 4;
+        dr = row & 15;
+    } else if (mode == PACK_ROTARY) {
+        int h = row / hd, o = row % hd, half = hd / 2;
+        int s = o >= half, oo = o % half;
+        dt = h * (hd / 16) + oo / 8;
+        dr = (oo & 7) + 8 * s;
+    } else {
+        dt = row >> 3;
+        dr = (row & 7) + (mode == PACK_UP ? 8 : 0);
+    }
 }
 
-__global__ void pack_bf16_kernel(const __bf16* __restrict__ src, uint4* __restrict__ dst, int n_tiles, int K, int mode,
-                                 int hd, int tile_mul, int tile_off) {
+__global__ void pack_bf16_kernel(const __bf16* __restrict__ src, uint4* __restrict__ dst, int n_rows, int K, int mode, int hd) {
     int KT = K / 32;
-    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;  // (src_tile, kt, lane)
-    long total = (long)n_tiles * KT * 64;
-    if (idx >= total) return;
-    int lane = idx & 63;
-    long r = idx >> 6;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;  // (row, kt, k_group)
+    if (idx >= (long)n_rows * KT * 4) return;
+    int lg = idx & 3;
+    long r = idx >> 2;
     int kt = r % KT;
-    int st = r / KT;
-    int dt = dst_tile_of(st, mode, hd, tile_mul, tile_off);
-    const uint4* sp = (const uint4*)(src + ((size_t)(st * 16 + (lane & 15)) * K + kt * 32 + (lane >> 4) * 8));
-    dst[((size_t)dt * KT + kt) * 64 + lane] = *sp;
+    int row = r / KT;
+    int dt, dr;
+    pack_place(row, mode, hd, dt, dr);
+    const uint4* sp = (const uint4*)(src + ((size_t)row * K + kt * 32 + lg * 8));
+    dst[((size_t)dt * KT + kt) * 64 + lg * 16 + dr] = *sp;
 }
 
-__global__ void pack_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int n_rows, int K, int mode, int hd,
-                                int tile_mul, int tile_off) {
+__global__ void pack_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int n_rows, int K, int mode, int hd) {
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)n_rows * K) return;
     int row = idx / K, k = idx % K;
-    int dt = dst_tile_of(row / 16, mode, hd, tile_mul, tile_off);
-    dst[((size_t)dt * 16 + (row & 15)) * K + k] = src[idx];
+    int dt, dr;
+    pack_place(row, mode, hd, dt, dr);
+    dst[((size_t)dt * 16 + dr) * K + k] = src[idx];
 }
 
-hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, int tile_mul,
-                       int tile_off, hipStream_t s) {
+hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, hipStream_t s) {
     if (dtype == EE_BF16) {
-        long total = (long)(n_rows / 16) * (K / 32) * 64;
-        EE_LAUNCH(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const __bf16*)src,
-                           (uint4*)dst, n_rows / 16, K, mode, hd, tile_mul, tile_off);
+        long total = (long)n_rows * (K / 32) * 4;
+        EE_LAUNCH(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const __bf16*)src, (uint4*)dst, n_rows, K,
+                  mode, hd);
     } else {
         long total = (long)n_rows * K;
-        EE_LAUNCH(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const float*)src,
-                           (float*)dst, n_rows, K, mode, hd, tile_mul, tile_off);
+        EE_LAUNCH(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, (const float*)src, (float*)dst, n_rows, K,
+                  mode, hd);
     }
     return hipGetLastError();
 }
@@ -170,12 +180,13 @@ hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens,
 
 // ------------------------------------------------------------------------------------------------
 // skinny GEMM: out[m][n] = r[m] * sum_k A[m][k] * W[n][k],  m < T <= MT*16
-// A workgroup owns G consecutive 16-column tiles; its G*KS waves split K in KS parts.
-// The result lands in LDS as out[MT*16][G*16] fp32 and is handed to the epilogue.
+// A workgroup owns ONE 16-column tile (128 KB of weights at K = 4096: small units keep the 256 CUs evenly
+// loaded) and its KS waves split K, so that each wave streams about 16 KB.  The result lands in LDS as
+// out[MT*16][16] fp32 and is handed to the epilogue.
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
     const void* W;
-    int KT;  // K / 32 (bf16) ; K (fp32 path uses K directly)
+    int KT;  // K / 32
     int K;
     const void* A;
     size_t a_lo;  // element offset of the lo term of A (bf16 only)
@@ -187,10 +198,10 @@ struct GemmArgs {
     int T;
 };
 
-template <int G, int KS, int MT>
+template <int KS, int MT>
 struct GemmSmem {
-    float red[KS][G][MT][256];
-    float out[MT * 16][G * 16];
+    float red[KS][MT][256];
+    float out[MT * 16][16];
     float rs[MT * 16];
 };
 
@@ -214,14 +225,26 @@ __device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
     }
 }
 
-template <int G, int KS, int MT>
-__device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int g = wave / KS, ks = wave % KS;
+template <int KS, int MT, typename Pre>
+__device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
+    const int ks = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int KT = a.KT;
     const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
-    const u32x4* wp = (const u32x4*)a.W + ((size_t)(tile0 + g) * KT + kt0) * 64 + lane;
+    const u32x4* wp = (const u32x4*)a.W + ((size_t)tile * KT + kt0) * 64 + lane;
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Ring of D tiles (1 KB of weights each) per wave: a slot is refilled with the tile D ahead as soon
+    // as its MFMAs are issued.  The first D weight loads go out before anything that depends on another
+    // load (row indirection, RMS partial sums, epilogue operands), so the stream starts at once.
+    constexpr int D = MT == 1 ? 7 : 4;
+    u32x4 w[D], ah[MT][D], al[MT][D];
+    const int n = kt1 - kt0;
+    auto fill_w = [&](int u, int t) { w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64); };
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n) fill_w(u, u);
     // Rows beyond T read row 0 again (always a valid address): their products are never looked at,
     // and an unpredicated load keeps the loop free of branches.
     const __bf16* ap[MT];
@@ -232,21 +255,16 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
         int idx = a.arow ? a.arow[row] : row;
         ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + (size_t)kt0 * 32 + lg * 8;
     }
-    f32x4 acc[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // Rolling pipeline of D tiles (1 KB of weights each) per wave: a slot is refilled with the tile D
-    // ahead as soon as its MFMAs are issued, so the wave always has about D KB of loads in flight.
-    constexpr int D = MT == 1 ? 8 : (MT == 2 ? 6 : 4);
-    u32x4 w[D], ah[MT][D], al[MT][D];
-    const int n = kt1 - kt0;
-    auto fill = [&](int u, int t) {  // slot u <- tile t (relative to kt0)
-        w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64);
+    auto fill_a = [&](int u, int t) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             ah[mt][u] = *(const u32x4*)(ap[mt] + (size_t)t * 32);
             al[mt][u] = *(const u32x4*)(ap[mt] + a.a_lo + (size_t)t * 32);
         }
+    };
+    auto fill = [&](int u, int t) {  // slot u <- tile t (relative to kt0)
+        fill_w(u, t);
+        fill_a(u, t);
     };
     auto use = [&](int u) {
 #pragma unroll
@@ -257,16 +275,18 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
                                                               __builtin_bit_cast(bf16x8, w[u]), acc[mt], 0, 0, 0);
         }
     };
-    const int full = n / D, rem = n - full * D;
 #pragma unroll
     for (int u = 0; u < D; ++u)
-        if (u < n) fill(u, u);
+        if (u < n) fill_a(u, u);
+    rms_scales<MT>(a, sm.rs);
+    pre();
+    const int full = n / D, rem = n - full * D;
     for (int gI = 0; gI + 1 < full; ++gI) {  // steady state: every refill is in range
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             use(u);
             fill(u, (gI + 1) * D + u);
-            __builtin_amdgcn_sched_barrier(0);  // keep the slot order: the wait before use(u+1) then covers one slot only
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     if (full > 0) {  // last full group: refill only the slots the remainder needs
@@ -283,30 +303,109 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile0,
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sm.red[ks][g][mt][(lg * 4 + r) * 16 + li] = acc[mt][r];
+        for (int r = 0; r < 4; ++r) sm.red[ks][mt][(lg * 4 + r) * 16 + li] = acc[mt][r];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < G * MT * 256; idx += blockDim.x) {
-        int e = idx & 255, mt = (idx >> 8) % MT, gg = idx / (256 * MT);
+    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+        int e = idx & 255, mt = idx >> 8;
         float s = 0.f;
 #pragma unroll
-        for (int k = 0; k < KS; ++k) s += sm.red[k][gg][mt][e];
+        for (int k = 0; k < KS; ++k) s += sm.red[k][mt][e];
         int m = mt * 16 + (e >> 4);
-        sm.out[m][gg * 16 + (e & 15)] = s * sm.rs[m];
+        sm.out[m][e & 15] = s * sm.rs[m];
+    }
+    __syncthreads();
+}
+
+// Variant for few rows (T*K small enough for LDS): the workgroup first copies its T activation rows
+// (hi and lo terms) into LDS, and the loop takes its A operands from there.  The vector-memory queue
+// then carries weight loads only (deeper ring, no registers spent on A look-ahead), and the lower
+// register count lets more workgroups share a CU.
+constexpr int A_LDS_MAX_BYTES = 48 * 1024;
+__host__ __device__ inline int a_lds_row_stride(int K) { return 2 * K + 32; }  // elements; +64 B staggers the banks of two rows
+
+template <int KS, typename Pre>
+__device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int tile, GemmSmem<KS, 1>& sm, Pre pre) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char ee_dyn_smem[];
+    __bf16* abuf = (__bf16*)ee_dyn_smem;
+    const int ks = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, lg = lane >> 4;
+    const int KT = a.KT, K = a.K;
+    const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
+    const u32x4* wp = (const u32x4*)a.W + ((size_t)tile * KT + kt0) * 64 + lane;
+    constexpr int D = 12;
+    u32x4 w[D];
+    const int n = kt1 - kt0;
+    auto fill = [&](int u, int t) { w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64); };
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n) fill(u, u);
+    const int rstride = a_lds_row_stride(K);
+    const int cpr = K / 8;  // 16-byte chunks per row and term
+    for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
+        int m = c / cpr, k8 = c - m * cpr;
+        int slot = a.arow ? a.arow[m] : m;
+        const __bf16* src = (const __bf16*)a.A + (size_t)slot * a.lda + k8 * 8;
+        u32x4 h = *(const u32x4*)src;
+        u32x4 l = *(const u32x4*)(src + a.a_lo);
+        *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
+        *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+    }
+    rms_scales<1>(a, sm.rs);
+    pre();
+    __syncthreads();
+    const __bf16* ar = abuf + (size_t)(li < a.T ? li : 0) * rstride + (size_t)kt0 * 32 + lg * 8;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto use = [&](int u, int t) {
+        bf16x8 h = *(const bf16x8*)(ar + (size_t)t * 32);
+        bf16x8 l = *(const bf16x8*)(ar + K + (size_t)t * 32);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(l, __builtin_bit_cast(bf16x8, w[u]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h, __builtin_bit_cast(bf16x8, w[u]), acc, 0, 0, 0);
+    };
+    const int full = n / D, rem = n - full * D;
+    for (int gI = 0; gI + 1 < full; ++gI) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u, gI * D + u);
+            fill(u, (gI + 1) * D + u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (full > 0) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u, (full - 1) * D + u);
+            if (u < rem) fill(u, full * D + u);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < rem) use(u, full * D + u);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sm.red[ks][0][(lg * 4 + r) * 16 + li] = acc[r];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 256; idx += blockDim.x) {
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) s += sm.red[k][0][idx];
+        int m = idx >> 4;
+        sm.out[m][idx & 15] = s * sm.rs[m];
     }
     __syncthreads();
 }
 
 // fp32 path (tiny model, parity only): plain FMA loop, weights row-major [tile][16][K]
-template <int G, int KS, int MT>
-__device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
+template <int KS, int MT, typename Pre>
+__device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
+    rms_scales<MT>(a, sm.rs);
+    pre();
     __syncthreads();
-    for (int idx = threadIdx.x; idx < MT * 16 * G * 16; idx += blockDim.x) {
-        int m = idx / (G * 16), c = idx % (G * 16);
+    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+        int m = idx >> 4, c = idx & 15;
         float s = 0.f;
         if (m < a.T) {
             int slot = a.arow ? a.arow[m] : m;
             const float* ar = (const float*)a.A + (size_t)slot * a.lda;
-            const float* wr = (const float*)a.W + ((size_t)tile0 * 16 + c) * a.K;
+            const float* wr = (const float*)a.W + ((size_t)tile * 16 + c) * a.K;
             for (int k = 0; k < a.K; ++k) s = fmaf(ar[k], wr[k], s);
         }
         sm.out[m][c] = s * sm.rs[m];
@@ -314,20 +413,19 @@ __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile0, 
     __syncthreads();
 }
 
-template <typename ST, int G, int KS, int MT>
-__device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, GemmSmem<G, KS, MT>& sm) {
-#ifdef EE_EXP_NOSSQ
-    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) sm.rs[m] = 1.f;
-#else
-    rms_scales<MT>(a, sm.rs);
-#endif
-    if constexpr (sizeof(ST) == 2)
-        gemm_mainloop_bf16<G, KS, MT>(a, tile0, sm);  // (its first __syncthreads orders rs before use)
+// `pre` runs once the first weight loads are in flight: the place to fetch what the epilogue needs.
+template <typename ST, int KS, int MT, bool ALDS, typename Pre>
+__device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
+    if constexpr (sizeof(ST) == 2 && ALDS)
+        gemm_mainloop_bf16_lds<KS>(a, tile, sm, pre);
+    else if constexpr (sizeof(ST) == 2)
+        gemm_mainloop_bf16<KS, MT>(a, tile, sm, pre);  // (its first __syncthreads orders rs before use)
     else
-        gemm_mainloop_f32<G, KS, MT>(a, tile0, sm);
+        gemm_mainloop_f32<KS, MT>(a, tile, sm, pre);
 }
 
-// ---- epilogue 1: rotary embedding, q to the workspace, k and v into the paged cache
+// ---- epilogue 1: rotary embedding, q to the workspace, k and v into the paged cache.
+// Tile (part, head h, c): columns 0..7 = features h*hd + c*8 + i, columns 8..15 = their rotary partners.
 template <typename ST>
 struct QkvArgs {
     ST* q;
@@ -340,37 +438,49 @@ struct QkvArgs {
     const SegDesc* desc;
 };
 
-template <typename ST, int KS, int MT>
-__global__ __launch_bounds__(2 * KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
-    __shared__ GemmSmem<2, KS, MT> sm;
-    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
-#ifdef EE_EXP_NOEPI
-    if (sm.out[0][0] != 12345.f) return;
-#endif
-    const int per_part = e.H * (e.hd / 32);
+template <typename ST, int KS, int MT, bool ALDS>
+__global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
+    __shared__ GemmSmem<KS, MT> sm;
+    const int per_head = e.hd / 16, per_part = e.H * per_head;
     const int part = blockIdx.x / per_part;  // 0 q, 1 k, 2 v
     const int rem = blockIdx.x % per_part;
-    const int h = rem / (e.hd / 32), c = rem % (e.hd / 32);
+    const int h = rem / per_head, c = rem % per_head;
     const int half = e.hd / 2;
-    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
-        int m = idx >> 4, i = idx & 15;
+    // epilogue operands of this thread's first (row, column pair), fetched while the weights stream
+    const int m0 = threadIdx.x >> 3, i0 = threadIdx.x & 7;
+    int pos0 = 0, blk0 = 0;
+    float2 cs0 = make_float2(1.f, 0.f);
+    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
+        if (m0 < a.T) {
+            pos0 = e.desc->pos[m0];
+            blk0 = e.desc->kvblk[m0];
+            if (part < 2) cs0 = e.rope_cs[(size_t)pos0 * half + c * 8 + i0];
+        }
+    });
+    for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
+        int m = idx >> 3, i = idx & 7;
         if (m >= a.T) continue;
-        float lo = sm.out[m][i], hi = sm.out[m][16 + i];
-        int pos = e.desc->pos[m];
+        float lo = sm.out[m][i], hi = sm.out[m][8 + i];
+        int pos = pos0, blk = blk0;
+        float2 cs = cs0;
+        if (idx != (int)threadIdx.x) {
+            pos = e.desc->pos[m];
+            blk = e.desc->kvblk[m];
+            if (part < 2) cs = e.rope_cs[(size_t)pos * half + c * 8 + i];
+        }
         if (part < 2) {
-            float2 cs = e.rope_cs[(size_t)pos * half + c * 16 + i];
             float nlo = lo * cs.x - hi * cs.y;
             float nhi = hi * cs.x + lo * cs.y;
             lo = nlo;
             hi = nhi;
         }
         if (part == 0) {
-            ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 16 + i;
+            ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 8 + i;
             store_split<ST>(qp, e.q_lo, lo);
             store_split<ST>(qp + half, e.q_lo, hi);
         } else {
-            ST* kp = e.kv_layer + (size_t)e.desc->kvblk[m] * e.blk_stride + (part == 2 ? (size_t)e.H * e.BT * e.hd : 0) +
-                     ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 16 + i;
+            ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + (part == 2 ? (size_t)e.H * e.BT * e.hd : 0) +
+                     ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
             kp[0] = cvt_st<ST>(lo);
             kp[half] = cvt_st<ST>(hi);
         }
@@ -392,23 +502,38 @@ struct ResidArgs {
     const SegDesc* desc;
 };
 
-template <typename ST, int KS, int MT>
+template <typename ST, int KS, int MT, bool ALDS>
 __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
-    __shared__ GemmSmem<1, KS, MT> sm;
-    gemm_mainloop<ST, 1, KS, MT>(a, blockIdx.x, sm);
+    __shared__ GemmSmem<KS, MT> sm;
     const int n0 = blockIdx.x * 16;
-#ifdef EE_EXP_NOEPI
-    if (sm.out[0][0] != 12345.f) return;
-#endif
+    // epilogue operands of this thread's first element, fetched while the weights stream
+    const int m0 = threadIdx.x >> 4, i0 = threadIdx.x & 15;
+    size_t o0 = 0;
+    float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
+    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
+        if (m0 < a.T) {
+            o0 = (size_t)e.desc->xrow[m0] * e.d + n0 + i0;
+            x0 = e.x[o0];
+            gn0 = e.g_next[n0 + i0];
+            if (e.xgh) gh0 = e.g_head[n0 + i0];
+        }
+    });
     for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
         int m = idx >> 4, i = idx & 15;
         if (m >= a.T) continue;
-        size_t o = (size_t)e.desc->xrow[m] * e.d + n0 + i;
-        float v = e.x[o] + sm.out[m][i];
+        size_t o = o0;
+        float xv = x0, gn = gn0, gh = gh0;
+        if (idx != (int)threadIdx.x) {
+            o = (size_t)e.desc->xrow[m] * e.d + n0 + i;
+            xv = e.x[o];
+            gn = e.g_next[n0 + i];
+            if (e.xgh) gh = e.g_head[n0 + i];
+        }
+        float v = xv + sm.out[m][i];
         e.x[o] = v;
         sm.out[m][i] = v;
-        store_split<ST>(e.xg + o, e.xs_lo, v * e.g_next[n0 + i]);
-        if (e.xgh) store_split<ST>(e.xgh + o, e.xs_lo, v * e.g_head[n0 + i]);
+        store_split<ST>(e.xg + o, e.xs_lo, v * gn);
+        if (e.xgh) store_split<ST>(e.xgh + o, e.xs_lo, v * gh);
     }
     __syncthreads();
     for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
@@ -420,21 +545,21 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
     }
 }
 
-// ---- epilogue 3: SwiGLU.  tile 2j holds gate features 16j.., tile 2j+1 the matching up features
-template <typename ST, int KS, int MT>
-__global__ __launch_bounds__(2 * KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F) {
-    __shared__ GemmSmem<2, KS, MT> sm;
-    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
-    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
-        int m = idx >> 4, i = idx & 15;
+// ---- epilogue 3: SwiGLU.  Tile j: columns 0..7 = gate features 8j.., columns 8..15 = the matching up features
+template <typename ST, int KS, int MT, bool ALDS>
+__global__ __launch_bounds__(KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F) {
+    __shared__ GemmSmem<KS, MT> sm;
+    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, []() {});
+    for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
+        int m = idx >> 3, i = idx & 7;
         if (m >= a.T) continue;
-        float gt = sm.out[m][i], up = sm.out[m][16 + i];
+        float gt = sm.out[m][i], up = sm.out[m][8 + i];
         float sl = gt / (1.0f + expf(-gt));
-        store_split<ST>(act + (size_t)m * F + blockIdx.x * 16 + i, act_lo, sl * up);
+        store_split<ST>(act + (size_t)m * F + blockIdx.x * 8 + i, act_lo, sl * up);
     }
 }
 
-// ---- epilogue 4: exit / final head.  Per workgroup: (max, arg max, sum exp) of its 32 logits per row.
+// ---- epilogue 4: exit / final head.  Per workgroup: (max, arg max, sum exp) of its 16 logits per row.
 // A one-workgroup kernel launched right after merges the partials in a fixed order and takes the exit
 // decision (an in-kernel "last workgroup merges" scheme needs a device-wide fence in every workgroup,
 // which costs more than the extra launch).
@@ -454,14 +579,14 @@ __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float 
     }
 }
 
-template <typename ST, int KS, int MT>
-__global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
-    __shared__ GemmSmem<2, KS, MT> sm;
-    gemm_mainloop<ST, 2, KS, MT>(a, blockIdx.x * 2, sm);
-    const int n0 = blockIdx.x * 32;
+template <typename ST, int KS, int MT, bool ALDS>
+__global__ __launch_bounds__(KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
+    __shared__ GemmSmem<KS, MT> sm;
+    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, []() {});
+    const int n0 = blockIdx.x * 16;
     if (e.logits) {
-        for (int idx = threadIdx.x; idx < MT * 16 * 32; idx += blockDim.x) {
-            int m = idx >> 5, c = idx & 31;
+        for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+            int m = idx >> 4, c = idx & 15;
             if (m < a.T) e.logits[(size_t)m * e.V + n0 + c] = sm.out[m][c];
         }
     }
@@ -469,13 +594,15 @@ __global__ __launch_bounds__(2 * KS * 64) void gemm_head_kernel(GemmArgs a, Head
         if (m >= a.T) continue;
         float mx = sm.out[m][0];
         int ix = 0;
-        for (int c = 1; c < 32; ++c)
+#pragma unroll
+        for (int c = 1; c < 16; ++c)
             if (sm.out[m][c] > mx) {
                 mx = sm.out[m][c];
                 ix = c;
             }
         float s = 0.f;
-        for (int c = 0; c < 32; ++c) s += expf(sm.out[m][c] - mx);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) s += expf(sm.out[m][c] - mx);
         HeadPartial p;
         p.max = mx;
         p.sum = s;
@@ -549,15 +676,48 @@ static GemmArgs make_args(const GemmCommon& c) {
 }
 
 static int mt_of(int T) { return T <= 16 ? 1 : (T <= 32 ? 2 : 4); }
+// waves per workgroup: each should stream about 16 k-tiles (16 KB)
+static int ks_of(const GemmCommon& c) {
+    if (c.dtype != EE_BF16) return 4;
+    int kt = c.K / 32;
+    if (kt <= 64) return 4;
+    if (kt <= 128 || c.T > 16) return 8;  // (16 waves of 1024 threads leave 128 registers each: one row tile only)
+    return 16;
+}
 
-#define EE_DISPATCH_MT(T, CALL)              \
-    switch (mt_of(T)) {                      \
-        case 1: { constexpr int MT = 1; CALL; } break; \
-        case 2: { constexpr int MT = 2; CALL; } break; \
-        default: { constexpr int MT = 4; CALL; } break; \
-    }
+// LDS bytes for the few-rows variant, or 0 when the rows do not fit
+static size_t a_lds_bytes(const GemmCommon& c) {
+    if (c.dtype != EE_BF16 || c.T > 16) return 0;
+    size_t b = (size_t)c.T * a_lds_row_stride(c.K) * 2;
+    return b <= (size_t)A_LDS_MAX_BYTES ? b : 0;
+}
 
-constexpr int KS_QKV = 4, KS_RES = 8, KS_SWI = 4, KS_HEAD = 4;
+#define EE_DISPATCH(ST, KERNEL, ...)                                                                               \
+    do {                                                                                                           \
+        const int _ks = ks_of(c), _mt = mt_of(c.T);                                                                \
+        const size_t _sm = a_lds_bytes(c);                                                                         \
+        dim3 block(_ks * 64);                                                                                      \
+        if (_sm) {                                                                                                 \
+            if (_ks == 4) EE_LAUNCH_SM((KERNEL<ST, 4, 1, true>), grid, block, _sm, s, __VA_ARGS__);                \
+            else if (_ks == 8) EE_LAUNCH_SM((KERNEL<ST, 8, 1, true>), grid, block, _sm, s, __VA_ARGS__);           \
+            else EE_LAUNCH_SM((KERNEL<ST, 16, 1, true>), grid, block, _sm, s, __VA_ARGS__);                        \
+        } else if (_ks == 4 && _mt == 1) EE_LAUNCH((KERNEL<ST, 4, 1, false>), grid, block, s, __VA_ARGS__);        \
+        else if (_ks == 4 && _mt == 2) EE_LAUNCH((KERNEL<ST, 4, 2, false>), grid, block, s, __VA_ARGS__);          \
+        else if (_ks == 4) EE_LAUNCH((KERNEL<ST, 4, 4, false>), grid, block, s, __VA_ARGS__);                      \
+        else if (_ks == 8 && _mt == 1) EE_LAUNCH((KERNEL<ST, 8, 1, false>), grid, block, s, __VA_ARGS__);          \
+        else if (_ks == 8 && _mt == 2) EE_LAUNCH((KERNEL<ST, 8, 2, false>), grid, block, s, __VA_ARGS__);          \
+        else if (_ks == 8) EE_LAUNCH((KERNEL<ST, 8, 4, false>), grid, block, s, __VA_ARGS__);                      \
+        else EE_LAUNCH((KERNEL<ST, 16, 1, false>), grid, block, s, __VA_ARGS__);                                   \
+    } while (0)
+
+#define EE_DISPATCH_F32(KERNEL, ...)                                                             \
+    do {                                                                                         \
+        const int _mt = mt_of(c.T);                                                              \
+        dim3 block(256);                                                                         \
+        if (_mt == 1) EE_LAUNCH((KERNEL<float, 4, 1, false>), grid, block, s, __VA_ARGS__);      \
+        else if (_mt == 2) EE_LAUNCH((KERNEL<float, 4, 2, false>), grid, block, s, __VA_ARGS__); \
+        else EE_LAUNCH((KERNEL<float, 4, 4, false>), grid, block, s, __VA_ARGS__);               \
+    } while (0)
 
 int gemm_resid_tiles_per_wg() { return 1; }
 
@@ -566,15 +726,15 @@ hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const floa
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
-    dim3 grid(c.N / 32), block(2 * KS_QKV * 64);
+    dim3 grid(c.N / 16);
     if (c.dtype == EE_BF16) {
         QkvArgs<__bf16> e{(__bf16*)q, q_lo, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
                           kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_qkv_kernel<__bf16, KS_QKV, MT>), grid, block, s, a, e));
+        EE_DISPATCH(__bf16, gemm_qkv_kernel, a, e);
     } else {
         QkvArgs<float> e{(float*)q, q_lo, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
                          kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_qkv_kernel<float, KS_QKV, MT>), grid, block, s, a, e));
+        EE_DISPATCH_F32(gemm_qkv_kernel, a, e);
     }
     return hipGetLastError();
 }
@@ -584,13 +744,13 @@ hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh,
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
-    dim3 grid(c.N / 16), block(KS_RES * 64);
+    dim3 grid(c.N / 16);
     if (c.dtype == EE_BF16) {
         ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_resid_kernel<__bf16, KS_RES, MT>), grid, block, s, a, e));
+        EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
     } else {
         ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_resid_kernel<float, KS_RES, MT>), grid, block, s, a, e));
+        EE_DISPATCH_F32(gemm_resid_kernel, a, e);
     }
     return hipGetLastError();
 }
@@ -599,31 +759,31 @@ hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
-    dim3 grid(c.N / 32), block(2 * KS_SWI * 64);
+    dim3 grid(c.N / 16);
     if (c.dtype == EE_BF16) {
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_swiglu_kernel<__bf16, KS_SWI, MT>), grid, block, s, a, (__bf16*)act, act_lo, F));
+        EE_DISPATCH(__bf16, gemm_swiglu_kernel, a, (__bf16*)act, act_lo, F);
     } else {
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_swiglu_kernel<float, KS_SWI, MT>), grid, block, s, a, (float*)act, act_lo, F));
+        EE_DISPATCH_F32(gemm_swiglu_kernel, a, (float*)act, act_lo, F);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
                             float threshold, HeadResult* results, hipStream_t s) {
+    (void)counter;
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
-    (void)counter;
     HeadArgs e{partials, logits, c.N};
-    dim3 grid(c.N / 32), block(2 * KS_HEAD * 64);
+    dim3 grid(c.N / 16);
     if (c.dtype == EE_BF16) {
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_head_kernel<__bf16, KS_HEAD, MT>), grid, block, s, a, e));
+        EE_DISPATCH(__bf16, gemm_head_kernel, a, e);
     } else {
-        EE_DISPATCH_MT(c.T, EE_LAUNCH((gemm_head_kernel<float, KS_HEAD, MT>), grid, block, s, a, e));
+        EE_DISPATCH_F32(gemm_head_kernel, a, e);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, partials, (int)grid.x, c.T, mode, threshold, results, c.desc);
+    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, (int)grid.x, c.T, mode, threshold, results, c.desc);
     return hipGetLastError();
 }
 
