@@ -386,6 +386,8 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
         for (int r = first; r < T; r += 16) {
             d->qt_row0[nqt] = r;
             d->qt_nq[nqt] = std::min(16, T - r);
+            d->qt_pos0[nqt] = d->pos[r];
+            d->qt_seq[nqt] = (int)b;
             ++nqt;
         }
         bool is_final = seg == m->n_seg() - 1;
@@ -867,6 +869,8 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
         for (int r = 0; r < n; r += 16) {
             d->qt_row0[d->n_qt] = r;
             d->qt_nq[d->n_qt] = std::min(16, n - r);
+            d->qt_pos0[d->n_qt] = p0 + r;
+            d->qt_seq[d->n_qt] = 0;
             ++d->n_qt;
         }
         if (last) d->xrow[n - 1] = c->slot_of(seq, n_tokens - 1);  // so that the newest hidden state can be read back

@@ -19,7 +19,9 @@ struct SegDesc {
     int32_t kvblk[EE_MAX_ROWS];  // physical KV block that holds pos[r]
     int32_t rseq[EE_MAX_ROWS];   // index of the row's sequence in this step's block-table array
     int32_t qt_row0[EE_MAX_ROWS];  // query tile: first row, number of rows (<= 16, one sequence,
-    int32_t qt_nq[EE_MAX_ROWS];    //   consecutive positions)
+    int32_t qt_nq[EE_MAX_ROWS];    //   consecutive positions),
+    int32_t qt_pos0[EE_MAX_ROWS];  //   position of its first row,
+    int32_t qt_seq[EE_MAX_ROWS];   //   index of its sequence in this step's block-table array
     int32_t head_xrow[EE_MAX_SEQS];  // residual-store slot of each head row
     int32_t head_slot[EE_MAX_SEQS];  // result slot of each head row
 };
@@ -39,7 +41,7 @@ struct HeadPartial {
 
 // Geometry of the paged cache as the kernels see it.
 struct KvGeom {
-    void* pool;           // [L][n_blocks][2][H][BT][hd]
+    void* pool;           // [L][n_blocks]{ K: [H][BT][hd], V transposed: [H][hd][BT] }
     size_t layer_stride;  // elements
     size_t blk_stride;    // elements: 2*H*BT*hd
     int32_t H, hd, BT, max_blocks_per_seq;

@@ -478,11 +478,15 @@ __global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<S
             ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 8 + i;
             store_split<ST>(qp, e.q_lo, lo);
             store_split<ST>(qp + half, e.q_lo, hi);
-        } else {
-            ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + (part == 2 ? (size_t)e.H * e.BT * e.hd : 0) +
-                     ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
+        } else if (part == 1) {  // K block: [head][position][feature]
+            ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
             kp[0] = cvt_st<ST>(lo);
             kp[half] = cvt_st<ST>(hi);
+        } else {  // V block, transposed: [head][feature][position], so that attention reads P.V operands directly
+            ST* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd +
+                     ((size_t)h * e.hd + c * 8 + i) * e.BT + (pos % e.BT);
+            vp[0] = cvt_st<ST>(lo);
+            vp[(size_t)half * e.BT] = cvt_st<ST>(hi);
         }
     }
 }
@@ -792,12 +796,18 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
 // cache positions 0..p of its sequence (which includes the rows before it in this launch: their K,V
 // were written by the QKV kernel).  Online soft-max over chunks of 1024 positions.
 // ------------------------------------------------------------------------------------------------
+// K of (head, position): pointer to its hd contiguous features.  V of (head, position, feature): one
+// element of the transposed V block [head][feature][position].
 template <typename ST>
-__device__ __forceinline__ const ST* kv_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int which, int h,
-                                             int pos) {
+__device__ __forceinline__ const ST* k_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int h, int pos) {
     int blk = bt[pos / kv.BT];
-    return layer_base + (size_t)blk * kv.blk_stride + (which ? (size_t)kv.H * kv.BT * kv.hd : 0) +
-           ((size_t)h * kv.BT + (pos % kv.BT)) * kv.hd;
+    return layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + (pos % kv.BT)) * kv.hd;
+}
+template <typename ST>
+__device__ __forceinline__ const ST* v_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int h, int pos, int c) {
+    int blk = bt[pos / kv.BT];
+    return layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * kv.hd + ((size_t)h * kv.hd + c) * kv.BT +
+           (pos % kv.BT);
 }
 
 __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
@@ -835,7 +845,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
         int nj = min(1024, n_ctx - j0);
         float cmax = -INFINITY;
         for (int jj = threadIdx.x; jj < nj; jj += 256) {
-            const ST* kp = kv_ptr(layer_base, kv, bt, 0, h, j0 + jj);
+            const ST* kp = k_ptr(layer_base, kv, bt, h, j0 + jj);
             float s = 0.f;
             for (int c = 0; c < hd; ++c) s = fmaf(qs[c], (float)kp[c], s);
             s *= scale;
@@ -855,7 +865,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
         l = l * corr + psum;
         if ((int)threadIdx.x < hd) {
             float a2 = 0.f;
-            for (int jj = 0; jj < nj; ++jj) a2 = fmaf(sc[jj], (float)kv_ptr(layer_base, kv, bt, 1, h, j0 + jj)[threadIdx.x], a2);
+            for (int jj = 0; jj < nj; ++jj) a2 = fmaf(sc[jj], (float)*v_ptr(layer_base, kv, bt, h, j0 + jj, (int)threadIdx.x), a2);
             acc = acc * corr + a2;
         }
         m = m_new;
@@ -879,37 +889,59 @@ constexpr int ATT_MAX_SPLITS = 16;
 
 __host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
 
-template <int HD>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
-                                                        size_t out_lo, const SegDesc* __restrict__ desc,
-                                                        const int32_t* __restrict__ btab, KvGeom kv,
-                                                        const __bf16* __restrict__ layer_base, int d, int NS,
-                                                        float* __restrict__ part) {
-    constexpr int KK = HD / 32, CG = HD / 16, VST = HD + 4;  // LDS row stride (elements): HD/2 + 2 dwords, conflict-free
-    constexpr int STAGE_BYTES = 4 * 32 * VST * 2;
-    constexpr int COMB_BYTES = (4 * 16 * (HD + 1) + 128) * 4;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > COMB_BYTES ? STAGE_BYTES : COMB_BYTES];
+template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
+                                                             size_t out_lo, const SegDesc* __restrict__ desc,
+                                                             const int32_t* __restrict__ btab, KvGeom kv,
+                                                             const __bf16* __restrict__ layer_base, int d, int NS,
+                                                             float* __restrict__ part) {
+    constexpr int KK = HD / 32, CG = HD / 16;
+    __shared__ float wO[NW * 16 * (HD + 1)];
+    __shared__ float wm[NW * 16], wl[NW * 16];
     const int qt = blockIdx.x / kv.H, h = blockIdx.x % kv.H, split = blockIdx.y;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: block-table reads become scalar loads
+    const int lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
     const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
-    const int pos0 = desc->pos[row0];
+    const int pos0 = desc->qt_pos0[qt];
     const int ctx = pos0 + nq;
-    const int32_t* bt = btab + (size_t)desc->rseq[row0] * kv.max_blocks_per_seq;
+    const int32_t* bt = btab + (size_t)desc->qt_seq[qt] * kv.max_blocks_per_seq;
     const int n_tiles = (ctx + 31) >> 5;
     const int tps = (n_tiles + NS - 1) / NS;
     const int t_lo = split * tps, t_hi = min(n_tiles, t_lo + tps);
     const bool qvalid = li < nq;
+    // MFMA row i of score half s stands for position (i/4)*8 + s*4 + i%4 of the tile, so that after the two
+    // halves a lane (query li, group lg) holds the probabilities of the 8 consecutive positions lg*8..lg*8+7:
+    // exactly the 16 bytes of a transposed-V row that the P.V product needs as its other operand.
+    const int krow0 = (li >> 2) * 8 + (li & 3);
+
+    // K and V of one 32-position tile, loaded straight into MFMA operand order
+    struct TileRegs {
+        u32x4 k[2 * KK];
+        u32x4 v[CG];
+    };
+    auto issue = [&](int t, TileRegs& r) {
+        const int tb = t << 5;
+        const int blk = bt[tb / kv.BT];
+        const int tin = tb % kv.BT;
+        const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + tin) * HD;
+        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * (HD / 4);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 8);
+        }
+#pragma unroll
+        for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (size_t)(c * 16 + li) * kv.BT + lg * 8);
+    };
 
     bf16x8 qh[KK], ql[KK];
     {
         const __bf16* qp = q + (size_t)(row0 + (qvalid ? li : 0)) * d + h * HD + lg * (HD / 4);
-        const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            u32x4 a = qvalid ? *(const u32x4*)(qp + kk * 8) : zero;
-            u32x4 b = qvalid ? *(const u32x4*)(qp + q_lo + kk * 8) : zero;
-            qh[kk] = __builtin_bit_cast(bf16x8, a);
-            ql[kk] = __builtin_bit_cast(bf16x8, b);
+            qh[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + kk * 8));
+            ql[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + q_lo + kk * 8));
         }
     }
     const float scale = 1.0f / sqrtf((float)HD);
@@ -917,42 +949,32 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict
     f32x4 o[CG];
 #pragma unroll
     for (int c = 0; c < CG; ++c) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    __bf16* vs = (__bf16*)smem + (size_t)wave * 32 * VST;
 
-    for (int t = t_lo + wave; t < t_hi; t += 4) {
+    TileRegs cur, nxt;
+    int t = t_lo + wave;
+    if (t < t_hi) issue(t, cur);
+    while (t < t_hi) {
+        const int tn = t + NW;
+        if (tn < t_hi) issue(tn, nxt);  // the next tile streams in while this one is worked on
         const int tb = t << 5;
-        const int blk = bt[tb / kv.BT];
-        const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + (tb % kv.BT)) * HD;
-        const __bf16* vbase = kbase + (size_t)kv.H * kv.BT * HD;
         // scores, transposed: rows = positions, columns = queries
         f32x4 sacc[2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             sacc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const __bf16* kp = kbase + (size_t)(sub * 16 + li) * HD + lg * (HD / 4);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                bf16x8 kf = __builtin_bit_cast(bf16x8, *(const u32x4*)(kp + kk * 8));
+                bf16x8 kf = __builtin_bit_cast(bf16x8, cur.k[sub * KK + kk]);
                 sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, ql[kk], sacc[sub], 0, 0, 0);
                 sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qh[kk], sacc[sub], 0, 0, 0);
             }
         }
-        // V tile -> LDS (rows beyond the context are zeroed: their probabilities are zero, their bits unknown)
-#pragma unroll
-        for (int ci = lane; ci < 32 * HD / 8; ci += 64) {
-            int p = ci / (HD / 8), c8 = ci % (HD / 8);
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (tb + p < ctx) v = *(const u32x4*)(vbase + (size_t)p * HD + c8 * 8);
-            uint2* dst = (uint2*)(vs + p * VST + c8 * 8);
-            dst[0] = make_uint2(v.x, v.y);
-            dst[1] = make_uint2(v.z, v.w);
-        }
-        // causal mask + online soft-max per query (column li); this lane holds positions lg*4+r of each half
+        // causal mask + online soft-max per query (column li); element e of this lane = position tb + lg*8 + e
         float pv[8];
         float tmax = -INFINITY;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            int pa = tb + (e >> 2) * 16 + lg * 4 + (e & 3);
+            int pa = tb + lg * 8 + e;
             float val = (qvalid && pa <= pos0 + li) ? sacc[e >> 2][e & 3] * scale : -INFINITY;
             pv[e] = val;
             tmax = fmaxf(tmax, val);
@@ -983,30 +1005,25 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict
             ph[e] = hi;
             pl[e] = (__bf16)(pv[e] - (float)hi);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // positions beyond the context hold unknown bits (their probabilities are zero): zero them
+        const bool ragged = tb + 32 > ctx;
 #pragma unroll
         for (int c = 0; c < CG; ++c) {
-            bf16x8 vf;
+            bf16x8 vf = __builtin_bit_cast(bf16x8, cur.v[c]);
+            if (ragged) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                int pe = (e >> 2) * 16 + lg * 4 + (e & 3);
-                vf[e] = vs[pe * VST + c * 16 + li];
+                for (int e = 0; e < 8; ++e)
+                    if (tb + lg * 8 + e >= ctx) vf[e] = (__bf16)0.f;
             }
             o[c] = o[c] * corr;
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        cur = nxt;
+        t = tn;
     }
 
-    // combine the 4 waves (fixed order)
-    __syncthreads();
-    float* wO = (float*)smem;  // [4][16][HD+1]
-    float* wm = wO + 4 * 16 * (HD + 1);
-    float* wl = wm + 64;
+    // combine the waves (fixed order)
 #pragma unroll
     for (int c = 0; c < CG; ++c)
 #pragma unroll
@@ -1017,14 +1034,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict
     }
     __syncthreads();
     float* pbase = part + ((size_t)(qt * kv.H + h) * NS + split) * att_part_stride(HD);
-    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+    for (int idx = threadIdx.x; idx < 16 * HD; idx += NW * 64) {
         int qq = idx / HD, cc = idx % HD;
         if (qq >= nq) continue;
-        float M = fmaxf(fmaxf(wm[qq], wm[16 + qq]), fmaxf(wm[32 + qq], wm[48 + qq]));
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, wm[w * 16 + qq]);
         float O = 0.f, L = 0.f;
         if (M > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < NW; ++w) {
                 float f = expf(wm[w * 16 + qq] - M);
                 O += f * wO[(w * 16 + qq) * (HD + 1) + cc];
                 L += f * wl[w * 16 + qq];
@@ -1074,15 +1093,18 @@ size_t attention_part_floats(int max_rows, int H, int hd) {
 template <int HD>
 static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, int n_qt, const int32_t* btab,
                                         const KvGeom& kv, int layer, int d, float* part, int max_ctx, hipStream_t s) {
-    int wgs = n_qt * kv.H;
+    const int wgs = n_qt * kv.H;
+    const int tiles = (max_ctx + 31) / 32;
+    const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
+    // KV splits: enough workgroups to cover the chip, at least ~4 tiles (one per wave) per split.  A
+    // wave works through its tiles one after another, so short splits keep the dependent chain short.
     int NS = 1024 / wgs;
-    int by_len = ((max_ctx + 31) / 32 + 3) / 4;  // at least ~4 tiles (one per wave) per split
+    int by_len = (tiles + 3) / 4;
     if (NS > by_len) NS = by_len;
     if (NS > ATT_MAX_SPLITS) NS = ATT_MAX_SPLITS;
     if (NS < 1) NS = 1;
-    const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
-    EE_LAUNCH(attn_mfma_kernel<HD>, dim3(wgs, NS), dim3(256), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, desc,
-                       btab, kv, lb, d, NS, part);
+    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs, NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, desc, btab, kv,
+              lb, d, NS, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
     EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, desc, kv.H, d);
@@ -1119,8 +1141,8 @@ __global__ void kv_gather_kernel(KvGeom kv, const ST* __restrict__ layer_base, c
     if (idx >= (long)n * d) return;
     int t = idx / d, c = idx % d;
     int h = c / kv.hd, i = c % kv.hd;
-    k_out[idx] = (float)kv_ptr(layer_base, kv, bt, 0, h, pos0 + t)[i];
-    v_out[idx] = (float)kv_ptr(layer_base, kv, bt, 1, h, pos0 + t)[i];
+    k_out[idx] = (float)k_ptr(layer_base, kv, bt, h, pos0 + t)[i];
+    v_out[idx] = (float)*v_ptr(layer_base, kv, bt, h, pos0 + t, i);
 }
 
 hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_t* btab_seq, int pos0, int n,
