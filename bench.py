@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel family (extra passes, stderr)")
     ap.add_argument("--cpu-threads", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
+    ap.add_argument("--pmc-run", action="store_true",
+                    help="short run for `rocprofv3 --pmc`: one 1-GiB device copy (counter calibration), then 12 decode steps")
     return ap.parse_args()
 
 
@@ -103,7 +105,7 @@ def cpu_baseline(shape, tensors_host, prompt, tau, max_pending, threads):
         om.set_tensor(kind, idx, arr)
     O.set_threads(threads)
     big = shape.d_model >= 2048
-    n_prompt, n_new = (8, 10) if big else (len(prompt), 32)
+    n_prompt, n_new = (8, 80) if big else (len(prompt), 32)
     st = O.State(om, n_prompt + n_new + 1, max_pending)
     dg = st.prefill(prompt[:n_prompt])
     tok = dg[-1]["argmax"]
@@ -155,6 +157,16 @@ def main():
     print(f"[bench] model {args.workload} ready in {time.perf_counter() - t_setup:.1f}s "
           f"({gm.weight_bytes / 1e9:.2f} GB weights)", file=sys.stderr, flush=True)
 
+    if args.pmc_run:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        b = torch.empty_like(a)
+        torch.add(a, 1.0, out=b)  # plain elementwise kernel: reads 1 GiB, writes 1 GiB; what FETCH_SIZE / WRITE_SIZE
+        torch.add(a, 1.0, out=b)  # report for it calibrates their unit (the float add kernel appears nowhere else)
+        torch.cuda.synchronize()
+        generate(ee, gm, cache, prompt, 1.0, 2, 10, shape, es, args.max_pending)
+        print("[bench] pmc run done", file=sys.stderr)
+        return
+    generate(ee, gm, cache, prompt, 1.0, 0, 40, shape, es, args.max_pending)  # untimed: clocks and caches warm
     full = generate(ee, gm, cache, prompt, 1.0, args.warmup, args.steps, shape, es, args.max_pending)
     early = generate(ee, gm, cache, prompt, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
                      profile_kernel=ee.EE_K_SWIGLU)
