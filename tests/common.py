@@ -136,3 +136,21 @@ def lockstep(gm: ee.Model, cache: ee.KvCache, om: O.Model, prompt, n_new: int, t
     rep.state = st
     rep.seqs = seqs
     return rep
+
+
+def build_pair(shape: ModelShape, seed: int = 0, gain_jitter: float = 0.0, max_positions: int = 256,
+               max_rows: int = 64, max_seqs: int = 1):
+    """(oracle model, GPU model) over the same seeded tensors: each tensor is generated once on the device
+    (the generator is bit-identical on CPU and GPU), handed to the library, and copied to the host for the
+    oracle."""
+    from oracle.from_workload import config_of, to_numpy
+
+    om = O.Model(config_of(shape))
+    gm = ee.Model(ee_config_of(shape, max_positions), max_rows, max_seqs)
+    for kind, idx in model_tensor_list(shape):
+        t = model_tensor(shape, kind, idx, seed, "cuda:0", gain_jitter).contiguous()
+        gm.set_tensor(int(kind), idx, t)
+        om.set_tensor(int(kind), idx, to_numpy(t))
+        torch.cuda.synchronize()
+        del t
+    return om, gm

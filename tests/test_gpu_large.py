@@ -1,0 +1,118 @@
+"""GPU parity at the real shapes of the benchmark workloads (C2 1.3B-shaped, C3 7B-shaped), through the C ABI,
+in the launch configuration bench.py times (batch 1, 64-token cache blocks, max_pending 15).
+
+Where the oracle can follow in seconds (reduced prompt / few layers) the check is the lockstep comparison;
+at the full 32-layer depth and 1024-token context it is the paper's invariants, which hold at any size:
+threshold 1 never exits, threshold 0 always exits at the first exit (up to the forced full passes), and after
+generation + flush the KV cache equals a full-depth prefill of the generated sequence (Section 4)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_04916_amd as ee
+from oracle import oracle as O
+from workload import CONFIGS, prompt_tokens
+
+from common import build_pair, load_gpu_model, lockstep, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2  # bf16 path: hidden states, logits, cached K/V (relative to the largest reference magnitude)
+
+
+def _lockstep_case(shape, n_prompt, n_new, taus, prompt_seed=1):
+    O.set_threads(16)
+    om, gm = build_pair(shape, 0, max_positions=n_prompt + n_new + 8)
+    prompt = prompt_tokens(shape.vocab, n_prompt, prompt_seed).numpy()
+    logits = gm.enable_logits(1)
+    try:
+        for tau in taus:
+            print(f"case: lockstep d={shape.d_model} L={shape.n_layers} prompt {n_prompt} tau {tau}", flush=True)
+            cache = ee.KvCache(gm, 1, n_prompt + n_new + 8, 64, 15)
+            rep = lockstep(gm, cache, om, prompt, n_new, tau, max_pending=15, logits=logits)
+            print(f"  exits {sorted(set(rep.exit_layers))} teacher-forced {rep.teacher_forced} hidden {rep.max_hidden_err:.2e} "
+                  f"logits {rep.max_logit_err:.2e} conf {rep.max_conf_err:.2e}", flush=True)
+            assert not rep.mismatches, rep.mismatches[:5]
+            assert rep.max_hidden_err <= TOL and rep.max_logit_err <= TOL and rep.max_conf_err <= TOL
+            assert rep.teacher_forced <= max(2, n_new // 8)
+            n_pos = n_prompt + n_new - 1
+            cache.flush([0])
+            rep.state.flush()
+            for l in (0, shape.exit_layers[0], shape.n_layers - 1):
+                k, v = cache.read(0, l, 0, n_pos)
+                ko, vo = rep.state.kv_read(l, 0, n_pos)
+                assert rel_err(k, ko) <= TOL and rel_err(v, vo) <= TOL, (l, rel_err(k, ko), rel_err(v, vo))
+            cache.close()
+    finally:
+        gm.close()
+        O.set_threads(1)
+
+
+def test_c2_shape_lockstep_reduced_prompt():
+    """1.3B-shaped model, all 24 layers; prompt cut to 96 tokens, 40 new tokens."""
+    _lockstep_case(CONFIGS["C2"].shape, 96, 40, (0.2, 0.8))
+
+
+def test_c3_shape_two_layers_long_context():
+    """7B-shaped layers and heads (every kernel in its benchmark launch shape), 2 layers, context 333+."""
+    shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
+    _lockstep_case(shape, 333, 20, (0.2,))
+
+
+def test_c3_full_depth_reduced_prompt():
+    """The full 7B-shaped model (32 layers, exits after 8 and 16) against the oracle: prompt 24, 12 new tokens."""
+    _lockstep_case(CONFIGS["C3"].shape, 24, 12, (0.2,))
+
+
+def test_c3_full_size_invariants():
+    """C3 as benchmarked: prompt 1024, batch 1, 64-token blocks, max_pending 15."""
+    wl = CONFIGS["C3"]
+    shape, n_prompt, n_new = wl.shape, wl.prompt_len[0], 48
+    gm = load_gpu_model(shape, wl.weight_seed, max_positions=n_prompt + n_new + 8, max_rows=64, max_seqs=2)
+    prompt = prompt_tokens(shape.vocab, n_prompt, wl.prompt_seed).numpy()
+    cache = ee.KvCache(gm, 2, 2 * (n_prompt + n_new + 8), 64, 15)
+    L, e1 = shape.n_layers, shape.exit_layers[0]
+
+    def run(tau):
+        cache.reset(0)
+        tok, ex, _ = ee.prefill(gm, cache, 0, prompt, tau)
+        seqs = ee.Sequences(L)
+        seqs.start(0, tok)
+        toks, exits = [tok], [ex]
+        for _ in range(n_new - 1):
+            ro, tk, pm = seqs.rows([0])
+            nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, tau)
+            seqs.update([0], nt, exl)
+            toks.append(int(nt[0]))
+            exits.append(int(exl[0]))
+            assert cache.pending(0) == len(seqs.pending[0]) <= 15
+        return toks, exits
+
+    try:
+        print("case: C3 full size tau 1.0", flush=True)
+        t1, x1 = run(1.0)
+        assert set(x1) == {L}
+        t1b, _ = run(1.0)
+        assert t1 == t1b, "two runs must be bit-identical (fixed-order reductions)"
+        print("case: C3 full size tau 0.0", flush=True)
+        t0, x0 = run(0.0)
+        # token 0 from prefill, then 15 early exits, then one forced full-depth step, repeating
+        assert x0[0] == e1 and all(x0[j] == (L if j % 16 == 0 else e1) for j in range(1, n_new))
+        print("case: C3 full size tau 0.2 + KV invariant", flush=True)
+        toks, exits = run(0.2)
+        assert len(set(exits)) >= 2, exits
+        cache.flush([0])
+        n_pos = n_prompt + n_new - 1
+        seq = np.concatenate([prompt, np.array(toks[:-1], np.int32)])
+        cache.reset(1)
+        ee.prefill(gm, cache, 1, seq, 1.0)
+        for l in (0, 7, 8, 15, 16, 31):
+            assert cache.filled(0, l) == n_pos and cache.filled(1, l) == n_pos
+            k0, v0 = cache.read(0, l, n_prompt - 8, n_new + 7)
+            k1, v1 = cache.read(1, l, n_prompt - 8, n_new + 7)
+            assert rel_err(k0, k1) <= TOL and rel_err(v0, v1) <= TOL, (l, rel_err(k0, k1), rel_err(v0, v1))
+    finally:
+        cache.close()
+        gm.close()

@@ -224,3 +224,15 @@ def test_other_head_dims_with_split_kv(hd, d, H):
           f"teacher-forced {rep.teacher_forced} exits {sorted(set(rep.exit_layers))}", flush=True)
     cache.close()
     gm.close()
+
+
+def test_workload_generator_is_device_independent():
+    """The seeded generator must give the same bits on the CPU (oracle side) and on the GPU (library side)."""
+    from workload import TensorKind, model_tensor
+    for shape in (C1.shape, TINY_BF16):
+        for kind in (TensorKind.EMBED, TensorKind.WG, TensorKind.EXIT_HEAD, TensorKind.ATTN_NORM):
+            a = model_tensor(shape, kind, 1 if kind != TensorKind.EMBED else 0, 5, "cpu", 0.1)
+            b = model_tensor(shape, kind, 1 if kind != TensorKind.EMBED else 0, 5, "cuda:0", 0.1).cpu()
+            assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                               b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
+    assert torch.equal(prompt_tokens(50304, 1000, 3, "cpu"), prompt_tokens(50304, 1000, 3, "cuda:0").cpu())
