@@ -420,7 +420,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     auto rebuild = [&](int from) -> int {
         for (int s = from; s < n_seg; ++s) {
             build_desc(m, c, m->host_desc(s), ss, s, decode, threshold, &rows[s]);
-            if (rows[s] > m->max_rows || rows[s] > 64) return EE_ERR_NOMEM;
+            if (rows[s] > m->max_rows) return EE_ERR_NOMEM;
         }
         return upload(m, st);
     };

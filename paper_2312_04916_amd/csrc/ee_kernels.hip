@@ -435,7 +435,8 @@ struct QkvArgs {
     ST* kv_layer;  // pool + layer * layer_stride
     size_t blk_stride;
     int H, hd, BT;
-    const SegDesc* desc;
+    const int32_t* pos;    // per row: position, physical KV block
+    const int32_t* kvblk;
 };
 
 template <typename ST, int KS, int MT, bool ALDS>
@@ -452,8 +453,8 @@ __global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<S
     float2 cs0 = make_float2(1.f, 0.f);
     gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
         if (m0 < a.T) {
-            pos0 = e.desc->pos[m0];
-            blk0 = e.desc->kvblk[m0];
+            pos0 = e.pos[m0];
+            blk0 = e.kvblk[m0];
             if (part < 2) cs0 = e.rope_cs[(size_t)pos0 * half + c * 8 + i0];
         }
     });
@@ -464,8 +465,8 @@ __global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<S
         int pos = pos0, blk = blk0;
         float2 cs = cs0;
         if (idx != (int)threadIdx.x) {
-            pos = e.desc->pos[m];
-            blk = e.desc->kvblk[m];
+            pos = e.pos[m];
+            blk = e.kvblk[m];
             if (part < 2) cs = e.rope_cs[(size_t)pos * half + c * 8 + i];
         }
         if (part < 2) {
@@ -503,7 +504,7 @@ struct ResidArgs {
     const float* g_next;
     const float* g_head;
     int d;
-    const SegDesc* desc;
+    const int32_t* xrow;  // per row: slot in the residual store
 };
 
 template <typename ST, int KS, int MT, bool ALDS>
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
     float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
     gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
         if (m0 < a.T) {
-            o0 = (size_t)e.desc->xrow[m0] * e.d + n0 + i0;
+            o0 = (size_t)e.xrow[m0] * e.d + n0 + i0;
             x0 = e.x[o0];
             gn0 = e.g_next[n0 + i0];
             if (e.xgh) gh0 = e.g_head[n0 + i0];
@@ -528,7 +529,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
         size_t o = o0;
         float xv = x0, gn = gn0, gh = gh0;
         if (idx != (int)threadIdx.x) {
-            o = (size_t)e.desc->xrow[m] * e.d + n0 + i;
+            o = (size_t)e.xrow[m] * e.d + n0 + i;
             xv = e.x[o];
             gn = e.g_next[n0 + i];
             if (e.xgh) gh = e.g_head[n0 + i];
@@ -545,7 +546,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s += sm.out[m][i] * sm.out[m][i];
-        e.ssq_out[(size_t)e.desc->xrow[m] * e.ssq_stride + blockIdx.x] = s;
+        e.ssq_out[(size_t)e.xrow[m] * e.ssq_stride + blockIdx.x] = s;
     }
 }
 
@@ -725,51 +726,81 @@ static size_t a_lds_bytes(const GemmCommon& c) {
 
 int gemm_resid_tiles_per_wg() { return 1; }
 
-hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
+// Rows are processed in passes of at most 64 (the largest row tile count the kernels are built for).
+constexpr int PASS_ROWS = 64;
+
+static GemmCommon pass_of(const GemmCommon& c, int r0) {
+    GemmCommon p = c;
+    p.T = c.T - r0 < PASS_ROWS ? c.T - r0 : PASS_ROWS;
+    if (c.arow)
+        p.arow = c.arow + r0;
+    else
+        p.A = (const char*)c.A + (size_t)r0 * c.lda * (c.dtype == EE_BF16 ? 2 : 4);
+    return p;
+}
+
+static const int32_t* desc_array(const SegDesc* d, size_t field_offset, int r0) {
+    return (const int32_t*)((const char*)d + field_offset) + r0;
+}
+
+hipError_t launch_gemm_qkv(const GemmCommon& cc, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
                            hipStream_t s) {
-    if (c.T <= 0) return hipSuccess;
-    if (c.T > 64) return hipErrorInvalidValue;
-    GemmArgs a = make_args(c);
-    dim3 grid(c.N / 16);
-    if (c.dtype == EE_BF16) {
-        QkvArgs<__bf16> e{(__bf16*)q, q_lo, c.N / 3, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
-                          kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH(__bf16, gemm_qkv_kernel, a, e);
-    } else {
-        QkvArgs<float> e{(float*)q, q_lo, c.N / 3, (const float2*)rope_cs, (float*)kv.pool + (size_t)layer * kv.layer_stride,
-                         kv.blk_stride, kv.H, kv.hd, kv.BT, c.desc};
-        EE_DISPATCH_F32(gemm_qkv_kernel, a, e);
+    for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
+        const GemmCommon c = pass_of(cc, r0);
+        GemmArgs a = make_args(c);
+        dim3 grid(c.N / 16);
+        const int d = c.N / 3;
+        const int32_t* pos = desc_array(c.desc, offsetof(SegDesc, pos), r0);
+        const int32_t* blk = desc_array(c.desc, offsetof(SegDesc, kvblk), r0);
+        if (c.dtype == EE_BF16) {
+            QkvArgs<__bf16> e{(__bf16*)q + (size_t)r0 * d, q_lo, d, (const float2*)rope_cs,
+                              (__bf16*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk};
+            EE_DISPATCH(__bf16, gemm_qkv_kernel, a, e);
+        } else {
+            QkvArgs<float> e{(float*)q + (size_t)r0 * d, q_lo, d, (const float2*)rope_cs,
+                             (float*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk};
+            EE_DISPATCH_F32(gemm_qkv_kernel, a, e);
+        }
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
-hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
+hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
                              const float* g_next, const float* g_head, int d, hipStream_t s) {
-    if (c.T <= 0) return hipSuccess;
-    if (c.T > 64) return hipErrorInvalidValue;
-    GemmArgs a = make_args(c);
-    dim3 grid(c.N / 16);
-    if (c.dtype == EE_BF16) {
-        ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
-    } else {
-        ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, c.desc};
-        EE_DISPATCH_F32(gemm_resid_kernel, a, e);
+    for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
+        const GemmCommon c = pass_of(cc, r0);
+        GemmArgs a = make_args(c);
+        dim3 grid(c.N / 16);
+        const int32_t* xrow = desc_array(c.desc, offsetof(SegDesc, xrow), r0);
+        if (c.dtype == EE_BF16) {
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
+        } else {
+            ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            EE_DISPATCH_F32(gemm_resid_kernel, a, e);
+        }
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
-hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int F, hipStream_t s) {
-    if (c.T <= 0) return hipSuccess;
-    if (c.T > 64) return hipErrorInvalidValue;
-    GemmArgs a = make_args(c);
-    dim3 grid(c.N / 16);
-    if (c.dtype == EE_BF16) {
-        EE_DISPATCH(__bf16, gemm_swiglu_kernel, a, (__bf16*)act, act_lo, F);
-    } else {
-        EE_DISPATCH_F32(gemm_swiglu_kernel, a, (float*)act, act_lo, F);
+hipError_t launch_gemm_swiglu(const GemmCommon& cc, void* act, size_t act_lo, int F, hipStream_t s) {
+    for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
+        const GemmCommon c = pass_of(cc, r0);
+        GemmArgs a = make_args(c);
+        dim3 grid(c.N / 16);
+        if (c.dtype == EE_BF16) {
+            EE_DISPATCH(__bf16, gemm_swiglu_kernel, a, (__bf16*)act + (size_t)r0 * F, act_lo, F);
+        } else {
+            EE_DISPATCH_F32(gemm_swiglu_kernel, a, (float*)act + (size_t)r0 * F, act_lo, F);
+        }
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,

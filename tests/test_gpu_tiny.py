@@ -236,3 +236,49 @@ def test_workload_generator_is_device_independent():
             assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
                                b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
     assert torch.equal(prompt_tokens(50304, 1000, 3, "cpu"), prompt_tokens(50304, 1000, 3, "cuda:0").cpu())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_batch_with_more_than_64_rows(dtype):
+    """Six ragged sequences at threshold 0.0 pile up deferred rows (up to 6 x 16 = 96 rows in one launch, more
+    than one 64-row pass); every sequence must give exactly what it gives alone, and one is checked in
+    lockstep against the oracle."""
+    print(f"case: ragged batch {dtype}", flush=True)
+    shape = C1.shape if dtype == "f32" else TINY_BF16
+    om = build_model(shape, 0, gain_jitter=0.1)
+    gm = load_gpu_model(shape, 0, gain_jitter=0.1, max_positions=256, max_rows=128, max_seqs=8)
+    n_seq, n_new, tau, cap = 6, 36, 0.0, 15
+    prompts = [prompt_tokens(shape.vocab, 9 + 7 * s, 20 + s).numpy() for s in range(n_seq)]
+    solo = []
+    for s in range(n_seq):
+        cache = ee.KvCache(gm, 8, 2048, 32, cap)
+        rep = lockstep(gm, cache, om, prompts[s], n_new, tau, max_pending=cap, check_hidden=(s == 0))
+        if s == 0:
+            assert not rep.mismatches and rep.max_hidden_err <= TOL[dtype]
+        solo.append((rep.tokens, rep.exit_layers))
+        cache.close()
+    cache = ee.KvCache(gm, 8, 2048, 32, cap)
+    seqs = ee.Sequences(shape.n_layers)
+    out = [([], []) for _ in range(n_seq)]
+    ids = list(range(n_seq))
+    for s in ids:
+        tok, ex, _ = ee.prefill(gm, cache, s, prompts[s], tau)
+        seqs.start(s, tok)
+        out[s][0].append(tok)
+        out[s][1].append(ex)
+    max_rows = 0
+    for _ in range(n_new - 1):
+        ro, tk, pm = seqs.rows(ids)
+        max_rows = max(max_rows, len(tk))
+        nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
+        seqs.update(ids, nt, exl)
+        for s in ids:
+            out[s][0].append(int(nt[s]))
+            out[s][1].append(int(exl[s]))
+    assert max_rows > 64
+    for s in ids:
+        assert out[s][0] == solo[s][0] and out[s][1] == solo[s][1], s
+    cache.flush(ids)
+    assert all(cache.pending(s) == 0 for s in ids)
+    cache.close()
+    gm.close()
