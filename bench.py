@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=15)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C5"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--threshold", type=float, default=0.8)
     ap.add_argument("--max-pending", type=int, default=15)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -40,31 +40,31 @@ def parse():
     return ap.parse_args()
 
 
-def step_bytes(shape, es, ctx, exit_layer, heads_tested, rows_per_layer):
-    """Algorithmic HBM bytes of one decode step of one sequence: weights of the layers run, the heads
-    evaluated, K and V of the context read once per layer, K and V of the active rows written, one
-    embedding row."""
-    d, F, V = shape.d_model, shape.d_ff, shape.vocab
-    w_layer = (4 * d * d + 3 * d * F) * es
-    w_head = d * V * es
-    b = exit_layer * w_layer + heads_tested * w_head + d * es
-    b += exit_layer * 2 * d * es * ctx
-    b += sum(rows_per_layer[:exit_layer]) * 2 * d * es
-    return b
+def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending, profile_kernel=None):
+    """Prefill every sequence, then (warmup + steps) decode steps over the whole batch; returns the timing of
+    the last `steps` and the algorithmic-bytes model of exactly those steps.
 
-
-def generate(ee, gm, cache, prompt, tau, warmup, steps, shape, es, max_pending, profile_kernel=None):
-    """Prefill + (warmup + steps) decode steps; returns timing of the last `steps` and the bytes model."""
+    Bytes of one step (what the method itself must move): the weights of every layer some sequence runs, once;
+    the heads that are evaluated (an exit head if some sequence tests it, the final head if some sequence
+    reaches it), once each; per sequence K and V of its context in every layer it runs, K and V of its active
+    rows written, one embedding row."""
     import torch
 
-    cache.reset(0)
-    tok, ex, _ = ee.prefill(gm, cache, 0, prompt, tau)
-    seqs = ee.Sequences(shape.n_layers)
-    seqs.start(0, tok)
+    B = len(prompts)
+    ids = list(range(B))
+    d, F, V, L = shape.d_model, shape.d_ff, shape.vocab, shape.n_layers
+    w_layer, w_head = (4 * d * d + 3 * d * F) * es, d * V * es
+    seg_ends = list(shape.exit_layers) + [L]
+    seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(L)]
+    seqs = ee.Sequences(L)
+    fl = []  # host mirror of the fill watermarks, for the bytes model only
+    for sq in ids:
+        cache.reset(sq)
+    for sq in ids:
+        tok, ex, _ = ee.prefill(gm, cache, sq, prompts[sq], tau)
+        seqs.start(sq, tok)
+        fl.append([len(prompts[sq])] * len(seg_ends))
     exits, nbytes, forced = [], 0, 0
-    seg_ends = list(shape.exit_layers) + [shape.n_layers]
-    seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(shape.n_layers)]
-    fl = [len(prompt)] * len(seg_ends)  # host mirror of the fill watermarks, for the bytes model only
     prof = None
     t0 = None
     for i in range(warmup + steps):
@@ -73,26 +73,33 @@ def generate(ee, gm, cache, prompt, tau, warmup, steps, shape, es, max_pending, 
             if profile_kernel is not None:
                 gm.profile_begin(profile_kernel)
             t0 = time.perf_counter()
-        ro, tk, pm = seqs.rows([0])
-        nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, tau)
-        seqs.update([0], nt, exl)
-        p, e = len(prompt) + i, int(exl[0])
+        ro, tk, pm = seqs.rows(ids)
+        nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
+        seqs.update(ids, nt, exl)
+        deepest, heads = 0, set()
+        for sq in ids:
+            p, e = len(prompts[sq]) + i, int(exl[sq])
+            if i >= warmup:
+                was_forced = ro[sq + 1] - ro[sq] - 1 >= max_pending
+                deepest = max(deepest, e)
+                if not (tau >= 1.0 or was_forced):
+                    heads |= {x for x in shape.exit_layers if x <= e}
+                if e == L:
+                    heads.add(L)
+                rows = sum(p - fl[sq][seg_of_layer[l]] + 1 for l in range(e))
+                nbytes += e * 2 * d * es * (p + 1) + rows * 2 * d * es + d * es
+                exits.append(e)
+                forced += int(was_forced)
+            for k, se in enumerate(seg_ends):
+                if se <= e:
+                    fl[sq][k] = p + 1
         if i >= warmup:
-            was_forced = len(tk) - 1 >= max_pending
-            rows = [p - fl[seg_of_layer[l]] + 1 for l in range(shape.n_layers)]
-            tested = 0 if (tau >= 1.0 or was_forced) else sum(1 for x in shape.exit_layers if x <= e)
-            tested += 1 if e == shape.n_layers else 0
-            nbytes += step_bytes(shape, es, p + 1, e, tested, rows)
-            exits.append(e)
-            forced += int(was_forced)
-        for k, se in enumerate(seg_ends):
-            if se <= e:
-                fl[k] = p + 1
+            nbytes += deepest * w_layer + len(heads) * w_head
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if profile_kernel is not None:
         prof = gm.profile_end()
-    return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof)
+    return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof, tokens=B * steps)
 
 
 def cpu_baseline(shape, tensors_host, prompt, tau, max_pending, threads):
@@ -134,15 +141,18 @@ def main():
     import paper_2312_04916_amd as ee
     from common import ee_config_of
     from oracle.from_workload import to_numpy
-    from workload import CONFIGS, model_tensor, model_tensor_list, prompt_tokens
+    from workload import CONFIGS, model_tensor, model_tensor_list, prompt_lengths, prompt_tokens
 
     wl = CONFIGS[args.workload]
     shape = wl.shape
     es = 2 if shape.dtype == "bf16" else 4
-    n_prompt = wl.prompt_len[0]
-    max_pos = n_prompt + args.warmup + args.steps + 8
+    B = wl.batch
+    lens = [wl.prompt_len[0]] * B if wl.prompt_len[0] == wl.prompt_len[1] else \
+        prompt_lengths(B, wl.prompt_len[0], wl.prompt_len[1], wl.length_seed)
+    n_prompt = lens[0] if B == 1 else f"{min(lens)}..{max(lens)}"
+    max_pos = max(lens) + args.warmup + args.steps + 48
     t_setup = time.perf_counter()
-    gm = ee.Model(ee_config_of(shape, max_pos), max_rows=64, max_seqs=1)
+    gm = ee.Model(ee_config_of(shape, max_pos), max_rows=min(256, 16 * B + 48), max_seqs=B)
     keep_host = not args.no_cpu_baseline
     tensors_host = {}
     for kind, idx in model_tensor_list(shape):
@@ -152,8 +162,9 @@ def main():
             tensors_host[(int(kind), idx)] = to_numpy(t)
         torch.cuda.synchronize()
         del t
-    cache = ee.KvCache(gm, 1, max_pos, 64, args.max_pending)
-    prompt = prompt_tokens(shape.vocab, n_prompt, wl.prompt_seed).numpy()
+    cache = ee.KvCache(gm, B, sum(lens) + B * (args.warmup + args.steps + 48), 64, args.max_pending)
+    prompts = [prompt_tokens(shape.vocab, lens[b], wl.prompt_seed + b).numpy() for b in range(B)]
+    prompt = prompts[0]
     print(f"[bench] model {args.workload} ready in {time.perf_counter() - t_setup:.1f}s "
           f"({gm.weight_bytes / 1e9:.2f} GB weights)", file=sys.stderr, flush=True)
 
@@ -163,24 +174,24 @@ def main():
         torch.add(a, 1.0, out=b)  # plain elementwise kernel: reads 1 GiB, writes 1 GiB; what FETCH_SIZE / WRITE_SIZE
         torch.add(a, 1.0, out=b)  # report for it calibrates their unit (the float add kernel appears nowhere else)
         torch.cuda.synchronize()
-        generate(ee, gm, cache, prompt, 1.0, 2, 10, shape, es, args.max_pending)
+        generate(ee, gm, cache, prompts, 1.0, 2, 10, shape, es, args.max_pending)
         print("[bench] pmc run done", file=sys.stderr)
         return
-    generate(ee, gm, cache, prompt, 1.0, 0, 40, shape, es, args.max_pending)  # untimed: clocks and caches warm
-    full = generate(ee, gm, cache, prompt, 1.0, args.warmup, args.steps, shape, es, args.max_pending)
-    early = generate(ee, gm, cache, prompt, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
+    generate(ee, gm, cache, prompts, 1.0, 0, 40, shape, es, args.max_pending)  # untimed: clocks and caches warm
+    full = generate(ee, gm, cache, prompts, 1.0, args.warmup, args.steps, shape, es, args.max_pending)
+    early = generate(ee, gm, cache, prompts, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
                      profile_kernel=ee.EE_K_SWIGLU)
-    tps_full = args.steps / full["seconds"]
-    tps = args.steps / early["seconds"]
+    tps_full = full["tokens"] / full["seconds"]
+    tps = early["tokens"] / early["seconds"]
     n_l, ms_l = early["prof"]
     w_swiglu = 2 * shape.d_ff * shape.d_model * es
     achieved = w_swiglu / (ms_l / n_l * 1e-3) / 1e9 if n_l else 0.0
     hist = {str(e): early["exits"].count(e) for e in sorted(set(early["exits"]))}
-    ideal_speedup = (full["bytes"] / args.steps) / (early["bytes"] / args.steps)
+    ideal_speedup = full["bytes"] / early["bytes"]
 
     if args.breakdown:
         for k, name in enumerate(ee.KERNEL_NAMES):
-            r = generate(ee, gm, cache, prompt, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
+            r = generate(ee, gm, cache, prompts, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
                          profile_kernel=k)
             n, ms = r["prof"]
             print(f"[bench] {name:10s} launches {n:6d} avg {ms / max(n, 1) * 1e3:8.2f} us total {ms:9.2f} ms "
@@ -191,8 +202,8 @@ def main():
         for tau in wl.thresholds:
             if tau in (1.0, args.threshold):
                 continue
-            r = generate(ee, gm, cache, prompt, tau, args.warmup, args.steps, shape, es, args.max_pending)
-            sweep[str(tau)] = {"tokens_per_s": args.steps / r["seconds"], "speedup_vs_full_depth": full["seconds"] / r["seconds"],
+            r = generate(ee, gm, cache, prompts, tau, args.warmup, args.steps, shape, es, args.max_pending)
+            sweep[str(tau)] = {"tokens_per_s": r["tokens"] / r["seconds"], "speedup_vs_full_depth": full["seconds"] / r["seconds"],
                                "bytes_model_speedup": full["bytes"] / r["bytes"], "forced_full_steps": r["forced"],
                                "exit_histogram": {str(e): r["exits"].count(e) for e in sorted(set(r["exits"]))}}
 
@@ -203,11 +214,12 @@ def main():
             traffic = json.load(f).get(f"swiglu_{args.workload}")
 
     out = {
-        "metric": "generated tokens/s at 7B early-exit decode (thr 0.8) vs full-depth; HBM GB/s",
+        "metric": ("generated tokens/s at 7B early-exit decode (thr 0.8) vs full-depth; HBM GB/s" if args.workload == "C3"
+                   else f"generated tokens/s, early-exit decode, workload {args.workload} ({wl.note})"),
         "value": tps, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": early["seconds"] / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {wl.note}, batch 1, prompt {n_prompt} random ids, greedy, "
+        "config": {"workload": f"{args.workload}: {wl.note}, batch {B}, prompt {n_prompt} random ids, greedy, "
                                f"threshold {args.threshold}, max_pending {args.max_pending}",
                    "threshold": args.threshold, "exit_layers": list(shape.exit_layers), "n_layers": shape.n_layers},
         "full_depth_tokens_per_s": tps_full, "full_depth_ms_per_step": full["seconds"] / args.steps * 1e3,
