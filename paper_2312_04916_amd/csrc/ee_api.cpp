@@ -262,10 +262,12 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
             Timed t(m, EE_K_QKV, st);
             HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
         }
+        int att_ns = 0;
         {
             Timed t(m, EE_K_ATTN, st);
             HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
-                                (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx, st));
+                                (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
+                                gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, st));
         }
         // x += W_o a ; operand for the MLP norm
         g.W = m->wbase + m->wl.wo[l];
@@ -275,10 +277,17 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.a_lo = m->lo_rows(d);
         g.arow = nullptr;
         g.ssq = nullptr;
+        if (att_ns > 0) {
+            g.att_part = (const float*)(m->ws + m->wsl.attn_part);
+            g.att_ns = att_ns;
+            g.att_H = cf.n_heads;
+            g.att_hd = cf.head_dim;
+        }
         {
             Timed t(m, EE_K_OPROJ, st);
             HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
         }
+        g.att_part = nullptr;
         // act = silu(W_g h) * (W_u h)
         g.W = m->wbase + m->wl.gu[l];
         g.N = 2 * F;
@@ -388,6 +397,7 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
             d->qt_nq[nqt] = std::min(16, T - r);
             d->qt_pos0[nqt] = d->pos[r];
             d->qt_seq[nqt] = (int)b;
+            for (int q = 0; q < d->qt_nq[nqt]; ++q) d->row_qt[r + q] = nqt * 16 + q;
             ++nqt;
         }
         bool is_final = seg == m->n_seg() - 1;
@@ -871,6 +881,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
             d->qt_nq[d->n_qt] = std::min(16, n - r);
             d->qt_pos0[d->n_qt] = p0 + r;
             d->qt_seq[d->n_qt] = 0;
+            for (int q = 0; q < d->qt_nq[d->n_qt]; ++q) d->row_qt[r + q] = d->n_qt * 16 + q;
             ++d->n_qt;
         }
         if (last) d->xrow[n - 1] = c->slot_of(seq, n_tokens - 1);  // so that the newest hidden state can be read back

@@ -18,6 +18,7 @@ struct SegDesc {
     int32_t pos[EE_MAX_ROWS];    // position of row r in its sequence
     int32_t kvblk[EE_MAX_ROWS];  // physical KV block that holds pos[r]
     int32_t rseq[EE_MAX_ROWS];   // index of the row's sequence in this step's block-table array
+    int32_t row_qt[EE_MAX_ROWS]; // 16 * (query tile of row r) + (index of row r inside that tile)
     int32_t qt_row0[EE_MAX_ROWS];  // query tile: first row, number of rows (<= 16, one sequence,
     int32_t qt_nq[EE_MAX_ROWS];    //   consecutive positions),
     int32_t qt_pos0[EE_MAX_ROWS];  //   position of its first row,
@@ -76,6 +77,10 @@ struct GemmCommon {
     float inv_d, eps;
     int T;  // rows
     const SegDesc* desc;
+    // O projection only: A still lies as the attention kernel's split partials (att_ns splits), to be merged
+    // while the rows are staged; NULL otherwise
+    const float* att_part;
+    int att_ns, att_H, att_hd;
 };
 
 hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
@@ -87,8 +92,11 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
                             float threshold, HeadResult* results, hipStream_t s);
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
-                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
+                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
                             hipStream_t s);
+// defer_ns != NULL: when the KV range was split, leave the partials unmerged and report the number of splits
+// (the O projection then merges them, see GemmCommon::att_part); 0 is reported when `out` is complete.
+bool gemm_rows_fit_lds(int dtype, int T, int K);  // true when the GEMMs stage this many rows in LDS
 
 hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_t* btab_seq, int pos0, int n,
                             float* k_out, float* v_out, hipStream_t s);

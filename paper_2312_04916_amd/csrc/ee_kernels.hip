@@ -196,6 +196,10 @@ struct GemmArgs {
     int ssq_stride, ssq_n;
     float inv_d, eps;
     int T;
+    // A given as split-KV attention partials instead of rows (few-rows variant of the O projection only)
+    const float* att_part;
+    const SegDesc* att_desc;
+    int att_ns, att_H, att_hd;
 };
 
 template <int KS, int MT>
@@ -323,7 +327,10 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile, 
 constexpr int A_LDS_MAX_BYTES = 48 * 1024;
 __host__ __device__ inline int a_lds_row_stride(int K) { return 2 * K + 32; }  // elements; +64 B staggers the banks of two rows
 
-template <int KS, typename Pre>
+constexpr int ATT_MAX_SPLITS = 16;
+__host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
+
+template <int KS, bool ATT, typename Pre>
 __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int tile, GemmSmem<KS, 1>& sm, Pre pre) {
     extern __shared__ __attribute__((aligned(16))) unsigned char ee_dyn_smem[];
     __bf16* abuf = (__bf16*)ee_dyn_smem;
@@ -341,14 +348,69 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
         if (u < n) fill(u, u);
     const int rstride = a_lds_row_stride(K);
     const int cpr = K / 8;  // 16-byte chunks per row and term
-    for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
-        int m = c / cpr, k8 = c - m * cpr;
-        int slot = a.arow ? a.arow[m] : m;
-        const __bf16* src = (const __bf16*)a.A + (size_t)slot * a.lda + k8 * 8;
-        u32x4 h = *(const u32x4*)src;
-        u32x4 l = *(const u32x4*)(src + a.a_lo);
-        *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
-        *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+    if constexpr (ATT) {
+        // The rows are attention outputs that still lie as per-split partials (max, sum, unnormalised
+        // output): merge the splits here, in split order, exactly as attn_merge_kernel does, and split the
+        // result into its two bf16 terms.  Saves a launch between attention and this projection.
+        const int pstride = att_part_stride(a.att_hd), NS = a.att_ns;
+        for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
+            const int m = c / cpr, k8 = c - m * cpr;
+            const int h = (k8 * 8) / a.att_hd, cc = (k8 * 8) % a.att_hd;
+            const int rq = a.att_desc->row_qt[m];
+            const int qt = rq >> 4, qq = rq & 15;
+            const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * NS * pstride;
+            // every load of every split goes out before the first is used: one memory round trip in all
+            float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
+            f32x4 o0[ATT_MAX_SPLITS], o1[ATT_MAX_SPLITS];
+#pragma unroll
+            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp) {
+                if (sp < NS) {  // (uniform over the workgroup)
+                    const float* ps = pb + (size_t)sp * pstride;
+                    ms[sp] = ps[qq];
+                    ls[sp] = ps[16 + qq];
+                    o0[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc);
+                    o1[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc + 4);
+                }
+            }
+            float M = -INFINITY;
+#pragma unroll
+            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp)
+                if (sp < NS) M = fmaxf(M, ms[sp]);
+            float O[8], L = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) O[e] = 0.f;
+#pragma unroll
+            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp) {
+                if (sp >= NS || ms[sp] == -INFINITY) continue;
+                const float f = expf(ms[sp] - M);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    O[e] += f * o0[sp][e];
+                    O[4 + e] += f * o1[sp][e];
+                }
+                L += f * ls[sp];
+            }
+            bf16x8 hv, lv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = O[e] / L;
+                const __bf16 hi = (__bf16)v;
+                hv[e] = hi;
+                lv[e] = (__bf16)(v - (float)hi);
+            }
+            *(bf16x8*)(abuf + (size_t)m * rstride + k8 * 8) = hv;
+            *(bf16x8*)(abuf + (size_t)m * rstride + K + k8 * 8) = lv;
+        }
+    } else {
+        for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
+            int m = c / cpr, k8 = c - m * cpr;
+            int slot = a.arow ? a.arow[m] : m;
+            const __bf16* src = (const __bf16*)a.A + (size_t)slot * a.lda + k8 * 8;
+            u32x4 h = *(const u32x4*)src;
+            u32x4 l = *(const u32x4*)(src + a.a_lo);
+            *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
+            *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+        }
     }
     rms_scales<1>(a, sm.rs);
     pre();
@@ -414,10 +476,10 @@ __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile, G
 }
 
 // `pre` runs once the first weight loads are in flight: the place to fetch what the epilogue needs.
-template <typename ST, int KS, int MT, bool ALDS, typename Pre>
+template <typename ST, int KS, int MT, bool ALDS, typename Pre, bool ATT = false>
 __device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
     if constexpr (sizeof(ST) == 2 && ALDS)
-        gemm_mainloop_bf16_lds<KS>(a, tile, sm, pre);
+        gemm_mainloop_bf16_lds<KS, ATT>(a, tile, sm, pre);
     else if constexpr (sizeof(ST) == 2)
         gemm_mainloop_bf16<KS, MT>(a, tile, sm, pre);  // (its first __syncthreads orders rs before use)
     else
@@ -507,22 +569,23 @@ struct ResidArgs {
     const int32_t* xrow;  // per row: slot in the residual store
 };
 
-template <typename ST, int KS, int MT, bool ALDS>
-__global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
+template <typename ST, int KS, int MT, bool ALDS, bool ATT>
+__device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidArgs<ST>& e) {
     __shared__ GemmSmem<KS, MT> sm;
     const int n0 = blockIdx.x * 16;
     // epilogue operands of this thread's first element, fetched while the weights stream
     const int m0 = threadIdx.x >> 4, i0 = threadIdx.x & 15;
     size_t o0 = 0;
     float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
-    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
+    auto pre = [&]() {
         if (m0 < a.T) {
             o0 = (size_t)e.xrow[m0] * e.d + n0 + i0;
             x0 = e.x[o0];
             gn0 = e.g_next[n0 + i0];
             if (e.xgh) gh0 = e.g_head[n0 + i0];
         }
-    });
+    };
+    gemm_mainloop<ST, KS, MT, ALDS, decltype(pre), ATT>(a, blockIdx.x, sm, pre);
     for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
         int m = idx >> 4, i = idx & 15;
         if (m >= a.T) continue;
@@ -548,6 +611,17 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidAr
         for (int i = 0; i < 16; ++i) s += sm.out[m][i] * sm.out[m][i];
         e.ssq_out[(size_t)e.xrow[m] * e.ssq_stride + blockIdx.x] = s;
     }
+}
+
+template <typename ST, int KS, int MT, bool ALDS>
+__global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
+    gemm_resid_body<ST, KS, MT, ALDS, false>(a, e);
+}
+
+// O projection whose input rows are merged from the attention kernel's split partials while being staged
+template <int KS>
+__global__ __launch_bounds__(KS * 64) void gemm_resid_att_kernel(GemmArgs a, ResidArgs<__bf16> e) {
+    gemm_resid_body<__bf16, KS, 1, true, true>(a, e);
 }
 
 // ---- epilogue 3: SwiGLU.  Tile j: columns 0..7 = gate features 8j.., columns 8..15 = the matching up features
@@ -677,6 +751,11 @@ static GemmArgs make_args(const GemmCommon& c) {
     a.inv_d = c.inv_d;
     a.eps = c.eps;
     a.T = c.T;
+    a.att_part = c.att_part;
+    a.att_desc = c.desc;
+    a.att_ns = c.att_ns;
+    a.att_H = c.att_H;
+    a.att_hd = c.att_hd;
     return a;
 }
 
@@ -726,6 +805,14 @@ static size_t a_lds_bytes(const GemmCommon& c) {
 
 int gemm_resid_tiles_per_wg() { return 1; }
 
+bool gemm_rows_fit_lds(int dtype, int T, int K) {
+    GemmCommon c{};
+    c.dtype = dtype;
+    c.T = T;
+    c.K = K;
+    return a_lds_bytes(c) != 0;
+}
+
 // Rows are processed in passes of at most 64 (the largest row tile count the kernels are built for).
 constexpr int PASS_ROWS = 64;
 
@@ -774,7 +861,17 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
         GemmArgs a = make_args(c);
         dim3 grid(c.N / 16);
         const int32_t* xrow = desc_array(c.desc, offsetof(SegDesc, xrow), r0);
-        if (c.dtype == EE_BF16) {
+        if (c.dtype == EE_BF16 && c.att_part != nullptr) {
+            // input still lies as attention split partials: only the few-rows variant can merge them
+            const size_t sm = a_lds_bytes(c);
+            if (sm == 0 || cc.T > PASS_ROWS) return hipErrorInvalidValue;
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            // (at most 8 waves: the merge holds every split's partials in registers at once)
+            const int ks = ks_of(c) == 4 ? 4 : 8;
+            dim3 block(ks * 64);
+            if (ks == 4) EE_LAUNCH_SM(gemm_resid_att_kernel<4>, grid, block, sm, s, a, e);
+            else EE_LAUNCH_SM(gemm_resid_att_kernel<8>, grid, block, sm, s, a, e);
+        } else if (c.dtype == EE_BF16) {
             ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
             EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
         } else {
@@ -916,9 +1013,6 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
 // q and P are fed as two bf16 terms each (hi + lo), so only K and V carry bf16 rounding.
 // Partials of the KV splits are merged by attn_merge_kernel in a fixed order.
 // ------------------------------------------------------------------------------------------------
-constexpr int ATT_MAX_SPLITS = 16;
-
-__host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
 
 template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
@@ -1123,7 +1217,8 @@ size_t attention_part_floats(int max_rows, int H, int hd) {
 
 template <int HD>
 static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, int n_qt, const int32_t* btab,
-                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, hipStream_t s) {
+                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, int* defer_ns,
+                                        hipStream_t s) {
     const int wgs = n_qt * kv.H;
     const int tiles = (max_ctx + 31) / 32;
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
@@ -1138,20 +1233,25 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
               lb, d, NS, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
+    if (defer_ns != nullptr) {  // the consumer merges the splits itself
+        *defer_ns = NS;
+        return e;
+    }
     EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, desc, kv.H, d);
     return hipGetLastError();
 }
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
-                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx,
+                            const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
                             hipStream_t s) {
     (void)counters;
+    if (defer_ns) *defer_ns = 0;
     if (T <= 0) return hipSuccess;
     if (dtype == EE_BF16) {
         switch (kv.hd) {
-            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
-            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
-            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, s);
+            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
+            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
+            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
             default: return hipErrorInvalidValue;
         }
     }
