@@ -167,6 +167,19 @@ int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_ho
 int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                int32_t* next_token, int32_t* exit_layer, float* conf, void* stream);
 
+/* ee_prefill that also scores every head on EVERY prompt position (the per-token view of Table 4: which
+ * token each exit would emit after each prefix, and how confident it is).  pos_token / pos_conf are host
+ * arrays [n_exits+1][n_tokens] (row i < n_exits: exit i, last row: final head), filled whatever the
+ * threshold: pos_token = arg max of the head's logits at that position (ties: lowest id), pos_conf = its
+ * soft-max probability.  Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
+ * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
+ * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
+ * min(max_positions, EE_PREFILL_ROWS) rows, rounded up to 128 (environment variable read when the model is
+ * sized and created; default 2048; 0 switches the path off), each projection one matrix-core GEMM. */
+int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
+                      int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf,
+                      void* stream);
+
 /* One decode step for n_seqs sequences.
  *   seq_ids      [n_seqs]   distinct sequence ids
  *   row_offsets  [n_seqs+1] rows of sequence i are tokens[row_offsets[i] .. row_offsets[i+1])

@@ -19,7 +19,8 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
            "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
-           "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_decode_step"]
+           "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
+           "ee_decode_step"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libee.so")
@@ -75,6 +76,7 @@ def lib():
         L.ee_kv_cache_free.argtypes = [vp]
         L.ee_debug_read_hidden.argtypes = [vp, vp, C.c_int, fp, vp]
         L.ee_prefill.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, vp]
+        L.ee_prefill_scored.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, i32p, fp, vp]
         L.ee_decode_step.argtypes = [vp, vp, C.c_int, i32p, i32p, i32p, C.POINTER(C.c_uint8), C.c_float, i32p, i32p,
                                      fp, vp]
         _lib = L
@@ -249,6 +251,19 @@ def prefill(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], thres
     _chk(lib().ee_prefill(model.h, cache.h, seq, _ip(t), len(t), threshold, C.byref(nt), C.byref(ex), _fp(conf),
                           _stream_ptr(stream)), "ee_prefill")
     return nt.value, ex.value, conf
+
+
+def prefill_scored(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], threshold: float, stream=None):
+    """ee_prefill_scored -> (next_token, exit_layer, conf[n_exits+1], pos_token[n_exits+1][n], pos_conf[n_exits+1][n])."""
+    t = _i32(tokens)
+    nt, ex = C.c_int32(), C.c_int32()
+    nh = model.cfg.n_exits + 1
+    conf = np.zeros(nh, np.float32)
+    ptok = np.zeros((nh, len(t)), np.int32)
+    pconf = np.zeros((nh, len(t)), np.float32)
+    _chk(lib().ee_prefill_scored(model.h, cache.h, seq, _ip(t), len(t), threshold, C.byref(nt), C.byref(ex), _fp(conf),
+                                 _ip(ptok), _fp(pconf), _stream_ptr(stream)), "ee_prefill_scored")
+    return nt.value, ex.value, conf, ptok, pconf
 
 
 def decode_step(model: Model, cache: KvCache, seq_ids: Sequence[int], row_offsets: Sequence[int], tokens: Sequence[int],

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libee.so")
-SOURCES = ["ee_api.cpp", "ee_kernels.hip"]
+SOURCES = ["ee_api.cpp", "ee_kernels.hip", "ee_prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

@@ -4,6 +4,7 @@
 // (Section 4 "KV recomputation", Section 5.2 exit rule, Appendix D.3 forced full pass).
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -87,7 +88,26 @@ struct WorkspaceLayout {
     size_t descs, btab, tokens;
     size_t q, attn, act, partials, counters, attn_part, stage, total;
     int max_blocks_per_seq;
+    // prompt phase (bf16 model): buffers for pf_rows positions at a time, activations in the packed operand layout
+    int pf_rows;  // 0: the prompt phase runs through the decode kernels in chunks
+    size_t pf_begin, pf_tokens, pf_x, pf_xg, pf_xgh, pf_q, pf_attn, pf_act, pf_ssq, pf_partials, pf_tok, pf_conf;
 };
+
+// Rows per pass of the prompt-phase GEMM path; 0 when the model does not qualify (fp32, or widths the
+// 256-column tiles do not divide evenly into the q|k|v parts).  EE_PREFILL_ROWS caps it (default 2048).
+constexpr int PF_MIN_TOKENS = 32;  // shorter prompts go through the decode kernels
+
+int pf_rows_of(const ee_config& c) {
+    if (c.dtype != EE_BF16 || c.d_model % 128) return 0;
+    int cap = 2048;
+    if (const char* e = std::getenv("EE_PREFILL_ROWS")) {
+        int v = std::atoi(e);
+        if (v <= 0) return 0;
+        cap = std::max(128, std::min(v, 8192));
+    }
+    int r = std::min((c.max_positions + 127) / 128 * 128, cap);
+    return r / 128 * 128;
+}
 
 WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs) {
     WorkspaceLayout w;
@@ -111,6 +131,22 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     w.counters = take(256 * 4);
     w.attn_part = take(attention_part_floats(max_rows, c.n_heads, c.head_dim) * 4);
     w.stage = take(2 * (size_t)max_rows * d * 4);
+    w.pf_rows = pf_rows_of(c);
+    w.pf_begin = off;
+    if (w.pf_rows) {
+        size_t Mp = w.pf_rows, F = c.d_ff;
+        w.pf_tokens = take(Mp * 4);
+        w.pf_x = take(Mp * d * 4);
+        w.pf_xg = take(2 * Mp * d * 2);
+        w.pf_xgh = take(2 * Mp * d * 2);
+        w.pf_q = take(2 * Mp * d * 2);
+        w.pf_attn = take(2 * Mp * d * 2);
+        w.pf_act = take(2 * Mp * F * 2);
+        w.pf_ssq = take(Mp * ((d + 255) / 256) * 4);
+        w.pf_partials = take(Mp * (((size_t)c.vocab + 255) / 256) * sizeof(HeadPartial));
+        w.pf_tok = take(Mp * 4);
+        w.pf_conf = take(Mp * 4);
+    }
     w.total = off;
     return w;
 }
@@ -129,6 +165,7 @@ struct ee_model {
     char* pinned;            // host staging for the upload region, then the head results
     HeadResult* results;     // host view
     HeadResult* results_dev; // device view of the same memory
+    int32_t* pf_host_tokens; // pinned staging of one prompt pass's token ids
     float* dbg_logits;
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
@@ -479,6 +516,132 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     return EE_OK;
 }
 
+// ---- prompt phase through the GEMM path: whole passes of up to pf_rows positions, every projection one
+// matrix-core GEMM over all rows, causal attention over the pass and the cache before it.  The last
+// position's residual row is handed to the decode-side store after each segment, where the usual heads
+// decide the first token.  score_tok / score_conf (host, [n_seg][n_tokens], optional): every head on
+// every position.
+int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* score_tok,
+                  float* score_conf, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    const WorkspaceLayout& w = m->wsl;
+    const int d = cf.d_model, F = cf.d_ff, V = cf.vocab, n_seg = m->n_seg();
+    const size_t Mp = w.pf_rows;
+    const int ssq_n = (d + 255) / 256;
+    SeqState& s = c->seqs[seq];
+    char* ws = m->ws;
+    float* x = (float*)(ws + w.pf_x);
+    char *xg_hi = ws + w.pf_xg, *xg_lo = xg_hi + Mp * d * 2;
+    char *xgh_hi = ws + w.pf_xgh, *xgh_lo = xgh_hi + Mp * d * 2;
+    char *q_hi = ws + w.pf_q, *q_lo = q_hi + Mp * d * 2;
+    char *at_hi = ws + w.pf_attn, *at_lo = at_hi + Mp * d * 2;
+    char *ac_hi = ws + w.pf_act, *ac_lo = ac_hi + Mp * F * 2;
+    float* ssq = (float*)(ws + w.pf_ssq);
+    const int slot = c->slot_of(seq, n_tokens - 1);
+    put_btab(m, c, 0, s);
+    for (int i = 0; i < n_seg; ++i) {  // one descriptor per head so that each writes its own result slot
+        SegDesc* di = m->host_desc(i);
+        di->T = 0;
+        di->n_qt = 0;
+        di->n_head = 1;
+        di->head_xrow[0] = slot;
+        di->head_slot[0] = i * EE_MAX_SEQS;
+    }
+    EECHK(upload(m, st));
+    const int32_t* bt = m->dev_btab();
+    PfGemm g{};
+    g.inv_d = 1.0f / (float)d;
+    g.eps = cf.rms_eps;
+    g.ssq_n = ssq_n;
+    for (int p0 = 0; p0 < n_tokens; p0 += (int)Mp) {
+        const int M = std::min((int)Mp, n_tokens - p0);
+        const bool last = p0 + M == n_tokens;
+        g.M = M;
+        std::memcpy(m->pf_host_tokens, tokens + p0, (size_t)M * 4);
+        HIPCHK(hipMemcpyAsync(ws + w.pf_tokens, m->pf_host_tokens, (size_t)M * 4, hipMemcpyHostToDevice, st));
+        HIPCHK(launch_pf_embed(m->wbase + m->wl.embed, (const int32_t*)(ws + w.pf_tokens), M, d, m->gain(m->wl.g1[0]), x, xg_hi, xg_lo, ssq,
+                               ssq_n, st));
+        for (int sgi = 0; sgi < n_seg; ++sgi) {
+            const bool fin = sgi == n_seg - 1;
+            for (int l = m->seg_begin(sgi); l < m->seg_end(sgi); ++l) {
+                g.W = m->wbase + m->wl.qkv[l];
+                g.N = 3 * d;
+                g.K = d;
+                g.A_hi = xg_hi;
+                g.A_lo = xg_lo;
+                g.ssq = ssq;
+                {
+                    Timed t(m, EE_K_QKV, st);
+                    HIPCHK(launch_pf_qkv(g, q_hi, q_lo, (const float*)(m->wbase + m->wl.rope), c->geom, l, bt, p0, st));
+                }
+                {
+                    Timed t(m, EE_K_ATTN, st);
+                    HIPCHK(launch_pf_attention(q_hi, q_lo, at_hi, at_lo, c->geom, l, bt, p0, M, d, st));
+                }
+                g.W = m->wbase + m->wl.wo[l];
+                g.N = d;
+                g.A_hi = at_hi;
+                g.A_lo = at_lo;
+                g.ssq = nullptr;
+                {
+                    Timed t(m, EE_K_OPROJ, st);
+                    HIPCHK(launch_pf_resid(g, x, xg_hi, xg_lo, nullptr, nullptr, m->gain(m->wl.g2[l]), nullptr, ssq, ssq_n, st));
+                }
+                g.W = m->wbase + m->wl.gu[l];
+                g.N = 2 * F;
+                g.A_hi = xg_hi;
+                g.A_lo = xg_lo;
+                g.ssq = ssq;
+                {
+                    Timed t(m, EE_K_SWIGLU, st);
+                    HIPCHK(launch_pf_swiglu(g, ac_hi, ac_lo, F, st));
+                }
+                g.W = m->wbase + m->wl.wd[l];
+                g.N = d;
+                g.K = F;
+                g.A_hi = ac_hi;
+                g.A_lo = ac_lo;
+                g.ssq = nullptr;
+                const float* g_next = (l + 1 < cf.n_layers) ? m->gain(m->wl.g1[l + 1]) : m->gain(m->wl.gf);
+                const float* g_head = (!fin && l + 1 == m->seg_end(sgi)) ? m->gain(m->wl.ge[sgi]) : nullptr;
+                {
+                    Timed t(m, EE_K_DOWN, st);
+                    HIPCHK(launch_pf_resid(g, x, xg_hi, xg_lo, g_head ? xgh_hi : nullptr, g_head ? xgh_lo : nullptr, g_next, g_head, ssq,
+                                           ssq_n, st));
+                }
+            }
+            if (score_tok || score_conf) {  // this segment's head on every position of the pass
+                g.W = m->wbase + (fin ? m->wl.wf : m->wl.we[sgi]);
+                g.N = V;
+                g.K = d;
+                g.A_hi = fin ? xg_hi : xgh_hi;
+                g.A_lo = fin ? xg_lo : xgh_lo;
+                g.ssq = ssq;
+                {
+                    Timed t(m, EE_K_HEAD, st);
+                    HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf), st));
+                }
+                if (score_tok)
+                    HIPCHK(hipMemcpyAsync(score_tok + (size_t)sgi * n_tokens + p0, ws + w.pf_tok, (size_t)M * 4, hipMemcpyDeviceToHost, st));
+                if (score_conf)
+                    HIPCHK(hipMemcpyAsync(score_conf + (size_t)sgi * n_tokens + p0, ws + w.pf_conf, (size_t)M * 4, hipMemcpyDeviceToHost, st));
+            }
+            if (last && (fin || threshold < 1.0f)) {
+                const int l_end = m->seg_end(sgi);
+                const float* g_a = fin ? m->gain(m->wl.gf) : m->gain(m->wl.g1[l_end]);
+                const float* g_b = fin ? nullptr : m->gain(m->wl.ge[sgi]);
+                const size_t es = 2;
+                HIPCHK(launch_pf_export_row(x + (size_t)(M - 1) * d, d, g_a, g_b, c->x() + (size_t)slot * d,
+                                            (char*)c->xg() + (size_t)slot * d * es, (char*)c->xgh() + (size_t)slot * d * es, c->xs_lo,
+                                            c->ssq() + (size_t)slot * c->ssq_stride, c->ssq_stride, st));
+                EECHK(run_head(m, c, sgi, sgi, 1, fin ? HEAD_EMIT : HEAD_RULE, threshold, st));
+            }
+        }
+        HIPCHK(hipStreamSynchronize(st));  // the pinned token staging is rewritten by the next pass
+    }
+    return EE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -528,7 +691,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     m->n_missing = m->n_tensors();
     m->dbg_logits = nullptr;
     m->dbg_rows = 0;
-    size_t res_bytes = sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1);
+    size_t res_bytes = align_up(sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1)) + (size_t)m->wsl.pf_rows * 4;
     hipError_t e = hipHostMalloc((void**)&m->pinned, align_up(m->wsl.upload_bytes) + res_bytes, hipHostMallocMapped);
     if (e != hipSuccess) {
         g_last_hip = (int)e;
@@ -537,11 +700,13 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     }
     std::memset(m->pinned, 0, align_up(m->wsl.upload_bytes) + res_bytes);
     m->results = (HeadResult*)(m->pinned + align_up(m->wsl.upload_bytes));
+    m->pf_host_tokens = (int32_t*)((char*)m->results + align_up(sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1)));
     hipStream_t st = (hipStream_t)stream;
     int rc = EE_OK;
     do {
         if ((e = hipHostGetDevicePointer((void**)&m->results_dev, m->results, 0)) != hipSuccess) break;
         if ((e = hipMemsetAsync(m->ws + m->wsl.counters, 0, 256 * 4, st)) != hipSuccess) break;
+        if (m->wsl.pf_rows && (e = hipMemsetAsync(m->ws + m->wsl.pf_begin, 0, m->wsl.total - m->wsl.pf_begin, st)) != hipSuccess) break;
         e = launch_rope_table((float*)(m->wbase + m->wl.rope), cfg->max_positions, cfg->head_dim, cfg->rope_base, st);
     } while (0);
     if (e != hipSuccess) {
@@ -847,8 +1012,26 @@ int ee_kv_cache_free(ee_kv_cache* c) {
 
 /* ------------------------------------------------------------------ prefill */
 
+namespace {
+int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* next_token,
+                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, void* stream);
+}
+
 int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                int32_t* next_token, int32_t* exit_layer, float* conf, void* stream) {
+    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, nullptr, nullptr, stream);
+}
+
+int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
+                      int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, void* stream) {
+    if (!pos_token || !pos_conf) return EE_ERR_ARG;
+    if (m && m->wsl.pf_rows == 0) return EE_ERR_CONFIG;
+    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, stream);
+}
+
+namespace {
+int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* next_token,
+                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, void* stream) {
     if (!m || !c || !tokens || !next_token || !exit_layer || c->m != m) return EE_ERR_ARG;
     if (m->n_missing) return EE_ERR_STATE;
     if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
@@ -862,8 +1045,10 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
     const ee_config& cf = m->cfg;
     const int n_seg = m->n_seg();
     const int CH = std::min(m->max_rows, 64);
+    const bool large = m->wsl.pf_rows > 0 && (score_tok != nullptr || n_tokens >= PF_MIN_TOKENS);
+    if (large) EECHK(prefill_large(m, c, seq, tokens, n_tokens, threshold, score_tok, score_conf, st));
     put_btab(m, c, 0, s);
-    for (int p0 = 0; p0 < n_tokens; p0 += CH) {
+    for (int p0 = 0; p0 < n_tokens && !large; p0 += CH) {
         int n = std::min(CH, n_tokens - p0);
         bool last = p0 + n == n_tokens;
         SegDesc* d = m->host_desc(0);
@@ -922,6 +1107,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
     for (auto& f : s.filled) f = n_tokens;
     return EE_OK;
 }
+}  // namespace
 
 /* ------------------------------------------------------------------ decode */
 

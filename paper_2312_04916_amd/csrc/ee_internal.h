@@ -101,6 +101,33 @@ bool gemm_rows_fit_lds(int dtype, int T, int K);  // true when the GEMMs stage t
 hipError_t launch_kv_gather(int dtype, const KvGeom& kv, int layer, const int32_t* btab_seq, int pos0, int n,
                             float* k_out, float* v_out, hipStream_t s);
 
+// ---- prompt phase (ee_prefill.hip): many rows at once, activations in the packed operand layout
+// [row/16][K/32][64 lanes][8 bf16] (hi and lo arrays), bf16 model only.
+struct PfGemm {
+    const void* W;    // packed weights
+    int N, K;         // output features, reduction length (multiple of 32)
+    const void* A_hi; // packed activations, rows padded to a multiple of 16
+    const void* A_lo;
+    const float* ssq; // [rows][ssq_n] partial sums of squares of the rows (RMS scale), or NULL
+    int ssq_n;
+    float inv_d, eps;
+    int M;            // rows
+};
+hipError_t launch_pf_embed(const void* embed, const int32_t* dev_tokens, int M, int d, const float* g_next, float* x, void* xg_hi,
+                           void* xg_lo, float* ssq, int ssq_n, hipStream_t s);
+hipError_t launch_pf_qkv(const PfGemm& g, void* q_hi, void* q_lo, const float* rope_cs, const KvGeom& kv, int layer, const int32_t* bt,
+                         int p0, hipStream_t s);
+hipError_t launch_pf_attention(const void* q_hi, const void* q_lo, void* out_hi, void* out_lo, const KvGeom& kv, int layer,
+                               const int32_t* bt, int p0, int M, int d, hipStream_t s);
+hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, void* xgh_hi, void* xgh_lo, const float* g_next,
+                           const float* g_head, float* ssq_out, int ssq_n_out, hipStream_t s);
+hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, hipStream_t s);
+// head on every row: (arg max, confidence) per row into tok / conf
+hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, hipStream_t s);
+// one fp32 row of the residual stream -> decode-side residual store entry (row-major two-term operands)
+hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
+                                size_t lo_off, float* dssq, int ssq_stride, hipStream_t s);
+
 int gemm_resid_tiles_per_wg();  // G of the residual epilogue: ssq partials per row = d / (16*G)
 size_t attention_part_floats(int max_rows, int H, int hd);  // scratch the attention kernel needs
 

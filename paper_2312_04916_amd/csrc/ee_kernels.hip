@@ -10,28 +10,22 @@
 // of the kernel that produced it.  No float atomics: every reduction has a fixed order.
 #include "ee_internal.h"
 
-#include <hip/hip_ext.h>
+#include "ee_launch.h"
 
 namespace ee {
 
-// Optional timing of the next launch: the event pair is attached to the dispatch itself, so the
-// elapsed time between the two events is the kernel's own execution time.
 static thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
 void set_launch_events(hipEvent_t start, hipEvent_t stop) {
     t_ev0 = start;
     t_ev1 = stop;
 }
-#define EE_LAUNCH_SM(kernel, grid, block, shmem, stream, ...)                                  \
-    do {                                                                                       \
-        if (t_ev0) {                                                                           \
-            hipEvent_t _a = t_ev0, _b = t_ev1;                                                 \
-            t_ev0 = t_ev1 = nullptr;                                                           \
-            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, _a, _b, 0, __VA_ARGS__); \
-        } else {                                                                               \
-            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);               \
-        }                                                                                      \
-    } while (0)
-#define EE_LAUNCH(kernel, grid, block, stream, ...) EE_LAUNCH_SM(kernel, grid, block, 0, stream, __VA_ARGS__)
+bool take_launch_events(hipEvent_t* start, hipEvent_t* stop) {
+    if (!t_ev0) return false;
+    *start = t_ev0;
+    *stop = t_ev1;
+    t_ev0 = t_ev1 = nullptr;
+    return true;
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));

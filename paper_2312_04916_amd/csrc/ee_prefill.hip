@@ -1,0 +1,800 @@
+// HIP kernels (gfx950) for the prompt phase: the full-depth causal forward of many positions at once
+// (the "prefilling phase" of Section 4), where the projections are true GEMMs and the matrix cores, not
+// HBM, are the bound; and the exit heads scored on every position (the per-position token / confidence
+// view of Table 4).
+//
+// Operand layout.  Weights keep the decode layout: 16-row tiles, [tile][K/32][64 lanes][8 bf16], which is
+// the register image of one 16x32 MFMA operand.  Activations of this path use THE SAME layout with rows =
+// positions: [row/16][K/32][64][8], one array for the hi term and one for the lo term (two-term bf16,
+// see ee_kernels.hip).  A workgroup therefore stages both operands with plain 1 KB global->LDS copies
+// (no register round trip, no swizzle, no bank conflicts) and every wave reads ready-made operands back.
+//
+// The product is formed transposed, D[n][m] (weights as the A operand): a lane then holds four
+// consecutive output features of one position, which is exactly an 8-byte piece of the next GEMM's
+// activation operand, of a K-cache row, or of a packed q row.
+#include "ee_internal.h"
+
+#include "ee_launch.h"
+
+namespace ee {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+#define EE_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+#define EE_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+
+namespace {
+
+constexpr int PF_NTL = 16;  // 16-column weight tiles per workgroup (256 output features)
+
+// element index of (row m, feature k) in a packed activation array with KT = K/32 tiles per row group
+__device__ __forceinline__ size_t pk_index(int m, int k, int KT) {
+    return (((size_t)(m >> 4) * KT + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
+}
+
+// stores four consecutive features (k % 4 == 0) of row m as two bf16 terms
+__device__ __forceinline__ void pk_store4(__bf16* hi, __bf16* lo, int m, int k, int KT, const float v[4]) {
+    const size_t o = pk_index(m, k, KT);
+    bf16x4 h, l;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const __bf16 t = (__bf16)v[r];
+        h[r] = t;
+        l[r] = (__bf16)(v[r] - (float)t);
+    }
+    *(bf16x4*)(hi + o) = h;
+    *(bf16x4*)(lo + o) = l;
+}
+
+struct PfArgs {
+    const u32x4* W;   // packed weights [n_tiles][KT][64]
+    const u32x4* Xh;  // packed activations [m_tiles][KT][64], hi and lo terms
+    const u32x4* Xl;
+    int KT, n_tiles, m_tiles;  // valid 16-wide tiles of W and X (loads of tiles beyond them are clamped)
+    int n_wgN, n_wgM;
+    int M, N;
+    const float* ssq;  // [rows][ssq_n] partial sums of squares of the rows of X before their gain, or NULL
+    int ssq_n;
+    float inv_d, eps;
+};
+
+// ---------------------------------------------------------------------------------------------------
+// main loop: acc[i][j] (+)= W tile i of this wave (8 of them) x activation tile j (MTL/2 of them).
+// Workgroup = 4 waves as 2 (features) x 2 (rows); tile = 256 features x MTL*16 rows; K advances 32 per
+// stage, two stages in LDS, the copy of stage k+1 runs while stage k is multiplied.  Two workgroups
+// share a CU, so that one's copy wait and operand reads hide behind the other's MFMAs.
+// ---------------------------------------------------------------------------------------------------
+template <int MTL>
+struct PfTile {
+    int nt0, mt0, n_wg, wn, wm;
+};
+
+template <int MTL>
+__device__ __forceinline__ bool pf_tile_of(const PfArgs& a, PfTile<MTL>& t) {
+    // Workgroups are dealt round-robin to the 8 XCDs: give each XCD whole column panels, all row tiles of
+    // a panel back to back, so that a weight panel is fetched from HBM once and then served by that XCD's L2.
+    const int w = blockIdx.x, xcd = w & 7, j = w >> 3;
+    t.n_wg = (j / a.n_wgM) * 8 + xcd;
+    const int m_wg = j % a.n_wgM;
+    if (t.n_wg >= a.n_wgN) return false;
+    t.nt0 = t.n_wg * PF_NTL;
+    t.mt0 = m_wg * MTL;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    t.wn = wave & 1;
+    t.wm = wave >> 1;
+    return true;
+}
+
+template <int MTL>
+__device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs, f32x4 (&acc)[8][MTL / 2]) {
+    constexpr int NF = PF_NTL + 2 * MTL;  // fragments (1 KB each) per stage
+    constexpr int FPW = NF / 4;           // copied per wave
+    constexpr int STAGE = NF * 64;        // u32x4 per stage
+    constexpr int MW = MTL / 2;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int KT = a.KT;
+    const u32x4* src[FPW];
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) {
+        const int f = wave * FPW + i;
+        if (f < PF_NTL) {
+            int tt = t.nt0 + f;
+            if (tt >= a.n_tiles) tt = a.n_tiles - 1;
+            src[i] = a.W + (size_t)tt * KT * 64 + lane;
+        } else {
+            const int g = f - PF_NTL;
+            int mt = t.mt0 + (g < MTL ? g : g - MTL);
+            if (mt >= a.m_tiles) mt = a.m_tiles - 1;
+            src[i] = (g < MTL ? a.Xh : a.Xl) + (size_t)mt * KT * 64 + lane;
+        }
+    }
+    auto issue = [&](int st, int kt) {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i)
+            __builtin_amdgcn_global_load_lds(EE_GLB_PTR(src[i] + (size_t)kt * 64), EE_LDS_PTR(lds + st * STAGE + (wave * FPW + i) * 64), 16,
+                                             0, 0);
+    };
+    issue(0, 0);
+    // r[m] = 1/sqrt(mean(x^2)+eps) of this tile's rows, from the producers' partial sums (fixed order)
+    for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
+        const int m = t.mt0 * 16 + ml;
+        float r = 1.f;
+        if (a.ssq != nullptr && m < a.M) {
+            const float* p = a.ssq + (size_t)m * a.ssq_n;
+            float s = 0.f;
+            for (int i = 0; i < a.ssq_n; ++i) s += p[i];
+            r = 1.0f / sqrtf(s * a.inv_d + a.eps);
+        }
+        rs[ml] = r;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < MW; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kt = 0; kt < KT; ++kt) {
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies of stage kt have landed
+        __syncthreads();                     // ... and everybody else's; stage kt-1 is no longer being read
+        const u32x4* sb = lds + (kt & 1) * STAGE;
+        u32x4 wf[8], xh[MW], xl[MW];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wf[i] = sb[(t.wn * 8 + i) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            xh[j] = sb[(PF_NTL + t.wm * MW + j) * 64 + lane];
+            xl[j] = sb[(PF_NTL + MTL + t.wm * MW + j) * 64 + lane];
+        }
+        if (kt + 1 < KT) issue((kt + 1) & 1, kt + 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < MW; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xl[j]),
+                                                                    acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < MW; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xh[j]),
+                                                                    acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();  // rs[] visible (also when KT were 0)
+}
+
+template <int MTL>
+constexpr size_t pf_lds_bytes() {
+    return 2 * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 3;  // two stages + rs[] + two reduction rows
+}
+
+template <int MTL>
+__device__ __forceinline__ float* pf_rs_ptr(u32x4* lds) {
+    return (float*)(lds + 2 * (PF_NTL + 2 * MTL) * 64);
+}
+
+// ---- epilogue 1: RMS scale, rotary embedding, q (packed), k and v into the paged cache
+struct PfQkv {
+    __bf16 *q_hi, *q_lo;  // packed [rows][d]
+    int d, H, hd;
+    const float2* rope_cs;
+    __bf16* kv_layer;
+    size_t blk_stride;
+    int BT;
+    const int32_t* bt;  // block table of the sequence
+    int p0;             // position of row 0 (multiple of 16)
+};
+
+template <int MTL>
+__global__ __launch_bounds__(256, 2) void pf_qkv_kernel(PfArgs a, PfQkv e) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<MTL> t;
+    if (!pf_tile_of<MTL>(a, t)) return;
+    constexpr int MW = MTL / 2;
+    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    const int tiles_per_part = e.d / 16, per_head = e.hd / 16, half = e.hd / 2;
+    f32x4 acc[8][MW];
+    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
+    const int KTd = e.d / 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int T = t.nt0 + t.wn * 8 + i;
+        if (T >= a.n_tiles) continue;  // (uniform over the wave)
+        const int part = T / tiles_per_part, rem = T % tiles_per_part;
+        const int h = rem / per_head, c = rem % per_head;
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int ml0 = (t.wm * MW + j) * 16;
+            if (part < 2) {
+                // lane: features rg*4..rg*4+3 of the tile (rows 0-7 = features c*8.., rows 8-15 = their rotary
+                // partners) for position m
+                const int ml = ml0 + li, m = t.mt0 * 16 + ml;
+                const float r = rs[ml];
+                f32x4 v = acc[i][j] * r;
+                f32x4 o;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o[q] = __shfl_xor(v[q], 32);
+                const bool is_hi = rg >= 2;
+                const int fi = c * 8 + (rg & 1) * 4;
+                if (m < a.M) {
+                    const int pos = e.p0 + m;
+                    const f32x4 cs0 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi);
+                    const f32x4 cs1 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi + 2);
+                    const float cx[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sx[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+                    float res[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) res[q] = is_hi ? v[q] * cx[q] + o[q] * sx[q] : v[q] * cx[q] - o[q] * sx[q];
+                    const int f = fi + (is_hi ? half : 0);
+                    if (part == 0) {
+                        pk_store4(e.q_hi, e.q_lo, m, h * e.hd + f, KTd, res);
+                    } else {
+                        const int blk = e.bt[pos / e.BT];
+                        __bf16* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + f;
+                        bf16x4 kb;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) kb[q] = (__bf16)res[q];
+                        *(bf16x4*)kp = kb;
+                    }
+                }
+            } else {
+                // V block, transposed [head][feature][position]: four 2-byte stores per lane; the 16 lanes of a
+                // group cover 16 consecutive positions of one feature
+                const int ml = ml0 + li, m = t.mt0 * 16 + ml;
+                if (m < a.M) {
+                    const float r = rs[ml];
+                    const int pos = e.p0 + m;
+                    const int blk = e.bt[pos / e.BT];
+                    const int f = c * 8 + (rg & 1) * 4 + (rg >= 2 ? half : 0);
+                    __bf16* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + ((size_t)h * e.hd + f) * e.BT +
+                                 (pos % e.BT);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) vp[(size_t)q * e.BT] = (__bf16)(acc[i][j][q] * r);
+                }
+            }
+        }
+    }
+}
+
+// ---- epilogue 2: residual add; operand(s) of what follows; sum-of-squares partial per (row, workgroup)
+struct PfResid {
+    float* x;  // [rows][d] fp32
+    __bf16 *xg_hi, *xg_lo, *xgh_hi, *xgh_lo;  // packed [rows][d]; xgh optional
+    const float *g_next, *g_head;
+    float* ssq_out;  // [rows][ssq_n_out]
+    int ssq_n_out, d;
+};
+
+template <int MTL>
+__global__ __launch_bounds__(256, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<MTL> t;
+    if (!pf_tile_of<MTL>(a, t)) return;
+    constexpr int MW = MTL / 2;
+    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    float* red = rs + MTL * 16;  // [2][MTL*16]
+    f32x4 acc[8][MW];
+    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
+    const int KTd = e.d / 32;
+    float sq[MW];
+#pragma unroll
+    for (int j = 0; j < MW; ++j) sq[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int T = t.nt0 + t.wn * 8 + i;
+        if (T >= a.n_tiles) continue;
+        const int n = T * 16 + rg * 4;
+        const f32x4 gn = *(const f32x4*)(e.g_next + n);
+        f32x4 gh = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (e.g_head) gh = *(const f32x4*)(e.g_head + n);
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int ml = (t.wm * MW + j) * 16 + li, m = t.mt0 * 16 + ml;
+            if (m >= a.M) continue;
+            float* xp = e.x + (size_t)m * e.d + n;
+            f32x4 v = *(const f32x4*)xp;
+            const float r = a.ssq ? rs[ml] : 1.f;
+            v += acc[i][j] * r;
+            *(f32x4*)xp = v;
+            float o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                o[q] = v[q] * gn[q];
+                sq[j] += v[q] * v[q];
+            }
+            pk_store4(e.xg_hi, e.xg_lo, m, n, KTd, o);
+            if (e.g_head) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o[q] = v[q] * gh[q];
+                pk_store4(e.xgh_hi, e.xgh_lo, m, n, KTd, o);
+            }
+        }
+    }
+    // sum of squares of this workgroup's 256 columns per row: over the four lane groups, then the two waves
+#pragma unroll
+    for (int j = 0; j < MW; ++j) {
+        float s = sq[j];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (rg == 0) red[t.wn * (MTL * 16) + (t.wm * MW + j) * 16 + li] = s;
+    }
+    __syncthreads();
+    for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
+        const int m = t.mt0 * 16 + ml;
+        if (m < a.M) e.ssq_out[(size_t)m * e.ssq_n_out + t.n_wg] = red[ml] + red[MTL * 16 + ml];
+    }
+}
+
+// ---- epilogue 3: SwiGLU.  Tile j of the packed gate|up matrix: rows 0-7 gate features 8j.., rows 8-15 the up features
+template <int MTL>
+__global__ __launch_bounds__(256, 2) void pf_swiglu_kernel(PfArgs a, __bf16* act_hi, __bf16* act_lo, int F) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<MTL> t;
+    if (!pf_tile_of<MTL>(a, t)) return;
+    constexpr int MW = MTL / 2;
+    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    f32x4 acc[8][MW];
+    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
+    const int KTf = F / 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int T = t.nt0 + t.wn * 8 + i;
+        if (T >= a.n_tiles) continue;
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int ml = (t.wm * MW + j) * 16 + li, m = t.mt0 * 16 + ml;
+            const f32x4 v = acc[i][j] * rs[ml];
+            f32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = __shfl_xor(v[q], 32);
+            if (rg < 2 && m < a.M) {
+                float res[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) res[q] = v[q] / (1.0f + expf(-v[q])) * o[q];
+                pk_store4(act_hi, act_lo, m, T * 8 + rg * 4, KTf, res);
+            }
+        }
+    }
+}
+
+// ---- epilogue 4: a head on every row: per (row, workgroup) max, arg max and sum of exponentials of its 256 logits
+struct PfHead {
+    HeadPartial* partials;  // [rows][n_wgN]
+    int V;
+};
+
+__device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, float s2, int i2) {
+    if (m2 > m || (m2 == m && i2 < i)) {
+        s = s * expf(m - m2) + s2;
+        m = m2;
+        i = i2;
+    } else if (m2 > -INFINITY) {
+        s = s + s2 * expf(m2 - m);
+    }
+}
+
+template <int MTL>
+__global__ __launch_bounds__(256, 2) void pf_head_kernel(PfArgs a, PfHead e) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<MTL> t;
+    if (!pf_tile_of<MTL>(a, t)) return;
+    constexpr int MW = MTL / 2;
+    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    float* red = rs + MTL * 16;  // wave wn = 1 hands (max, sum) over here, the index in a second array
+    f32x4 acc[8][MW];
+    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    int* redi = (int*)pf_lds;  // (the stage buffers are free now)
+    const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < MW; ++j) {
+        const int ml = (t.wm * MW + j) * 16 + li;
+        const float r = rs[ml];
+        float mx = -INFINITY, sm = 0.f;
+        int ix = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int n = (t.nt0 + t.wn * 8 + i) * 16 + rg * 4;
+            if (n >= e.V) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float z = acc[i][j][q] * r;
+                if (z > mx) {
+                    mx = z;
+                    ix = n + q;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int n = (t.nt0 + t.wn * 8 + i) * 16 + rg * 4;
+            if (n >= e.V) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sm += expf(acc[i][j][q] * r - mx);
+        }
+        // the four lane groups of a row, in a fixed order
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+            const float m2 = __shfl_xor(mx, o), s2 = __shfl_xor(sm, o);
+            const int i2 = __shfl_xor(ix, o);
+            if (lane & o) {  // the upper partner takes (lower, upper) order as well, so both end up equal
+                float m1 = m2, s1 = s2;
+                int i1 = i2;
+                pf_merge(m1, s1, i1, mx, sm, ix);
+                mx = m1;
+                sm = s1;
+                ix = i1;
+            } else {
+                pf_merge(mx, sm, ix, m2, s2, i2);
+            }
+        }
+        if (t.wn == 1 && rg == 0) {
+            red[ml] = mx;
+            red[MTL * 16 + ml] = sm;
+            redi[ml] = ix;
+        }
+        __syncthreads();
+        if (t.wn == 0 && rg == 0) {
+            pf_merge(mx, sm, ix, red[ml], red[MTL * 16 + ml], redi[ml]);
+            const int m = t.mt0 * 16 + ml;
+            if (m < a.M) {
+                HeadPartial p;
+                p.max = mx;
+                p.sum = sm;
+                p.idx = ix;
+                p.pad = 0;
+                e.partials[(size_t)m * a.n_wgN + t.n_wg] = p;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// one wave per row: merges the row's partials in workgroup order; token = arg max, confidence = 1 / sum exp(z - max)
+__global__ __launch_bounds__(64) void pf_head_merge_kernel(const HeadPartial* __restrict__ partials, int n_wg, int M,
+                                                           int32_t* __restrict__ tok, float* __restrict__ conf) {
+    const int m = blockIdx.x, lane = threadIdx.x;
+    if (m >= M) return;
+    float mx = -INFINITY, sm = 0.f;
+    int ix = 0x7fffffff;
+    for (int w = lane; w < n_wg; w += 64) {
+        const HeadPartial p = partials[(size_t)m * n_wg + w];
+        pf_merge(mx, sm, ix, p.max, p.sum, p.idx);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float m2 = __shfl_xor(mx, o), s2 = __shfl_xor(sm, o);
+        const int i2 = __shfl_xor(ix, o);
+        if (lane & o) {
+            float m1 = m2, s1 = s2;
+            int i1 = i2;
+            pf_merge(m1, s1, i1, mx, sm, ix);
+            mx = m1;
+            sm = s1;
+            ix = i1;
+        } else {
+            pf_merge(mx, sm, ix, m2, s2, i2);
+        }
+    }
+    if (lane == 0) {
+        tok[m] = ix;
+        conf[m] = 1.0f / sm;
+    }
+}
+
+// ---- embedding rows -> residual stream, operand of layer 1, sum-of-squares partials (one per 256 columns)
+__global__ __launch_bounds__(256) void pf_embed_kernel(const __bf16* __restrict__ embed, const int32_t* __restrict__ tokens, int d,
+                                                       const float* __restrict__ g_next, float* __restrict__ x,
+                                                       __bf16* __restrict__ xg_hi, __bf16* __restrict__ xg_lo,
+                                                       float* __restrict__ ssq, int ssq_n) {
+    __shared__ float red[4];
+    const int m = blockIdx.x, KTd = d / 32;
+    const __bf16* er = embed + (size_t)tokens[m] * d;
+    for (int c0 = 0, part = 0; c0 < d; c0 += 256, ++part) {
+        const int col = c0 + threadIdx.x;
+        float v = 0.f;
+        if (col < d) {
+            v = (float)er[col];
+            x[(size_t)m * d + col] = v;
+            const float o = v * g_next[col];
+            const __bf16 h = (__bf16)o;
+            const size_t pi = pk_index(m, col, KTd);
+            xg_hi[pi] = h;
+            xg_lo[pi] = (__bf16)(o - (float)h);
+        }
+        float s = v * v;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) ssq[(size_t)m * ssq_n + part] = (red[0] + red[1]) + (red[2] + red[3]);
+        __syncthreads();
+    }
+}
+
+// ---- one row of the residual stream handed to the decode-side residual store (row-major operands, one
+// sum-of-squares entry holding the whole sum), so that the decode heads can run on it
+__global__ __launch_bounds__(256) void pf_export_row_kernel(const float* __restrict__ x, int d, const float* __restrict__ g_a,
+                                                            const float* __restrict__ g_b, float* __restrict__ dx,
+                                                            __bf16* __restrict__ dxg, __bf16* __restrict__ dxgh, size_t lo_off,
+                                                            float* __restrict__ dssq, int ssq_stride) {
+    __shared__ float red[4];
+    float s = 0.f;
+    for (int col = threadIdx.x; col < d; col += 256) {
+        const float v = x[col];
+        dx[col] = v;
+        float o = v * g_a[col];
+        __bf16 h = (__bf16)o;
+        dxg[col] = h;
+        dxg[lo_off + col] = (__bf16)(o - (float)h);
+        if (g_b) {
+            o = v * g_b[col];
+            h = (__bf16)o;
+            dxgh[col] = h;
+            dxgh[lo_off + col] = (__bf16)(o - (float)h);
+        }
+        s += v * v;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    for (int i = threadIdx.x; i < ssq_stride; i += 256) dssq[i] = i == 0 ? (red[0] + red[1]) + (red[2] + red[3]) : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// causal attention over many query rows of one sequence.  A wave owns 16 consecutive query positions of
+// one head and walks the keys 0 .. its last position in tiles of 32, with the arithmetic of the decode
+// kernel (S^T = K Q^T so that P^T is already a B operand; q and P as two bf16 terms; K, V^T tiles read
+// straight from the paged cache into operand order).  No LDS, no cross-wave traffic.
+// ---------------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ q_hi, const u32x4* __restrict__ q_lo,
+                                                      __bf16* __restrict__ out_hi, __bf16* __restrict__ out_lo,
+                                                      const __bf16* __restrict__ layer_base, KvGeom kv,
+                                                      const int32_t* __restrict__ bt, int p0, int M, int d) {
+    constexpr int KK = HD / 32, CG = HD / 16;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
+    // heavier tiles (later positions) first
+    const int qt = (int)(gridDim.x - 1 - blockIdx.x) * 4 + wave, h = blockIdx.y;
+    const int r0 = qt * 16;
+    if (r0 >= M) return;
+    const int nq = min(16, M - r0);
+    const int pos0 = p0 + r0, ctx = pos0 + nq;
+    const int n_tiles = (ctx + 31) >> 5;
+    const int KTd = d / 32;
+    const bool qvalid = li < nq;
+    const int krow0 = (li >> 2) * 8 + (li & 3);  // see attn_mfma_kernel: row permutation of the score tile
+    bf16x8 qh[KK], ql[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const size_t qi = ((size_t)qt * KTd + h * KK + kk) * 64 + lane;
+        qh[kk] = __builtin_bit_cast(bf16x8, q_hi[qi]);
+        ql[kk] = __builtin_bit_cast(bf16x8, q_lo[qi]);
+    }
+    struct TileRegs {
+        u32x4 k[2 * KK];
+        u32x4 v[CG];
+    };
+    auto issue = [&](int t, TileRegs& r) {
+        const int tb = t << 5;
+        const int blk = bt[tb / kv.BT];
+        const int tin = tb % kv.BT;
+        const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + tin) * HD;
+        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * 8;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 32);
+        }
+#pragma unroll
+        for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (size_t)(c * 16 + li) * kv.BT + lg * 8);
+    };
+    const float scale = 1.0f / sqrtf((float)HD);
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 o[CG];
+#pragma unroll
+    for (int c = 0; c < CG; ++c) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    TileRegs cur, nxt;
+    issue(0, cur);
+    for (int t = 0; t < n_tiles; ++t) {
+        if (t + 1 < n_tiles) issue(t + 1, nxt);
+        const int tb = t << 5;
+        f32x4 sacc[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            sacc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, cur.k[sub * KK + kk]);
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, ql[kk], sacc[sub], 0, 0, 0);
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qh[kk], sacc[sub], 0, 0, 0);
+            }
+        }
+        float pv[8];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int pa = tb + lg * 8 + e;
+            const float val = (qvalid && pa <= pos0 + li) ? sacc[e >> 2][e & 3] * scale : -INFINITY;
+            pv[e] = val;
+            tmax = fmaxf(tmax, val);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        float corr = 1.f, psum = 0.f;
+        if (m_new == -INFINITY) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv[e] = 0.f;
+        } else {
+            corr = expf(m_run - m_new);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = expf(pv[e] - m_new);
+                psum += pv[e];
+            }
+        }
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+        bf16x8 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const __bf16 hi = (__bf16)pv[e];
+            ph[e] = hi;
+            pl[e] = (__bf16)(pv[e] - (float)hi);
+        }
+        const bool ragged = tb + 32 > ctx;  // positions beyond the context hold unknown bits: zero them
+#pragma unroll
+        for (int c = 0; c < CG; ++c) {
+            bf16x8 vf = __builtin_bit_cast(bf16x8, cur.v[c]);
+            if (ragged) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (tb + lg * 8 + e >= ctx) vf[e] = (__bf16)0.f;
+            }
+            o[c] = o[c] * corr;
+            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
+            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
+        }
+        cur = nxt;
+    }
+    // O^T: lane (query li, group lg) holds features c*16 + lg*4 .. +3
+    if (qvalid) {
+        const float inv = 1.0f / l_run;
+#pragma unroll
+        for (int c = 0; c < CG; ++c) {
+            float res[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) res[r] = o[c][r] * inv;
+            pk_store4(out_hi, out_lo, r0 + li, h * HD + c * 16 + lg * 4, KTd, res);
+        }
+    }
+}
+
+template <int MTL>
+int pf_grid(const PfArgs& a) {
+    return ((a.n_wgN + 7) / 8) * 8 * a.n_wgM;
+}
+
+PfArgs pf_args(const PfGemm& g, int MTL) {
+    PfArgs a;
+    a.W = (const u32x4*)g.W;
+    a.Xh = (const u32x4*)g.A_hi;
+    a.Xl = (const u32x4*)g.A_lo;
+    a.KT = g.K / 32;
+    a.n_tiles = g.N / 16;
+    a.m_tiles = (g.M + 15) / 16;
+    a.n_wgN = (g.N + 255) / 256;
+    a.n_wgM = (g.M + MTL * 16 - 1) / (MTL * 16);
+    a.M = g.M;
+    a.N = g.N;
+    a.ssq = g.ssq;
+    a.ssq_n = g.ssq_n;
+    a.inv_d = g.inv_d;
+    a.eps = g.eps;
+    return a;
+}
+
+// rows per workgroup tile: 128, or 64 when 128 would leave CUs without work
+int pf_mtl(const PfGemm& g) {
+    const long wgs128 = (long)((g.N + 255) / 256) * ((g.M + 127) / 128);
+    return wgs128 >= 384 ? 8 : 4;
+}
+
+template <typename K>
+hipError_t pf_set_lds(K kernel, size_t bytes) {
+    return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+}  // namespace
+
+#define PF_DISPATCH(KERNEL, ...)                                                                      \
+    do {                                                                                              \
+        if (pf_mtl(g) == 8) {                                                                         \
+            PfArgs a = pf_args(g, 8);                                                                 \
+            static hipError_t once = pf_set_lds(KERNEL<8>, pf_lds_bytes<8>());                        \
+            if (once != hipSuccess) return once;                                                      \
+            EE_LAUNCH_SM(KERNEL<8>, dim3(pf_grid<8>(a)), dim3(256), pf_lds_bytes<8>(), s, a, __VA_ARGS__); \
+        } else {                                                                                      \
+            PfArgs a = pf_args(g, 4);                                                                 \
+            static hipError_t once = pf_set_lds(KERNEL<4>, pf_lds_bytes<4>());                        \
+            if (once != hipSuccess) return once;                                                      \
+            EE_LAUNCH_SM(KERNEL<4>, dim3(pf_grid<4>(a)), dim3(256), pf_lds_bytes<4>(), s, a, __VA_ARGS__); \
+        }                                                                                             \
+        return hipGetLastError();                                                                     \
+    } while (0)
+
+hipError_t launch_pf_qkv(const PfGemm& g, void* q_hi, void* q_lo, const float* rope_cs, const KvGeom& kv, int layer, const int32_t* bt,
+                         int p0, hipStream_t s) {
+    const int d = g.N / 3;
+    PfQkv e{(__bf16*)q_hi, (__bf16*)q_lo, d, kv.H, kv.hd, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
+            kv.blk_stride, kv.BT, bt, p0};
+    PF_DISPATCH(pf_qkv_kernel, e);
+}
+
+hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, void* xgh_hi, void* xgh_lo, const float* g_next,
+                           const float* g_head, float* ssq_out, int ssq_n_out, hipStream_t s) {
+    PfResid e{x, (__bf16*)xg_hi, (__bf16*)xg_lo, (__bf16*)xgh_hi, (__bf16*)xgh_lo, g_next, g_head, ssq_out, ssq_n_out, g.N};
+    PF_DISPATCH(pf_resid_kernel, e);
+}
+
+hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, hipStream_t s) {
+    PF_DISPATCH(pf_swiglu_kernel, (__bf16*)act_hi, (__bf16*)act_lo, F);
+}
+
+hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, hipStream_t s) {
+    const int n_wg = (g.N + 255) / 256;
+    {
+        PfHead e{partials, g.N};
+        PfArgs a = pf_args(g, 8);
+        static hipError_t once = pf_set_lds(pf_head_kernel<8>, pf_lds_bytes<8>());
+        if (once != hipSuccess) return once;
+        EE_LAUNCH_SM(pf_head_kernel<8>, dim3(pf_grid<8>(a)), dim3(256), pf_lds_bytes<8>(), s, a, e);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    EE_LAUNCH(pf_head_merge_kernel, dim3(g.M), dim3(64), s, (const HeadPartial*)partials, n_wg, g.M, tok, conf);
+    return hipGetLastError();
+}
+
+hipError_t launch_pf_embed(const void* embed, const int32_t* dev_tokens, int M, int d, const float* g_next, float* x, void* xg_hi,
+                           void* xg_lo, float* ssq, int ssq_n, hipStream_t s) {
+    EE_LAUNCH(pf_embed_kernel, dim3(M), dim3(256), s, (const __bf16*)embed, dev_tokens, d, g_next, x, (__bf16*)xg_hi, (__bf16*)xg_lo, ssq,
+              ssq_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
+                                size_t lo_off, float* dssq, int ssq_stride, hipStream_t s) {
+    EE_LAUNCH(pf_export_row_kernel, dim3(1), dim3(256), s, x_row, d, g_a, g_b, dx, (__bf16*)dxg, (__bf16*)dxgh, lo_off, dssq, ssq_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_pf_attention(const void* q_hi, const void* q_lo, void* out_hi, void* out_lo, const KvGeom& kv, int layer,
+                               const int32_t* bt, int p0, int M, int d, hipStream_t s) {
+    const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
+    dim3 grid((M + 63) / 64, kv.H), block(256);
+    switch (kv.hd) {
+        case 32:
+            EE_LAUNCH(pf_attn_kernel<32>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv, bt,
+                      p0, M, d);
+            break;
+        case 64:
+            EE_LAUNCH(pf_attn_kernel<64>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv, bt,
+                      p0, M, d);
+            break;
+        case 128:
+            EE_LAUNCH(pf_attn_kernel<128>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv,
+                      bt, p0, M, d);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ee
