@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel family (extra passes, stderr)")
     ap.add_argument("--cpu-threads", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
+    ap.add_argument("--no-prefill-bench", action="store_true", help="skip the timing of the prompt phase")
+    ap.add_argument("--prefill-only", action="store_true", help="time the prompt phase only and print its figures")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short run for `rocprofv3 --pmc`: one 1-GiB device copy (counter calibration), then 12 decode steps")
     return ap.parse_args()
@@ -100,6 +102,66 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
     if profile_kernel is not None:
         prof = gm.profile_end()
     return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof, tokens=B * steps)
+
+
+MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
+
+
+def prefill_bench(ee, gm, cache, prompt, shape, breakdown):
+    """Times the prompt phase (GEMM path) on one prompt: plain ee_prefill, the scored variant (every head on
+    every position), and the gate|up GEMM alone (HIP events on its dispatches).  Algorithmic flops: 2*P*params
+    of the layers + causal attention; every activation operand is two bf16 terms, so the matrix cores issue
+    twice that."""
+    import torch
+
+    P = len(prompt)
+    d, F, V, L = shape.d_model, shape.d_ff, shape.vocab, shape.n_layers
+    layer_flops = 2.0 * P * (4 * d * d + 3 * d * F) + 4.0 * d * P * (P + 1) / 2
+    head_flops = 2.0 * P * d * V
+
+    def run(scored, kernel=None):
+        cache.reset(0)
+        torch.cuda.synchronize()
+        if kernel is not None:
+            gm.profile_begin(kernel)
+        t0 = time.perf_counter()
+        if scored:
+            ee.prefill_scored(gm, cache, 0, prompt, 1.0)
+        else:
+            ee.prefill(gm, cache, 0, prompt, 1.0)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt, (gm.profile_end() if kernel is not None else None)
+
+    run(False)
+    run(True)
+    plain = min(run(False)[0] for _ in range(3))
+    scored = min(run(True)[0] for _ in range(3))
+    _, (n_sw, ms_sw) = run(False, ee.EE_K_SWIGLU)
+    _, (n_hd, ms_hd) = run(True, ee.EE_K_HEAD)
+    sw_tflops = 2.0 * P * 2 * F * d / (ms_sw / max(n_sw, 1) * 1e-3) / 1e12
+    # scored: the head GEMM dispatches are the first of each pair (GEMM, merge); the last launch is the final-head
+    # decode kernel on the last row: time of the GEMMs alone = scored - plain, over n_exits + 1 heads
+    n_heads = len(shape.exit_layers) + 1
+    hd_tflops = n_heads * head_flops / max(scored - plain, 1e-9) / 1e12
+    out = {
+        "prompt_tokens": P, "ms": plain * 1e3, "prompt_tokens_per_s": P / plain,
+        "algorithmic_tflops": (L * layer_flops + 2.0 * d * V) / plain / 1e12,
+        "scored_ms": scored * 1e3, "scored_heads": n_heads,
+        "scored_algorithmic_tflops": (L * layer_flops + n_heads * head_flops) / scored / 1e12,
+        "head_gemm_algorithmic_tflops_from_difference": hd_tflops,
+        "roofline": {"bound": "mfma", "kernel": "pf_swiglu_kernel (gate|up GEMM over all prompt rows + SwiGLU)",
+                     "achieved": sw_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sw_tflops / MFMA_PEAK_TFLOPS,
+                     "mfma_issue_tflops": 2 * sw_tflops, "mfma_issue_frac": 2 * sw_tflops / MFMA_PEAK_TFLOPS,
+                     "launches": n_sw, "avg_us": ms_sw / max(n_sw, 1) * 1e3, "flops_per_launch": 2.0 * P * 2 * F * d,
+                     "traffic": None},
+    }
+    if breakdown:
+        for k, name in enumerate(ee.KERNEL_NAMES):
+            _, (n, ms) = run(True, k)
+            print(f"[bench] prefill {name:10s} launches {n:5d} avg {ms / max(n, 1) * 1e3:9.2f} us total {ms:8.2f} ms",
+                  file=sys.stderr, flush=True)
+    return out
 
 
 def cpu_baseline(shape, tensors_host, prompt, tau, max_pending, threads):
@@ -177,6 +239,14 @@ def main():
         generate(ee, gm, cache, prompts, 1.0, 2, 10, shape, es, args.max_pending)
         print("[bench] pmc run done", file=sys.stderr)
         return
+    prefill = None
+    if shape.dtype == "bf16" and shape.d_model % 128 == 0 and not args.no_prefill_bench:
+        prefill = prefill_bench(ee, gm, cache, prompts[0], shape, args.breakdown)
+        print(f"[bench] prefill {prefill['prompt_tokens']} tokens: {prefill['ms']:.2f} ms, "
+              f"{prefill['algorithmic_tflops']:.0f} TFLOP/s algorithmic", file=sys.stderr, flush=True)
+        if args.prefill_only:
+            print(json.dumps({"prefill": prefill}), flush=True)
+            return
     generate(ee, gm, cache, prompts, 1.0, 0, 40, shape, es, args.max_pending)  # untimed: clocks and caches warm
     full = generate(ee, gm, cache, prompts, 1.0, args.warmup, args.steps, shape, es, args.max_pending)
     early = generate(ee, gm, cache, prompts, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
@@ -233,6 +303,8 @@ def main():
                      "launches": n_l, "avg_us": ms_l / max(n_l, 1) * 1e3, "bytes_per_launch": w_swiglu,
                      "traffic": traffic},
     }
+    if prefill is not None:
+        out["prefill"] = prefill
     if not args.no_cpu_baseline:
         threads = args.cpu_threads or min(16, os.cpu_count() or 1)
         cache.close()

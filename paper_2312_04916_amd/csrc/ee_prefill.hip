@@ -67,12 +67,17 @@ struct PfArgs {
 // stage, two stages in LDS, the copy of stage k+1 runs while stage k is multiplied.  Two workgroups
 // share a CU, so that one's copy wait and operand reads hide behind the other's MFMAs.
 // ---------------------------------------------------------------------------------------------------
+// NWAVE waves per workgroup, arranged (NWAVE/2) along the features x 2 along the rows: a wave owns
+// WNF = 32/NWAVE weight tiles and MTL/2 row tiles.  The GEMMs run 8 waves (two per SIMD: a single wave
+// cannot issue 16x16x32 MFMAs back to back fast enough to keep the matrix core busy) with one workgroup
+// per CU and four stages; the head kernel keeps 4 waves, two workgroups per CU and two stages (measured
+// equal, and its row reduction is written for two waves along the features).
 template <int MTL>
 struct PfTile {
     int nt0, mt0, n_wg, wn, wm;
 };
 
-template <int MTL>
+template <int MTL, int NWAVE>
 __device__ __forceinline__ bool pf_tile_of(const PfArgs& a, PfTile<MTL>& t) {
     // Workgroups are dealt round-robin to the 8 XCDs: give each XCD whole column panels, all row tiles of
     // a panel back to back, so that a weight panel is fetched from HBM once and then served by that XCD's L2.
@@ -83,17 +88,41 @@ __device__ __forceinline__ bool pf_tile_of(const PfArgs& a, PfTile<MTL>& t) {
     t.nt0 = t.n_wg * PF_NTL;
     t.mt0 = m_wg * MTL;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    t.wn = wave & 1;
-    t.wm = wave >> 1;
+    t.wn = wave % (NWAVE / 2);
+    t.wm = wave / (NWAVE / 2);
     return true;
 }
 
-template <int MTL>
-__device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs, f32x4 (&acc)[8][MTL / 2]) {
+// Stages in LDS: 2 where two workgroups share a CU (the other workgroup's MFMAs cover this one's copy
+// wait), 4 where a CU holds a single workgroup and only a deeper copy queue can cover the latency.
+template <int MTL, int NWAVE>
+constexpr int pf_stages() {
+    return NWAVE == 4 ? 2 : 4;
+}
+
+// The operand reads and the wait counts are written by hand: the compiler would make every LDS read wait
+// for ALL outstanding global->LDS copies (it cannot tell which buffer a copy targets), which would
+// serialise the stages.  vmcnt counts this wave's copies in issue order: stage kt has landed once at most
+// (stages - 2) * FPW younger copies are still in flight.
+#define PF_DSR(dst, base, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(base), "n"(off))
+
+template <int N>
+__device__ __forceinline__ void pf_wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MTL, int NWAVE>
+__device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs,
+                                            f32x4 (&acc)[32 / NWAVE][MTL / 2]) {
+    constexpr int WNF = 32 / NWAVE;
     constexpr int NF = PF_NTL + 2 * MTL;  // fragments (1 KB each) per stage
-    constexpr int FPW = NF / 4;           // copied per wave
+    constexpr int FPW = NF / NWAVE;       // copied per wave
+    constexpr int NST = pf_stages<MTL, NWAVE>();
+    static_assert(NF % NWAVE == 0, "fragments must divide over the waves");
+    static_assert((NST - 2) * FPW < 64, "vmcnt range");
     constexpr int STAGE = NF * 64;        // u32x4 per stage
     constexpr int MW = MTL / 2;
+    static_assert(MW == 2 || MW == 4, "row tiles per wave");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int KT = a.KT;
     const u32x4* src[FPW];
@@ -117,7 +146,6 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             __builtin_amdgcn_global_load_lds(EE_GLB_PTR(src[i] + (size_t)kt * 64), EE_LDS_PTR(lds + st * STAGE + (wave * FPW + i) * 64), 16,
                                              0, 0);
     };
-    issue(0, 0);
     // r[m] = 1/sqrt(mean(x^2)+eps) of this tile's rows, from the producers' partial sums (fixed order)
     for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
         const int m = t.mt0 * 16 + ml;
@@ -131,46 +159,72 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
         rs[ml] = r;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < WNF; ++i)
 #pragma unroll
         for (int j = 0; j < MW; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // (the copy count per iteration is kept uniform: beyond the last stage the last one is fetched again
+    // into a buffer nobody reads any more)
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) issue(p, p < KT ? p : KT - 1);
+    const unsigned lds0 = (unsigned)(size_t)EE_LDS_PTR(lds) + lane * 16;
+    const unsigned woff = t.wn * WNF * 1024, xoff = (PF_NTL + t.wm * MW) * 1024;
+    int st_r = 0, st_w = NST - 1;
     for (int kt = 0; kt < KT; ++kt) {
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies of stage kt have landed
-        __syncthreads();                     // ... and everybody else's; stage kt-1 is no longer being read
-        const u32x4* sb = lds + (kt & 1) * STAGE;
-        u32x4 wf[8], xh[MW], xl[MW];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) wf[i] = sb[(t.wn * 8 + i) * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < MW; ++j) {
-            xh[j] = sb[(PF_NTL + t.wm * MW + j) * 64 + lane];
-            xl[j] = sb[(PF_NTL + MTL + t.wm * MW + j) * 64 + lane];
+        pf_wait_vm<(NST - 2) * FPW>();     // this wave's copies of stage kt have landed
+        __builtin_amdgcn_s_barrier();      // ... and everybody else's; the buffer refilled below is no longer read
+        const unsigned wb = lds0 + st_r * (STAGE * 16) + woff, xb = lds0 + st_r * (STAGE * 16) + xoff;
+        u32x4 wf[WNF], xh[MW], xl[MW];
+        PF_DSR(wf[0], wb, 0); PF_DSR(wf[1], wb, 1024); PF_DSR(wf[2], wb, 2048); PF_DSR(wf[3], wb, 3072);
+        if constexpr (WNF == 8) {
+            PF_DSR(wf[4], wb, 4096); PF_DSR(wf[5], wb, 5120); PF_DSR(wf[6], wb, 6144); PF_DSR(wf[7], wb, 7168);
         }
-        if (kt + 1 < KT) issue((kt + 1) & 1, kt + 1);
+        PF_DSR(xh[0], xb, 0); PF_DSR(xh[1], xb, 1024);
+        PF_DSR(xl[0], xb, MTL * 1024); PF_DSR(xl[1], xb, MTL * 1024 + 1024);
+        if constexpr (MW == 4) {
+            PF_DSR(xh[2], xb, 2048); PF_DSR(xh[3], xb, 3072);
+            PF_DSR(xl[2], xb, MTL * 1024 + 2048); PF_DSR(xl[3], xb, MTL * 1024 + 3072);
+        }
+        issue(st_w, kt + NST - 1 < KT ? kt + NST - 1 : KT - 1);
+        st_r = st_r + 1 == NST ? 0 : st_r + 1;
+        st_w = st_w + 1 == NST ? 0 : st_w + 1;
+        // operands are in registers from here on (and the MFMAs below may not move above this point)
+        if constexpr (WNF == 8 && MW == 4)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(wf[4]), "+v"(wf[5]), "+v"(wf[6]),
+                         "+v"(wf[7]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]), "+v"(xh[3]), "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
+        else if constexpr (WNF == 8)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(wf[4]), "+v"(wf[5]), "+v"(wf[6]),
+                         "+v"(wf[7]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xl[0]), "+v"(xl[1]));
+        else if constexpr (MW == 4)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]),
+                         "+v"(xh[3]), "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xl[0]),
+                         "+v"(xl[1]));
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < WNF; ++i)
 #pragma unroll
             for (int j = 0; j < MW; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xl[j]),
                                                                     acc[i][j], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < WNF; ++i)
 #pragma unroll
             for (int j = 0; j < MW; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xh[j]),
                                                                     acc[i][j], 0, 0, 0);
     }
-    __syncthreads();  // rs[] visible (also when KT were 0)
+    pf_wait_vm<0>();  // the surplus copies too, before the epilogue reuses the stage buffers
+    __syncthreads();  // (also makes rs[] visible)
 }
 
-template <int MTL>
-constexpr size_t pf_lds_bytes() {
-    return 2 * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 3;  // two stages + rs[] + two reduction rows
+template <int MTL, int NWAVE>
+constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to four reduction rows
+    return pf_stages<MTL, NWAVE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 5;
 }
 
-template <int MTL>
+template <int MTL, int NWAVE>
 __device__ __forceinline__ float* pf_rs_ptr(u32x4* lds) {
-    return (float*)(lds + 2 * (PF_NTL + 2 * MTL) * 64);
+    return (float*)(lds + pf_stages<MTL, NWAVE>() * (PF_NTL + 2 * MTL) * 64);
 }
 
 // ---- epilogue 1: RMS scale, rotary embedding, q (packed), k and v into the paged cache
@@ -185,21 +239,22 @@ struct PfQkv {
     int p0;             // position of row 0 (multiple of 16)
 };
 
-template <int MTL>
-__global__ __launch_bounds__(256, 2) void pf_qkv_kernel(PfArgs a, PfQkv e) {
+template <int MTL, int NWAVE>
+__global__ __launch_bounds__(NWAVE * 64, 2) void pf_qkv_kernel(PfArgs a, PfQkv e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
-    if (!pf_tile_of<MTL>(a, t)) return;
+    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+    constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
     const int tiles_per_part = e.d / 16, per_head = e.hd / 16, half = e.hd / 2;
-    f32x4 acc[8][MW];
-    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    f32x4 acc[WNF][MW];
+    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int T = t.nt0 + t.wn * 8 + i;
+    for (int i = 0; i < WNF; ++i) {
+        const int T = t.nt0 + t.wn * WNF + i;
         if (T >= a.n_tiles) continue;  // (uniform over the wave)
         const int part = T / tiles_per_part, rem = T % tiles_per_part;
         const int h = rem / per_head, c = rem % per_head;
@@ -265,24 +320,25 @@ struct PfResid {
     int ssq_n_out, d;
 };
 
-template <int MTL>
-__global__ __launch_bounds__(256, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
+template <int MTL, int NWAVE>
+__global__ __launch_bounds__(NWAVE * 64, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
-    if (!pf_tile_of<MTL>(a, t)) return;
+    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+    constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL>(pf_lds);
-    float* red = rs + MTL * 16;  // [2][MTL*16]
-    f32x4 acc[8][MW];
-    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
+    f32x4 acc[WNF][MW];
+    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
     float sq[MW];
 #pragma unroll
     for (int j = 0; j < MW; ++j) sq[j] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int T = t.nt0 + t.wn * 8 + i;
+    for (int i = 0; i < WNF; ++i) {
+        const int T = t.nt0 + t.wn * WNF + i;
         if (T >= a.n_tiles) continue;
         const int n = T * 16 + rg * 4;
         const f32x4 gn = *(const f32x4*)(e.g_next + n);
@@ -311,7 +367,7 @@ __global__ __launch_bounds__(256, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
             }
         }
     }
-    // sum of squares of this workgroup's 256 columns per row: over the four lane groups, then the two waves
+    // sum of squares of this workgroup's 256 columns per row: over the four lane groups, then the waves along the features
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
         float s = sq[j];
@@ -322,25 +378,31 @@ __global__ __launch_bounds__(256, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
     __syncthreads();
     for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
         const int m = t.mt0 * 16 + ml;
-        if (m < a.M) e.ssq_out[(size_t)m * e.ssq_n_out + t.n_wg] = red[ml] + red[MTL * 16 + ml];
+        if (m < a.M) {
+            float sum = red[ml];
+#pragma unroll
+            for (int wv = 1; wv < NWAVE / 2; ++wv) sum += red[wv * (MTL * 16) + ml];
+            e.ssq_out[(size_t)m * e.ssq_n_out + t.n_wg] = sum;
+        }
     }
 }
 
 // ---- epilogue 3: SwiGLU.  Tile j of the packed gate|up matrix: rows 0-7 gate features 8j.., rows 8-15 the up features
-template <int MTL>
-__global__ __launch_bounds__(256, 2) void pf_swiglu_kernel(PfArgs a, __bf16* act_hi, __bf16* act_lo, int F) {
+template <int MTL, int NWAVE>
+__global__ __launch_bounds__(NWAVE * 64, 2) void pf_swiglu_kernel(PfArgs a, __bf16* act_hi, __bf16* act_lo, int F) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
-    if (!pf_tile_of<MTL>(a, t)) return;
+    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+    constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL>(pf_lds);
-    f32x4 acc[8][MW];
-    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    f32x4 acc[WNF][MW];
+    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTf = F / 32;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int T = t.nt0 + t.wn * 8 + i;
+    for (int i = 0; i < WNF; ++i) {
+        const int T = t.nt0 + t.wn * WNF + i;
         if (T >= a.n_tiles) continue;
 #pragma unroll
         for (int j = 0; j < MW; ++j) {
@@ -375,16 +437,18 @@ __device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, f
     }
 }
 
-template <int MTL>
-__global__ __launch_bounds__(256, 2) void pf_head_kernel(PfArgs a, PfHead e) {
+template <int MTL, int NWAVE>
+__global__ __launch_bounds__(NWAVE * 64, 2) void pf_head_kernel(PfArgs a, PfHead e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
-    if (!pf_tile_of<MTL>(a, t)) return;
+    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+    constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    static_assert(NWAVE == 4, "the merge below is written for two waves along the features");
     float* red = rs + MTL * 16;  // wave wn = 1 hands (max, sum) over here, the index in a second array
-    f32x4 acc[8][MW];
-    pf_mainloop<MTL>(a, t, pf_lds, rs, acc);
+    f32x4 acc[WNF][MW];
+    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
     int* redi = (int*)pf_lds;  // (the stage buffers are free now)
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
 #pragma unroll
@@ -394,8 +458,8 @@ __global__ __launch_bounds__(256, 2) void pf_head_kernel(PfArgs a, PfHead e) {
         float mx = -INFINITY, sm = 0.f;
         int ix = 0x7fffffff;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int n = (t.nt0 + t.wn * 8 + i) * 16 + rg * 4;
+        for (int i = 0; i < WNF; ++i) {
+            const int n = (t.nt0 + t.wn * WNF + i) * 16 + rg * 4;
             if (n >= e.V) continue;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -407,8 +471,8 @@ __global__ __launch_bounds__(256, 2) void pf_head_kernel(PfArgs a, PfHead e) {
             }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int n = (t.nt0 + t.wn * 8 + i) * 16 + rg * 4;
+        for (int i = 0; i < WNF; ++i) {
+            const int n = (t.nt0 + t.wn * WNF + i) * 16 + rg * 4;
             if (n >= e.V) continue;
 #pragma unroll
             for (int q = 0; q < 4; ++q) sm += expf(acc[i][j][q] * r - mx);
@@ -544,63 +608,117 @@ __global__ __launch_bounds__(256) void pf_export_row_kernel(const float* __restr
 }
 
 // ---------------------------------------------------------------------------------------------------
-// causal attention over many query rows of one sequence.  A wave owns 16 consecutive query positions of
-// one head and walks the keys 0 .. its last position in tiles of 32, with the arithmetic of the decode
-// kernel (S^T = K Q^T so that P^T is already a B operand; q and P as two bf16 terms; K, V^T tiles read
-// straight from the paged cache into operand order).  No LDS, no cross-wave traffic.
+// causal attention over many query rows of one sequence.  A workgroup owns 64 consecutive query positions
+// of one head (16 per wave) and walks the keys 0 .. its last position in tiles of 32.  Each K / V^T tile
+// is copied once per workgroup from the paged cache into LDS, already permuted into MFMA operand order
+// by the copy's source addressing (so that the reads back are plain 1 KB wave reads without bank
+// conflicts), through a ring of stages that keeps several tiles in flight; the arithmetic is the decode
+// kernel's (S^T = K Q^T so that P^T is already a B operand; q and P as two bf16 terms).
 // ---------------------------------------------------------------------------------------------------
+constexpr int PFA_STAGES = 4;
+
 template <int HD>
 __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ q_hi, const u32x4* __restrict__ q_lo,
                                                       __bf16* __restrict__ out_hi, __bf16* __restrict__ out_lo,
                                                       const __bf16* __restrict__ layer_base, KvGeom kv,
                                                       const int32_t* __restrict__ bt, int p0, int M, int d) {
     constexpr int KK = HD / 32, CG = HD / 16;
+    constexpr int NCH = 2 * KK + CG;  // 1 KB chunks per tile: K score halves x k-steps, then V feature groups
+    constexpr int FPW = NCH / 4;      // copied per wave
+    constexpr int STAGE = NCH * 64;   // u32x4
+    static_assert(NCH % 4 == 0, "chunks must divide over the four waves");
+    extern __shared__ u32x4 pfa_lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
-    // heavier tiles (later positions) first
-    const int qt = (int)(gridDim.x - 1 - blockIdx.x) * 4 + wave, h = blockIdx.y;
+    // heavier blocks (later positions) first
+    const int qb = (int)(gridDim.x - 1 - blockIdx.x), h = blockIdx.y;
+    const int qt = qb * 4 + wave;
     const int r0 = qt * 16;
-    if (r0 >= M) return;
-    const int nq = min(16, M - r0);
+    const int nq = max(0, min(16, M - r0));
     const int pos0 = p0 + r0, ctx = pos0 + nq;
-    const int n_tiles = (ctx + 31) >> 5;
+    const int my_tiles = nq > 0 ? (ctx + 31) >> 5 : 0;
+    const int wg_last = min(M, qb * 64 + 64);                 // rows of this workgroup end here
+    const int wg_tiles = (p0 + wg_last + 31) >> 5;            // >= my_tiles of every wave
     const int KTd = d / 32;
     const bool qvalid = li < nq;
     const int krow0 = (li >> 2) * 8 + (li & 3);  // see attn_mfma_kernel: row permutation of the score tile
     bf16x8 qh[KK], ql[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-        const size_t qi = ((size_t)qt * KTd + h * KK + kk) * 64 + lane;
+        const size_t qi = ((size_t)(nq > 0 ? qt : 0) * KTd + h * KK + kk) * 64 + lane;
         qh[kk] = __builtin_bit_cast(bf16x8, q_hi[qi]);
         ql[kk] = __builtin_bit_cast(bf16x8, q_lo[qi]);
     }
-    struct TileRegs {
-        u32x4 k[2 * KK];
-        u32x4 v[CG];
-    };
-    auto issue = [&](int t, TileRegs& r) {
+    // copy of tile t into stage st: chunk c = wave*FPW + i; this lane's 16 bytes of it
+    auto issue = [&](int st, int t) {
         const int tb = t << 5;
         const int blk = bt[tb / kv.BT];
         const int tin = tb % kv.BT;
         const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + tin) * HD;
         const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * 8;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 32);
+        for (int i = 0; i < FPW; ++i) {
+            const int c = wave * FPW + i;
+            const __bf16* src;
+            if (c < 2 * KK) {
+                const int sub = c / KK, kk = c % KK;
+                src = kbase + (size_t)(krow0 + sub * 4) * HD + kk * 32 + lg * 8;
+            } else {
+                src = vbase + (size_t)((c - 2 * KK) * 16 + li) * kv.BT + lg * 8;
+            }
+            __builtin_amdgcn_global_load_lds(EE_GLB_PTR(src), EE_LDS_PTR(pfa_lds + st * STAGE + c * 64), 16, 0, 0);
         }
-#pragma unroll
-        for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (size_t)(c * 16 + li) * kv.BT + lg * 8);
     };
     const float scale = 1.0f / sqrtf((float)HD);
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 o[CG];
 #pragma unroll
     for (int c = 0; c < CG; ++c) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    TileRegs cur, nxt;
-    issue(0, cur);
-    for (int t = 0; t < n_tiles; ++t) {
-        if (t + 1 < n_tiles) issue(t + 1, nxt);
+#pragma unroll
+    for (int p = 0; p < PFA_STAGES - 1; ++p) issue(p, p < wg_tiles ? p : wg_tiles - 1);
+    const unsigned lds0 = (unsigned)(size_t)EE_LDS_PTR(pfa_lds) + lane * 16;
+    int st_r = 0, st_w = PFA_STAGES - 1;
+    for (int t = 0; t < wg_tiles; ++t) {
+        pf_wait_vm<(PFA_STAGES - 2) * FPW>();
+        __builtin_amdgcn_s_barrier();
+        const unsigned sb = lds0 + st_r * (STAGE * 16);
+        u32x4 kf[2 * KK], vf_[CG];
+        PF_DSR(kf[0], sb, 0);
+        PF_DSR(kf[1], sb, 1024);
+        if constexpr (KK >= 2) {
+            PF_DSR(kf[2], sb, 2048);
+            PF_DSR(kf[3], sb, 3072);
+        }
+        if constexpr (KK == 4) {
+            PF_DSR(kf[4], sb, 4096);
+            PF_DSR(kf[5], sb, 5120);
+            PF_DSR(kf[6], sb, 6144);
+            PF_DSR(kf[7], sb, 7168);
+        }
+        PF_DSR(vf_[0], sb, 2 * KK * 1024);
+        PF_DSR(vf_[1], sb, 2 * KK * 1024 + 1024);
+        if constexpr (CG >= 4) {
+            PF_DSR(vf_[2], sb, 2 * KK * 1024 + 2048);
+            PF_DSR(vf_[3], sb, 2 * KK * 1024 + 3072);
+        }
+        if constexpr (CG == 8) {
+            PF_DSR(vf_[4], sb, 2 * KK * 1024 + 4096);
+            PF_DSR(vf_[5], sb, 2 * KK * 1024 + 5120);
+            PF_DSR(vf_[6], sb, 2 * KK * 1024 + 6144);
+            PF_DSR(vf_[7], sb, 2 * KK * 1024 + 7168);
+        }
+        issue(st_w, t + PFA_STAGES - 1 < wg_tiles ? t + PFA_STAGES - 1 : wg_tiles - 1);
+        st_r = st_r + 1 == PFA_STAGES ? 0 : st_r + 1;
+        st_w = st_w + 1 == PFA_STAGES ? 0 : st_w + 1;
+        if constexpr (HD == 128)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]),
+                         "+v"(kf[7]), "+v"(vf_[0]), "+v"(vf_[1]), "+v"(vf_[2]), "+v"(vf_[3]), "+v"(vf_[4]), "+v"(vf_[5]), "+v"(vf_[6]),
+                         "+v"(vf_[7]));
+        else if constexpr (HD == 64)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(vf_[0]), "+v"(vf_[1]), "+v"(vf_[2]),
+                         "+v"(vf_[3]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(vf_[0]), "+v"(vf_[1]));
+        if (t >= my_tiles) continue;  // (uniform over the wave) keys beyond this wave's rows
         const int tb = t << 5;
         f32x4 sacc[2];
 #pragma unroll
@@ -608,9 +726,9 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
             sacc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 kf = __builtin_bit_cast(bf16x8, cur.k[sub * KK + kk]);
-                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, ql[kk], sacc[sub], 0, 0, 0);
-                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qh[kk], sacc[sub], 0, 0, 0);
+                const bf16x8 kfr = __builtin_bit_cast(bf16x8, kf[sub * KK + kk]);
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, ql[kk], sacc[sub], 0, 0, 0);
+                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, qh[kk], sacc[sub], 0, 0, 0);
             }
         }
         float pv[8];
@@ -648,10 +766,10 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
             ph[e] = hi;
             pl[e] = (__bf16)(pv[e] - (float)hi);
         }
-        const bool ragged = tb + 32 > ctx;  // positions beyond the context hold unknown bits: zero them
+        const bool ragged = tb + 32 > ctx;  // positions beyond this wave's context may hold unknown bits: zero them
 #pragma unroll
         for (int c = 0; c < CG; ++c) {
-            bf16x8 vf = __builtin_bit_cast(bf16x8, cur.v[c]);
+            bf16x8 vf = __builtin_bit_cast(bf16x8, vf_[c]);
             if (ragged) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -661,8 +779,8 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
         }
-        cur = nxt;
     }
+    pf_wait_vm<0>();  // surplus copies of the ring
     // O^T: lane (query li, group lg) holds features c*16 + lg*4 .. +3
     if (qvalid) {
         const float inv = 1.0f / l_run;
@@ -700,10 +818,14 @@ PfArgs pf_args(const PfGemm& g, int MTL) {
     return a;
 }
 
-// rows per workgroup tile: 128, or 64 when 128 would leave CUs without work
+// Rows per workgroup tile, 128 or 64.  One workgroup occupies a CU, so a launch takes about
+// ceil(workgroups / 256) rounds of a time proportional to the tile's rows: take the cheaper, 128 on a tie
+// (half the activation traffic from L2).
 int pf_mtl(const PfGemm& g) {
-    const long wgs128 = (long)((g.N + 255) / 256) * ((g.M + 127) / 128);
-    return wgs128 >= 384 ? 8 : 4;
+    const long n_wgN = (g.N + 255) / 256;
+    const long r8 = (n_wgN * ((g.M + 127) / 128) + 255) / 256 * 8;
+    const long r4 = (n_wgN * ((g.M + 63) / 64) + 255) / 256 * 4;
+    return r4 < r8 ? 4 : 8;
 }
 
 template <typename K>
@@ -713,20 +835,22 @@ hipError_t pf_set_lds(K kernel, size_t bytes) {
 
 }  // namespace
 
-#define PF_DISPATCH(KERNEL, ...)                                                                      \
-    do {                                                                                              \
-        if (pf_mtl(g) == 8) {                                                                         \
-            PfArgs a = pf_args(g, 8);                                                                 \
-            static hipError_t once = pf_set_lds(KERNEL<8>, pf_lds_bytes<8>());                        \
-            if (once != hipSuccess) return once;                                                      \
-            EE_LAUNCH_SM(KERNEL<8>, dim3(pf_grid<8>(a)), dim3(256), pf_lds_bytes<8>(), s, a, __VA_ARGS__); \
-        } else {                                                                                      \
-            PfArgs a = pf_args(g, 4);                                                                 \
-            static hipError_t once = pf_set_lds(KERNEL<4>, pf_lds_bytes<4>());                        \
-            if (once != hipSuccess) return once;                                                      \
-            EE_LAUNCH_SM(KERNEL<4>, dim3(pf_grid<4>(a)), dim3(256), pf_lds_bytes<4>(), s, a, __VA_ARGS__); \
-        }                                                                                             \
-        return hipGetLastError();                                                                     \
+#define PF_DISPATCH(KERNEL, ...)                                                                          \
+    do {                                                                                                  \
+        if (pf_mtl(g) == 8) {                                                                             \
+            PfArgs a = pf_args(g, 8);                                                                     \
+            constexpr size_t lds_b = pf_lds_bytes<8, 8>();                                                \
+            static hipError_t once = pf_set_lds(KERNEL<8, 8>, lds_b);                                     \
+            if (once != hipSuccess) return once;                                                          \
+            EE_LAUNCH_SM((KERNEL<8, 8>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, __VA_ARGS__);       \
+        } else {                                                                                          \
+            PfArgs a = pf_args(g, 4);                                                                     \
+            constexpr size_t lds_b = pf_lds_bytes<4, 8>();                                                \
+            static hipError_t once = pf_set_lds(KERNEL<4, 8>, lds_b);                                     \
+            if (once != hipSuccess) return once;                                                          \
+            EE_LAUNCH_SM((KERNEL<4, 8>), dim3(pf_grid<4>(a)), dim3(512), lds_b, s, a, __VA_ARGS__);       \
+        }                                                                                                 \
+        return hipGetLastError();                                                                         \
     } while (0)
 
 hipError_t launch_pf_qkv(const PfGemm& g, void* q_hi, void* q_lo, const float* rope_cs, const KvGeom& kv, int layer, const int32_t* bt,
@@ -752,9 +876,10 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
     {
         PfHead e{partials, g.N};
         PfArgs a = pf_args(g, 8);
-        static hipError_t once = pf_set_lds(pf_head_kernel<8>, pf_lds_bytes<8>());
+        constexpr size_t lds_b = pf_lds_bytes<8, 4>();
+        static hipError_t once = pf_set_lds(pf_head_kernel<8, 4>, lds_b);
         if (once != hipSuccess) return once;
-        EE_LAUNCH_SM(pf_head_kernel<8>, dim3(pf_grid<8>(a)), dim3(256), pf_lds_bytes<8>(), s, a, e);
+        EE_LAUNCH_SM((pf_head_kernel<8, 4>), dim3(pf_grid<8>(a)), dim3(256), lds_b, s, a, e);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
@@ -779,18 +904,19 @@ hipError_t launch_pf_attention(const void* q_hi, const void* q_lo, void* out_hi,
                                const int32_t* bt, int p0, int M, int d, hipStream_t s) {
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
     dim3 grid((M + 63) / 64, kv.H), block(256);
+    const size_t lds = (size_t)PFA_STAGES * (2 * (kv.hd / 32) + kv.hd / 16) * 1024;  // at most 64 KB
     switch (kv.hd) {
         case 32:
-            EE_LAUNCH(pf_attn_kernel<32>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv, bt,
-                      p0, M, d);
+            EE_LAUNCH_SM(pf_attn_kernel<32>, grid, block, lds, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo,
+                         lb, kv, bt, p0, M, d);
             break;
         case 64:
-            EE_LAUNCH(pf_attn_kernel<64>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv, bt,
-                      p0, M, d);
+            EE_LAUNCH_SM(pf_attn_kernel<64>, grid, block, lds, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo,
+                         lb, kv, bt, p0, M, d);
             break;
         case 128:
-            EE_LAUNCH(pf_attn_kernel<128>, grid, block, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo, lb, kv,
-                      bt, p0, M, d);
+            EE_LAUNCH_SM(pf_attn_kernel<128>, grid, block, lds, s, (const u32x4*)q_hi, (const u32x4*)q_lo, (__bf16*)out_hi, (__bf16*)out_lo,
+                         lb, kv, bt, p0, M, d);
             break;
         default: return hipErrorInvalidValue;
     }
