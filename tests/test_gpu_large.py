@@ -116,3 +116,37 @@ def test_c3_full_size_invariants():
     finally:
         cache.close()
         gm.close()
+
+
+def test_c3_shape_prompt_phase_scored():
+    """Prompt phase through the GEMM path at the 7B widths (2 layers, exit after the first): cached K/V of every
+    position and both heads scored on sampled positions against the oracle's cache-free forward."""
+    from common import GUARD
+    shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
+    n = 200
+    O.set_threads(16)
+    om, gm = build_pair(shape, 0, max_positions=256)
+    try:
+        print("case: C3-shaped scored prompt phase", flush=True)
+        p = prompt_tokens(shape.vocab, n, 5).numpy()
+        cache = ee.KvCache(gm, 1, 256, 64, 15)
+        tok, ex, conf, ptok, pconf = ee.prefill_scored(gm, cache, 0, p, 0.2)
+        hid, ko, vo = om.forward_sequence(p)
+        for l in range(2):
+            k, v = cache.read(0, l, 0, n)
+            assert rel_err(k, ko[l]) <= TOL and rel_err(v, vo[l]) <= TOL, (l, rel_err(k, ko[l]), rel_err(v, vo[l]))
+        assert rel_err(cache.read_hidden(0), hid[2][n - 1]) <= TOL
+        forced = 0
+        for hi, layer in enumerate((1, 2)):
+            for pos in list(range(0, n, 9)) + list(range(n - 6, n)):
+                _, dg = om.head_row(hi, hid[layer][pos])
+                if int(ptok[hi, pos]) != dg["argmax"]:
+                    assert dg["top1"] - dg["top2"] < GUARD and int(ptok[hi, pos]) == dg["arg2"], (hi, pos, dg)
+                    forced += 1
+                assert abs(float(pconf[hi, pos]) - dg["conf"]) <= TOL, (hi, pos, float(pconf[hi, pos]), dg["conf"])
+        assert forced <= 3
+        assert abs(float(conf[1]) - float(pconf[1, n - 1])) <= 1e-4
+        cache.close()
+    finally:
+        gm.close()
+        O.set_threads(1)
