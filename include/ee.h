@@ -119,6 +119,10 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
 
 int ee_model_free(ee_model* m);
 
+/* Test hook: the GEMMs of a step with many rows give a workgroup several 16-column tiles as long as at least
+ * n workgroups remain (default 512); tests lower it so that small models reach those kernel variants.
+ * Process-wide. */
+int ee_debug_set_gemm_min_workgroups(int n);
 /* Test hook: if dev_logits != NULL, every head evaluation also stores its fp32 logits there,
  * [row][vocab] for the rows it evaluates (capacity_rows rows).  NULL switches it off. */
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);

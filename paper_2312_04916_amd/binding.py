@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
@@ -64,6 +64,7 @@ def lib():
                                     C.POINTER(vp)]
         L.ee_model_free.argtypes = [vp]
         L.ee_debug_set_logits.argtypes = [vp, vp, C.c_int]
+        L.ee_debug_set_gemm_min_workgroups.argtypes = [C.c_int]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
@@ -241,6 +242,11 @@ class KvCache:
             self.close()
         except Exception:
             pass
+
+
+def set_gemm_min_workgroups(n: int) -> None:
+    """ee_debug_set_gemm_min_workgroups (test hook, process-wide)."""
+    _chk(lib().ee_debug_set_gemm_min_workgroups(int(n)), "ee_debug_set_gemm_min_workgroups")
 
 
 def prefill(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], threshold: float, stream=None):

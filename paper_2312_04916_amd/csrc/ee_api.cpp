@@ -86,7 +86,7 @@ WeightLayout weight_layout(const ee_config& c) {
 struct WorkspaceLayout {
     size_t upload, upload_bytes;  // [descs][btab][tokens], one host-to-device copy per step
     size_t descs, btab, tokens;
-    size_t q, attn, act, partials, counters, attn_part, stage, total;
+    size_t q, attn, act, xg_pk, head_pk, partials, counters, attn_part, stage, total;
     int max_blocks_per_seq;
     // prompt phase (bf16 model): buffers for pf_rows positions at a time, activations in the packed operand layout
     int pf_rows;  // 0: the prompt phase runs through the decode kernels in chunks
@@ -109,6 +109,8 @@ int pf_rows_of(const ee_config& c) {
     return r / 128 * 128;
 }
 
+inline size_t rows_padded(int max_rows) { return ((size_t)max_rows + 63) / 64 * 64; }
+
 WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs) {
     WorkspaceLayout w;
     size_t es = esize(c.dtype), d = c.d_model, off = 0;
@@ -124,9 +126,12 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     w.tokens = take(EE_MAX_ROWS * 4);
     w.upload_bytes = off - w.upload;
     size_t terms = c.dtype == EE_BF16 ? 2 : 1;  // bf16 activations are stored as hi and lo terms
-    w.q = take(terms * max_rows * d * es);
-    w.attn = take(terms * max_rows * d * es);
-    w.act = take(terms * max_rows * c.d_ff * es);
+    size_t rows = rows_padded(max_rows);        // (packed arrays hold whole groups of 16 rows)
+    w.q = take(terms * rows * d * es);
+    w.attn = take(terms * rows * d * es);
+    w.act = take(terms * rows * c.d_ff * es);
+    w.xg_pk = take(terms * rows * d * es);
+    w.head_pk = take(terms * 64 * d * es);
     w.partials = take((size_t)(c.vocab / 16) * EE_MAX_SEQS * sizeof(HeadPartial));
     w.counters = take(256 * 4);
     w.attn_part = take(attention_part_floats(max_rows, c.n_heads, c.head_dim) * 4);
@@ -171,7 +176,7 @@ struct ee_model {
     int prof_kernel = -1;               // kernel family being timed, or -1
     std::vector<hipEvent_t> prof_ev;    // event pairs
     size_t prof_used = 0;               // events recorded so far
-    size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? (size_t)max_rows * ld : 0; }  // hi -> lo distance
+    size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? rows_padded(max_rows) * ld : 0; }  // hi -> lo distance
     int n_seg() const { return cfg.n_exits + 1; }
     int seg_begin(int s) const { return s == 0 ? 0 : cfg.exit_layers[s - 1]; }
     int seg_end(int s) const { return s < cfg.n_exits ? cfg.exit_layers[s] : cfg.n_layers; }
@@ -277,6 +282,14 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
     const int d = cf.d_model, F = cf.d_ff, dt = cf.dtype;
     SegDesc* dd = m->dev_desc(di);
     const int32_t* xrow = (const int32_t*)((char*)dd + offsetof(SegDesc, xrow));
+    // More rows than a workgroup can stage in LDS: the GEMMs then take their row operands from packed arrays
+    // (dense rows of this launch in MFMA operand order) that the producing epilogues write, and the segment
+    // starts by packing the rows' x.g operands out of the residual store.
+    const bool pk_d = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, d);
+    const bool pk_F = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, F);
+    char* xg_pk = m->ws + m->wsl.xg_pk;
+    if (pk_d && l0 < l1)
+        HIPCHK(launch_pack_rows(c->xg(), c->xs_lo, d, xrow, T, d, xg_pk, m->lo_rows(d), st));
     for (int l = l0; l < l1; ++l) {
         GemmCommon g{};
         g.dtype = dt;
@@ -290,8 +303,9 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.W = m->wbase + m->wl.qkv[l];
         g.N = 3 * d;
         g.K = d;
-        g.A = c->xg();
-        g.a_lo = c->xs_lo;
+        g.A = pk_d ? (void*)xg_pk : c->xg();
+        g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
+        g.a_packed = pk_d;
         g.lda = d;
         g.arow = xrow;
         g.ssq = c->ssq();
@@ -304,7 +318,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
             Timed t(m, EE_K_ATTN, st);
             HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
                                 (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
-                                gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, st));
+                                gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, pk_d, st));
         }
         // x += W_o a ; operand for the MLP norm
         g.W = m->wbase + m->wl.wo[l];
@@ -312,6 +326,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.K = d;
         g.A = m->ws + m->wsl.attn;
         g.a_lo = m->lo_rows(d);
+        g.a_packed = pk_d;
         g.arow = nullptr;
         g.ssq = nullptr;
         if (att_ns > 0) {
@@ -322,20 +337,22 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         }
         {
             Timed t(m, EE_K_OPROJ, st);
-            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d, st));
+            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d,
+                                     pk_d ? xg_pk : nullptr, m->lo_rows(d), st));
         }
         g.att_part = nullptr;
         // act = silu(W_g h) * (W_u h)
         g.W = m->wbase + m->wl.gu[l];
         g.N = 2 * F;
         g.K = d;
-        g.A = c->xg();
-        g.a_lo = c->xs_lo;
+        g.A = pk_d ? (void*)xg_pk : c->xg();
+        g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
+        g.a_packed = pk_d;
         g.arow = xrow;
         g.ssq = c->ssq();
         {
             Timed t(m, EE_K_SWIGLU, st);
-            HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, st));
+            HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, pk_F, st));
         }
         // x += W_d act ; operand for the next layer (or the final head), and for an exit head after this layer
         g.W = m->wbase + m->wl.wd[l];
@@ -343,6 +360,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.K = F;
         g.A = m->ws + m->wsl.act;
         g.a_lo = m->lo_rows(F);
+        g.a_packed = pk_F;
         g.lda = F;
         g.arow = nullptr;
         g.ssq = nullptr;
@@ -352,7 +370,9 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
             if (cf.exit_layers[i] == l + 1) g_head = m->gain(m->wl.ge[i]);
         {
             Timed t(m, EE_K_DOWN, st);
-            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d, st));
+            // (the next layer of this call reads the packed copy; across calls the residual store is the interface)
+            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d,
+                                     pk_d && l + 1 < l1 ? xg_pk : nullptr, m->lo_rows(d), st));
         }
     }
     return EE_OK;
@@ -372,6 +392,13 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.a_lo = c->xs_lo;
     g.lda = cf.d_model;
     g.arow = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
+    if (cf.dtype == EE_BF16 && !gemm_rows_fit_lds(cf.dtype, n_head, cf.d_model)) {  // many rows: packed operands
+        char* hp = m->ws + m->wsl.head_pk;
+        HIPCHK(launch_pack_rows(g.A, g.a_lo, cf.d_model, g.arow, n_head, cf.d_model, hp, (size_t)64 * cf.d_model, st));
+        g.A = hp;
+        g.a_lo = (size_t)64 * cf.d_model;
+        g.a_packed = 1;
+    }
     g.ssq = c->ssq();
     g.ssq_stride = c->ssq_stride;
     g.ssq_n = c->ssq_stride;
@@ -871,6 +898,11 @@ int ee_model_free(ee_model* m) {
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     if (m->pinned) (void)hipHostFree(m->pinned);
     delete m;
+    return EE_OK;
+}
+
+int ee_debug_set_gemm_min_workgroups(int n) {
+    set_gemm_min_wgs(n);
     return EE_OK;
 }
 

@@ -72,6 +72,8 @@ struct GemmCommon {
     size_t a_lo;       // element offset from the hi term of A to its lo term (bf16 model), else 0
     int lda;
     const int32_t* arow;  // row indirection into A (and into ssq), or NULL
+    int a_packed;         // A holds dense rows in MFMA operand order [row/16][K/32][64 lanes][8] (bf16 model); arow then
+                          // only indexes ssq
     const float* ssq;     // partial sums of squares [slot][ssq_stride], or NULL (no RMS scale)
     int ssq_stride, ssq_n;
     float inv_d, eps;
@@ -85,15 +87,19 @@ struct GemmCommon {
 
 hipError_t launch_gemm_qkv(const GemmCommon& c, void* q, size_t q_lo, const float* rope_cs, const KvGeom& kv, int layer,
                            hipStream_t s);
+// xg_pk (optional, bf16 model): a second copy of the x.g operand, dense rows of this launch in packed order
 hipError_t launch_gemm_resid(const GemmCommon& c, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
-                             const float* g_next, const float* g_head, int d, hipStream_t s);
-hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int F, hipStream_t s);
+                             const float* g_next, const float* g_head, int d, void* xg_pk, size_t xg_pk_lo, hipStream_t s);
+hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int F, bool act_packed, hipStream_t s);
+// rows of a row-major two-term array (through an index list, or dense when NULL) -> packed array
+hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_t* rows, int T, int K, void* dst, size_t dst_lo,
+                            hipStream_t s);
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
                             float threshold, HeadResult* results, hipStream_t s);
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
-                            hipStream_t s);
+                            bool out_packed, hipStream_t s);
 // defer_ns != NULL: when the KV range was split, leave the partials unmerged and report the number of splits
 // (the O projection then merges them, see GemmCommon::att_part); 0 is reported when `out` is complete.
 bool gemm_rows_fit_lds(int dtype, int T, int K);  // true when the GEMMs stage this many rows in LDS
@@ -128,6 +134,7 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
 hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
                                 size_t lo_off, float* dssq, int ssq_stride, hipStream_t s);
 
+void set_gemm_min_wgs(int n);  // workgroups a GEMM launch keeps when it gives a workgroup several column tiles
 int gemm_resid_tiles_per_wg();  // G of the residual epilogue: ssq partials per row = d / (16*G)
 size_t attention_part_floats(int max_rows, int H, int hd);  // scratch the attention kernel needs
 

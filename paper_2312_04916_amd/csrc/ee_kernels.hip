@@ -12,6 +12,8 @@
 
 #include "ee_launch.h"
 
+#include <cstdlib>
+
 namespace ee {
 
 static thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
@@ -50,6 +52,41 @@ template <typename ST> __device__ __forceinline__ float load_split(const ST* p, 
 template <> __device__ __forceinline__ float load_split<float>(const float* p, size_t) { return *p; }
 template <> __device__ __forceinline__ float load_split<__bf16>(const __bf16* p, size_t lo_off) {
     return (float)p[0] + (float)p[lo_off];
+}
+
+// Element index of (row m, feature k) in an operand-order ("packed") activation array: 16-row groups,
+// [m/16][K/32][64 lanes][8], lane = ((k%32)/8)*16 + m%16: one k-step of one row group is 1 KB that a wave
+// loads as a ready MFMA operand.  Used for the rows of a launch when there are too many for LDS.
+__device__ __forceinline__ size_t pk_index(int m, int k, int KT) {
+    return (((size_t)(m >> 4) * KT + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
+}
+
+// one value as two bf16 terms into a row-major (pk_kt == 0) or a packed array
+template <typename ST>
+__device__ __forceinline__ void store_split_at(ST* base, size_t lo_off, int m, int k, int ld, int pk_kt, float v) {
+    store_split<ST>(base + (pk_kt ? pk_index(m, k, pk_kt) : (size_t)m * ld + k), lo_off, v);
+}
+
+// rows (row-major, two terms, through an index list) -> packed array
+__global__ __launch_bounds__(256) void pack_rows_kernel(const __bf16* __restrict__ src, size_t src_lo, int ld, const int32_t* __restrict__ rows,
+                                                        int T, int K, __bf16* __restrict__ dst, size_t dst_lo) {
+    const int cpr = K / 8;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)T * cpr) return;
+    const int m = (int)(idx / cpr), k = (int)(idx % cpr) * 8;
+    const __bf16* sp = src + (size_t)(rows ? rows[m] : m) * ld + k;
+    const size_t o = pk_index(m, k, K / 32);
+    *(u32x4*)(dst + o) = *(const u32x4*)sp;
+    *(u32x4*)(dst + dst_lo + o) = *(const u32x4*)(sp + src_lo);
+}
+
+hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_t* rows, int T, int K, void* dst, size_t dst_lo,
+                            hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    const long n = (long)T * (K / 8);
+    EE_LAUNCH(pack_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), s, (const __bf16*)src, src_lo, ld, rows, T, K, (__bf16*)dst,
+              dst_lo);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -190,16 +227,21 @@ struct GemmArgs {
     int ssq_stride, ssq_n;
     float inv_d, eps;
     int T;
+    int n_tiles;  // N / 16
+    int a_packed; // A is stored in MFMA operand order [row/16][K/32][64 lanes][8] (dense rows, no indirection)
     // A given as split-KV attention partials instead of rows (few-rows variant of the O projection only)
     const float* att_part;
     const SegDesc* att_desc;
     int att_ns, att_H, att_hd;
 };
 
-template <int KS, int MT>
+// G = 16-column tiles a workgroup owns (1 for few rows; more when there are many rows, so that the
+// activation operands a wave has loaded serve several weight tiles and the L2 traffic of the rows,
+// which every workgroup re-reads in full, shrinks accordingly)
+template <int KS, int MT, int G = 1>
 struct GemmSmem {
     float red[KS][MT][256];
-    float out[MT * 16][16];
+    float out[G][MT * 16][16];
     float rs[MT * 16];
 };
 
@@ -245,19 +287,26 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile, 
         if (u < n) fill_w(u, u);
     // Rows beyond T read row 0 again (always a valid address): their products are never looked at,
     // and an unpredicated load keeps the loop free of branches.
+    // A operands: row-major rows (a load gathers 16 rows x 64 bytes), or already in operand order
+    // (packed: one contiguous KB per load)
     const __bf16* ap[MT];
+    const int astep = a.a_packed ? 512 : 32;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int row = mt * 16 + li;
-        if (row >= a.T) row = 0;
-        int idx = a.arow ? a.arow[row] : row;
-        ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + (size_t)kt0 * 32 + lg * 8;
+        if (a.a_packed) {
+            ap[mt] = (const __bf16*)a.A + ((size_t)mt * KT + kt0) * 512 + lane * 8;
+        } else {
+            int row = mt * 16 + li;
+            if (row >= a.T) row = 0;
+            int idx = a.arow ? a.arow[row] : row;
+            ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + (size_t)kt0 * 32 + lg * 8;
+        }
     }
     auto fill_a = [&](int u, int t) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            ah[mt][u] = *(const u32x4*)(ap[mt] + (size_t)t * 32);
-            al[mt][u] = *(const u32x4*)(ap[mt] + a.a_lo + (size_t)t * 32);
+            ah[mt][u] = *(const u32x4*)(ap[mt] + (size_t)t * astep);
+            al[mt][u] = *(const u32x4*)(ap[mt] + a.a_lo + (size_t)t * astep);
         }
     };
     auto fill = [&](int u, int t) {  // slot u <- tile t (relative to kt0)
@@ -309,9 +358,120 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile, 
 #pragma unroll
         for (int k = 0; k < KS; ++k) s += sm.red[k][mt][e];
         int m = mt * 16 + (e >> 4);
-        sm.out[m][e & 15] = s * sm.rs[m];
+        sm.out[0][m][e & 15] = s * sm.rs[m];
     }
     __syncthreads();
+}
+
+// Register path with G tiles per workgroup: every ring slot holds one k-step of G weight tiles and of the
+// MT row tiles (both terms); the G*MT products of a slot share its activation registers.
+template <int KS, int MT, int G, typename Pre>
+__device__ __forceinline__ void gemm_mainloop_bf16_multi(const GemmArgs& a, int tile0, GemmSmem<KS, MT, G>& sm, Pre pre) {
+    const int ks = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, lg = lane >> 4;
+    const int KT = a.KT;
+    const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
+    const u32x4* wp[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        int t = tile0 + g;
+        if (t >= a.n_tiles) t = a.n_tiles - 1;  // (a surplus tile repeats the last one; its result is dropped)
+        wp[g] = (const u32x4*)a.W + ((size_t)t * KT + kt0) * 64 + lane;
+    }
+    f32x4 acc[G][MT];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[g][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int D = MT == 4 ? 2 : 4;
+    u32x4 w[G][D], ah[MT][D], al[MT][D];
+    const int n = kt1 - kt0;
+    auto fill_w = [&](int u, int t) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) w[g][u] = __builtin_nontemporal_load(wp[g] + (size_t)t * 64);
+    };
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n) fill_w(u, u);
+    // A operands: row-major rows (a load gathers 16 rows x 64 bytes), or already in operand order
+    // (packed: one contiguous KB per load)
+    const __bf16* ap[MT];
+    const int astep = a.a_packed ? 512 : 32;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (a.a_packed) {
+            ap[mt] = (const __bf16*)a.A + ((size_t)mt * KT + kt0) * 512 + lane * 8;
+        } else {
+            int row = mt * 16 + li;
+            if (row >= a.T) row = 0;
+            int idx = a.arow ? a.arow[row] : row;
+            ap[mt] = (const __bf16*)a.A + (size_t)idx * a.lda + (size_t)kt0 * 32 + lg * 8;
+        }
+    }
+    auto fill_a = [&](int u, int t) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            ah[mt][u] = *(const u32x4*)(ap[mt] + (size_t)t * astep);
+            al[mt][u] = *(const u32x4*)(ap[mt] + a.a_lo + (size_t)t * astep);
+        }
+    };
+    auto use = [&](int u) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[g][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, al[mt][u]),
+                                                                     __builtin_bit_cast(bf16x8, w[g][u]), acc[g][mt], 0, 0, 0);
+                acc[g][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ah[mt][u]),
+                                                                     __builtin_bit_cast(bf16x8, w[g][u]), acc[g][mt], 0, 0, 0);
+            }
+    };
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n) fill_a(u, u);
+    rms_scales<MT>(a, sm.rs);
+    pre();
+    const int full = n / D, rem = n - full * D;
+    for (int gI = 0; gI + 1 < full; ++gI) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u);
+            fill_w(u, (gI + 1) * D + u);
+            fill_a(u, (gI + 1) * D + u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (full > 0) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            use(u);
+            if (u < rem) {
+                fill_w(u, full * D + u);
+                fill_a(u, full * D + u);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < rem) use(u);
+    // cross-wave reduction, one tile after the other through the same buffer
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sm.red[ks][mt][(lg * 4 + r) * 16 + li] = acc[g][mt][r];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+            int e = idx & 255, mt = idx >> 8;
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) s += sm.red[k][mt][e];
+            int m = mt * 16 + (e >> 4);
+            sm.out[g][m][e & 15] = s * sm.rs[m];
+        }
+        __syncthreads();
+    }
 }
 
 // Variant for few rows (T*K small enough for LDS): the workgroup first copies its T activation rows
@@ -444,7 +604,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
 #pragma unroll
         for (int k = 0; k < KS; ++k) s += sm.red[k][0][idx];
         int m = idx >> 4;
-        sm.out[m][idx & 15] = s * sm.rs[m];
+        sm.out[0][m][idx & 15] = s * sm.rs[m];
     }
     __syncthreads();
 }
@@ -464,20 +624,24 @@ __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile, G
             const float* wr = (const float*)a.W + ((size_t)tile * 16 + c) * a.K;
             for (int k = 0; k < a.K; ++k) s = fmaf(ar[k], wr[k], s);
         }
-        sm.out[m][c] = s * sm.rs[m];
+        sm.out[0][m][c] = s * sm.rs[m];
     }
     __syncthreads();
 }
 
 // `pre` runs once the first weight loads are in flight: the place to fetch what the epilogue needs.
-template <typename ST, int KS, int MT, bool ALDS, typename Pre, bool ATT = false>
-__device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
-    if constexpr (sizeof(ST) == 2 && ALDS)
-        gemm_mainloop_bf16_lds<KS, ATT>(a, tile, sm, pre);
+// Leaves tile g of the workgroup (g < G, tile index tile0 + g) in sm.out[g].
+template <typename ST, int KS, int MT, bool ALDS, int G, typename Pre, bool ATT = false>
+__device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, GemmSmem<KS, MT, G>& sm, Pre pre) {
+    if constexpr (G > 1) {
+        static_assert(sizeof(ST) == 2 && !ALDS, "several tiles per workgroup: bf16 register path only");
+        gemm_mainloop_bf16_multi<KS, MT, G>(a, tile0, sm, pre);
+    } else if constexpr (sizeof(ST) == 2 && ALDS)
+        gemm_mainloop_bf16_lds<KS, ATT>(a, tile0, sm, pre);
     else if constexpr (sizeof(ST) == 2)
-        gemm_mainloop_bf16<KS, MT>(a, tile, sm, pre);  // (its first __syncthreads orders rs before use)
+        gemm_mainloop_bf16<KS, MT>(a, tile0, sm, pre);  // (its first __syncthreads orders rs before use)
     else
-        gemm_mainloop_f32<KS, MT>(a, tile, sm, pre);
+        gemm_mainloop_f32<KS, MT>(a, tile0, sm, pre);
 }
 
 // ---- epilogue 1: rotary embedding, q to the workspace, k and v into the paged cache.
@@ -495,55 +659,62 @@ struct QkvArgs {
     const int32_t* kvblk;
 };
 
-template <typename ST, int KS, int MT, bool ALDS>
+template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
-    __shared__ GemmSmem<KS, MT> sm;
+    __shared__ GemmSmem<KS, MT, G> sm;
     const int per_head = e.hd / 16, per_part = e.H * per_head;
-    const int part = blockIdx.x / per_part;  // 0 q, 1 k, 2 v
-    const int rem = blockIdx.x % per_part;
-    const int h = rem / per_head, c = rem % per_head;
     const int half = e.hd / 2;
-    // epilogue operands of this thread's first (row, column pair), fetched while the weights stream
+    const int tile0 = blockIdx.x * G;
+    // epilogue operands of this thread's first (row, column pair) of the first tile, fetched while the weights stream
     const int m0 = threadIdx.x >> 3, i0 = threadIdx.x & 7;
     int pos0 = 0, blk0 = 0;
     float2 cs0 = make_float2(1.f, 0.f);
-    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, [&]() {
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, [&]() {
         if (m0 < a.T) {
             pos0 = e.pos[m0];
             blk0 = e.kvblk[m0];
-            if (part < 2) cs0 = e.rope_cs[(size_t)pos0 * half + c * 8 + i0];
+            if (tile0 / per_part < 2) cs0 = e.rope_cs[(size_t)pos0 * half + (tile0 % per_head) * 8 + i0];
         }
     });
-    for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
-        int m = idx >> 3, i = idx & 7;
-        if (m >= a.T) continue;
-        float lo = sm.out[m][i], hi = sm.out[m][8 + i];
-        int pos = pos0, blk = blk0;
-        float2 cs = cs0;
-        if (idx != (int)threadIdx.x) {
-            pos = e.pos[m];
-            blk = e.kvblk[m];
-            if (part < 2) cs = e.rope_cs[(size_t)pos * half + c * 8 + i];
-        }
-        if (part < 2) {
-            float nlo = lo * cs.x - hi * cs.y;
-            float nhi = hi * cs.x + lo * cs.y;
-            lo = nlo;
-            hi = nhi;
-        }
-        if (part == 0) {
-            ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 8 + i;
-            store_split<ST>(qp, e.q_lo, lo);
-            store_split<ST>(qp + half, e.q_lo, hi);
-        } else if (part == 1) {  // K block: [head][position][feature]
-            ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
-            kp[0] = cvt_st<ST>(lo);
-            kp[half] = cvt_st<ST>(hi);
-        } else {  // V block, transposed: [head][feature][position], so that attention reads P.V operands directly
-            ST* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd +
-                     ((size_t)h * e.hd + c * 8 + i) * e.BT + (pos % e.BT);
-            vp[0] = cvt_st<ST>(lo);
-            vp[(size_t)half * e.BT] = cvt_st<ST>(hi);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int tile = tile0 + g;
+        if (tile >= a.n_tiles) break;
+        const float(*out)[16] = sm.out[g];
+        const int part = tile / per_part;  // 0 q, 1 k, 2 v
+        const int rem = tile % per_part;
+        const int h = rem / per_head, c = rem % per_head;
+        for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
+            int m = idx >> 3, i = idx & 7;
+            if (m >= a.T) continue;
+            float lo = out[m][i], hi = out[m][8 + i];
+            int pos = pos0, blk = blk0;
+            float2 cs = cs0;
+            if (g != 0 || idx != (int)threadIdx.x) {
+                pos = e.pos[m];
+                blk = e.kvblk[m];
+                if (part < 2) cs = e.rope_cs[(size_t)pos * half + c * 8 + i];
+            }
+            if (part < 2) {
+                float nlo = lo * cs.x - hi * cs.y;
+                float nhi = hi * cs.x + lo * cs.y;
+                lo = nlo;
+                hi = nhi;
+            }
+            if (part == 0) {
+                ST* qp = e.q + (size_t)m * e.d + h * e.hd + c * 8 + i;
+                store_split<ST>(qp, e.q_lo, lo);
+                store_split<ST>(qp + half, e.q_lo, hi);
+            } else if (part == 1) {  // K block: [head][position][feature]
+                ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
+                kp[0] = cvt_st<ST>(lo);
+                kp[half] = cvt_st<ST>(hi);
+            } else {  // V block, transposed: [head][feature][position], so that attention reads P.V operands directly
+                ST* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd +
+                         ((size_t)h * e.hd + c * 8 + i) * e.BT + (pos % e.BT);
+                vp[0] = cvt_st<ST>(lo);
+                vp[(size_t)half * e.BT] = cvt_st<ST>(hi);
+            }
         }
     }
 }
@@ -561,74 +732,91 @@ struct ResidArgs {
     const float* g_head;
     int d;
     const int32_t* xrow;  // per row: slot in the residual store
+    ST* xg_pk;            // optional: the same operand again, dense rows of this launch in packed order
+    size_t xg_pk_lo;
 };
 
-template <typename ST, int KS, int MT, bool ALDS, bool ATT>
+template <typename ST, int KS, int MT, bool ALDS, bool ATT, int G>
 __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidArgs<ST>& e) {
-    __shared__ GemmSmem<KS, MT> sm;
-    const int n0 = blockIdx.x * 16;
-    // epilogue operands of this thread's first element, fetched while the weights stream
+    __shared__ GemmSmem<KS, MT, G> sm;
+    const int tile0 = blockIdx.x * G;
+    // epilogue operands of this thread's first element of the first tile, fetched while the weights stream
     const int m0 = threadIdx.x >> 4, i0 = threadIdx.x & 15;
     size_t o0 = 0;
     float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
     auto pre = [&]() {
         if (m0 < a.T) {
-            o0 = (size_t)e.xrow[m0] * e.d + n0 + i0;
+            o0 = (size_t)e.xrow[m0] * e.d + tile0 * 16 + i0;
             x0 = e.x[o0];
-            gn0 = e.g_next[n0 + i0];
-            if (e.xgh) gh0 = e.g_head[n0 + i0];
+            gn0 = e.g_next[tile0 * 16 + i0];
+            if (e.xgh) gh0 = e.g_head[tile0 * 16 + i0];
         }
     };
-    gemm_mainloop<ST, KS, MT, ALDS, decltype(pre), ATT>(a, blockIdx.x, sm, pre);
-    for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
-        int m = idx >> 4, i = idx & 15;
-        if (m >= a.T) continue;
-        size_t o = o0;
-        float xv = x0, gn = gn0, gh = gh0;
-        if (idx != (int)threadIdx.x) {
-            o = (size_t)e.xrow[m] * e.d + n0 + i;
-            xv = e.x[o];
-            gn = e.g_next[n0 + i];
-            if (e.xgh) gh = e.g_head[n0 + i];
-        }
-        float v = xv + sm.out[m][i];
-        e.x[o] = v;
-        sm.out[m][i] = v;
-        store_split<ST>(e.xg + o, e.xs_lo, v * gn);
-        if (e.xgh) store_split<ST>(e.xgh + o, e.xs_lo, v * gh);
-    }
-    __syncthreads();
-    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
-        if (m >= a.T) continue;
-        float s = 0.f;
+    gemm_mainloop<ST, KS, MT, ALDS, G, decltype(pre), ATT>(a, tile0, sm, pre);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s += sm.out[m][i] * sm.out[m][i];
-        e.ssq_out[(size_t)e.xrow[m] * e.ssq_stride + blockIdx.x] = s;
+    for (int g = 0; g < G; ++g) {
+        const int tile = tile0 + g;
+        if (tile >= a.n_tiles) break;  // (uniform over the workgroup)
+        float(*out)[16] = sm.out[g];
+        const int n0 = tile * 16;
+        for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+            int m = idx >> 4, i = idx & 15;
+            if (m >= a.T) continue;
+            size_t o = o0;
+            float xv = x0, gn = gn0, gh = gh0;
+            if (g != 0 || idx != (int)threadIdx.x) {
+                o = (size_t)e.xrow[m] * e.d + n0 + i;
+                xv = e.x[o];
+                gn = e.g_next[n0 + i];
+                if (e.xgh) gh = e.g_head[n0 + i];
+            }
+            float v = xv + out[m][i];
+            e.x[o] = v;
+            out[m][i] = v;
+            store_split<ST>(e.xg + o, e.xs_lo, v * gn);
+            if (e.xgh) store_split<ST>(e.xgh + o, e.xs_lo, v * gh);
+            if (e.xg_pk) store_split<ST>(e.xg_pk + pk_index(m, n0 + i, e.d / 32), e.xg_pk_lo, v * gn);
+        }
+        __syncthreads();
+        for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+            if (m >= a.T) continue;
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s += out[m][i] * out[m][i];
+            e.ssq_out[(size_t)e.xrow[m] * e.ssq_stride + tile] = s;
+        }
     }
 }
 
-template <typename ST, int KS, int MT, bool ALDS>
+template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
-    gemm_resid_body<ST, KS, MT, ALDS, false>(a, e);
+    gemm_resid_body<ST, KS, MT, ALDS, false, G>(a, e);
 }
 
 // O projection whose input rows are merged from the attention kernel's split partials while being staged
 template <int KS>
 __global__ __launch_bounds__(KS * 64) void gemm_resid_att_kernel(GemmArgs a, ResidArgs<__bf16> e) {
-    gemm_resid_body<__bf16, KS, 1, true, true>(a, e);
+    gemm_resid_body<__bf16, KS, 1, true, true, 1>(a, e);
 }
 
 // ---- epilogue 3: SwiGLU.  Tile j: columns 0..7 = gate features 8j.., columns 8..15 = the matching up features
-template <typename ST, int KS, int MT, bool ALDS>
-__global__ __launch_bounds__(KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F) {
-    __shared__ GemmSmem<KS, MT> sm;
-    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, []() {});
-    for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
-        int m = idx >> 3, i = idx & 7;
-        if (m >= a.T) continue;
-        float gt = sm.out[m][i], up = sm.out[m][8 + i];
-        float sl = gt / (1.0f + expf(-gt));
-        store_split<ST>(act + (size_t)m * F + blockIdx.x * 8 + i, act_lo, sl * up);
+template <typename ST, int KS, int MT, bool ALDS, int G = 1>
+__global__ __launch_bounds__(KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F, int act_pk) {
+    __shared__ GemmSmem<KS, MT, G> sm;
+    const int tile0 = blockIdx.x * G;
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int tile = tile0 + g;
+        if (tile >= a.n_tiles) break;
+        const float(*out)[16] = sm.out[g];
+        for (int idx = threadIdx.x; idx < MT * 128; idx += blockDim.x) {
+            int m = idx >> 3, i = idx & 7;
+            if (m >= a.T) continue;
+            float gt = out[m][i], up = out[m][8 + i];
+            float sl = gt / (1.0f + expf(-gt));
+            store_split_at<ST>(act, act_lo, m, tile * 8 + i, F, act_pk, sl * up);
+        }
     }
 }
 
@@ -652,36 +840,43 @@ __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float 
     }
 }
 
-template <typename ST, int KS, int MT, bool ALDS>
+template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
-    __shared__ GemmSmem<KS, MT> sm;
-    gemm_mainloop<ST, KS, MT, ALDS>(a, blockIdx.x, sm, []() {});
-    const int n0 = blockIdx.x * 16;
-    if (e.logits) {
-        for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
-            int m = idx >> 4, c = idx & 15;
-            if (m < a.T) e.logits[(size_t)m * e.V + n0 + c] = sm.out[m][c];
-        }
-    }
-    for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
-        if (m >= a.T) continue;
-        float mx = sm.out[m][0];
-        int ix = 0;
+    __shared__ GemmSmem<KS, MT, G> sm;
+    const int tile0 = blockIdx.x * G;
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
 #pragma unroll
-        for (int c = 1; c < 16; ++c)
-            if (sm.out[m][c] > mx) {
-                mx = sm.out[m][c];
-                ix = c;
+    for (int g = 0; g < G; ++g) {
+        const int tile = tile0 + g;
+        if (tile >= a.n_tiles) break;
+        const float(*out)[16] = sm.out[g];
+        const int n0 = tile * 16;
+        if (e.logits) {
+            for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
+                int m = idx >> 4, c = idx & 15;
+                if (m < a.T) e.logits[(size_t)m * e.V + n0 + c] = out[m][c];
             }
-        float s = 0.f;
+        }
+        for (int m = threadIdx.x; m < MT * 16; m += blockDim.x) {
+            if (m >= a.T) continue;
+            float mx = out[m][0];
+            int ix = 0;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) s += expf(sm.out[m][c] - mx);
-        HeadPartial p;
-        p.max = mx;
-        p.sum = s;
-        p.idx = n0 + ix;
-        p.pad = 0;
-        e.partials[(size_t)blockIdx.x * EE_MAX_SEQS + m] = p;
+            for (int c = 1; c < 16; ++c)
+                if (out[m][c] > mx) {
+                    mx = out[m][c];
+                    ix = c;
+                }
+            float s = 0.f;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) s += expf(out[m][c] - mx);
+            HeadPartial p;
+            p.max = mx;
+            p.sum = s;
+            p.idx = n0 + ix;
+            p.pad = 0;
+            e.partials[(size_t)tile * EE_MAX_SEQS + m] = p;
+        }
     }
 }
 
@@ -745,6 +940,8 @@ static GemmArgs make_args(const GemmCommon& c) {
     a.inv_d = c.inv_d;
     a.eps = c.eps;
     a.T = c.T;
+    a.n_tiles = c.N / 16;
+    a.a_packed = c.a_packed;
     a.att_part = c.att_part;
     a.att_desc = c.desc;
     a.att_ns = c.att_ns;
@@ -770,28 +967,50 @@ static size_t a_lds_bytes(const GemmCommon& c) {
     return b <= (size_t)A_LDS_MAX_BYTES ? b : 0;
 }
 
+// Column tiles per workgroup for the register path: as many (4 for one row tile, else 2) as still leave
+// gemm_min_wgs() workgroups, so that the rows' operands are re-read from L2 by fewer workgroups without
+// starving the chip of weight streams.  (512 unless a test lowers it to reach these variants on small models.)
+static int g_min_wgs = 512;
+void set_gemm_min_wgs(int n) { g_min_wgs = n < 1 ? 1 : n; }
+static int gemm_min_wgs() { return g_min_wgs; }
+static int g_of(int mt, int n_tiles) {
+    if (mt == 1 && n_tiles / 4 >= gemm_min_wgs()) return 4;
+    if (n_tiles / 2 >= gemm_min_wgs()) return 2;
+    return 1;
+}
+
+#define EE_LAUNCH_G(ST, KERNEL, KS_, MT_, ...)                                                        \
+    do {                                                                                              \
+        if (_g == 4 && MT_ == 1) EE_LAUNCH((KERNEL<ST, KS_, 1, false, (KS_ == 16 ? 2 : 4)>), grid, block, s, __VA_ARGS__); \
+        else if (_g >= 2) EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 2>), grid, block, s, __VA_ARGS__);   \
+        else EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 1>), grid, block, s, __VA_ARGS__);                \
+    } while (0)
+
 #define EE_DISPATCH(ST, KERNEL, ...)                                                                               \
     do {                                                                                                           \
-        const int _ks = ks_of(c), _mt = mt_of(c.T);                                                                \
+        const int _ks = ks_of(c), _mt = mt_of(c.T), _nt = c.N / 16;                                                \
         const size_t _sm = a_lds_bytes(c);                                                                         \
-        dim3 block(_ks * 64);                                                                                      \
+        int _g = _sm ? 1 : g_of(_mt, _nt);                                                                         \
+        if (_ks == 16 && _g == 4) _g = 2; /* 1024 threads leave 128 registers per lane */                          \
+        dim3 grid((_nt + _g - 1) / _g), block(_ks * 64);                                                           \
         if (_sm) {                                                                                                 \
-            if (_ks == 4) EE_LAUNCH_SM((KERNEL<ST, 4, 1, true>), grid, block, _sm, s, __VA_ARGS__);                \
-            else if (_ks == 8) EE_LAUNCH_SM((KERNEL<ST, 8, 1, true>), grid, block, _sm, s, __VA_ARGS__);           \
-            else EE_LAUNCH_SM((KERNEL<ST, 16, 1, true>), grid, block, _sm, s, __VA_ARGS__);                        \
-        } else if (_ks == 4 && _mt == 1) EE_LAUNCH((KERNEL<ST, 4, 1, false>), grid, block, s, __VA_ARGS__);        \
-        else if (_ks == 4 && _mt == 2) EE_LAUNCH((KERNEL<ST, 4, 2, false>), grid, block, s, __VA_ARGS__);          \
-        else if (_ks == 4) EE_LAUNCH((KERNEL<ST, 4, 4, false>), grid, block, s, __VA_ARGS__);                      \
-        else if (_ks == 8 && _mt == 1) EE_LAUNCH((KERNEL<ST, 8, 1, false>), grid, block, s, __VA_ARGS__);          \
-        else if (_ks == 8 && _mt == 2) EE_LAUNCH((KERNEL<ST, 8, 2, false>), grid, block, s, __VA_ARGS__);          \
-        else if (_ks == 8) EE_LAUNCH((KERNEL<ST, 8, 4, false>), grid, block, s, __VA_ARGS__);                      \
-        else EE_LAUNCH((KERNEL<ST, 16, 1, false>), grid, block, s, __VA_ARGS__);                                   \
+            if (_ks == 4) EE_LAUNCH_SM((KERNEL<ST, 4, 1, true, 1>), grid, block, _sm, s, __VA_ARGS__);             \
+            else if (_ks == 8) EE_LAUNCH_SM((KERNEL<ST, 8, 1, true, 1>), grid, block, _sm, s, __VA_ARGS__);        \
+            else EE_LAUNCH_SM((KERNEL<ST, 16, 1, true, 1>), grid, block, _sm, s, __VA_ARGS__);                     \
+        } else if (_ks == 4 && _mt == 1) EE_LAUNCH_G(ST, KERNEL, 4, 1, __VA_ARGS__);                               \
+        else if (_ks == 4 && _mt == 2) EE_LAUNCH_G(ST, KERNEL, 4, 2, __VA_ARGS__);                                 \
+        else if (_ks == 4) EE_LAUNCH_G(ST, KERNEL, 4, 4, __VA_ARGS__);                                             \
+        else if (_ks == 8 && _mt == 1) EE_LAUNCH_G(ST, KERNEL, 8, 1, __VA_ARGS__);                                 \
+        else if (_ks == 8 && _mt == 2) EE_LAUNCH_G(ST, KERNEL, 8, 2, __VA_ARGS__);                                 \
+        else if (_ks == 8) EE_LAUNCH_G(ST, KERNEL, 8, 4, __VA_ARGS__);                                             \
+        else EE_LAUNCH_G(ST, KERNEL, 16, 1, __VA_ARGS__);                                                          \
     } while (0)
 
 #define EE_DISPATCH_F32(KERNEL, ...)                                                             \
     do {                                                                                         \
         const int _mt = mt_of(c.T);                                                              \
         dim3 block(256);                                                                         \
+        dim3 grid(c.N / 16);                                                                     \
         if (_mt == 1) EE_LAUNCH((KERNEL<float, 4, 1, false>), grid, block, s, __VA_ARGS__);      \
         else if (_mt == 2) EE_LAUNCH((KERNEL<float, 4, 2, false>), grid, block, s, __VA_ARGS__); \
         else EE_LAUNCH((KERNEL<float, 4, 4, false>), grid, block, s, __VA_ARGS__);               \
@@ -813,9 +1032,10 @@ constexpr int PASS_ROWS = 64;
 static GemmCommon pass_of(const GemmCommon& c, int r0) {
     GemmCommon p = c;
     p.T = c.T - r0 < PASS_ROWS ? c.T - r0 : PASS_ROWS;
-    if (c.arow)
-        p.arow = c.arow + r0;
-    else
+    if (c.arow) p.arow = c.arow + r0;
+    if (c.a_packed)  // (r0 is a multiple of 16: whole row groups)
+        p.A = (const char*)c.A + (size_t)(r0 / 16) * (c.K / 32) * 512 * 2;
+    else if (!c.arow)
         p.A = (const char*)c.A + (size_t)r0 * c.lda * (c.dtype == EE_BF16 ? 2 : 4);
     return p;
 }
@@ -829,7 +1049,6 @@ hipError_t launch_gemm_qkv(const GemmCommon& cc, void* q, size_t q_lo, const flo
     for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
         const GemmCommon c = pass_of(cc, r0);
         GemmArgs a = make_args(c);
-        dim3 grid(c.N / 16);
         const int d = c.N / 3;
         const int32_t* pos = desc_array(c.desc, offsetof(SegDesc, pos), r0);
         const int32_t* blk = desc_array(c.desc, offsetof(SegDesc, kvblk), r0);
@@ -849,27 +1068,28 @@ hipError_t launch_gemm_qkv(const GemmCommon& cc, void* q, size_t q_lo, const flo
 }
 
 hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
-                             const float* g_next, const float* g_head, int d, hipStream_t s) {
+                             const float* g_next, const float* g_head, int d, void* xg_pk, size_t xg_pk_lo, hipStream_t s) {
     for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
         const GemmCommon c = pass_of(cc, r0);
         GemmArgs a = make_args(c);
-        dim3 grid(c.N / 16);
         const int32_t* xrow = desc_array(c.desc, offsetof(SegDesc, xrow), r0);
         if (c.dtype == EE_BF16 && c.att_part != nullptr) {
             // input still lies as attention split partials: only the few-rows variant can merge them
             const size_t sm = a_lds_bytes(c);
             if (sm == 0 || cc.T > PASS_ROWS) return hipErrorInvalidValue;
-            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0};
             // (at most 8 waves: the merge holds every split's partials in registers at once)
             const int ks = ks_of(c) == 4 ? 4 : 8;
-            dim3 block(ks * 64);
+            dim3 grid(c.N / 16), block(ks * 64);
             if (ks == 4) EE_LAUNCH_SM(gemm_resid_att_kernel<4>, grid, block, sm, s, a, e);
             else EE_LAUNCH_SM(gemm_resid_att_kernel<8>, grid, block, sm, s, a, e);
         } else if (c.dtype == EE_BF16) {
-            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            // (the packed copy of a later pass starts r0/16 row groups further on)
+            __bf16* pk = xg_pk ? (__bf16*)xg_pk + (size_t)(r0 / 16) * (d / 32) * 512 : nullptr;
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, pk, xg_pk_lo};
             EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
         } else {
-            ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow};
+            ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0};
             EE_DISPATCH_F32(gemm_resid_kernel, a, e);
         }
         hipError_t err = hipGetLastError();
@@ -878,15 +1098,15 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
     return hipSuccess;
 }
 
-hipError_t launch_gemm_swiglu(const GemmCommon& cc, void* act, size_t act_lo, int F, hipStream_t s) {
+hipError_t launch_gemm_swiglu(const GemmCommon& cc, void* act, size_t act_lo, int F, bool act_packed, hipStream_t s) {
     for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
         const GemmCommon c = pass_of(cc, r0);
         GemmArgs a = make_args(c);
-        dim3 grid(c.N / 16);
         if (c.dtype == EE_BF16) {
-            EE_DISPATCH(__bf16, gemm_swiglu_kernel, a, (__bf16*)act + (size_t)r0 * F, act_lo, F);
+            __bf16* ap = act_packed ? (__bf16*)act + (size_t)(r0 / 16) * (F / 32) * 512 : (__bf16*)act + (size_t)r0 * F;
+            EE_DISPATCH(__bf16, gemm_swiglu_kernel, a, ap, act_lo, F, act_packed ? F / 32 : 0);
         } else {
-            EE_DISPATCH_F32(gemm_swiglu_kernel, a, (float*)act + (size_t)r0 * F, act_lo, F);
+            EE_DISPATCH_F32(gemm_swiglu_kernel, a, (float*)act + (size_t)r0 * F, act_lo, F, 0);
         }
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
@@ -901,7 +1121,6 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
     if (c.T > 64) return hipErrorInvalidValue;
     GemmArgs a = make_args(c);
     HeadArgs e{partials, logits, c.N};
-    dim3 grid(c.N / 16);
     if (c.dtype == EE_BF16) {
         EE_DISPATCH(__bf16, gemm_head_kernel, a, e);
     } else {
@@ -909,7 +1128,7 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, (int)grid.x, c.T, mode, threshold, results, c.desc);
+    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, c.N / 16, c.T, mode, threshold, results, c.desc);
     return hipGetLastError();
 }
 
@@ -1010,7 +1229,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
 
 template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
-                                                             size_t out_lo, const SegDesc* __restrict__ desc,
+                                                             size_t out_lo, int out_pk, const SegDesc* __restrict__ desc,
                                                              const int32_t* __restrict__ btab, KvGeom kv,
                                                              const __bf16* __restrict__ layer_base, int d, int NS,
                                                              float* __restrict__ part) {
@@ -1169,7 +1388,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
             }
         }
         if (NS == 1) {
-            store_split<__bf16>(out + (size_t)(row0 + qq) * d + h * HD + cc, out_lo, O / L);
+            store_split_at<__bf16>(out, out_lo, row0 + qq, h * HD + cc, d, out_pk, O / L);
         } else {
             pbase[32 + qq * HD + cc] = O;
             if (cc == 0) {
@@ -1182,7 +1401,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
 
 template <int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, int NS, __bf16* __restrict__ out,
-                                                         size_t out_lo, const SegDesc* __restrict__ desc, int H, int d) {
+                                                         size_t out_lo, int out_pk, const SegDesc* __restrict__ desc, int H, int d) {
     const int qt = blockIdx.x / H, h = blockIdx.x % H;
     const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
     const float* pb = part + (size_t)(qt * H + h) * NS * att_part_stride(HD);
@@ -1199,7 +1418,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
             O += f * ps[32 + qq * HD + cc];
             L += f * ps[16 + qq];
         }
-        store_split<__bf16>(out + (size_t)(row0 + qq) * d + h * HD + cc, out_lo, O / L);
+        store_split_at<__bf16>(out, out_lo, row0 + qq, h * HD + cc, d, out_pk, O / L);
     }
 }
 
@@ -1211,8 +1430,9 @@ size_t attention_part_floats(int max_rows, int H, int hd) {
 
 template <int HD>
 static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, int n_qt, const int32_t* btab,
-                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, int* defer_ns,
+                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, int* defer_ns, bool out_packed,
                                         hipStream_t s) {
+    const int out_pk = out_packed ? d / 32 : 0;
     const int wgs = n_qt * kv.H;
     const int tiles = (max_ctx + 31) / 32;
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
@@ -1223,7 +1443,7 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     if (NS > by_len) NS = by_len;
     if (NS > ATT_MAX_SPLITS) NS = ATT_MAX_SPLITS;
     if (NS < 1) NS = 1;
-    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs, NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, desc, btab, kv,
+    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs, NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc, btab, kv,
               lb, d, NS, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
@@ -1231,21 +1451,21 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
         *defer_ns = NS;
         return e;
     }
-    EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, desc, kv.H, d);
+    EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
     return hipGetLastError();
 }
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
-                            hipStream_t s) {
+                            bool out_packed, hipStream_t s) {
     (void)counters;
     if (defer_ns) *defer_ns = 0;
     if (T <= 0) return hipSuccess;
     if (dtype == EE_BF16) {
         switch (kv.hd) {
-            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
-            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
-            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, s);
+            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
+            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
+            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
             default: return hipErrorInvalidValue;
         }
     }

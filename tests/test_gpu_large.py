@@ -150,3 +150,48 @@ def test_c3_shape_prompt_phase_scored():
     finally:
         gm.close()
         O.set_threads(1)
+
+
+def test_c3_shape_batch_many_rows_equals_solo():
+    """7B widths, 2 layers, three ragged sequences at threshold 0: the deferred rows pile up to 3 x 16 = 48 rows per
+    launch (packed row operands, several column tiles per workgroup, 2 and 4 row tiles); every sequence must emit
+    exactly what it emits alone (the solo path is the one checked against the oracle above)."""
+    shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
+    gm = load_gpu_model(shape, 0, max_positions=256, max_rows=64, max_seqs=4)
+    n_new, tau, cap = 40, 0.0, 15
+    prompts = [prompt_tokens(shape.vocab, 20 + 13 * s, 60 + s).numpy() for s in range(3)]
+    ids = [0, 1, 2]
+
+    def run(which):
+        cache = ee.KvCache(gm, 4, 1024, 64, cap)
+        seqs = ee.Sequences(shape.n_layers)
+        out = {s: ([], []) for s in which}
+        for s in which:
+            tok, ex, _ = ee.prefill(gm, cache, s, prompts[s], tau)
+            seqs.start(s, tok)
+            out[s][0].append(tok)
+            out[s][1].append(ex)
+        max_rows = 0
+        for _ in range(n_new - 1):
+            ro, tk, pm = seqs.rows(which)
+            max_rows = max(max_rows, len(tk))
+            nt, exl, _ = ee.decode_step(gm, cache, which, ro, tk, pm, tau)
+            seqs.update(which, nt, exl)
+            for j, s in enumerate(which):
+                out[s][0].append(int(nt[j]))
+                out[s][1].append(int(exl[j]))
+        cache.flush(which)
+        kv = {s: cache.read(s, 1, 0, len(prompts[s]) + n_new - 1) for s in which}
+        cache.close()
+        return out, max_rows, kv
+
+    try:
+        print("case: C3-shaped batch of many rows", flush=True)
+        both, max_rows, kvb = run(ids)
+        assert max_rows > 32
+        for s in ids:
+            solo, _, kvs = run([s])
+            assert both[s][0] == solo[s][0] and both[s][1] == solo[s][1], s
+            assert rel_err(kvb[s][0], kvs[s][0]) <= 1e-3 and rel_err(kvb[s][1], kvs[s][1]) <= 1e-3
+    finally:
+        gm.close()

@@ -238,6 +238,17 @@ def test_workload_generator_is_device_independent():
     assert torch.equal(prompt_tokens(50304, 1000, 3, "cpu"), prompt_tokens(50304, 1000, 3, "cuda:0").cpu())
 
 
+def test_ragged_batch_with_several_tiles_per_workgroup():
+    """The same ragged batch with the GEMMs forced to give every workgroup several column tiles (the variants that
+    the 7B shapes take when a step has many rows), including a head over more rows than LDS holds."""
+    ee.set_gemm_min_workgroups(1)
+    try:
+        test_ragged_batch_with_more_than_64_rows("bf16")
+        test_other_head_dims_with_split_kv(64, 256, 4)
+    finally:
+        ee.set_gemm_min_workgroups(512)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ragged_batch_with_more_than_64_rows(dtype):
     """Six ragged sequences at threshold 0.0 pile up deferred rows (up to 6 x 16 = 96 rows in one launch, more
