@@ -168,9 +168,11 @@ struct ee_model {
     std::vector<uint8_t> have;  // per tensor: set?
     int n_missing;
     char* pinned;            // host staging for the upload region, then the head results
+    char* pinned_dev;        // device view of the same memory
     HeadResult* results;     // host view
     HeadResult* results_dev; // device view of the same memory
     int32_t* pf_host_tokens; // pinned staging of one prompt pass's token ids
+    int head_tag = 0;        // tag of the latest head evaluation (see HeadResult::pad)
     float* dbg_logits;
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
@@ -408,9 +410,35 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.desc = dd;
     float* logits = (m->dbg_logits && n_head <= m->dbg_rows) ? m->dbg_logits : nullptr;
     Timed t(m, EE_K_HEAD, st);
+    m->head_tag = m->head_tag == 0x7fffffff ? 1 : m->head_tag + 1;
     HIPCHK(launch_gemm_head(g, (HeadPartial*)(m->ws + m->wsl.partials), (int32_t*)(m->ws + m->wsl.counters), logits, mode,
-                            threshold, m->results_dev, st));
+                            threshold, m->results_dev, m->head_tag, st));
     return EE_OK;
+}
+
+// Waits until the head evaluation launched last has written the results of the n_head rows listed in `hd`.
+// The results are in host memory: polling their tags returns a few microseconds after the kernel's store,
+// where a stream synchronisation takes tens of microseconds to wake the caller up.  The stream is queried
+// every so often, so that a failed launch (or a drained stream) ends the wait.
+int wait_head_results(ee_model* m, const SegDesc* hd, hipStream_t st) {
+    const int tag = m->head_tag;
+    for (unsigned spins = 1;; ++spins) {
+        bool all = true;
+        for (int i = 0; i < hd->n_head && all; ++i)
+            all = __atomic_load_n(&m->results[hd->head_slot[i]].pad, __ATOMIC_ACQUIRE) == tag;
+        if (all) return EE_OK;
+        if ((spins & 1023) == 0) {
+            hipError_t q = hipStreamQuery(st);
+            if (q == hipSuccess) {
+                HIPCHK(hipStreamSynchronize(st));
+                return EE_OK;
+            }
+            if (q != hipErrorNotReady) HIPCHK(q);
+        }
+#if defined(__x86_64__)
+        __builtin_ia32_pause();
+#endif
+    }
 }
 
 int ensure_blocks(ee_kv_cache* c, SeqState& s, int n_positions) {
@@ -430,7 +458,7 @@ void put_btab(const ee_model* m, const ee_kv_cache* c, int row, const SeqState& 
 }
 
 int upload(ee_model* m, hipStream_t st) {
-    HIPCHK(hipMemcpyAsync(m->ws + m->wsl.upload, m->pinned, m->wsl.upload_bytes, hipMemcpyHostToDevice, st));
+    HIPCHK(launch_copy16(m->pinned_dev, m->ws + m->wsl.upload, m->wsl.upload_bytes, st));
     return EE_OK;
 }
 
@@ -511,7 +539,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
         bool is_final = s == n_seg - 1;
         if (decode && hd->n_head > 0) {
             EECHK(run_head(m, c, s, s, hd->n_head, is_final ? HEAD_EMIT : HEAD_RULE, threshold, st));
-            HIPCHK(hipStreamSynchronize(st));
+            EECHK(wait_head_results(m, hd, st));
             int fired_now = 0;
             for (int i = 0; i < hd->n_head; ++i) {
                 int slot = hd->head_slot[i];
@@ -732,6 +760,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     int rc = EE_OK;
     do {
         if ((e = hipHostGetDevicePointer((void**)&m->results_dev, m->results, 0)) != hipSuccess) break;
+        if ((e = hipHostGetDevicePointer((void**)&m->pinned_dev, m->pinned, 0)) != hipSuccess) break;
         if ((e = hipMemsetAsync(m->ws + m->wsl.counters, 0, 256 * 4, st)) != hipSuccess) break;
         if (m->wsl.pf_rows && (e = hipMemsetAsync(m->ws + m->wsl.pf_begin, 0, m->wsl.total - m->wsl.pf_begin, st)) != hipSuccess) break;
         e = launch_rope_table((float*)(m->wbase + m->wl.rope), cfg->max_positions, cfg->head_dim, cfg->rope_base, st);

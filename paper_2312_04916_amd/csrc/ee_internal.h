@@ -32,7 +32,7 @@ struct HeadResult {
     int32_t token;
     float conf;
     int32_t fired;
-    int32_t pad;
+    int32_t pad;  // tag of the evaluation that wrote this entry, stored last (the host may poll it)
 };
 
 struct HeadPartial {
@@ -54,6 +54,9 @@ enum HeadMode { HEAD_RULE = 0, HEAD_EMIT = 1 };
 void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
 // ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
+
+// bytes (rounded up to 16; both buffers are sized and aligned for that) from host-mapped pinned memory to the device
+hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s);
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);
 
@@ -95,7 +98,7 @@ hipError_t launch_gemm_swiglu(const GemmCommon& c, void* act, size_t act_lo, int
 hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_t* rows, int T, int K, void* dst, size_t dst_lo,
                             hipStream_t s);
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
-                            float threshold, HeadResult* results, hipStream_t s);
+                            float threshold, HeadResult* results, int tag, hipStream_t s);
 
 hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,

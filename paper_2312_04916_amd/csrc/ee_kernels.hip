@@ -89,6 +89,20 @@ hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_
     return hipGetLastError();
 }
 
+// Copy from host-mapped pinned memory into the workspace by a kernel: the step's descriptors reach the device
+// in stream order without a hand-over to the copy engine (whose completion signal costs the next kernel some
+// twenty microseconds of waiting).
+__global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = (bytes + 15) / 16;
+    const unsigned grid = (unsigned)((n16 + 255) / 256 < 64 ? (n16 + 255) / 256 : 64);
+    EE_LAUNCH(copy16_kernel, dim3(grid ? grid : 1), dim3(256), s, (const u32x4*)src_mapped, (u32x4*)dst, n16);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // rotary table: cs[pos][i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
 // ------------------------------------------------------------------------------------------------
@@ -883,7 +897,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs
 // confidence = 1 / sum_i exp(z_i - z_max); exit iff confidence >= threshold (or always, for the final head)
 __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __restrict__ partials, int n_wg, int T, int mode,
                                                          float threshold, HeadResult* results,
-                                                         const SegDesc* __restrict__ desc) {
+                                                         const SegDesc* __restrict__ desc, int tag) {
     __shared__ float redm[512], reds[512];
     __shared__ int redi[512];
     // thread t folds workgroups t, t+512, ... in ascending order, then a fixed tree over the threads
@@ -918,7 +932,14 @@ __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __re
             r.conf = conf;
             r.fired = (mode == HEAD_EMIT) || (conf >= threshold);
             r.pad = 0;
-            results[desc->head_slot[m]] = r;
+            // The results live in host memory that the host polls: the tag goes last, after a system-wide
+            // fence, so that a host that sees the tag sees the rest.
+            HeadResult* dst = results + desc->head_slot[m];
+            dst->token = r.token;
+            dst->conf = r.conf;
+            dst->fired = r.fired;
+            __threadfence_system();
+            __hip_atomic_store(&dst->pad, tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         __syncthreads();
     }
@@ -1115,7 +1136,7 @@ hipError_t launch_gemm_swiglu(const GemmCommon& cc, void* act, size_t act_lo, in
 }
 
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
-                            float threshold, HeadResult* results, hipStream_t s) {
+                            float threshold, HeadResult* results, int tag, hipStream_t s) {
     (void)counter;
     if (c.T <= 0) return hipSuccess;
     if (c.T > 64) return hipErrorInvalidValue;
@@ -1128,7 +1149,7 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, c.N / 16, c.T, mode, threshold, results, c.desc);
+    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, c.N / 16, c.T, mode, threshold, results, c.desc, tag);
     return hipGetLastError();
 }
 
