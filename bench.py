@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel family (extra passes, stderr)")
     ap.add_argument("--cpu-threads", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
+    ap.add_argument("--refeed", action="store_true",
+                    help="deferred tokens are fed again from the embedding (paper-literal) instead of resuming")
     ap.add_argument("--no-prefill-bench", action="store_true", help="skip the timing of the prompt phase")
     ap.add_argument("--prefill-only", action="store_true", help="time the prompt phase only and print its figures")
     ap.add_argument("--pmc-run", action="store_true",
@@ -225,6 +227,7 @@ def main():
         torch.cuda.synchronize()
         del t
     cache = ee.KvCache(gm, B, sum(lens) + B * (args.warmup + args.steps + 48), 64, args.max_pending)
+    cache.set_refeed(args.refeed)
     prompts = [prompt_tokens(shape.vocab, lens[b], wl.prompt_seed + b).numpy() for b in range(B)]
     prompt = prompts[0]
     print(f"[bench] model {args.workload} ready in {time.perf_counter() - t_setup:.1f}s "
@@ -277,6 +280,24 @@ def main():
                                "bytes_model_speedup": full["bytes"] / r["bytes"], "forced_full_steps": r["forced"],
                                "exit_histogram": {str(e): r["exits"].count(e) for e in sorted(set(r["exits"]))}}
 
+    # cap on the deferred-token list (Appendix D.3) x how the deferred tokens are carried (resume / re-feed), at the
+    # workload's lowest threshold: where carrying more rows stops being free
+    pending_sweep = {}
+    if not args.no_sweep and B == 1:
+        # threshold 0: every token leaves at the first exit, the list always grows to the cap and is then cleared by
+        # one forced full-depth step over cap + 1 rows (the cost of carrying rows in its purest form)
+        for tau_s in (min(wl.thresholds), 0.0):
+            res = {}
+            for cap in (1, 3, 7, 15, 31, 63):
+                for mode in ("resume", "refeed"):
+                    pc = ee.KvCache(gm, B, sum(lens) + B * (args.warmup + args.steps + 48), 64, cap)
+                    pc.set_refeed(mode == "refeed")
+                    r = generate(ee, gm, pc, prompts, tau_s, args.warmup, args.steps, shape, es, cap)
+                    res[f"{mode}_{cap}"] = {"tokens_per_s": r["tokens"] / r["seconds"], "forced_full_steps": r["forced"],
+                                            "speedup_vs_full_depth": full["seconds"] / r["seconds"]}
+                    pc.close()
+            pending_sweep[f"threshold_{tau_s}"] = res
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
@@ -295,6 +316,7 @@ def main():
         "full_depth_tokens_per_s": tps_full, "full_depth_ms_per_step": full["seconds"] / args.steps * 1e3,
         "speedup_vs_full_depth": tps / tps_full, "bytes_model_speedup": ideal_speedup,
         "exit_histogram": hist, "forced_full_steps": early["forced"], "threshold_sweep": sweep,
+        "max_pending_sweep": pending_sweep, "deferred_tokens": "refeed" if args.refeed else "resume",
         "hbm_gbps": early["bytes"] / early["seconds"] / 1e9, "hbm_frac": early["bytes"] / early["seconds"] / 1e9 / HBM_PEAK_GBPS,
         "full_depth_hbm_gbps": full["bytes"] / full["seconds"] / 1e9,
         "full_depth_hbm_frac": full["bytes"] / full["seconds"] / 1e9 / HBM_PEAK_GBPS,

@@ -138,6 +138,12 @@ int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms);
 
 /* ---------------------------------------------------------------- KV cache */
 
+/* How the deferred tokens of this cache are carried along (Section 4, "KV recomputation").  on = 0 (default):
+ * each resumes from the residual row saved at the depth it reached and joins only the layers it still lacks.
+ * on = 1: the paper's wording taken literally, the deferred tokens are fed again from the embedding, so
+ * every layer of the step sees them and rewrites their (identical) shallow KV entries.  Results are the same;
+ * the second does more work per step.  May be switched at any time. */
+int ee_kv_cache_set_refeed(ee_kv_cache* c, int on);
 /* The cache is paged: a pool of blocks of block_tokens positions (a multiple of 32), shared by up to
  * max_seqs sequences, max_tokens_total positions in all.  Besides K and V it holds, per sequence, the
  * residual rows of the deferred tokens (max_pending + 1 rows) so that a deferred token resumes above

@@ -18,7 +18,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
            "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
-           "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
+           "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
 
@@ -70,6 +70,7 @@ def lib():
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
         L.ee_kv_cache_reset.argtypes = [vp, C.c_int]
+        L.ee_kv_cache_set_refeed.argtypes = [vp, C.c_int]
         L.ee_kv_cache_filled.argtypes = [vp, C.c_int, C.c_int, i32p]
         L.ee_kv_cache_pending.argtypes = [vp, C.c_int, i32p]
         L.ee_kv_cache_read.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, fp, fp, vp]
@@ -203,6 +204,9 @@ class KvCache:
 
     def reset(self, seq: int) -> None:
         _chk(lib().ee_kv_cache_reset(self.h, seq), "ee_kv_cache_reset")
+
+    def set_refeed(self, on: bool) -> None:
+        _chk(lib().ee_kv_cache_set_refeed(self.h, 1 if on else 0), "ee_kv_cache_set_refeed")
 
     def filled(self, seq: int, layer: int) -> int:
         n = C.c_int32()

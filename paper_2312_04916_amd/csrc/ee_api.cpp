@@ -221,6 +221,7 @@ struct SeqState {
 struct ee_kv_cache {
     const ee_model* m;
     int max_seqs, BT, S, max_pending, n_blocks;
+    int refeed = 0;  // deferred tokens re-enter at layer 1 (the paper's wording) instead of resuming where they stopped
     char* pool;
     size_t off_x, off_xg, off_xgh, off_ssq;
     size_t xs_lo;    // element distance from the hi to the lo term in xg / xgh (0 for fp32)
@@ -474,12 +475,13 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
     for (size_t b = 0; b < ss.size(); ++b) {
         if (!ss[b].active) continue;
         const SeqState& s = c->seqs[ss[b].seq];
-        int lo = s.filled[seg];
+        int lo = c->refeed ? s.filled.back() : s.filled[seg];
         int hi = ss[b].p >= 0 ? ss[b].p : s.filled[0] - 1;  // inclusive
         int first = T;
         for (int pos = lo; pos <= hi; ++pos, ++T) {
             if (T >= EE_MAX_ROWS) { *rows_out = EE_MAX_ROWS + 1; return; }
             d->xrow[T] = c->slot_of(ss[b].seq, pos);
+            if (seg == 0) m->host_tokens()[T] = s.tokring[pos % c->S];  // rows that start at the embedding
             d->pos[T] = pos;
             d->kvblk[T] = s.blocks[pos / c->BT];
             d->rseq[T] = (int)b;
@@ -531,7 +533,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     for (int s = 0; s < n_seg && n_active > 0; ++s) {
         const SegDesc* hd = m->host_desc(s);
         if (hd->T > 0) {
-            if (s == 0 && decode)
+            if (s == 0 && (decode || c->refeed))
                 HIPCHK(launch_embed(m->cfg.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), hd->T, m->cfg.d_model,
                                     m->gain(m->wl.g1[0]), c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
             EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
@@ -989,6 +991,12 @@ int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total
     return EE_OK;
 }
 
+int ee_kv_cache_set_refeed(ee_kv_cache* c, int on) {
+    if (!c) return EE_ERR_ARG;
+    c->refeed = on ? 1 : 0;
+    return EE_OK;
+}
+
 int ee_kv_cache_reset(ee_kv_cache* c, int seq) {
     if (!c) return EE_ERR_ARG;
     if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
@@ -1213,7 +1221,6 @@ int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_i
         EECHK(ensure_blocks(c, s, ss[b].p + 1));
         int tok = tokens[row_offsets[b + 1] - 1];
         s.tokring[ss[b].p % c->S] = tok;
-        m->host_tokens()[b] = tok;  // segment 0 has exactly one row per sequence, in step order
     }
     return run_step(m, c, ss, threshold, true, next_token, exit_layer, conf, (hipStream_t)stream);
 }

@@ -102,6 +102,34 @@ def test_forced_full_depth(pair, prompt, cap):
     cache.close()
 
 
+@pytest.mark.parametrize("tau,cap", [(0.0, 3), (0.35, 40), (0.2, 6)])
+def test_refeed_mode_matches_oracle_and_resume_mode(pair, prompt, tau, cap):
+    """Deferred tokens fed again from the embedding (the paper's literal wording, which is what the oracle's G1 does)
+    give the same tokens, exit layers and KV as resuming them from their saved residual rows."""
+    shape, om, gm = pair
+    print(f"case: refeed {shape.dtype} tau={tau} cap={cap}", flush=True)
+    outs = []
+    for refeed in (False, True):
+        cache = new_cache(gm, max_pending=cap)
+        cache.set_refeed(refeed)
+        rep = lockstep(gm, cache, om, prompt, 26, tau, max_pending=cap)
+        assert not rep.mismatches, rep.mismatches[:5]
+        assert rep.max_hidden_err <= TOL[shape.dtype]
+        n_pos = len(prompt) + 25
+        cache.flush([0])
+        assert cache.pending(0) == 0
+        kv = [cache.read(0, l, 0, n_pos) for l in range(shape.n_layers)]
+        outs.append((rep.tokens, rep.exit_layers, kv))
+        rep.state.flush()
+        for l in range(shape.n_layers):
+            ko, vo = rep.state.kv_read(l, 0, n_pos)
+            assert rel_err(kv[l][0], ko) <= TOL[shape.dtype] and rel_err(kv[l][1], vo) <= TOL[shape.dtype]
+        cache.close()
+    assert outs[0][0] == outs[1][0] and outs[0][1] == outs[1][1]
+    for l in range(shape.n_layers):
+        assert rel_err(outs[1][2][l][0], outs[0][2][l][0]) <= 1e-3 and rel_err(outs[1][2][l][1], outs[0][2][l][1]) <= 1e-3
+
+
 def test_two_sequences_equal_each_alone(pair, prompt):
     """Sequences are independent: a batch of two ragged sequences gives what each gives alone."""
     shape, om, gm = pair
