@@ -70,8 +70,8 @@ struct PfArgs {
 // NWAVE waves per workgroup, arranged (NWAVE/2) along the features x 2 along the rows: a wave owns
 // WNF = 32/NWAVE weight tiles and MTL/2 row tiles.  The GEMMs run 8 waves (two per SIMD: a single wave
 // cannot issue 16x16x32 MFMAs back to back fast enough to keep the matrix core busy) with one workgroup
-// per CU and four stages; the head kernel keeps 4 waves, two workgroups per CU and two stages (measured
-// equal, and its row reduction is written for two waves along the features).
+// per CU and four stages.  The head GEMM, whose grid is several times the chip, keeps 4 waves and two workgroups
+// per CU with two stages.
 template <int MTL>
 struct PfTile {
     int nt0, mt0, n_wg, wn, wm;
@@ -218,8 +218,8 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
 }
 
 template <int MTL, int NWAVE>
-constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to four reduction rows
-    return pf_stages<MTL, NWAVE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 5;
+constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to seven reduction rows
+    return pf_stages<MTL, NWAVE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
 }
 
 template <int MTL, int NWAVE>
@@ -445,11 +445,11 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_head_kernel(PfArgs a, PfHead
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
     float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
-    static_assert(NWAVE == 4, "the merge below is written for two waves along the features");
-    float* red = rs + MTL * 16;  // wave wn = 1 hands (max, sum) over here, the index in a second array
+    constexpr int WN = NWAVE / 2;        // waves along the features
+    float* red = rs + MTL * 16;          // waves wn > 0 hand (max, sum) over here: [2 * (wn - 1) + {0, 1}][MTL * 16]
     f32x4 acc[WNF][MW];
     pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
-    int* redi = (int*)pf_lds;  // (the stage buffers are free now)
+    int* redi = (int*)pf_lds;            // ... and the index here (the stage buffers are free now): [wn - 1][MTL * 16]
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
@@ -493,14 +493,17 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_head_kernel(PfArgs a, PfHead
                 pf_merge(mx, sm, ix, m2, s2, i2);
             }
         }
-        if (t.wn == 1 && rg == 0) {
-            red[ml] = mx;
-            red[MTL * 16 + ml] = sm;
-            redi[ml] = ix;
+        if (t.wn > 0 && rg == 0) {
+            red[(2 * (t.wn - 1)) * (MTL * 16) + ml] = mx;
+            red[(2 * (t.wn - 1) + 1) * (MTL * 16) + ml] = sm;
+            redi[(t.wn - 1) * (MTL * 16) + ml] = ix;
         }
         __syncthreads();
         if (t.wn == 0 && rg == 0) {
-            pf_merge(mx, sm, ix, red[ml], red[MTL * 16 + ml], redi[ml]);
+#pragma unroll
+            for (int wv = 1; wv < WN; ++wv)
+                pf_merge(mx, sm, ix, red[(2 * (wv - 1)) * (MTL * 16) + ml], red[(2 * (wv - 1) + 1) * (MTL * 16) + ml],
+                         redi[(wv - 1) * (MTL * 16) + ml]);
             const int m = t.mt0 * 16 + ml;
             if (m < a.M) {
                 HeadPartial p;
@@ -876,6 +879,8 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
     {
         PfHead e{partials, g.N};
         PfArgs a = pf_args(g, 8);
+        // (4 waves, two workgroups per CU: with ~1600 workgroups the shared CUs smooth the last round; 8 waves with
+        // one workgroup per CU measured 750 us against 640 us at 1024 rows)
         constexpr size_t lds_b = pf_lds_bytes<8, 4>();
         static hipError_t once = pf_set_lds(pf_head_kernel<8, 4>, lds_b);
         if (once != hipSuccess) return once;
