@@ -8,7 +8,9 @@ batch.  Inputs are seeded and synthetic (workload/gen.py): the 7B-shaped model o
 a 1024-token uniform-random prompt, greedy decoding.  Weights and the KV cache are resident in HBM
 before the timed region starts.
 
-Prints ONE JSON line (see the design doc for every field).
+Prints ONE JSON line: the headline metric, `roofline` (the dominant decode kernel against HBM bandwidth),
+`prefill` (the prompt phase, with its own `roofline` against the matrix-core peak), the threshold and
+deferred-token-cap sweeps, and `cpu_baseline` (the CPU oracle timed on a bounded sample).
 """
 import argparse
 import json
@@ -109,7 +111,7 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
 MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 
 
-def prefill_bench(ee, gm, cache, prompt, shape, breakdown):
+def prefill_bench(ee, gm, cache, prompt, shape, breakdown, traffic=None):
     """Times the prompt phase (GEMM path) on one prompt: plain ee_prefill, the scored variant (every head on
     every position), and the gate|up GEMM alone (HIP events on its dispatches).  Algorithmic flops: 2*P*params
     of the layers + causal attention; every activation operand is two bf16 terms, so the matrix cores issue
@@ -156,7 +158,7 @@ def prefill_bench(ee, gm, cache, prompt, shape, breakdown):
                      "achieved": sw_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sw_tflops / MFMA_PEAK_TFLOPS,
                      "mfma_issue_tflops": 2 * sw_tflops, "mfma_issue_frac": 2 * sw_tflops / MFMA_PEAK_TFLOPS,
                      "launches": n_sw, "avg_us": ms_sw / max(n_sw, 1) * 1e3, "flops_per_launch": 2.0 * P * 2 * F * d,
-                     "traffic": None},
+                     "traffic": traffic},
     }
     if breakdown:
         for k, name in enumerate(ee.KERNEL_NAMES):
@@ -164,6 +166,15 @@ def prefill_bench(ee, gm, cache, prompt, shape, breakdown):
             print(f"[bench] prefill {name:10s} launches {n:5d} avg {ms / max(n, 1) * 1e3:9.2f} us total {ms:8.2f} ms",
                   file=sys.stderr, flush=True)
     return out
+
+
+def stored_traffic(key):
+    """HBM bytes per launch measured with rocprofv3 counters (profiles/pmc_traffic.json), or None."""
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if not os.path.exists(tpath):
+        return None
+    with open(tpath) as f:
+        return json.load(f).get(key)
 
 
 def cpu_baseline(shape, tensors_host, prompt, tau, max_pending, threads):
@@ -244,7 +255,7 @@ def main():
         return
     prefill = None
     if shape.dtype == "bf16" and shape.d_model % 128 == 0 and not args.no_prefill_bench:
-        prefill = prefill_bench(ee, gm, cache, prompts[0], shape, args.breakdown)
+        prefill = prefill_bench(ee, gm, cache, prompts[0], shape, args.breakdown, stored_traffic(f"pf_swiglu_{args.workload}"))
         print(f"[bench] prefill {prefill['prompt_tokens']} tokens: {prefill['ms']:.2f} ms, "
               f"{prefill['algorithmic_tflops']:.0f} TFLOP/s algorithmic", file=sys.stderr, flush=True)
         if args.prefill_only:
@@ -298,11 +309,7 @@ def main():
                     pc.close()
             pending_sweep[f"threshold_{tau_s}"] = res
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(f"swiglu_{args.workload}")
+    traffic = stored_traffic(f"swiglu_{args.workload}")
 
     out = {
         "metric": ("generated tokens/s at 7B early-exit decode (thr 0.8) vs full-depth; HBM GB/s" if args.workload == "C3"
