@@ -130,6 +130,41 @@ def test_refeed_mode_matches_oracle_and_resume_mode(pair, prompt, tau, cap):
         assert rel_err(outs[1][2][l][0], outs[0][2][l][0]) <= 1e-3 and rel_err(outs[1][2][l][1], outs[0][2][l][1]) <= 1e-3
 
 
+def test_cap_zero_is_plain_greedy_and_cap_63_fills_a_whole_pass(pair, prompt):
+    """Degenerate caps: with max_pending 0 every step is forced to full depth (plain greedy decoding whatever the
+    threshold); with the largest cap (63) and threshold 0 one sequence piles up 64 rows before the forced step."""
+    shape, om, gm = pair
+    print(f"case: caps 0 / 63 {shape.dtype}", flush=True)
+    def decode(cap, tau_decode):
+        cache = new_cache(gm, max_pending=cap)
+        tok, ex, _ = ee.prefill(gm, cache, 0, prompt, 0.0)
+        seqs = ee.Sequences(shape.n_layers)
+        seqs.start(0, tok)
+        toks, exits = [tok], [ex]
+        for _ in range(11):
+            ro, tk, pm = seqs.rows([0])
+            nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, tau_decode)
+            seqs.update([0], nt, exl)
+            toks.append(int(nt[0]))
+            exits.append(int(exl[0]))
+        assert cache.pending(0) == 0
+        cache.close()
+        return toks, exits
+
+    forced_toks, forced_exits = decode(0, 0.0)      # threshold 0, but every step is forced
+    plain_toks, _ = decode(15, 1.0)                 # exits disabled
+    assert forced_toks == plain_toks and set(forced_exits[1:]) == {shape.n_layers}
+    if shape.dtype == "f32":
+        ref = om.generate_plain(np.concatenate([prompt, [forced_toks[0]]]).astype(np.int32), 11).tolist()
+        assert forced_toks[1:] == ref
+    cache = ee.KvCache(gm, 1, 512, 32, 63)
+    rep = lockstep(gm, cache, om, prompt, 70, 0.0, max_pending=63, max_positions=128)
+    assert not rep.mismatches, rep.mismatches[:5]
+    assert rep.exit_layers[64] == shape.n_layers and rep.forced_full == 1 and cache.pending(0) == 5
+    assert rep.max_hidden_err <= TOL[shape.dtype]
+    cache.close()
+
+
 def test_two_sequences_equal_each_alone(pair, prompt):
     """Sequences are independent: a batch of two ragged sequences gives what each gives alone."""
     shape, om, gm = pair
@@ -251,6 +286,51 @@ def test_other_head_dims_with_split_kv(hd, d, H):
     print(f"head_dim {hd}: hidden err {rep.max_hidden_err:.2e} logit err {rep.max_logit_err:.2e} "
           f"teacher-forced {rep.teacher_forced} exits {sorted(set(rep.exit_layers))}", flush=True)
     cache.close()
+    gm.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_maximum_rows_per_step(dtype):
+    """Four sequences with the largest cap at threshold 0 reach 4 x 64 = 256 rows in one launch (the library's
+    maximum, four row passes); each must emit what it emits alone, and one row more is refused."""
+    print(f"case: 256 rows {dtype}", flush=True)
+    shape = C1.shape if dtype == "f32" else TINY_BF16
+    gm = load_gpu_model(shape, 0, gain_jitter=0.1, max_positions=256, max_rows=256, max_seqs=5)
+    n_new, cap = 66, 63
+    prompts = [prompt_tokens(shape.vocab, 5 + 3 * s, 70 + s).numpy() for s in range(5)]
+
+    def run(which, expect_fail_at=None):
+        cache = ee.KvCache(gm, 5, 2048, 32, cap)
+        seqs = ee.Sequences(shape.n_layers)
+        out = {s: [] for s in which}
+        for s in which:
+            tok, ex, _ = ee.prefill(gm, cache, s, prompts[s], 0.0)
+            seqs.start(s, tok)
+            out[s].append((tok, ex))
+        max_rows = 0
+        for step in range(n_new - 1):
+            ro, tk, pm = seqs.rows(which)
+            max_rows = max(max_rows, len(tk))
+            if expect_fail_at is not None and len(tk) > 256:
+                with pytest.raises(ee.EeError) as e:
+                    ee.decode_step(gm, cache, which, ro, tk, pm, 0.0)
+                assert e.value.code == -2
+                cache.close()
+                return None, max_rows
+            nt, exl, _ = ee.decode_step(gm, cache, which, ro, tk, pm, 0.0)
+            seqs.update(which, nt, exl)
+            for j, s in enumerate(which):
+                out[s].append((int(nt[j]), int(exl[j])))
+        cache.close()
+        return out, max_rows
+
+    both, max_rows = run([0, 1, 2, 3])
+    assert max_rows == 256
+    for s in range(4):
+        solo, _ = run([s])
+        assert both[s] == solo[s], s
+    _, max_rows = run([0, 1, 2, 3, 4], expect_fail_at=True)   # five sequences would need 257+ rows: refused
+    assert max_rows > 256
     gm.close()
 
 
