@@ -298,6 +298,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         g.dtype = dt;
         g.T = T;
         g.desc = dd;
+        g.desc_host = m->host_desc(di);
         g.inv_d = 1.0f / (float)d;
         g.eps = cf.rms_eps;
         g.ssq_stride = c->ssq_stride;
@@ -409,6 +410,7 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.eps = cf.rms_eps;
     g.T = n_head;
     g.desc = dd;
+    g.desc_host = m->host_desc(di);
     float* logits = (m->dbg_logits && n_head <= m->dbg_rows) ? m->dbg_logits : nullptr;
     Timed t(m, EE_K_HEAD, st);
     m->head_tag = m->head_tag == 0x7fffffff ? 1 : m->head_tag + 1;

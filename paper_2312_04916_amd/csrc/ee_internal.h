@@ -82,6 +82,7 @@ struct GemmCommon {
     float inv_d, eps;
     int T;  // rows
     const SegDesc* desc;
+    const SegDesc* desc_host;  // host copy of *desc, or NULL: launches of up to 16 rows then carry the row indices by value
     // O projection only: A still lies as the attention kernel's split partials (att_ns splits), to be merged
     // while the rows are staged; NULL otherwise
     const float* att_part;

@@ -242,6 +242,11 @@ struct GemmArgs {
     float inv_d, eps;
     int T;
     int n_tiles;  // N / 16
+    // Up to 16 rows: the row indirection (and, for the attention merge, row -> query tile) by value, so that the
+    // first loads of a workgroup do not hang off a load of the descriptor.
+    int has_row_v;
+    int32_t arow_v[16];
+    int32_t rq_v[16];
     int a_packed; // A is stored in MFMA operand order [row/16][K/32][64 lanes][8] (dense rows, no indirection)
     // A given as split-KV attention partials instead of rows (few-rows variant of the O projection only)
     const float* att_part;
@@ -259,6 +264,10 @@ struct GemmSmem {
     float rs[MT * 16];
 };
 
+__device__ __forceinline__ int gemm_slot(const GemmArgs& a, int m) {
+    return a.has_row_v ? a.arow_v[m] : (a.arow ? a.arow[m] : m);
+}
+
 template <int MT>
 __device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
     // r[m] = 1/sqrt(mean(x^2)+eps).  The sum of squares arrives as ssq_n partial sums (one per producing
@@ -267,7 +276,7 @@ __device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
     for (int m = wave; m < MT * 16; m += nw) {
         float r = 1.f;
         if (a.ssq != nullptr && m < a.T) {
-            int slot = a.arow ? a.arow[m] : m;
+            int slot = gemm_slot(a, m);
             const float* p = a.ssq + (size_t)slot * a.ssq_stride;
             float s = 0.f;
             for (int i = lane; i < a.ssq_n; i += 64) s += p[i];
@@ -511,6 +520,20 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
     u32x4 w[D];
     const int n = kt1 - kt0;
     auto fill = [&](int u, int t) { w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64); };
+    // Sum-of-squares partials of the rows: wave w takes rows w, w + KS.  The loads go out first, ahead of the
+    // weight stream, and are reduced after the rows have been staged.
+    constexpr int RPW = (16 + KS - 1) / KS;  // rows per wave
+    float ssq_part[RPW];
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int m = ks + j * KS;
+        float sp = 0.f;
+        if (a.ssq != nullptr && m < a.T) {
+            const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
+            for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
+        }
+        ssq_part[j] = sp;
+    }
 #pragma unroll
     for (int u = 0; u < D; ++u)
         if (u < n) fill(u, u);
@@ -524,7 +547,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
         for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
             const int m = c / cpr, k8 = c - m * cpr;
             const int h = (k8 * 8) / a.att_hd, cc = (k8 * 8) % a.att_hd;
-            const int rq = a.att_desc->row_qt[m];
+            const int rq = a.has_row_v ? a.rq_v[m] : a.att_desc->row_qt[m];
             const int qt = rq >> 4, qq = rq & 15;
             const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * NS * pstride;
             // every load of every split goes out before the first is used: one memory round trip in all
@@ -570,17 +593,25 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
             *(bf16x8*)(abuf + (size_t)m * rstride + K + k8 * 8) = lv;
         }
     } else {
-        for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
-            int m = c / cpr, k8 = c - m * cpr;
-            int slot = a.arow ? a.arow[m] : m;
-            const __bf16* src = (const __bf16*)a.A + (size_t)slot * a.lda + k8 * 8;
-            u32x4 h = *(const u32x4*)src;
-            u32x4 l = *(const u32x4*)(src + a.a_lo);
-            *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
-            *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+        for (int m = 0; m < a.T; ++m) {  // (row by row: the row's slot is uniform, a scalar load at most)
+            const __bf16* srow = (const __bf16*)a.A + (size_t)gemm_slot(a, m) * a.lda;
+            for (int k8 = threadIdx.x; k8 < cpr; k8 += blockDim.x) {
+                u32x4 h = *(const u32x4*)(srow + k8 * 8);
+                u32x4 l = *(const u32x4*)(srow + a.a_lo + k8 * 8);
+                *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
+                *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+            }
         }
     }
-    rms_scales<1>(a, sm.rs);
+    // r[m] = 1/sqrt(mean(x^2)+eps): lane partials (fetched at the top, long back by now) through a fixed butterfly
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int m = ks + j * KS;
+        float sp = ssq_part[j];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+        if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
+    }
     pre();
     __syncthreads();
     const __bf16* ar = abuf + (size_t)(li < a.T ? li : 0) * rstride + (size_t)kt0 * 32 + lg * 8;
@@ -658,6 +689,8 @@ __device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, Gemm
         gemm_mainloop_f32<KS, MT>(a, tile0, sm, pre);
 }
 
+// (Launch bounds of the few-rows variants: 6 waves per SIMD, i.e. at most 80 registers per lane, so that three
+// 8-wave workgroups share a CU; a few registers more would cost a whole workgroup of residency.)
 // ---- epilogue 1: rotary embedding, q to the workspace, k and v into the paged cache.
 // Tile (part, head h, c): columns 0..7 = features h*hd + c*8 + i, columns 8..15 = their rotary partners.
 template <typename ST>
@@ -674,7 +707,7 @@ struct QkvArgs {
 };
 
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
-__global__ __launch_bounds__(KS * 64) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
+__global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_qkv_kernel(GemmArgs a, QkvArgs<ST> e) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int per_head = e.hd / 16, per_part = e.H * per_head;
     const int half = e.hd / 2;
@@ -748,7 +781,14 @@ struct ResidArgs {
     const int32_t* xrow;  // per row: slot in the residual store
     ST* xg_pk;            // optional: the same operand again, dense rows of this launch in packed order
     size_t xg_pk_lo;
+    int has_v;            // up to 16 rows: the slots by value
+    int32_t xrow_v[16];
 };
+
+template <typename ST>
+__device__ __forceinline__ int resid_slot(const ResidArgs<ST>& e, int m) {
+    return e.has_v ? e.xrow_v[m] : e.xrow[m];
+}
 
 template <typename ST, int KS, int MT, bool ALDS, bool ATT, int G>
 __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidArgs<ST>& e) {
@@ -760,7 +800,7 @@ __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidAr
     float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
     auto pre = [&]() {
         if (m0 < a.T) {
-            o0 = (size_t)e.xrow[m0] * e.d + tile0 * 16 + i0;
+            o0 = (size_t)resid_slot(e, m0) * e.d + tile0 * 16 + i0;
             x0 = e.x[o0];
             gn0 = e.g_next[tile0 * 16 + i0];
             if (e.xgh) gh0 = e.g_head[tile0 * 16 + i0];
@@ -779,7 +819,7 @@ __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidAr
             size_t o = o0;
             float xv = x0, gn = gn0, gh = gh0;
             if (g != 0 || idx != (int)threadIdx.x) {
-                o = (size_t)e.xrow[m] * e.d + n0 + i;
+                o = (size_t)resid_slot(e, m) * e.d + n0 + i;
                 xv = e.x[o];
                 gn = e.g_next[n0 + i];
                 if (e.xgh) gh = e.g_head[n0 + i];
@@ -797,13 +837,13 @@ __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidAr
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += out[m][i] * out[m][i];
-            e.ssq_out[(size_t)e.xrow[m] * e.ssq_stride + tile] = s;
+            e.ssq_out[(size_t)resid_slot(e, m) * e.ssq_stride + tile] = s;
         }
     }
 }
 
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
-__global__ __launch_bounds__(KS * 64) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
+__global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
     gemm_resid_body<ST, KS, MT, ALDS, false, G>(a, e);
 }
 
@@ -815,7 +855,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_resid_att_kernel(GemmArgs a, Res
 
 // ---- epilogue 3: SwiGLU.  Tile j: columns 0..7 = gate features 8j.., columns 8..15 = the matching up features
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
-__global__ __launch_bounds__(KS * 64) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F, int act_pk) {
+__global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F, int act_pk) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int tile0 = blockIdx.x * G;
     gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
@@ -855,7 +895,7 @@ __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float 
 }
 
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
-__global__ __launch_bounds__(KS * 64) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
+__global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int tile0 = blockIdx.x * G;
     gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
@@ -962,6 +1002,15 @@ static GemmArgs make_args(const GemmCommon& c) {
     a.eps = c.eps;
     a.T = c.T;
     a.n_tiles = c.N / 16;
+    a.has_row_v = 0;
+    if (c.desc_host != nullptr && c.T <= 16) {
+        a.has_row_v = 1;
+        const int32_t* rows = c.arow ? (const int32_t*)((const char*)c.desc_host + ((const char*)c.arow - (const char*)c.desc)) : nullptr;
+        for (int i = 0; i < 16; ++i) {
+            a.arow_v[i] = i < c.T ? (rows ? rows[i] : i) : 0;
+            a.rq_v[i] = i < c.T ? c.desc_host->row_qt[i] : 0;
+        }
+    }
     a.a_packed = c.a_packed;
     a.att_part = c.att_part;
     a.att_desc = c.desc;
@@ -1088,6 +1137,13 @@ hipError_t launch_gemm_qkv(const GemmCommon& cc, void* q, size_t q_lo, const flo
     return hipSuccess;
 }
 
+template <typename ST>
+static void fill_rows(ResidArgs<ST>& e, const GemmCommon& c, int T_all) {
+    if (c.desc_host == nullptr || T_all > 16) return;
+    e.has_v = 1;
+    for (int i = 0; i < T_all; ++i) e.xrow_v[i] = c.desc_host->xrow[i];
+}
+
 hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh, size_t xs_lo, float* ssq_out,
                              const float* g_next, const float* g_head, int d, void* xg_pk, size_t xg_pk_lo, hipStream_t s) {
     for (int r0 = 0; r0 < cc.T; r0 += PASS_ROWS) {
@@ -1098,7 +1154,8 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
             // input still lies as attention split partials: only the few-rows variant can merge them
             const size_t sm = a_lds_bytes(c);
             if (sm == 0 || cc.T > PASS_ROWS) return hipErrorInvalidValue;
-            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0};
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0, 0, {}};
+            fill_rows(e, c, cc.T);
             // (at most 8 waves: the merge holds every split's partials in registers at once)
             const int ks = ks_of(c) == 4 ? 4 : 8;
             dim3 grid(c.N / 16), block(ks * 64);
@@ -1107,10 +1164,12 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
         } else if (c.dtype == EE_BF16) {
             // (the packed copy of a later pass starts r0/16 row groups further on)
             __bf16* pk = xg_pk ? (__bf16*)xg_pk + (size_t)(r0 / 16) * (d / 32) * 512 : nullptr;
-            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, pk, xg_pk_lo};
+            ResidArgs<__bf16> e{x, (__bf16*)xg, (__bf16*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, pk, xg_pk_lo, 0, {}};
+            fill_rows(e, c, cc.T);
             EE_DISPATCH(__bf16, gemm_resid_kernel, a, e);
         } else {
-            ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0};
+            ResidArgs<float> e{x, (float*)xg, (float*)xgh, xs_lo, ssq_out, c.ssq_stride, g_next, g_head, d, xrow, nullptr, 0, 0, {}};
+            fill_rows(e, c, cc.T);
             EE_DISPATCH_F32(gemm_resid_kernel, a, e);
         }
         hipError_t err = hipGetLastError();
