@@ -311,6 +311,11 @@ def main():
 
     traffic = stored_traffic(f"swiglu_{args.workload}")
 
+    # what a kernel that only reads gets out of this GPU's memory: the whole weight buffer in one launch, and launches
+    # of the roofline kernel's own size back to back
+    stream_all = gm.measure_stream_read(0, 3)
+    stream_k = gm.measure_stream_read(w_swiglu, 50)
+
     out = {
         "metric": ("generated tokens/s at 7B early-exit decode (thr 0.8) vs full-depth; HBM GB/s" if args.workload == "C3"
                    else f"generated tokens/s, early-exit decode, workload {args.workload} ({wl.note})"),
@@ -331,6 +336,9 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "launches": n_l, "avg_us": ms_l / max(n_l, 1) * 1e3, "bytes_per_launch": w_swiglu,
                      "traffic": traffic},
+        "measured_stream_read": {"unit": "GB/s", "whole_weight_buffer": stream_all, "launches_of_roofline_kernel_size": stream_k,
+                                 "roofline_kernel_frac_of_it": achieved / stream_k if stream_k > 0 else None,
+                                 "full_depth_step_frac_of_whole_buffer_rate": full["bytes"] / full["seconds"] / 1e9 / stream_all if stream_all > 0 else None},
     }
     if prefill is not None:
         out["prefill"] = prefill

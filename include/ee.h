@@ -136,6 +136,14 @@ enum { EE_K_QKV = 0, EE_K_ATTN = 1, EE_K_OPROJ = 2, EE_K_SWIGLU = 3, EE_K_DOWN =
 int ee_profile_begin(ee_model* m, int kernel, int max_launches);
 int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms);
 
+/* Measurement hook: a kernel that only reads (16 bytes per lane and load, eight loads in flight per wave) is run
+ * n_launches times (1..1000) back to back over `bytes` bytes of the model's own weight buffer (0, or more than the
+ * buffer holds: all of it; a shorter read moves its start between launches), timed with a HIP event pair on
+ * `stream`; *gb_per_s (host) receives bytes read / time in 1e9 bytes per second.  It is what this GPU's memory
+ * delivers to a pure read of that size, launch overhead included: the benchmark quotes the decode step against it
+ * beside the nominal 8 TB/s (Section 4 relies on weight streaming dominating a decode step).  Blocks until done. */
+int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_per_s, void* stream);
+
 /* ---------------------------------------------------------------- KV cache */
 
 /* How the deferred tokens of this cache are carried along (Section 4, "KV recomputation").  on = 0 (default):

@@ -162,6 +162,8 @@ struct eo_model {
     std::vector<const void*> wq, wk, wv, wo, wg, wu, wd;
     std::vector<const float*> ge;
     std::vector<const void*> we;
+    std::vector<const float*> gm;           // exit MLP: norm gain
+    std::vector<const void*> ewg, ewu, ewd; // exit MLP: gate, up, down
     const float* gf = nullptr;
     const void* wf = nullptr;
     int n_seg() const { return c.n_exits + 1; }
@@ -209,14 +211,29 @@ void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) 
     for (int i = 0; i < d; ++i) x[i] += y[i];
 }
 
+// Head `head` on one row (Section 2, "Model architectures"): an exit is, in this order, an optional MLP block,
+// an optional normalisation, and an output embedding matrix that is its own or the input embedding.
 void head_row(const eo_model* m, int head, const float* x, float* z, eo_diag* diag) {
     const eo_config& c = m->c;
+    const int d = c.d_model, F = c.d_ff, dt = c.dtype;
     bool fin = head >= c.n_exits;
-    const float* g = fin ? m->gf : m->ge[head];
-    const void* W = fin ? m->wf : m->we[head];
-    std::vector<float> h(c.d_model);
-    double r = norm_input(x, g, c.d_model, c.rms_eps, h.data());
-    matvec(c.dtype, W, c.vocab, c.d_model, h.data(), r, z);
+    const void* W = (c.exit_flags & EO_TIE_EMBEDDINGS) ? m->embed : (fin ? m->wf : m->we[head]);
+    std::vector<float> xe(x, x + d), h(d > F ? d : F);
+    if (!fin && (c.exit_flags & EO_EXIT_MLP)) {
+        std::vector<float> gate(F), up(F), y(d);
+        double rm = norm_input(xe.data(), m->gm[head], d, c.rms_eps, h.data());
+        matvec(dt, m->ewg[head], F, d, h.data(), rm, gate.data());
+        matvec(dt, m->ewu[head], F, d, h.data(), rm, up.data());
+        swiglu(gate.data(), up.data(), F, h.data());
+        matvec(dt, m->ewd[head], d, F, h.data(), 1.0, y.data());
+        for (int i = 0; i < d; ++i) xe[i] += y[i];
+    }
+    double r = 1.0;
+    if (!fin && (c.exit_flags & EO_EXIT_NO_NORM))
+        for (int i = 0; i < d; ++i) h[i] = xe[i];
+    else
+        r = norm_input(xe.data(), fin ? m->gf : m->ge[head], d, c.rms_eps, h.data());
+    matvec(dt, W, c.vocab, d, h.data(), r, z);
     if (diag) {
         softmax_max(z, c.vocab, diag);
         diag->layer = fin ? c.n_layers : c.exit_layers[head];
@@ -249,7 +266,8 @@ float eo_bf16_round(float v) { return bf16_round(v); }
 eo_model* eo_model_create(const eo_config* cfg) {
     const eo_config& c = *cfg;
     if (c.n_layers < 1 || c.d_model < 1 || c.n_heads < 1 || c.head_dim < 2 || (c.head_dim & 1) ||
-        c.n_heads * c.head_dim != c.d_model || c.d_ff < 1 || c.vocab < 2 || c.n_exits < 0 || c.n_exits > 8)
+        c.n_heads * c.head_dim != c.d_model || c.d_ff < 1 || c.vocab < 2 || c.n_exits < 0 || c.n_exits > 8 ||
+        (c.exit_flags & ~(EO_EXIT_NO_NORM | EO_TIE_EMBEDDINGS | EO_EXIT_MLP)))
         return nullptr;
     for (int i = 0; i < c.n_exits; ++i) {
         if (c.exit_layers[i] < 1 || c.exit_layers[i] >= c.n_layers) return nullptr;
@@ -263,6 +281,8 @@ eo_model* eo_model_create(const eo_config* cfg) {
     for (auto* v : {&m->wq, &m->wk, &m->wv, &m->wo, &m->wg, &m->wu, &m->wd}) v->assign(L, nullptr);
     m->ge.assign(c.n_exits, nullptr);
     m->we.assign(c.n_exits, nullptr);
+    m->gm.assign(c.n_exits, nullptr);
+    for (auto* v : {&m->ewg, &m->ewu, &m->ewd}) v->assign(c.n_exits, nullptr);
     return m;
 }
 
@@ -284,6 +304,10 @@ int eo_model_set_tensor(eo_model* m, int kind, int index, const void* data) {
         case EO_EXIT_HEAD: if (!lay(E)) return -1; m->we[index] = data; return 0;
         case EO_FINAL_NORM: m->gf = (const float*)data; return 0;
         case EO_FINAL_HEAD: m->wf = data; return 0;
+        case EO_EXIT_MLP_NORM: if (!lay(E)) return -1; m->gm[index] = (const float*)data; return 0;
+        case EO_EXIT_WG: if (!lay(E)) return -1; m->ewg[index] = data; return 0;
+        case EO_EXIT_WU: if (!lay(E)) return -1; m->ewu[index] = data; return 0;
+        case EO_EXIT_WD: if (!lay(E)) return -1; m->ewd[index] = data; return 0;
     }
     return -1;
 }

@@ -43,12 +43,24 @@ typedef struct {
     int32_t n_exits, exit_layers[8]; /* 1-based "after layer e", ascending, < n_layers */
     int32_t dtype;                   /* EO_F32 | EO_BF16: storage of matrices and the embedding */
     float rms_eps, rope_base;
+    int32_t exit_flags;              /* EO_EXIT_* below; 0 = RMSNorm + own output embedding per exit */
 } eo_config;
+
+/* Structure of the exits (paper Section 2, "Model architectures": an output embedding matrix with an
+ * optional normalisation in front of it, optionally preceded by an MLP; input and output embedding
+ * matrices tied or untied):
+ *   EO_EXIT_NO_NORM    exits apply their output embedding to the residual stream as it is (the final head
+ *                      keeps its norm);
+ *   EO_TIE_EMBEDDINGS  every exit and the final head use the input embedding matrix [vocab][d];
+ *   EO_EXIT_MLP        exit i first applies an MLP block of its own, of the same form as a layer's:
+ *                      x' = x + W_d (silu(W_g h) * (W_u h)), h = rmsnorm(x; g_mlp), and its (norm and)
+ *                      output embedding read x'.  The backbone's x is not changed. */
+enum { EO_EXIT_NO_NORM = 1, EO_TIE_EMBEDDINGS = 2, EO_EXIT_MLP = 4 };
 
 /* tensor kinds, same numbering as the workload generator's TensorKind */
 enum { EO_EMBED = 0, EO_ATTN_NORM = 1, EO_WQ = 2, EO_WK = 3, EO_WV = 4, EO_WO = 5, EO_MLP_NORM = 6,
        EO_WG = 7, EO_WU = 8, EO_WD = 9, EO_EXIT_NORM = 10, EO_EXIT_HEAD = 11, EO_FINAL_NORM = 12,
-       EO_FINAL_HEAD = 13 };
+       EO_FINAL_HEAD = 13, EO_EXIT_MLP_NORM = 14, EO_EXIT_WG = 15, EO_EXIT_WU = 16, EO_EXIT_WD = 17 };
 
 typedef struct eo_model eo_model;
 typedef struct eo_state eo_state;

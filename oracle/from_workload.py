@@ -19,7 +19,7 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 def config_of(shape: ModelShape) -> O.EoConfig:
     return O.make_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff,
-                         shape.vocab, shape.exit_layers, shape.dtype, shape.rms_eps, shape.rope_base)
+                         shape.vocab, shape.exit_layers, shape.dtype, shape.rms_eps, shape.rope_base, shape.exit_flags)
 
 
 def build_model(shape: ModelShape, seed: int = 0, gain_jitter: float = 0.0, layers=None) -> O.Model:

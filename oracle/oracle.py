@@ -19,7 +19,10 @@ class EoConfig(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
                 ("n_exits", C.c_int32), ("exit_layers", C.c_int32 * 8), ("dtype", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32)]
+
+
+EO_EXIT_NO_NORM, EO_TIE_EMBEDDINGS, EO_EXIT_MLP = 1, 2, 4
 
 
 class EoDiag(C.Structure):
@@ -101,7 +104,7 @@ def get_threads() -> int:
 
 
 def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, dtype,
-                rms_eps=1e-5, rope_base=10000.0) -> EoConfig:
+                rms_eps=1e-5, rope_base=10000.0, exit_flags=0) -> EoConfig:
     c = EoConfig()
     c.n_layers, c.d_model, c.n_heads, c.head_dim, c.d_ff, c.vocab = n_layers, d_model, n_heads, head_dim, d_ff, vocab
     c.n_exits = len(exit_layers)
@@ -109,6 +112,7 @@ def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, 
         c.exit_layers[i] = e
     c.dtype = EO_BF16 if dtype in ("bf16", EO_BF16) else EO_F32
     c.rms_eps, c.rope_base = rms_eps, rope_base
+    c.exit_flags = exit_flags
     return c
 
 

@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
@@ -67,6 +67,7 @@ def lib():
         L.ee_debug_set_gemm_min_workgroups.argtypes = [C.c_int]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
+        L.ee_measure_stream_read.argtypes = [vp, sz, C.c_int, fp, vp]
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
         L.ee_kv_cache_reset.argtypes = [vp, C.c_int]
@@ -154,6 +155,12 @@ class Model:
         n, ms = C.c_int32(), C.c_float()
         _chk(lib().ee_profile_end(self.h, C.byref(n), C.byref(ms)), "ee_profile_end")
         return n.value, ms.value
+
+    def measure_stream_read(self, n_bytes: int = 0, n_launches: int = 20) -> float:
+        """GB/s (1e9) of a read-only kernel over n_bytes of the weight buffer (0: all of it)."""
+        g = C.c_float()
+        _chk(lib().ee_measure_stream_read(self.h, n_bytes, n_launches, C.byref(g), _stream_ptr(None)), "ee_measure_stream_read")
+        return g.value
 
     def close(self):
         if self.h:

@@ -926,6 +926,31 @@ int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms) {
     return EE_OK;
 }
 
+int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_per_s, void* stream) {
+    if (!m || !gb_per_s || n_launches < 1 || n_launches > 1000) return EE_ERR_ARG;
+    if (bytes == 0 || bytes > m->wl.total) bytes = m->wl.total;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    HIPCHK(hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = launch_stream_read(m->wbase, bytes, nullptr, st);  // untimed first pass
+    if (e == hipSuccess) e = hipEventRecord(e0, st);
+    for (int i = 0; i < n_launches && e == hipSuccess; ++i) {
+        // successive launches start at different offsets so a short read is not served from the caches
+        const size_t off = bytes < m->wl.total ? ((size_t)i * bytes) % (m->wl.total - bytes + 1) & ~(size_t)1023 : 0;
+        e = launch_stream_read(m->wbase + off, bytes, nullptr, st);
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    HIPCHK(e);
+    *gb_per_s = ms > 0.f ? (float)((double)(bytes / 1024 * 1024) * n_launches / (ms * 1e6)) : 0.f;
+    return EE_OK;
+}
+
 int ee_model_free(ee_model* m) {
     if (!m) return EE_ERR_ARG;
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);

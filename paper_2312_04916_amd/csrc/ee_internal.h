@@ -56,6 +56,7 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 // ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
 
 // bytes (rounded up to 16; both buffers are sized and aligned for that) from host-mapped pinned memory to the device
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s);
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);

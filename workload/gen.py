@@ -116,9 +116,13 @@ class TensorKind(enum.IntEnum):
     EXIT_HEAD = 11   # [vocab][d] per exit
     FINAL_NORM = 12  # [d]
     FINAL_HEAD = 13  # [vocab][d]
+    EXIT_MLP_NORM = 14  # [d]        per exit, only with an MLP in the exit (gain of the norm in front of it)
+    EXIT_WG = 15        # [d_ff][d]  per exit
+    EXIT_WU = 16        # [d_ff][d]
+    EXIT_WD = 17        # [d][d_ff]
 
 
-_NORMS = (TensorKind.ATTN_NORM, TensorKind.MLP_NORM, TensorKind.EXIT_NORM, TensorKind.FINAL_NORM)
+_NORMS = (TensorKind.ATTN_NORM, TensorKind.MLP_NORM, TensorKind.EXIT_NORM, TensorKind.FINAL_NORM, TensorKind.EXIT_MLP_NORM)
 _HEADS = (TensorKind.EXIT_HEAD, TensorKind.FINAL_HEAD)
 
 
@@ -136,6 +140,15 @@ class ModelShape:
     head_sigma: float = 0.3               # std of exit / final heads
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    # structure of the exits (Section 2: an output embedding matrix, an optional normalisation in front of it,
+    # optionally an MLP before that; input and output embeddings tied or untied)
+    exit_norm: bool = True                # RMSNorm in front of each exit's output embedding
+    tie_embeddings: bool = False          # every exit and the final head use the input embedding matrix
+    exit_mlp: bool = False                # each exit starts with an MLP block of its own (same form as a layer's)
+
+    @property
+    def exit_flags(self) -> int:
+        return (0 if self.exit_norm else 1) | (2 if self.tie_embeddings else 0) | (4 if self.exit_mlp else 0)
 
     def tensor_shape(self, kind: TensorKind) -> Tuple[int, ...]:
         d, f, v = self.d_model, self.d_ff, self.vocab
@@ -145,6 +158,8 @@ class ModelShape:
             TensorKind.MLP_NORM: (d,), TensorKind.WG: (f, d), TensorKind.WU: (f, d),
             TensorKind.WD: (d, f), TensorKind.EXIT_NORM: (d,), TensorKind.EXIT_HEAD: (v, d),
             TensorKind.FINAL_NORM: (d,), TensorKind.FINAL_HEAD: (v, d),
+            TensorKind.EXIT_MLP_NORM: (d,), TensorKind.EXIT_WG: (f, d), TensorKind.EXIT_WU: (f, d),
+            TensorKind.EXIT_WD: (d, f),
         }[TensorKind(kind)]
 
     def n_params(self) -> int:
@@ -193,10 +208,16 @@ def model_tensor_list(shape: ModelShape) -> List[Tuple[TensorKind, int]]:
                   TensorKind.MLP_NORM, TensorKind.WG, TensorKind.WU, TensorKind.WD):
             out.append((k, l))
     for i in range(len(shape.exit_layers)):
-        out.append((TensorKind.EXIT_NORM, i))
-        out.append((TensorKind.EXIT_HEAD, i))
+        if shape.exit_mlp:
+            for k in (TensorKind.EXIT_MLP_NORM, TensorKind.EXIT_WG, TensorKind.EXIT_WU, TensorKind.EXIT_WD):
+                out.append((k, i))
+        if shape.exit_norm:
+            out.append((TensorKind.EXIT_NORM, i))
+        if not shape.tie_embeddings:
+            out.append((TensorKind.EXIT_HEAD, i))
     out.append((TensorKind.FINAL_NORM, 0))
-    out.append((TensorKind.FINAL_HEAD, 0))
+    if not shape.tie_embeddings:
+        out.append((TensorKind.FINAL_HEAD, 0))
     return out
 
 
@@ -212,12 +233,12 @@ def model_tensor(shape: ModelShape, kind: TensorKind, index: int, seed: int = 0,
     kind = TensorKind(kind)
     dims = shape.tensor_shape(kind)
     numel = math.prod(dims)
-    tid = int(kind) + 16 * index
+    tid = int(kind) + 16 * index if kind < TensorKind.EXIT_MLP_NORM else 100000 + (int(kind) - 14) + 4 * index
     if kind in _NORMS:
         if gain_jitter == 0.0:
             return torch.ones(dims, dtype=torch.float32, device=device)
         return gaussian_tensor(seed, tid, numel, gain_jitter, 1.0, device).reshape(dims)
-    sigma = shape.head_sigma if kind in _HEADS else shape.sigma
+    sigma = shape.head_sigma if kind in _HEADS or (kind == TensorKind.EMBED and shape.tie_embeddings) else shape.sigma
     t = gaussian_tensor(seed, tid, numel, sigma, 0.0, device).reshape(dims)
     if shape.dtype == "bf16":
         t = t.to(torch.bfloat16)
@@ -239,7 +260,8 @@ def write_weight_file(path: str, shape: ModelShape, seed: int = 0, max_positions
     """Writes the seeded model in the library's weight-file format: the 8 bytes "EEWT0001", the config
     (19 little-endian 32-bit fields: n_layers, d_model, n_heads, head_dim, d_ff, vocab, n_exits,
     exit_layers[8], dtype, max_positions, rms_eps, rope_base), then every tensor in canonical order as
-    raw elements (matrices in the storage dtype, gains fp32)."""
+    raw elements (matrices in the storage dtype, gains fp32).  A model whose exits are not the default
+    structure is written as "EEWT0002": the same with a 20th field, exit_flags, after rope_base."""
     import struct
 
     ex = list(shape.exit_layers) + [0] * (8 - len(shape.exit_layers))
@@ -247,7 +269,11 @@ def write_weight_file(path: str, shape: ModelShape, seed: int = 0, max_positions
                       shape.vocab, len(shape.exit_layers), *ex, 1 if shape.dtype == "bf16" else 0, max_positions,
                       shape.rms_eps, shape.rope_base)
     with open(path, "wb") as f:
-        f.write(b"EEWT0001")
+        if shape.exit_flags:
+            f.write(b"EEWT0002")
+            hdr += struct.pack("<i", shape.exit_flags)
+        else:
+            f.write(b"EEWT0001")
         f.write(hdr)
         for kind, idx in model_tensor_list(shape):
             t = model_tensor(shape, kind, idx, seed, "cpu", gain_jitter).contiguous()
