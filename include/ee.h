@@ -51,9 +51,21 @@ enum {
 
 /*
  * Model: pre-RMSNorm decoder, rotary position embedding (half-split pairs, angle
- * pos * rope_base^(-2i/head_dim)), SwiGLU MLP, no biases, untied heads.  Exit i sits after layer
- * exit_layers[i] (1-based) and is an RMSNorm gain plus its own d_model x vocab matrix
- * (Section 2: minimalistic exit = optional norm + output embedding).
+ * pos * rope_base^(-2i/head_dim)), SwiGLU MLP, no biases.  Exit i sits after layer exit_layers[i]
+ * (1-based).  By default (exit_flags = 0) it is an RMSNorm gain plus its own d_model x vocab matrix;
+ * exit_flags selects the other structures of Section 2 ("Model architectures": an output embedding
+ * matrix, an optional normalisation in front of it, optionally an MLP before that, input and output
+ * embeddings tied or untied):
+ *   EE_EXIT_NO_NORM    exits apply their output embedding to the residual stream as it is (the final
+ *                      head keeps its norm); the model has no EE_T_EXIT_NORM tensors;
+ *   EE_TIE_EMBEDDINGS  every exit and the final head use the input embedding matrix; the model has no
+ *                      EE_T_EXIT_HEAD / EE_T_FINAL_HEAD tensors (the library keeps the embedding twice:
+ *                      by rows for the token look-up, in tile order for the heads);
+ *   EE_EXIT_MLP        exit i starts with an MLP block of its own, of the same form as a layer's:
+ *                      x' = x + W_d (silu(W_g h) * (W_u h)), h = rmsnorm(x; g_mlp); its (norm and) output
+ *                      embedding read x', the backbone's x is unchanged.  Tensors EE_T_EXIT_MLP_NORM,
+ *                      EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD per exit, hidden width d_ff.
+ * Setting a tensor that the configured structure does not have returns EE_ERR_CONFIG.
  * Supported: d_model = n_heads*head_dim; head_dim in {32, 64, 128}; d_model, d_ff multiples of 32;
  * vocab a multiple of 32.
  */
@@ -63,7 +75,10 @@ typedef struct {
     int32_t dtype;                              /* EE_F32 | EE_BF16: storage of matrices, embedding, KV */
     int32_t max_positions;                      /* longest sequence (prompt + generated) */
     float rms_eps, rope_base;
+    int32_t exit_flags;                         /* EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP; 0 = default */
 } ee_config;
+
+enum { EE_EXIT_NO_NORM = 1, EE_TIE_EMBEDDINGS = 2, EE_EXIT_MLP = 4 };
 
 /* Tensor kinds for ee_model_set_tensor (index = layer for per-layer kinds, exit number for EXIT_*). */
 enum {
@@ -81,7 +96,11 @@ enum {
     EE_T_EXIT_HEAD = 11, /* [vocab][d_model], per exit                              */
     EE_T_FINAL_NORM = 12,
     EE_T_FINAL_HEAD = 13,
-    EE_T_KINDS = 14
+    EE_T_EXIT_MLP_NORM = 14, /* [d_model] fp32 gain, per exit (EE_EXIT_MLP only)    */
+    EE_T_EXIT_WG = 15,       /* [d_ff][d_model], per exit                           */
+    EE_T_EXIT_WU = 16,       /* [d_ff][d_model]                                     */
+    EE_T_EXIT_WD = 17,       /* [d_model][d_ff]                                     */
+    EE_T_KINDS = 18
 };
 
 typedef struct ee_model ee_model;
@@ -112,6 +131,9 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
 /* Reads a weight file and sets every tensor.  File: the 8 bytes "EEWT0001", the ee_config struct,
  * then every tensor in the order EMBED, per layer {ATTN_NORM, WQ, WK, WV, WO, MLP_NORM, WG, WU, WD},
  * per exit {EXIT_NORM, EXIT_HEAD}, FINAL_NORM, FINAL_HEAD, each as raw little-endian elements.
+ * A model with exit_flags != 0 is stored as "EEWT0002": exit_flags follows rope_base in the config, and
+ * the per-exit group is {EXIT_MLP_NORM, EXIT_WG, EXIT_WU, EXIT_WD (with EE_EXIT_MLP)}, {EXIT_NORM (unless
+ * EE_EXIT_NO_NORM)}, {EXIT_HEAD (unless tied)}; FINAL_HEAD is absent when tied.
  * dev_staging is a device scratch buffer of at least staging_bytes = the largest tensor. */
 int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weights, size_t weight_bytes,
                   void* dev_workspace, size_t workspace_bytes, int max_rows, int max_seqs, void* dev_staging,
@@ -190,7 +212,8 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
  * arrays [n_exits+1][n_tokens] (row i < n_exits: exit i, last row: final head), filled whatever the
  * threshold: pos_token = arg max of the head's logits at that position (ties: lowest id), pos_conf = its
  * soft-max probability.  Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
- * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
+ * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128, and exits without an MLP of
+ * their own (EE_ERR_CONFIG otherwise).
  * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
  * min(max_positions, EE_PREFILL_ROWS) rows, rounded up to 128 (environment variable read when the model is
  * sized and created; default 2048; 0 switches the path off), each projection one matrix-core GEMM. */

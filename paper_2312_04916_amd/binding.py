@@ -30,7 +30,11 @@ class ee_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("n_exits", C.c_int32),
                 ("exit_layers", C.c_int32 * EE_MAX_EXITS), ("dtype", C.c_int32), ("max_positions", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32)]
+
+
+EE_EXIT_NO_NORM, EE_TIE_EMBEDDINGS, EE_EXIT_MLP = 1, 2, 4
+(EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD) = range(14, 18)
 
 
 class EeError(RuntimeError):
@@ -92,7 +96,7 @@ def _chk(code: int, where: str) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, dtype, max_positions,
-                rms_eps=1e-5, rope_base=10000.0) -> ee_config:
+                rms_eps=1e-5, rope_base=10000.0, exit_flags=0) -> ee_config:
     c = ee_config()
     c.n_layers, c.d_model, c.n_heads, c.head_dim, c.d_ff, c.vocab = n_layers, d_model, n_heads, head_dim, d_ff, vocab
     c.n_exits = len(exit_layers)
@@ -101,6 +105,7 @@ def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, 
     c.dtype = EE_BF16 if dtype in ("bf16", EE_BF16) else EE_F32
     c.max_positions = max_positions
     c.rms_eps, c.rope_base = rms_eps, rope_base
+    c.exit_flags = exit_flags
     return c
 
 

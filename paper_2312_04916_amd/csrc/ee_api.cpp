@@ -47,12 +47,14 @@ int check_config(const ee_config& c) {
     }
     if (c.max_positions < 1 || c.max_positions > (1 << 20)) return EE_ERR_CONFIG;
     if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return EE_ERR_CONFIG;
+    if (c.exit_flags & ~(EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP)) return EE_ERR_CONFIG;
     return EE_OK;
 }
 
 struct WeightLayout {
-    size_t embed, rope, gf, wf, total;
+    size_t embed, rope, gf, wf, ones, total;
     std::vector<size_t> g1, qkv, wo, g2, gu, wd, ge, we;
+    std::vector<size_t> gm, egu, ewd;  // exits with an MLP: its norm gain, gate|up, down
 };
 
 WeightLayout weight_layout(const ee_config& c) {
@@ -72,12 +74,20 @@ WeightLayout weight_layout(const ee_config& c) {
         w.gu.push_back(take(2 * F * d * es));
         w.wd.push_back(take(d * F * es));
     }
+    const bool tied = c.exit_flags & EE_TIE_EMBEDDINGS;
     for (int i = 0; i < c.n_exits; ++i) {
+        if (c.exit_flags & EE_EXIT_MLP) {
+            w.gm.push_back(take(d * 4));
+            w.egu.push_back(take(2 * F * d * es));
+            w.ewd.push_back(take(d * F * es));
+        }
         w.ge.push_back(take(d * 4));
-        w.we.push_back(take(V * d * es));
+        if (!tied) w.we.push_back(take(V * d * es));
     }
     w.gf = take(d * 4);
-    w.wf = take(V * d * es);
+    w.wf = take(V * d * es);  // tied embeddings: the one matrix every head reads, in the GEMM's tile order
+    if (tied) w.we.assign(c.n_exits, w.wf);
+    w.ones = take(d * 4);     // a gain of 1 for exits without a norm
     w.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 8);
     w.total = off;
     return w;
@@ -121,7 +131,8 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     };
     w.max_blocks_per_seq = c.max_positions / 32 + 1;
     w.upload = off;
-    w.descs = take(sizeof(SegDesc) * (EE_MAX_EXITS + 1));
+    // one descriptor per segment; with an MLP in the exits, one more per segment for the rows that MLP works on
+    w.descs = take(sizeof(SegDesc) * (EE_MAX_EXITS + 1) * ((c.exit_flags & EE_EXIT_MLP) ? 2 : 1));
     w.btab = take((size_t)max_seqs * w.max_blocks_per_seq * 4);
     w.tokens = take(EE_MAX_ROWS * 4);
     w.upload_bytes = off - w.upload;
@@ -207,9 +218,33 @@ struct ee_model {
         static const int per_layer[] = {EE_T_ATTN_NORM, EE_T_WQ, EE_T_WK, EE_T_WV, EE_T_WO, EE_T_MLP_NORM, EE_T_WG, EE_T_WU, EE_T_WD};
         for (int j = 0; j < 9; ++j)
             if (per_layer[j] == kind) return index >= 0 && index < L ? 3 + 2 * E + index * 9 + j : -1;
+        static const int per_exit[] = {EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD};
+        for (int j = 0; j < 4; ++j)
+            if (per_exit[j] == kind) return index >= 0 && index < E ? 3 + 2 * E + 9 * L + index * 4 + j : -1;
         return -1;
     }
-    int n_tensors() const { return 3 + 2 * cfg.n_exits + 9 * cfg.n_layers; }
+    int n_tensors() const { return 3 + 2 * cfg.n_exits + 9 * cfg.n_layers + 4 * cfg.n_exits; }
+    bool exit_mlp() const { return cfg.exit_flags & EE_EXIT_MLP; }
+    int mlp_desc(int seg) const { return EE_MAX_EXITS + 1 + seg; }  // descriptor of the rows exit `seg`'s MLP works on
+    bool exit_norm() const { return !(cfg.exit_flags & EE_EXIT_NO_NORM); }
+    bool tied() const { return cfg.exit_flags & EE_TIE_EMBEDDINGS; }
+    // is this tensor part of the model as configured?
+    bool applicable(int kind) const {
+        switch (kind) {
+            case EE_T_EXIT_NORM: return exit_norm();
+            case EE_T_EXIT_HEAD:
+            case EE_T_FINAL_HEAD: return !tied();
+            case EE_T_EXIT_MLP_NORM:
+            case EE_T_EXIT_WG:
+            case EE_T_EXIT_WU:
+            case EE_T_EXIT_WD: return exit_mlp();
+            default: return true;
+        }
+    }
+    // gain folded into the operand that exit i reads first (its MLP's norm, else its own norm, else none)
+    const float* exit_in_gain(int i) const { return gain(exit_mlp() ? wl.gm[i] : (exit_norm() ? wl.ge[i] : wl.ones)); }
+    // gain in front of exit i's output embedding
+    const float* exit_out_gain(int i) const { return gain(exit_norm() ? wl.ge[i] : wl.ones); }
 };
 
 struct SeqState {
@@ -235,10 +270,17 @@ struct ee_kv_cache {
     float* ssq() const { return (float*)(pool + off_ssq); }
     int slot_of(int seq, int pos) const { return seq * S + pos % S; }
     int transient_slot(int r) const { return max_seqs * S + r; }
+    int exit_slot(int r) const { return max_seqs * S + m->max_rows + r; }  // copies an exit's MLP works on
     int n_pending(const SeqState& s) const { return s.filled.front() - s.filled.back(); }
 };
 
 namespace {
+
+// rows of the residual store: one per position a sequence may have deferred plus its current one, the transient rows
+// of a prompt chunk, and the copies that exits with an MLP work on
+size_t store_slots(const ee_model* m, int max_seqs, int max_pending) {
+    return (size_t)max_seqs * (max_pending + 1) + m->max_rows + (m->exit_mlp() ? m->max_seqs : 0);
+}
 
 size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending, int* n_blocks,
                       size_t* off_x, size_t* off_xg, size_t* off_xgh, size_t* off_ssq) {
@@ -247,7 +289,7 @@ size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total,
     int nb = (int)((max_tokens_total + BT - 1) / BT) + max_seqs;
     size_t blk = 2 * (size_t)c.n_heads * BT * c.head_dim;
     size_t off = align_up((size_t)c.n_layers * nb * blk * es);
-    size_t slots = (size_t)max_seqs * (max_pending + 1) + m->max_rows;
+    size_t slots = store_slots(m, max_seqs, max_pending);
     size_t P = d / (16 * gemm_resid_tiles_per_wg());
     if (n_blocks) *n_blocks = nb;
     if (off_x) *off_x = off;
@@ -278,6 +320,46 @@ struct Timed {
         }
     }
 };
+
+// The MLP half of a block over the rows of g.desc: x += W_d (silu(W_g h) * (W_u h)), h = the rows' x.g operand in
+// `a_src` (slots `arow`) scaled by their RMS.  Leaves x.g_next (and x.g_head in the second operand store when
+// g_head is given) and the sum-of-squares partials of the new x.  Used by every layer and by exits with an MLP.
+int run_mlp(ee_model* m, ee_kv_cache* c, GemmCommon g, const char* w_gu, const char* w_d, void* a_src, const int32_t* arow, bool pk_d,
+            bool pk_F, const float* g_next, const float* g_head, bool pack_next, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    const int d = cf.d_model, F = cf.d_ff;
+    char* xg_pk = m->ws + m->wsl.xg_pk;
+    // act = silu(W_g h) * (W_u h)
+    g.W = w_gu;
+    g.N = 2 * F;
+    g.K = d;
+    g.A = pk_d ? (void*)xg_pk : a_src;
+    g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
+    g.a_packed = pk_d;
+    g.lda = d;
+    g.arow = arow;
+    g.ssq = c->ssq();
+    {
+        Timed t(m, EE_K_SWIGLU, st);
+        HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, pk_F, st));
+    }
+    // x += W_d act ; operand for what reads x next
+    g.W = w_d;
+    g.N = d;
+    g.K = F;
+    g.A = m->ws + m->wsl.act;
+    g.a_lo = m->lo_rows(F);
+    g.a_packed = pk_F;
+    g.lda = F;
+    g.arow = nullptr;
+    g.ssq = nullptr;
+    {
+        Timed t(m, EE_K_DOWN, st);
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d,
+                                 pack_next ? xg_pk : nullptr, m->lo_rows(d), st));
+    }
+    return EE_OK;
+}
 
 // ---- the per-layer launch sequence over the rows described by dev_desc(di)
 int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st) {
@@ -345,72 +427,90 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
                                      pk_d ? xg_pk : nullptr, m->lo_rows(d), st));
         }
         g.att_part = nullptr;
-        // act = silu(W_g h) * (W_u h)
-        g.W = m->wbase + m->wl.gu[l];
-        g.N = 2 * F;
-        g.K = d;
-        g.A = pk_d ? (void*)xg_pk : c->xg();
-        g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
-        g.a_packed = pk_d;
-        g.arow = xrow;
-        g.ssq = c->ssq();
-        {
-            Timed t(m, EE_K_SWIGLU, st);
-            HIPCHK(launch_gemm_swiglu(g, m->ws + m->wsl.act, m->lo_rows(F), F, pk_F, st));
-        }
-        // x += W_d act ; operand for the next layer (or the final head), and for an exit head after this layer
-        g.W = m->wbase + m->wl.wd[l];
-        g.N = d;
-        g.K = F;
-        g.A = m->ws + m->wsl.act;
-        g.a_lo = m->lo_rows(F);
-        g.a_packed = pk_F;
-        g.lda = F;
-        g.arow = nullptr;
-        g.ssq = nullptr;
         const float* g_next = (l + 1 < cf.n_layers) ? m->gain(m->wl.g1[l + 1]) : m->gain(m->wl.gf);
         const float* g_head = nullptr;
         for (int i = 0; i < cf.n_exits; ++i)
-            if (cf.exit_layers[i] == l + 1) g_head = m->gain(m->wl.ge[i]);
-        {
-            Timed t(m, EE_K_DOWN, st);
-            // (the next layer of this call reads the packed copy; across calls the residual store is the interface)
-            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), g_head ? c->xgh() : nullptr, c->xs_lo, c->ssq(), g_next, g_head, d,
-                                     pk_d && l + 1 < l1 ? xg_pk : nullptr, m->lo_rows(d), st));
-        }
+            if (cf.exit_layers[i] == l + 1) g_head = m->exit_in_gain(i);
+        // (the next layer of this call reads the packed copy; across calls the residual store is the interface)
+        EECHK(run_mlp(m, c, g, m->wbase + m->wl.gu[l], m->wbase + m->wl.wd[l], c->xg(), xrow, pk_d, pk_F, g_next, g_head,
+                      pk_d && l + 1 < l1, st));
     }
     return EE_OK;
+}
+
+// Rows that exit `seg`'s MLP works on: copies, in slots of their own, of the head rows listed in host_desc(seg).
+// Call after the head rows of host_desc(seg) are set and before the descriptors are uploaded.
+void fill_mlp_desc(const ee_model* m, const ee_kv_cache* c, int seg) {
+    if (!m->exit_mlp() || seg >= m->cfg.n_exits) return;
+    const SegDesc* d = m->host_desc(seg);
+    SegDesc* e = m->host_desc(m->mlp_desc(seg));
+    e->T = d->n_head;
+    e->n_qt = 0;
+    e->n_head = d->n_head;
+    e->pad = 0;
+    for (int r = 0; r < d->n_head; ++r) {
+        e->xrow[r] = c->exit_slot(r);
+        e->row_qt[r] = r;
+        e->pos[r] = e->kvblk[r] = e->rseq[r] = 0;
+        e->head_xrow[r] = c->exit_slot(r);
+        e->head_slot[r] = d->head_slot[r];
+    }
 }
 
 // head `hi` (exit number, or n_exits for the final head) on the rows listed in dev_desc(di).head_*
 int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, float threshold, hipStream_t st) {
     const ee_config& cf = m->cfg;
+    const int d = cf.d_model, dt = cf.dtype;
     bool fin = hi >= cf.n_exits;
     SegDesc* dd = m->dev_desc(di);
     GemmCommon g{};
-    g.dtype = cf.dtype;
-    g.W = m->wbase + (fin ? m->wl.wf : m->wl.we[hi]);
-    g.N = cf.vocab;
-    g.K = cf.d_model;
-    g.A = fin ? c->xg() : c->xgh();
-    g.a_lo = c->xs_lo;
-    g.lda = cf.d_model;
-    g.arow = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
-    if (cf.dtype == EE_BF16 && !gemm_rows_fit_lds(cf.dtype, n_head, cf.d_model)) {  // many rows: packed operands
-        char* hp = m->ws + m->wsl.head_pk;
-        HIPCHK(launch_pack_rows(g.A, g.a_lo, cf.d_model, g.arow, n_head, cf.d_model, hp, (size_t)64 * cf.d_model, st));
-        g.A = hp;
-        g.a_lo = (size_t)64 * cf.d_model;
-        g.a_packed = 1;
-    }
-    g.ssq = c->ssq();
+    g.dtype = dt;
+    g.inv_d = 1.0f / (float)d;
+    g.eps = cf.rms_eps;
     g.ssq_stride = c->ssq_stride;
     g.ssq_n = c->ssq_stride;
-    g.inv_d = 1.0f / (float)cf.d_model;
-    g.eps = cf.rms_eps;
     g.T = n_head;
+    void* a_rows = fin ? c->xg() : c->xgh();  // x.g of the gain this head reads first
+    const SegDesc* hd = m->host_desc(di);
+    if (!fin && m->exit_mlp()) {
+        // The exit's MLP works on copies of the head rows, so that the backbone's rows stay as they are; its down
+        // projection leaves x'.g (g: the exit's norm gain, or 1) in the first operand store at the copies' slots.
+        const int me = m->mlp_desc(di);
+        const SegDesc* eh = m->host_desc(me);
+        if (eh->T != n_head || hd->n_head != n_head) return EE_ERR_STATE;
+        SegDesc* ed = m->dev_desc(me);
+        const int32_t* src = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
+        const int32_t* dst = (const int32_t*)((char*)ed + offsetof(SegDesc, xrow));
+        HIPCHK(launch_copy_slots(dt, src, dst, n_head, d, c->x(), c->xgh(), c->xs_lo, c->ssq(), c->ssq_stride, st));
+        const bool pk_d = dt == EE_BF16 && !gemm_rows_fit_lds(dt, n_head, d);
+        const bool pk_F = dt == EE_BF16 && !gemm_rows_fit_lds(dt, n_head, cf.d_ff);
+        if (pk_d) HIPCHK(launch_pack_rows(c->xgh(), c->xs_lo, d, dst, n_head, d, m->ws + m->wsl.xg_pk, m->lo_rows(d), st));
+        g.desc = ed;
+        g.desc_host = eh;
+        EECHK(run_mlp(m, c, g, m->wbase + m->wl.egu[hi], m->wbase + m->wl.ewd[hi], c->xgh(), dst, pk_d, pk_F, m->exit_out_gain(hi),
+                      nullptr, false, st));
+        dd = ed;
+        hd = eh;
+        a_rows = c->xg();
+    }
     g.desc = dd;
-    g.desc_host = m->host_desc(di);
+    g.desc_host = hd;
+    g.W = m->wbase + (fin ? m->wl.wf : m->wl.we[hi]);
+    g.N = cf.vocab;
+    g.K = d;
+    g.A = a_rows;
+    g.a_lo = c->xs_lo;
+    g.a_packed = 0;
+    g.lda = d;
+    g.arow = (const int32_t*)((char*)dd + offsetof(SegDesc, head_xrow));
+    if (dt == EE_BF16 && !gemm_rows_fit_lds(dt, n_head, d)) {  // many rows: packed operands
+        char* hp = m->ws + m->wsl.head_pk;
+        HIPCHK(launch_pack_rows(g.A, g.a_lo, d, g.arow, n_head, d, hp, (size_t)64 * d, st));
+        g.A = hp;
+        g.a_lo = (size_t)64 * d;
+        g.a_packed = 1;
+    }
+    g.ssq = (fin || m->exit_norm()) ? c->ssq() : nullptr;  // an exit without a norm reads x as it is
     float* logits = (m->dbg_logits && n_head <= m->dbg_rows) ? m->dbg_logits : nullptr;
     Timed t(m, EE_K_HEAD, st);
     m->head_tag = m->head_tag == 0x7fffffff ? 1 : m->head_tag + 1;
@@ -507,6 +607,7 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
     d->n_qt = nqt;
     d->n_head = nh;
     d->pad = 0;
+    fill_mlp_desc(m, c, seg);
     *rows_out = T;
 }
 
@@ -605,6 +706,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
         di->n_head = 1;
         di->head_xrow[0] = slot;
         di->head_slot[0] = i * EE_MAX_SEQS;
+        fill_mlp_desc(m, c, i);
     }
     EECHK(upload(m, st));
     const int32_t* bt = m->dev_btab();
@@ -662,7 +764,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                 g.A_lo = ac_lo;
                 g.ssq = nullptr;
                 const float* g_next = (l + 1 < cf.n_layers) ? m->gain(m->wl.g1[l + 1]) : m->gain(m->wl.gf);
-                const float* g_head = (!fin && l + 1 == m->seg_end(sgi)) ? m->gain(m->wl.ge[sgi]) : nullptr;
+                const float* g_head = (!fin && l + 1 == m->seg_end(sgi)) ? m->exit_in_gain(sgi) : nullptr;
                 {
                     Timed t(m, EE_K_DOWN, st);
                     HIPCHK(launch_pf_resid(g, x, xg_hi, xg_lo, g_head ? xgh_hi : nullptr, g_head ? xgh_lo : nullptr, g_next, g_head, ssq,
@@ -675,7 +777,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                 g.K = d;
                 g.A_hi = fin ? xg_hi : xgh_hi;
                 g.A_lo = fin ? xg_lo : xgh_lo;
-                g.ssq = ssq;
+                g.ssq = (fin || m->exit_norm()) ? ssq : nullptr;  // an exit without a norm reads x as it is
                 {
                     Timed t(m, EE_K_HEAD, st);
                     HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf), st));
@@ -688,7 +790,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
             if (last && (fin || threshold < 1.0f)) {
                 const int l_end = m->seg_end(sgi);
                 const float* g_a = fin ? m->gain(m->wl.gf) : m->gain(m->wl.g1[l_end]);
-                const float* g_b = fin ? nullptr : m->gain(m->wl.ge[sgi]);
+                const float* g_b = fin ? nullptr : m->exit_in_gain(sgi);
                 const size_t es = 2;
                 HIPCHK(launch_pf_export_row(x + (size_t)(M - 1) * d, d, g_a, g_b, c->x() + (size_t)slot * d,
                                             (char*)c->xg() + (size_t)slot * d * es, (char*)c->xgh() + (size_t)slot * d * es, c->xs_lo,
@@ -748,6 +850,11 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     m->wsl = workspace_layout(*cfg, max_rows, max_seqs);
     m->have.assign(m->n_tensors(), 0);
     m->n_missing = m->n_tensors();
+    for (int kind = 0; kind < EE_T_KINDS; ++kind)
+        for (int idx = 0; !m->applicable(kind) && m->tensor_slot(kind, idx) >= 0; ++idx) {
+            m->have[m->tensor_slot(kind, idx)] = 1;
+            --m->n_missing;
+        }
     m->dbg_logits = nullptr;
     m->dbg_rows = 0;
     size_t res_bytes = align_up(sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1)) + (size_t)m->wsl.pf_rows * 4;
@@ -766,6 +873,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
         if ((e = hipHostGetDevicePointer((void**)&m->results_dev, m->results, 0)) != hipSuccess) break;
         if ((e = hipHostGetDevicePointer((void**)&m->pinned_dev, m->pinned, 0)) != hipSuccess) break;
         if ((e = hipMemsetAsync(m->ws + m->wsl.counters, 0, 256 * 4, st)) != hipSuccess) break;
+        if ((e = launch_fill_f32((float*)(m->wbase + m->wl.ones), 1.0f, (size_t)cfg->d_model, st)) != hipSuccess) break;
         if (m->wsl.pf_rows && (e = hipMemsetAsync(m->ws + m->wsl.pf_begin, 0, m->wsl.total - m->wsl.pf_begin, st)) != hipSuccess) break;
         e = launch_rope_table((float*)(m->wbase + m->wl.rope), cfg->max_positions, cfg->head_dim, cfg->rope_base, st);
     } while (0);
@@ -784,6 +892,7 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
     if (!m || !dev_src) return EE_ERR_ARG;
     int slot = m->tensor_slot(kind, index);
     if (slot < 0) return EE_ERR_RANGE;
+    if (!m->applicable(kind)) return EE_ERR_CONFIG;
     const ee_config& c = m->cfg;
     const size_t d = c.d_model, F = c.d_ff, V = c.vocab, es = esize(c.dtype);
     const int dt = c.dtype, hd = c.head_dim;
@@ -803,7 +912,7 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
         case EE_T_EMBED:
             if (n_elems != V * d) return EE_ERR_ARG;
             HIPCHK(hipMemcpyAsync(m->wbase + m->wl.embed, dev_src, V * d * es, hipMemcpyDeviceToDevice, st));
-            rc = EE_OK;
+            rc = m->tied() ? mat(m->wl.wf, V, d, PACK_PLAIN) : EE_OK;  // tied: also every head's matrix
             break;
         case EE_T_ATTN_NORM: rc = gain(m->wl.g1[index]); break;
         case EE_T_MLP_NORM: rc = gain(m->wl.g2[index]); break;
@@ -818,6 +927,10 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
         case EE_T_WD: rc = mat(m->wl.wd[index], d, F, PACK_PLAIN); break;
         case EE_T_EXIT_HEAD: rc = mat(m->wl.we[index], V, d, PACK_PLAIN); break;
         case EE_T_FINAL_HEAD: rc = mat(m->wl.wf, V, d, PACK_PLAIN); break;
+        case EE_T_EXIT_MLP_NORM: rc = gain(m->wl.gm[index]); break;
+        case EE_T_EXIT_WG: rc = mat(m->wl.egu[index], F, d, PACK_GATE); break;
+        case EE_T_EXIT_WU: rc = mat(m->wl.egu[index], F, d, PACK_UP); break;
+        case EE_T_EXIT_WD: rc = mat(m->wl.ewd[index], d, F, PACK_PLAIN); break;
         default: return EE_ERR_RANGE;
     }
     if (rc != EE_OK) return rc;
@@ -836,7 +949,13 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
     if (!f) return EE_ERR_IO;
     char magic[8];
     ee_config fc;
-    if (std::fread(magic, 1, 8, f) != 8 || std::memcmp(magic, "EEWT0001", 8) != 0 || std::fread(&fc, sizeof fc, 1, f) != 1) {
+    std::memset(&fc, 0, sizeof fc);
+    bool ok = std::fread(magic, 1, 8, f) == 8;
+    // "EEWT0001": the config without exit_flags (the default exit structure); "EEWT0002": with it
+    const bool v2 = ok && std::memcmp(magic, "EEWT0002", 8) == 0;
+    ok = ok && (v2 || std::memcmp(magic, "EEWT0001", 8) == 0);
+    ok = ok && std::fread(&fc, v2 ? sizeof fc : offsetof(ee_config, exit_flags), 1, f) == 1;
+    if (!ok || fc.exit_flags != cfg->exit_flags) {
         std::fclose(f);
         return EE_ERR_IO;
     }
@@ -883,11 +1002,17 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
             rc = one(kinds[j], l, ns[j], (kinds[j] == EE_T_ATTN_NORM || kinds[j] == EE_T_MLP_NORM) ? 4 : es);
     }
     for (int i = 0; rc == EE_OK && i < cfg->n_exits; ++i) {
-        rc = one(EE_T_EXIT_NORM, i, d, 4);
-        if (rc == EE_OK) rc = one(EE_T_EXIT_HEAD, i, V * d, es);
+        if (m->exit_mlp()) {
+            rc = one(EE_T_EXIT_MLP_NORM, i, d, 4);
+            if (rc == EE_OK) rc = one(EE_T_EXIT_WG, i, F * d, es);
+            if (rc == EE_OK) rc = one(EE_T_EXIT_WU, i, F * d, es);
+            if (rc == EE_OK) rc = one(EE_T_EXIT_WD, i, d * F, es);
+        }
+        if (rc == EE_OK && m->exit_norm()) rc = one(EE_T_EXIT_NORM, i, d, 4);
+        if (rc == EE_OK && !m->tied()) rc = one(EE_T_EXIT_HEAD, i, V * d, es);
     }
     if (rc == EE_OK) rc = one(EE_T_FINAL_NORM, 0, d, 4);
-    if (rc == EE_OK) rc = one(EE_T_FINAL_HEAD, 0, V * d, es);
+    if (rc == EE_OK && !m->tied()) rc = one(EE_T_FINAL_HEAD, 0, V * d, es);
     std::fclose(f);
     (void)hipHostFree(host);
     if (rc != EE_OK) {
@@ -1000,7 +1125,7 @@ int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total
     c->max_pending = max_pending;
     c->pool = (char*)dev_pool;
     c->ssq_stride = cf.d_model / (16 * gemm_resid_tiles_per_wg());
-    c->xs_lo = cf.dtype == EE_BF16 ? ((size_t)max_seqs * (max_pending + 1) + m->max_rows) * cf.d_model : 0;
+    c->xs_lo = cf.dtype == EE_BF16 ? store_slots(m, max_seqs, max_pending) * cf.d_model : 0;
     c->geom.pool = dev_pool;
     c->geom.blk_stride = 2 * (size_t)cf.n_heads * block_tokens * cf.head_dim;
     c->geom.layer_stride = (size_t)c->n_blocks * c->geom.blk_stride;
@@ -1121,7 +1246,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
 int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                       int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, void* stream) {
     if (!pos_token || !pos_conf) return EE_ERR_ARG;
-    if (m && m->wsl.pf_rows == 0) return EE_ERR_CONFIG;
+    if (m && (m->wsl.pf_rows == 0 || m->exit_mlp())) return EE_ERR_CONFIG;
     return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, stream);
 }
 
@@ -1177,6 +1302,7 @@ int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, in
             di->head_xrow[0] = d->head_xrow[0];
             di->head_slot[0] = i * EE_MAX_SEQS;
         }
+        for (int i = 0; i < n_seg; ++i) fill_mlp_desc(m, c, i);
         EECHK(upload(m, st));
         HIPCHK(launch_embed(cf.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), n, cf.d_model, m->gain(m->wl.g1[0]),
                             c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));

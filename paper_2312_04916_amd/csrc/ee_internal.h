@@ -57,6 +57,9 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
 // bytes (rounded up to 16; both buffers are sized and aligned for that) from host-mapped pinned memory to the device
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
+hipError_t launch_copy_slots(int dtype, const int32_t* dev_src, const int32_t* dev_dst, int n, int d, float* x, void* xgh, size_t lo,
+                             float* ssq, int ssq_stride, hipStream_t s);
 hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s);
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);

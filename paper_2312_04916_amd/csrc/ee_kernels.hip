@@ -132,6 +132,42 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStre
     return hipGetLastError();
 }
 
+__global__ void fill_f32_kernel(float* p, float v, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    EE_LAUNCH(fill_f32_kernel, dim3((unsigned)((n + 255) / 256 < 256 ? (n + 255) / 256 : 256)), dim3(256), s, p, v, n);
+    return hipGetLastError();
+}
+
+// Rows of the residual store copied to other slots of the same store: the residual row, the operand row x.g that
+// an exit reads (both terms for bf16) and the row's sum-of-squares partials.  An exit that starts with an MLP
+// works on such a copy, so that the backbone's row stays as it is.
+template <typename ST>
+__global__ __launch_bounds__(256) void copy_slots_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int d,
+                                                         float* __restrict__ x, ST* __restrict__ xgh, size_t lo,
+                                                         float* __restrict__ ssq, int ssq_stride) {
+    const int a = src[blockIdx.x], b = dst[blockIdx.x];
+    for (int i = threadIdx.x; i < d; i += 256) {
+        x[(size_t)b * d + i] = x[(size_t)a * d + i];
+        xgh[(size_t)b * d + i] = xgh[(size_t)a * d + i];
+        if (lo) xgh[lo + (size_t)b * d + i] = xgh[lo + (size_t)a * d + i];
+    }
+    for (int i = threadIdx.x; i < ssq_stride; i += 256) ssq[(size_t)b * ssq_stride + i] = ssq[(size_t)a * ssq_stride + i];
+}
+
+hipError_t launch_copy_slots(int dtype, const int32_t* dev_src, const int32_t* dev_dst, int n, int d, float* x, void* xgh, size_t lo,
+                             float* ssq, int ssq_stride, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    if (dtype == EE_BF16)
+        EE_LAUNCH(copy_slots_kernel<__bf16>, dim3(n), dim3(256), s, dev_src, dev_dst, d, x, (__bf16*)xgh, lo, ssq, ssq_stride);
+    else
+        EE_LAUNCH(copy_slots_kernel<float>, dim3(n), dim3(256), s, dev_src, dev_dst, d, x, (float*)xgh, (size_t)0, ssq, ssq_stride);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // rotary table: cs[pos][i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
 // ------------------------------------------------------------------------------------------------

@@ -17,7 +17,7 @@ GUARD = 1e-2  # oracle confidence within this of the threshold, or top-2 logit g
 
 def ee_config_of(shape: ModelShape, max_positions: int) -> ee.ee_config:
     return ee.make_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
-                          shape.exit_layers, shape.dtype, max_positions, shape.rms_eps, shape.rope_base)
+                          shape.exit_layers, shape.dtype, max_positions, shape.rms_eps, shape.rope_base, shape.exit_flags)
 
 
 def load_gpu_model(shape: ModelShape, seed: int = 0, gain_jitter: float = 0.0, max_positions: int = 256,
