@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
     ap.add_argument("--refeed", action="store_true",
                     help="deferred tokens are fed again from the embedding (paper-literal) instead of resuming")
+    ap.add_argument("--exit-structure", default="default", choices=["default", "no_norm", "tied", "mlp", "all"],
+                    help="structure of the exits (Section 2): RMSNorm + own matrix (default), no norm, embeddings tied, "
+                         "an MLP in front of each exit, or all three")
     ap.add_argument("--no-prefill-bench", action="store_true", help="skip the timing of the prompt phase")
     ap.add_argument("--prefill-only", action="store_true", help="time the prompt phase only and print its figures")
     ap.add_argument("--pmc-run", action="store_true",
@@ -60,6 +63,7 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
     ids = list(range(B))
     d, F, V, L = shape.d_model, shape.d_ff, shape.vocab, shape.n_layers
     w_layer, w_head = (4 * d * d + 3 * d * F) * es, d * V * es
+    w_exit = w_head + (3 * d * F * es if shape.exit_mlp else 0)  # an exit with an MLP also streams that MLP
     seg_ends = list(shape.exit_layers) + [L]
     seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(L)]
     seqs = ee.Sequences(L)
@@ -100,7 +104,7 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
                 if se <= e:
                     fl[sq][k] = p + 1
         if i >= warmup:
-            nbytes += deepest * w_layer + len(heads) * w_head
+            nbytes += deepest * w_layer + sum(w_head if h == L else w_exit for h in heads)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if profile_kernel is not None:
@@ -220,6 +224,11 @@ def main():
 
     wl = CONFIGS[args.workload]
     shape = wl.shape
+    if args.exit_structure != "default":
+        import dataclasses
+        shape = dataclasses.replace(shape, exit_norm=args.exit_structure not in ("no_norm", "all"),
+                                    tie_embeddings=args.exit_structure in ("tied", "all"),
+                                    exit_mlp=args.exit_structure in ("mlp", "all"))
     es = 2 if shape.dtype == "bf16" else 4
     B = wl.batch
     lens = [wl.prompt_len[0]] * B if wl.prompt_len[0] == wl.prompt_len[1] else \
@@ -324,7 +333,8 @@ def main():
         "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: {wl.note}, batch {B}, prompt {n_prompt} random ids, greedy, "
                                f"threshold {args.threshold}, max_pending {args.max_pending}",
-                   "threshold": args.threshold, "exit_layers": list(shape.exit_layers), "n_layers": shape.n_layers},
+                   "threshold": args.threshold, "exit_layers": list(shape.exit_layers), "n_layers": shape.n_layers,
+                   "exit_structure": args.exit_structure},
         "full_depth_tokens_per_s": tps_full, "full_depth_ms_per_step": full["seconds"] / args.steps * 1e3,
         "speedup_vs_full_depth": tps / tps_full, "bytes_model_speedup": ideal_speedup,
         "exit_histogram": hist, "forced_full_steps": early["forced"], "threshold_sweep": sweep,

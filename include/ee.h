@@ -212,8 +212,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
  * arrays [n_exits+1][n_tokens] (row i < n_exits: exit i, last row: final head), filled whatever the
  * threshold: pos_token = arg max of the head's logits at that position (ties: lowest id), pos_conf = its
  * soft-max probability.  Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
- * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128, and exits without an MLP of
- * their own (EE_ERR_CONFIG otherwise).
+ * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
  * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
  * min(max_positions, EE_PREFILL_ROWS) rows, rounded up to 128 (environment variable read when the model is
  * sized and created; default 2048; 0 switches the path off), each projection one matrix-core GEMM. */

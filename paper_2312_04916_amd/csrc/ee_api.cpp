@@ -100,7 +100,7 @@ struct WorkspaceLayout {
     int max_blocks_per_seq;
     // prompt phase (bf16 model): buffers for pf_rows positions at a time, activations in the packed operand layout
     int pf_rows;  // 0: the prompt phase runs through the decode kernels in chunks
-    size_t pf_begin, pf_tokens, pf_x, pf_xg, pf_xgh, pf_q, pf_attn, pf_act, pf_ssq, pf_partials, pf_tok, pf_conf;
+    size_t pf_begin, pf_tokens, pf_x, pf_xg, pf_xgh, pf_q, pf_attn, pf_act, pf_ssq, pf_ssqe, pf_partials, pf_tok, pf_conf;
 };
 
 // Rows per pass of the prompt-phase GEMM path; 0 when the model does not qualify (fp32, or widths the
@@ -159,6 +159,7 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
         w.pf_attn = take(2 * Mp * d * 2);
         w.pf_act = take(2 * Mp * F * 2);
         w.pf_ssq = take(Mp * ((d + 255) / 256) * 4);
+        w.pf_ssqe = take(Mp * ((d + 255) / 256) * 4);  // the same for the rows an exit's MLP has changed
         w.pf_partials = take(Mp * (((size_t)c.vocab + 255) / 256) * sizeof(HeadPartial));
         w.pf_tok = take(Mp * 4);
         w.pf_conf = take(Mp * 4);
@@ -772,12 +773,44 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                 }
             }
             if (score_tok || score_conf) {  // this segment's head on every position of the pass
+                const float* head_ssq = ssq;
+                const char *ha_hi = fin ? xg_hi : xgh_hi, *ha_lo = fin ? xg_lo : xgh_lo;
+                if (!fin && m->exit_mlp()) {
+                    // The exit's MLP on every position, on a copy of the residual rows: the buffers of q and of the
+                    // attention output are free between layers and take the copy and its operand x'.g.
+                    float* xe = (float*)q_hi;
+                    float* ssq_e = (float*)(ws + w.pf_ssqe);
+                    HIPCHK(hipMemcpyAsync(xe, x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
+                    g.W = m->wbase + m->wl.egu[sgi];
+                    g.N = 2 * F;
+                    g.K = d;
+                    g.A_hi = xgh_hi;
+                    g.A_lo = xgh_lo;
+                    g.ssq = ssq;
+                    {
+                        Timed t(m, EE_K_SWIGLU, st);
+                        HIPCHK(launch_pf_swiglu(g, ac_hi, ac_lo, F, st));
+                    }
+                    g.W = m->wbase + m->wl.ewd[sgi];
+                    g.N = d;
+                    g.K = F;
+                    g.A_hi = ac_hi;
+                    g.A_lo = ac_lo;
+                    g.ssq = nullptr;
+                    {
+                        Timed t(m, EE_K_DOWN, st);
+                        HIPCHK(launch_pf_resid(g, xe, at_hi, at_lo, nullptr, nullptr, m->exit_out_gain(sgi), nullptr, ssq_e, ssq_n, st));
+                    }
+                    ha_hi = at_hi;
+                    ha_lo = at_lo;
+                    head_ssq = ssq_e;
+                }
                 g.W = m->wbase + (fin ? m->wl.wf : m->wl.we[sgi]);
                 g.N = V;
                 g.K = d;
-                g.A_hi = fin ? xg_hi : xgh_hi;
-                g.A_lo = fin ? xg_lo : xgh_lo;
-                g.ssq = (fin || m->exit_norm()) ? ssq : nullptr;  // an exit without a norm reads x as it is
+                g.A_hi = ha_hi;
+                g.A_lo = ha_lo;
+                g.ssq = (fin || m->exit_norm()) ? head_ssq : nullptr;  // an exit without a norm reads x as it is
                 {
                     Timed t(m, EE_K_HEAD, st);
                     HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf), st));
@@ -1246,7 +1279,7 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
 int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                       int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, void* stream) {
     if (!pos_token || !pos_conf) return EE_ERR_ARG;
-    if (m && (m->wsl.pf_rows == 0 || m->exit_mlp())) return EE_ERR_CONFIG;
+    if (m && m->wsl.pf_rows == 0) return EE_ERR_CONFIG;
     return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, stream);
 }
 

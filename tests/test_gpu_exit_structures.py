@@ -137,7 +137,7 @@ def test_weight_file_with_exit_flags_and_tensor_checks():
     gm3.close()
 
 
-@pytest.mark.parametrize("name", ["no_norm", "tied"])
+@pytest.mark.parametrize("name", list(VARIANTS))
 def test_scored_prompt_phase_with_other_exit_structures(name):
     """Every head on every prompt position through the prompt-phase GEMMs (bf16, d_model = 256)."""
     shape = dataclasses.replace(ModelShape(3, 256, 4, 64, 512, 2048, (1, 2), "bf16", 0.02, 0.3 / 2 ** 0.5), **VARIANTS[name])
@@ -163,14 +163,13 @@ def test_scored_prompt_phase_with_other_exit_structures(name):
     gm.close()
 
 
-def test_scored_prompt_phase_refuses_exit_mlps():
+def test_plain_prompt_phase_runs_the_exit_mlps_on_the_last_position():
+    """The plain entry point evaluates the exits on the last position only: their MLPs run through the decode
+    kernels on a copy of that row."""
     shape = dataclasses.replace(ModelShape(3, 256, 4, 64, 512, 2048, (1, 2), "bf16", 0.02, 0.3 / 2 ** 0.5), exit_mlp=True)
+    print("case: plain prompt phase with exit MLPs", flush=True)
     gm = load_gpu_model(shape, 21, gain_jitter=0.1, max_positions=128, max_rows=16, max_seqs=1)
     cache = ee.KvCache(gm, 1, 128, 64, 8)
-    with pytest.raises(ee.EeError) as e:
-        ee.prefill_scored(gm, cache, 0, prompt_tokens(shape.vocab, 40, 1).numpy(), 0.5)
-    assert e.value.code == -1
-    # the plain entry point works (the last position's exits run their MLPs through the decode kernels)
     om = build_model(shape, 21, gain_jitter=0.1)
     p = prompt_tokens(shape.vocab, 40, 1).numpy()
     tok, ex, conf = ee.prefill(gm, cache, 0, p, 0.3)
@@ -178,5 +177,6 @@ def test_scored_prompt_phase_refuses_exit_mlps():
     for hi, layer in enumerate(list(shape.exit_layers) + [shape.n_layers]):
         _, dg = om.head_row(hi, hid[layer][-1])
         assert abs(float(conf[hi]) - dg["conf"]) <= 2e-2, (hi, float(conf[hi]), dg["conf"])
+    assert rel_err(cache.read_hidden(0), hid[shape.n_layers][-1]) <= 2e-2
     cache.close()
     gm.close()
