@@ -145,6 +145,19 @@ int ee_model_free(ee_model* m);
  * n workgroups remain (default 512); tests lower it so that small models reach those kernel variants.
  * Process-wide. */
 int ee_debug_set_gemm_min_workgroups(int n);
+/* Test hook, host only (no GPU is touched): the step plan that ee_decode_step and ee_kv_cache_flush apply to one
+ * sequence (Section 4: the deferred tokens join the current token's pass; Appendix D.3: a full-depth pass is forced
+ * once the list has reached the cap).  filled[n_segments] (host, in/out) are the sequence's fill watermarks:
+ * filled[s] = positions whose K and V are present in every layer of segment s, non-increasing in s; the
+ * deferred tokens are the positions [filled[last], filled[0]).  For a step whose current token sits at
+ * `position` (= filled[0]; negative: a flush) the call reports *forced (1 if the list has reached max_pending)
+ * and, per segment, the inclusive range of positions row_lo[s]..row_hi[s] that pass through it (refeed != 0:
+ * deferred tokens re-enter at layer 1; else they resume where their KV is missing).  If reached >= 0 the
+ * watermarks are then advanced as when the step ended in segment `reached` (a flush must reach the last one);
+ * reached < 0 leaves them unchanged.  forced, row_lo, row_hi may be NULL.  EE_ERR_STATE if the watermarks are not
+ * non-increasing, EE_ERR_ARG on bad counts. */
+int ee_debug_plan(int n_segments, int32_t* filled, int position, int max_pending, int refeed, int reached,
+                  int32_t* forced, int32_t* row_lo, int32_t* row_hi);
 /* Test hook: if dev_logits != NULL, every head evaluation also stores its fp32 logits there,
  * [row][vocab] for the rows it evaluates (capacity_rows rows).  NULL switches it off. */
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);

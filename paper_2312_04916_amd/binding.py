@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
@@ -69,6 +69,7 @@ def lib():
         L.ee_model_free.argtypes = [vp]
         L.ee_debug_set_logits.argtypes = [vp, vp, C.c_int]
         L.ee_debug_set_gemm_min_workgroups.argtypes = [C.c_int]
+        L.ee_debug_plan.argtypes = [C.c_int, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
         L.ee_measure_stream_read.argtypes = [vp, sz, C.c_int, fp, vp]
@@ -258,6 +259,17 @@ class KvCache:
             self.close()
         except Exception:
             pass
+
+
+def plan(filled: Sequence[int], position: int, max_pending: int, refeed: bool = False, reached: int = -1):
+    """ee_debug_plan (host only) -> (forced, [(lo, hi) per segment], watermarks after the optional commit)."""
+    n = len(filled)
+    f = (C.c_int32 * n)(*[int(v) for v in filled])
+    lo, hi = (C.c_int32 * n)(), (C.c_int32 * n)()
+    forced = C.c_int32()
+    _chk(lib().ee_debug_plan(n, f, int(position), int(max_pending), int(bool(refeed)), int(reached), C.byref(forced), lo, hi),
+         "ee_debug_plan")
+    return bool(forced.value), [(lo[i], hi[i]) for i in range(n)], [f[i] for i in range(n)]
 
 
 def set_gemm_min_workgroups(n: int) -> None:

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "ee_internal.h"
+#include "ee_plan.h"
 
 using namespace ee;
 
@@ -272,7 +273,7 @@ struct ee_kv_cache {
     int slot_of(int seq, int pos) const { return seq * S + pos % S; }
     int transient_slot(int r) const { return max_seqs * S + r; }
     int exit_slot(int r) const { return max_seqs * S + m->max_rows + r; }  // copies an exit's MLP works on
-    int n_pending(const SeqState& s) const { return s.filled.front() - s.filled.back(); }
+    int n_pending(const SeqState& s) const { return plan::pending(s.filled.data(), (int)s.filled.size()); }
 };
 
 namespace {
@@ -578,8 +579,8 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
     for (size_t b = 0; b < ss.size(); ++b) {
         if (!ss[b].active) continue;
         const SeqState& s = c->seqs[ss[b].seq];
-        int lo = c->refeed ? s.filled.back() : s.filled[seg];
-        int hi = ss[b].p >= 0 ? ss[b].p : s.filled[0] - 1;  // inclusive
+        int lo, hi;  // inclusive
+        plan::rows(s.filled.data(), (int)s.filled.size(), seg, ss[b].p, c->refeed != 0, &lo, &hi);
         int first = T;
         for (int pos = lo; pos <= hi; ++pos, ++T) {
             if (T >= EE_MAX_ROWS) { *rows_out = EE_MAX_ROWS + 1; return; }
@@ -657,7 +658,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
                     if (conf) conf[b] = r.conf;
                     ss[b].active = false;
                     SeqState& sq = c->seqs[ss[b].seq];
-                    for (int k = 0; k <= s; ++k) sq.filled[k] = ss[b].p + 1;
+                    plan::commit(sq.filled.data(), s, ss[b].p);
                     ++fired_now;
                 }
             }
@@ -668,7 +669,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
             if (!decode) {
                 for (auto& q : ss) {
                     SeqState& sq = c->seqs[q.seq];
-                    for (int k = 1; k < n_seg; ++k) sq.filled[k] = sq.filled[0];
+                    plan::flushed(sq.filled.data(), n_seg);
                 }
                 HIPCHK(hipStreamSynchronize(st));
             }
@@ -1122,6 +1123,21 @@ int ee_debug_set_gemm_min_workgroups(int n) {
     return EE_OK;
 }
 
+int ee_debug_plan(int n_segments, int32_t* filled, int position, int max_pending, int refeed, int reached, int32_t* forced,
+                  int32_t* row_lo, int32_t* row_hi) {
+    if (n_segments < 1 || n_segments > EE_MAX_EXITS + 1 || !filled || max_pending < 0 || reached >= n_segments) return EE_ERR_ARG;
+    for (int k = 0; k < n_segments; ++k)
+        if (filled[k] < 0 || (k && filled[k] > filled[k - 1])) return EE_ERR_STATE;
+    if (forced) *forced = plan::forced(filled, n_segments, max_pending) ? 1 : 0;
+    for (int k = 0; k < n_segments && row_lo && row_hi; ++k) plan::rows(filled, n_segments, k, position, refeed != 0, row_lo + k, row_hi + k);
+    if (reached >= 0) {
+        if (position < 0 && reached != n_segments - 1) return EE_ERR_ARG;
+        if (position >= 0) plan::commit(filled, reached, position);
+        else plan::flushed(filled, n_segments);
+    }
+    return EE_OK;
+}
+
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows) {
     if (!m) return EE_ERR_ARG;
     m->dbg_logits = (float*)dev_logits;
@@ -1399,7 +1415,7 @@ int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_i
         if ((p + c->BT) / c->BT > c->geom.max_blocks_per_seq) return EE_ERR_RANGE;
         if ((p + c->BT) / c->BT > (int)s.blocks.size()) ++blocks_needed;
         if (blocks_needed > c->free_blocks.size()) return EE_ERR_NOMEM;
-        ss.push_back(StepSeq{sid, p, pend >= c->max_pending, true});
+        ss.push_back(StepSeq{sid, p, plan::forced(s.filled.data(), (int)s.filled.size(), c->max_pending), true});
     }
     // pass 2: commit the current tokens
     for (int b = 0; b < n_seqs; ++b) {
