@@ -61,6 +61,20 @@ def test_c3_shape_two_layers_long_context():
     _lockstep_case(shape, 333, 20, (0.2,))
 
 
+def test_c5_shape_two_layers():
+    """30B-shaped layers and heads (d = 6656, 52 heads, d_ff = 17920: widths that are not powers of two), 2 layers;
+    the prompt of 72 tokens goes through the prompt-phase GEMMs, the steps through the decode kernels."""
+    shape = dataclasses.replace(CONFIGS["C5"].shape, n_layers=2, exit_layers=(1,))
+    _lockstep_case(shape, 72, 12, (0.2,))
+
+
+def test_c3_shape_exit_mlp_and_tied_embeddings():
+    """7B widths, 2 layers, the exit with an MLP of its own and no norm, every head tied to the embedding."""
+    shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,), exit_norm=False, tie_embeddings=True,
+                                exit_mlp=True, head_sigma=0.1)
+    _lockstep_case(shape, 48, 12, (0.05,))
+
+
 def test_c3_full_depth_reduced_prompt():
     """The full 7B-shaped model (32 layers, exits after 8 and 16) against the oracle: prompt 24, 12 new tokens."""
     _lockstep_case(CONFIGS["C3"].shape, 24, 12, (0.2,))
