@@ -132,6 +132,62 @@ def test_c3_full_size_invariants():
         gm.close()
 
 
+def test_c4_full_size_batch_invariants():
+    """C4 as benchmarked (the full 7B-shaped model, 16 ragged sequences, threshold 0.6, max_pending 15, 256 rows per
+    launch at most): sampled sequences must emit exactly what they emit alone, and after a flush the cache of a
+    sampled sequence equals a full-depth prompt phase over what it generated (Section 4: no KV entry is missing)."""
+    from workload import prompt_lengths
+    wl = CONFIGS["C4"]
+    shape, B, n_new, tau = wl.shape, wl.batch, 24, wl.thresholds[0]
+    lens = prompt_lengths(B, wl.prompt_len[0], wl.prompt_len[1], wl.length_seed)
+    prompts = [prompt_tokens(shape.vocab, lens[b], wl.prompt_seed + b).numpy() for b in range(B)]
+    gm = load_gpu_model(shape, wl.weight_seed, max_positions=max(lens) + n_new + 8, max_rows=256, max_seqs=B)
+    cache = ee.KvCache(gm, B + 1, sum(lens) + max(lens) + (B + 1) * (n_new + 72), 64, 15)
+    L = shape.n_layers
+
+    def run(ids):
+        seqs = ee.Sequences(L)
+        out = {s: ([], []) for s in ids}
+        for s in ids:
+            cache.reset(s)
+            tok, ex, _ = ee.prefill(gm, cache, s, prompts[s], tau)
+            seqs.start(s, tok)
+            out[s][0].append(int(tok))
+            out[s][1].append(int(ex))
+        for _ in range(n_new - 1):
+            ro, tk, pm = seqs.rows(ids)
+            nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
+            seqs.update(ids, nt, exl)
+            for j, s in enumerate(ids):
+                out[s][0].append(int(nt[j]))
+                out[s][1].append(int(exl[j]))
+        return out
+
+    try:
+        print(f"case: C4 full size, batch {B}, prompts {min(lens)}..{max(lens)}", flush=True)
+        both = run(list(range(B)))
+        picks = sorted({int(np.argmin(lens)), int(np.argmax(lens)), B // 2})
+        s0 = picks[-1]
+        # the cache of one sequence after the batch run + flush, against a full-depth prompt phase over its tokens
+        cache.flush(list(range(B)))
+        n_pos = lens[s0] + n_new - 1
+        seq = np.concatenate([prompts[s0], np.array(both[s0][0][:-1], np.int32)])
+        ee.prefill(gm, cache, B, seq, 1.0)
+        for l in (0, 8, 16, 31):
+            assert cache.filled(s0, l) == n_pos and cache.filled(B, l) == n_pos
+            k0, v0 = cache.read(s0, l, lens[s0] - 8, n_new + 7)
+            k1, v1 = cache.read(B, l, lens[s0] - 8, n_new + 7)
+            assert rel_err(k0, k1) <= TOL and rel_err(v0, v1) <= TOL, (l, rel_err(k0, k1), rel_err(v0, v1))
+        cache.reset(B)
+        for s in picks:
+            print(f"case: C4 full size, sequence {s} alone (prompt {lens[s]})", flush=True)
+            solo = run([s])
+            assert solo[s] == both[s], (s, solo[s], both[s])
+    finally:
+        cache.close()
+        gm.close()
+
+
 def test_c3_shape_prompt_phase_scored():
     """Prompt phase through the GEMM path at the 7B widths (2 layers, exit after the first): cached K/V of every
     position and both heads scored on sampled positions against the oracle's cache-free forward."""
