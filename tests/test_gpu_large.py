@@ -188,6 +188,62 @@ def test_c4_full_size_batch_invariants():
         gm.close()
 
 
+def test_c5_full_size_invariants():
+    """C5 as benchmarked (30B-shaped, 60 layers, 65 GB of weights, 4 sequences of 2048 prompt tokens): threshold 1 is
+    repeatable bit for bit and never exits, threshold 0 exits at the first exit except on forced steps, and after a
+    flush the cache of a sequence equals a full-depth prompt phase over what it generated."""
+    wl = CONFIGS["C5"]
+    shape, B, n_prompt, n_new = wl.shape, wl.batch, wl.prompt_len[0], 20
+    prompts = [prompt_tokens(shape.vocab, n_prompt, wl.prompt_seed + b).numpy() for b in range(B)]
+    gm = load_gpu_model(shape, wl.weight_seed, max_positions=n_prompt + n_new + 8, max_rows=min(256, 16 * B + 48), max_seqs=B)
+    cache = ee.KvCache(gm, B + 1, (B + 1) * (n_prompt + n_new + 72), 64, 15)
+    L, e1 = shape.n_layers, shape.exit_layers[0]
+    ids = list(range(B))
+
+    def run(tau):
+        seqs = ee.Sequences(L)
+        out = {s: ([], []) for s in ids}
+        for s in ids:
+            cache.reset(s)
+            tok, ex, _ = ee.prefill(gm, cache, s, prompts[s], tau)
+            seqs.start(s, tok)
+            out[s][0].append(int(tok))
+            out[s][1].append(int(ex))
+        for _ in range(n_new - 1):
+            ro, tk, pm = seqs.rows(ids)
+            nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
+            seqs.update(ids, nt, exl)
+            for j, s in enumerate(ids):
+                out[s][0].append(int(nt[j]))
+                out[s][1].append(int(exl[j]))
+        return out
+
+    try:
+        print("case: C5 full size tau 1.0", flush=True)
+        a = run(1.0)
+        assert all(set(a[s][1]) == {L} for s in ids)
+        assert run(1.0) == a, "two runs must be bit-identical (fixed-order reductions)"
+        print("case: C5 full size tau 0.0", flush=True)
+        z = run(0.0)
+        for s in ids:
+            x0 = z[s][1]
+            assert x0[0] == e1 and all(x0[j] == (L if j % 16 == 0 else e1) for j in range(1, n_new)), x0
+        print("case: C5 full size tau 0.5 + KV invariant", flush=True)
+        h = run(wl.thresholds[0])
+        cache.flush(ids)
+        n_pos = n_prompt + n_new - 1
+        seq = np.concatenate([prompts[1], np.array(h[1][0][:-1], np.int32)])
+        ee.prefill(gm, cache, B, seq, 1.0)
+        for l in (0, 14, 15, 30, 59):
+            assert cache.filled(1, l) == n_pos and cache.filled(B, l) == n_pos
+            k0, v0 = cache.read(1, l, n_prompt - 8, n_new + 7)
+            k1, v1 = cache.read(B, l, n_prompt - 8, n_new + 7)
+            assert rel_err(k0, k1) <= TOL and rel_err(v0, v1) <= TOL, (l, rel_err(k0, k1), rel_err(v0, v1))
+    finally:
+        cache.close()
+        gm.close()
+
+
 def test_c3_shape_prompt_phase_scored():
     """Prompt phase through the GEMM path at the 7B widths (2 layers, exit after the first): cached K/V of every
     position and both heads scored on sampled positions against the oracle's cache-free forward."""
