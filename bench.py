@@ -145,7 +145,8 @@ def prefill_bench(ee, gm, cache, prompt, shape, breakdown, traffic=None):
     run(True)
     plain = min(run(False)[0] for _ in range(3))
     scored = min(run(True)[0] for _ in range(3))
-    _, (n_sw, ms_sw) = run(False, ee.EE_K_SWIGLU)
+    # (the clock moves with the load: the kernel's mean over one prompt phase is taken from the best of three passes)
+    n_sw, ms_sw = min((run(False, ee.EE_K_SWIGLU)[1] for _ in range(3)), key=lambda r: r[1])
     _, (n_hd, ms_hd) = run(True, ee.EE_K_HEAD)
     sw_tflops = 2.0 * P * 2 * F * d / (ms_sw / max(n_sw, 1) * 1e-3) / 1e12
     # scored: the head GEMM dispatches are the first of each pair (GEMM, merge); the last launch is the final-head

@@ -111,7 +111,7 @@ __device__ __forceinline__ void pf_wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int MTL, int NWAVE>
+template <int MTL, int NWAVE, bool PIPE = (NWAVE == 8)>
 __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs,
                                             f32x4 (&acc)[32 / NWAVE][MTL / 2]) {
     constexpr int WNF = 32 / NWAVE;
@@ -169,49 +169,88 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
     const unsigned lds0 = (unsigned)(size_t)EE_LDS_PTR(lds) + lane * 16;
     const unsigned woff = t.wn * WNF * 1024, xoff = (PF_NTL + t.wm * MW) * 1024;
     int st_r = 0, st_w = NST - 1;
-    for (int kt = 0; kt < KT; ++kt) {
+    struct Frags {
+        u32x4 wf[WNF], xh[MW], xl[MW];
+    };
+    // front half of a k-tile: wait until its stage has landed for everybody, start the operand reads of this wave
+    // and refill the buffer that was read one k-tile earlier
+    auto fetch = [&](Frags& f, int kt) {
         pf_wait_vm<(NST - 2) * FPW>();     // this wave's copies of stage kt have landed
         __builtin_amdgcn_s_barrier();      // ... and everybody else's; the buffer refilled below is no longer read
         const unsigned wb = lds0 + st_r * (STAGE * 16) + woff, xb = lds0 + st_r * (STAGE * 16) + xoff;
-        u32x4 wf[WNF], xh[MW], xl[MW];
-        PF_DSR(wf[0], wb, 0); PF_DSR(wf[1], wb, 1024); PF_DSR(wf[2], wb, 2048); PF_DSR(wf[3], wb, 3072);
+        PF_DSR(f.wf[0], wb, 0); PF_DSR(f.wf[1], wb, 1024); PF_DSR(f.wf[2], wb, 2048); PF_DSR(f.wf[3], wb, 3072);
         if constexpr (WNF == 8) {
-            PF_DSR(wf[4], wb, 4096); PF_DSR(wf[5], wb, 5120); PF_DSR(wf[6], wb, 6144); PF_DSR(wf[7], wb, 7168);
+            PF_DSR(f.wf[4], wb, 4096); PF_DSR(f.wf[5], wb, 5120); PF_DSR(f.wf[6], wb, 6144); PF_DSR(f.wf[7], wb, 7168);
         }
-        PF_DSR(xh[0], xb, 0); PF_DSR(xh[1], xb, 1024);
-        PF_DSR(xl[0], xb, MTL * 1024); PF_DSR(xl[1], xb, MTL * 1024 + 1024);
+        PF_DSR(f.xh[0], xb, 0); PF_DSR(f.xh[1], xb, 1024);
+        PF_DSR(f.xl[0], xb, MTL * 1024); PF_DSR(f.xl[1], xb, MTL * 1024 + 1024);
         if constexpr (MW == 4) {
-            PF_DSR(xh[2], xb, 2048); PF_DSR(xh[3], xb, 3072);
-            PF_DSR(xl[2], xb, MTL * 1024 + 2048); PF_DSR(xl[3], xb, MTL * 1024 + 3072);
+            PF_DSR(f.xh[2], xb, 2048); PF_DSR(f.xh[3], xb, 3072);
+            PF_DSR(f.xl[2], xb, MTL * 1024 + 2048); PF_DSR(f.xl[3], xb, MTL * 1024 + 3072);
         }
         issue(st_w, kt + NST - 1 < KT ? kt + NST - 1 : KT - 1);
         st_r = st_r + 1 == NST ? 0 : st_r + 1;
         st_w = st_w + 1 == NST ? 0 : st_w + 1;
-        // operands are in registers from here on (and the MFMAs below may not move above this point)
+    };
+    // the operands are in registers after this (and the MFMAs that use them may not move above it)
+    auto landed = [&](Frags& f) {
         if constexpr (WNF == 8 && MW == 4)
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(wf[4]), "+v"(wf[5]), "+v"(wf[6]),
-                         "+v"(wf[7]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]), "+v"(xh[3]), "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.wf[4]), "+v"(f.wf[5]),
+                         "+v"(f.wf[6]), "+v"(f.wf[7]), "+v"(f.xh[0]), "+v"(f.xh[1]), "+v"(f.xh[2]), "+v"(f.xh[3]), "+v"(f.xl[0]),
+                         "+v"(f.xl[1]), "+v"(f.xl[2]), "+v"(f.xl[3]));
         else if constexpr (WNF == 8)
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(wf[4]), "+v"(wf[5]), "+v"(wf[6]),
-                         "+v"(wf[7]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xl[0]), "+v"(xl[1]));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.wf[4]), "+v"(f.wf[5]),
+                         "+v"(f.wf[6]), "+v"(f.wf[7]), "+v"(f.xh[0]), "+v"(f.xh[1]), "+v"(f.xl[0]), "+v"(f.xl[1]));
         else if constexpr (MW == 4)
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]),
-                         "+v"(xh[3]), "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.xh[0]), "+v"(f.xh[1]),
+                         "+v"(f.xh[2]), "+v"(f.xh[3]), "+v"(f.xl[0]), "+v"(f.xl[1]), "+v"(f.xl[2]), "+v"(f.xl[3]));
         else
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xl[0]),
-                         "+v"(xl[1]));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.xh[0]), "+v"(f.xh[1]),
+                         "+v"(f.xl[0]), "+v"(f.xl[1]));
+    };
+    auto multiply = [&](const Frags& f) {
 #pragma unroll
         for (int i = 0; i < WNF; ++i)
 #pragma unroll
             for (int j = 0; j < MW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xl[j]),
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.wf[i]), __builtin_bit_cast(bf16x8, f.xl[j]),
                                                                     acc[i][j], 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < WNF; ++i)
 #pragma unroll
             for (int j = 0; j < MW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xh[j]),
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.wf[i]), __builtin_bit_cast(bf16x8, f.xh[j]),
                                                                     acc[i][j], 0, 0, 0);
+    };
+    if constexpr (PIPE) {
+        // One workgroup per CU: its eight waves pass the barrier together, so with reads and MFMAs of the same k-tile
+        // back to back the LDS and the matrix cores would take turns.  Two register sets instead: the operand reads of
+        // k-tile kt+1 are in flight while the MFMAs of k-tile kt run.
+        Frags fa, fb;
+        fetch(fa, 0);
+        landed(fa);
+        for (int kt = 0; kt < KT; kt += 2) {
+            if (kt + 1 < KT) fetch(fb, kt + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(fa);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 >= KT) break;
+            landed(fb);
+            if (kt + 2 < KT) fetch(fa, kt + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(fb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 2 < KT) landed(fa);
+        }
+    } else {
+        // two workgroups per CU: the other workgroup's MFMAs cover this one's reads (also taken where the second
+        // register set would not fit)
+        for (int kt = 0; kt < KT; ++kt) {
+            Frags f;
+            fetch(f, kt);
+            landed(f);
+            multiply(f);
+        }
     }
     pf_wait_vm<0>();  // the surplus copies too, before the epilogue reuses the stage buffers
     __syncthreads();  // (also makes rs[] visible)
@@ -330,7 +369,7 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_resid_kernel(PfArgs a, PfRes
     float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
     float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, (NWAVE == 8 && MTL == 4)>(a, t, pf_lds, rs, acc);  // (8 row tiles: no room for two operand sets)
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
     float sq[MW];
