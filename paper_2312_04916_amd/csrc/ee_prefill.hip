@@ -62,16 +62,15 @@ struct PfArgs {
 };
 
 // ---------------------------------------------------------------------------------------------------
-// main loop: acc[i][j] (+)= W tile i of this wave (8 of them) x activation tile j (MTL/2 of them).
-// Workgroup = 4 waves as 2 (features) x 2 (rows); tile = 256 features x MTL*16 rows; K advances 32 per
-// stage, two stages in LDS, the copy of stage k+1 runs while stage k is multiplied.  Two workgroups
-// share a CU, so that one's copy wait and operand reads hide behind the other's MFMAs.
+// main loop: acc[i][j] (+)= W tile i of this wave x activation tile j (MTL/2 of them), for both terms of the
+// activations.  Tile = 256 features x MTL*16 rows; K advances 32 per stage; the stages are filled by direct
+// global->LDS copies that run ahead of the MFMAs.
 // ---------------------------------------------------------------------------------------------------
 // NWAVE waves per workgroup, arranged (NWAVE/2) along the features x 2 along the rows: a wave owns
-// WNF = 32/NWAVE weight tiles and MTL/2 row tiles.  The GEMMs run 8 waves (two per SIMD: a single wave
-// cannot issue 16x16x32 MFMAs back to back fast enough to keep the matrix core busy) with one workgroup
-// per CU and four stages.  The head GEMM, whose grid is several times the chip, keeps 4 waves and two workgroups
-// per CU with two stages.
+// WNF = 32/NWAVE weight tiles and MTL/2 row tiles.  A single wave per SIMD cannot issue 16x16x32 MFMAs back to
+// back fast enough to keep the matrix core busy, and the more waves share a SIMD the better it is fed: the QKV and
+// gate|up GEMMs run 8 waves with two workgroups per CU (four waves per SIMD), the residual GEMMs (whose epilogue
+// needs more registers) 8 waves with one workgroup per CU, the head GEMM 4 waves with two workgroups per CU.
 template <int MTL>
 struct PfTile {
     int nt0, mt0, n_wg, wn, wm;
@@ -93,11 +92,19 @@ __device__ __forceinline__ bool pf_tile_of(const PfArgs& a, PfTile<MTL>& t) {
     return true;
 }
 
-// Stages in LDS: 2 where two workgroups share a CU (the other workgroup's MFMAs cover this one's copy
-// wait), 4 where a CU holds a single workgroup and only a deeper copy queue can cover the latency.
-template <int MTL, int NWAVE>
+// Two ways to keep the matrix cores fed, chosen per kernel (WIDE):
+//  - WIDE: two workgroups of 8 waves share a CU (four waves per SIMD, at most 128 registers each): the other
+//    workgroup's MFMAs cover this one's barriers and copy waits, so few stages suffice (2 for the 128-row tile, 3
+//    for the 64-row tile, which also has room for a second operand set in registers);
+//  - otherwise one workgroup per CU with four stages and two operand sets (the residual epilogue needs the registers).
+// The head GEMM (4 waves, two workgroups per CU, 2 stages) is its own case.
+template <int MTL, int NWAVE, bool WIDE>
 constexpr int pf_stages() {
-    return NWAVE == 4 ? 2 : 4;
+    return NWAVE == 4 ? 2 : (WIDE ? (MTL == 8 ? 2 : 3) : 4);
+}
+template <int MTL, int NWAVE, bool WIDE>
+constexpr bool pf_pipe() {
+    return NWAVE == 8 && MTL == 4;
 }
 
 // The operand reads and the wait counts are written by hand: the compiler would make every LDS read wait
@@ -111,13 +118,14 @@ __device__ __forceinline__ void pf_wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int MTL, int NWAVE, bool PIPE = (NWAVE == 8)>
+template <int MTL, int NWAVE, bool WIDE>
 __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs,
                                             f32x4 (&acc)[32 / NWAVE][MTL / 2]) {
     constexpr int WNF = 32 / NWAVE;
     constexpr int NF = PF_NTL + 2 * MTL;  // fragments (1 KB each) per stage
     constexpr int FPW = NF / NWAVE;       // copied per wave
-    constexpr int NST = pf_stages<MTL, NWAVE>();
+    constexpr int NST = pf_stages<MTL, NWAVE, WIDE>();
+    constexpr bool PIPE = pf_pipe<MTL, NWAVE, WIDE>();
     static_assert(NF % NWAVE == 0, "fragments must divide over the waves");
     static_assert((NST - 2) * FPW < 64, "vmcnt range");
     constexpr int STAGE = NF * 64;        // u32x4 per stage
@@ -208,13 +216,15 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.xh[0]), "+v"(f.xh[1]),
                          "+v"(f.xl[0]), "+v"(f.xl[1]));
     };
-    auto multiply = [&](const Frags& f) {
+    auto multiply_lo = [&](const Frags& f) {
 #pragma unroll
         for (int i = 0; i < WNF; ++i)
 #pragma unroll
             for (int j = 0; j < MW; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.wf[i]), __builtin_bit_cast(bf16x8, f.xl[j]),
                                                                     acc[i][j], 0, 0, 0);
+    };
+    auto multiply_hi = [&](const Frags& f) {
 #pragma unroll
         for (int i = 0; i < WNF; ++i)
 #pragma unroll
@@ -225,20 +235,25 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
     if constexpr (PIPE) {
         // One workgroup per CU: its eight waves pass the barrier together, so with reads and MFMAs of the same k-tile
         // back to back the LDS and the matrix cores would take turns.  Two register sets instead: the operand reads of
-        // k-tile kt+1 are in flight while the MFMAs of k-tile kt run.
+        // k-tile kt+1 are in flight while the MFMAs of k-tile kt run, and the barrier that guards them sits in the
+        // middle of that MFMA stream (after the lo-term half), so the matrix core has queued work while the waves meet.
         Frags fa, fb;
         fetch(fa, 0);
         landed(fa);
         for (int kt = 0; kt < KT; kt += 2) {
+            multiply_lo(fa);
+            __builtin_amdgcn_sched_barrier(0);
             if (kt + 1 < KT) fetch(fb, kt + 1);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(fa);
+            multiply_hi(fa);
             __builtin_amdgcn_sched_barrier(0);
             if (kt + 1 >= KT) break;
             landed(fb);
+            multiply_lo(fb);
+            __builtin_amdgcn_sched_barrier(0);
             if (kt + 2 < KT) fetch(fa, kt + 2);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(fb);
+            multiply_hi(fb);
             __builtin_amdgcn_sched_barrier(0);
             if (kt + 2 < KT) landed(fa);
         }
@@ -249,21 +264,22 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             Frags f;
             fetch(f, kt);
             landed(f);
-            multiply(f);
+            multiply_lo(f);
+            multiply_hi(f);
         }
     }
     pf_wait_vm<0>();  // the surplus copies too, before the epilogue reuses the stage buffers
     __syncthreads();  // (also makes rs[] visible)
 }
 
-template <int MTL, int NWAVE>
+template <int MTL, int NWAVE, bool WIDE>
 constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to seven reduction rows
-    return pf_stages<MTL, NWAVE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
+    return pf_stages<MTL, NWAVE, WIDE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
 }
 
-template <int MTL, int NWAVE>
+template <int MTL, int NWAVE, bool WIDE>
 __device__ __forceinline__ float* pf_rs_ptr(u32x4* lds) {
-    return (float*)(lds + pf_stages<MTL, NWAVE>() * (PF_NTL + 2 * MTL) * 64);
+    return (float*)(lds + pf_stages<MTL, NWAVE, WIDE>() * (PF_NTL + 2 * MTL) * 64);
 }
 
 // ---- epilogue 1: RMS scale, rotary embedding, q (packed), k and v into the paged cache
@@ -279,16 +295,16 @@ struct PfQkv {
 };
 
 template <int MTL, int NWAVE>
-__global__ __launch_bounds__(NWAVE * 64, 2) void pf_qkv_kernel(PfArgs a, PfQkv e) {
+__global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_qkv_kernel(PfArgs a, PfQkv e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, true>(pf_lds);
     const int tiles_per_part = e.d / 16, per_head = e.hd / 16, half = e.hd / 2;
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, true>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
 #pragma unroll
@@ -366,10 +382,10 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_resid_kernel(PfArgs a, PfRes
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, false>(pf_lds);
     float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE, (NWAVE == 8 && MTL == 4)>(a, t, pf_lds, rs, acc);  // (8 row tiles: no room for two operand sets)
+    pf_mainloop<MTL, NWAVE, false>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
     float sq[MW];
@@ -428,15 +444,15 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_resid_kernel(PfArgs a, PfRes
 
 // ---- epilogue 3: SwiGLU.  Tile j of the packed gate|up matrix: rows 0-7 gate features 8j.., rows 8-15 the up features
 template <int MTL, int NWAVE>
-__global__ __launch_bounds__(NWAVE * 64, 2) void pf_swiglu_kernel(PfArgs a, __bf16* act_hi, __bf16* act_lo, int F) {
+__global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_swiglu_kernel(PfArgs a, __bf16* act_hi, __bf16* act_lo, int F) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, true>(pf_lds);
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, true>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTf = F / 32;
 #pragma unroll
@@ -483,11 +499,11 @@ __global__ __launch_bounds__(NWAVE * 64, 2) void pf_head_kernel(PfArgs a, PfHead
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, false>(pf_lds);
     constexpr int WN = NWAVE / 2;        // waves along the features
     float* red = rs + MTL * 16;          // waves wn > 0 hand (max, sum) over here: [2 * (wn - 1) + {0, 1}][MTL * 16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, false>(a, t, pf_lds, rs, acc);
     int* redi = (int*)pf_lds;            // ... and the index here (the stage buffers are free now): [wn - 1][MTL * 16]
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
 #pragma unroll
@@ -860,8 +876,8 @@ PfArgs pf_args(const PfGemm& g, int MTL) {
     return a;
 }
 
-// Rows per workgroup tile, 128 or 64.  One workgroup occupies a CU, so a launch takes about
-// ceil(workgroups / 256) rounds of a time proportional to the tile's rows: take the cheaper, 128 on a tie
+// Rows per workgroup tile, 128 or 64.  A CU works through about ceil(workgroups / 256) tiles (whether one after
+// another or two side by side), each for a time proportional to its rows: take the cheaper, 128 on a tie
 // (half the activation traffic from L2).
 int pf_mtl(const PfGemm& g) {
     const long n_wgN = (g.N + 255) / 256;
@@ -877,17 +893,17 @@ hipError_t pf_set_lds(K kernel, size_t bytes) {
 
 }  // namespace
 
-#define PF_DISPATCH(KERNEL, ...)                                                                          \
+#define PF_DISPATCH(KERNEL, WIDE, ...)                                                                        \
     do {                                                                                                  \
         if (pf_mtl(g) == 8) {                                                                             \
             PfArgs a = pf_args(g, 8);                                                                     \
-            constexpr size_t lds_b = pf_lds_bytes<8, 8>();                                                \
+            constexpr size_t lds_b = pf_lds_bytes<8, 8, WIDE>();                                              \
             static hipError_t once = pf_set_lds(KERNEL<8, 8>, lds_b);                                     \
             if (once != hipSuccess) return once;                                                          \
             EE_LAUNCH_SM((KERNEL<8, 8>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, __VA_ARGS__);       \
         } else {                                                                                          \
             PfArgs a = pf_args(g, 4);                                                                     \
-            constexpr size_t lds_b = pf_lds_bytes<4, 8>();                                                \
+            constexpr size_t lds_b = pf_lds_bytes<4, 8, WIDE>();                                              \
             static hipError_t once = pf_set_lds(KERNEL<4, 8>, lds_b);                                     \
             if (once != hipSuccess) return once;                                                          \
             EE_LAUNCH_SM((KERNEL<4, 8>), dim3(pf_grid<4>(a)), dim3(512), lds_b, s, a, __VA_ARGS__);       \
@@ -900,17 +916,17 @@ hipError_t launch_pf_qkv(const PfGemm& g, void* q_hi, void* q_lo, const float* r
     const int d = g.N / 3;
     PfQkv e{(__bf16*)q_hi, (__bf16*)q_lo, d, kv.H, kv.hd, (const float2*)rope_cs, (__bf16*)kv.pool + (size_t)layer * kv.layer_stride,
             kv.blk_stride, kv.BT, bt, p0};
-    PF_DISPATCH(pf_qkv_kernel, e);
+    PF_DISPATCH(pf_qkv_kernel, true, e);
 }
 
 hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, void* xgh_hi, void* xgh_lo, const float* g_next,
                            const float* g_head, float* ssq_out, int ssq_n_out, hipStream_t s) {
     PfResid e{x, (__bf16*)xg_hi, (__bf16*)xg_lo, (__bf16*)xgh_hi, (__bf16*)xgh_lo, g_next, g_head, ssq_out, ssq_n_out, g.N};
-    PF_DISPATCH(pf_resid_kernel, e);
+    PF_DISPATCH(pf_resid_kernel, false, e);
 }
 
 hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, hipStream_t s) {
-    PF_DISPATCH(pf_swiglu_kernel, (__bf16*)act_hi, (__bf16*)act_lo, F);
+    PF_DISPATCH(pf_swiglu_kernel, true, (__bf16*)act_hi, (__bf16*)act_lo, F);
 }
 
 hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, hipStream_t s) {
@@ -920,7 +936,7 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
         PfArgs a = pf_args(g, 8);
         // (4 waves, two workgroups per CU: with ~1600 workgroups the shared CUs smooth the last round; 8 waves with
         // one workgroup per CU measured 750 us against 640 us at 1024 rows)
-        constexpr size_t lds_b = pf_lds_bytes<8, 4>();
+        constexpr size_t lds_b = pf_lds_bytes<8, 4, false>();
         static hipError_t once = pf_set_lds(pf_head_kernel<8, 4>, lds_b);
         if (once != hipSuccess) return once;
         EE_LAUNCH_SM((pf_head_kernel<8, 4>), dim3(pf_grid<8>(a)), dim3(256), lds_b, s, a, e);
