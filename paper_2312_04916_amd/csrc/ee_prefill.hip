@@ -69,8 +69,9 @@ struct PfArgs {
 // NWAVE waves per workgroup, arranged (NWAVE/2) along the features x 2 along the rows: a wave owns
 // WNF = 32/NWAVE weight tiles and MTL/2 row tiles.  A single wave per SIMD cannot issue 16x16x32 MFMAs back to
 // back fast enough to keep the matrix core busy, and the more waves share a SIMD the better it is fed: the QKV and
-// gate|up GEMMs run 8 waves with two workgroups per CU (four waves per SIMD), the residual GEMMs (whose epilogue
-// needs more registers) 8 waves with one workgroup per CU, the head GEMM 4 waves with two workgroups per CU.
+// gate|up GEMMs run 8 waves with two workgroups per CU (four waves per SIMD), and so does the head GEMM; the residual
+// GEMMs (a grid of one workgroup per CU at 1024 rows, and an epilogue that needs more registers) run 8 waves with one
+// workgroup per CU and a deeper ring.
 template <int MTL>
 struct PfTile {
     int nt0, mt0, n_wg, wn, wm;
@@ -493,17 +494,17 @@ __device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, f
 }
 
 template <int MTL, int NWAVE>
-__global__ __launch_bounds__(NWAVE * 64, 2) void pf_head_kernel(PfArgs a, PfHead e) {
+__global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel(PfArgs a, PfHead e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE, false>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, (NWAVE == 8)>(pf_lds);
     constexpr int WN = NWAVE / 2;        // waves along the features
     float* red = rs + MTL * 16;          // waves wn > 0 hand (max, sum) over here: [2 * (wn - 1) + {0, 1}][MTL * 16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE, false>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, (NWAVE == 8)>(a, t, pf_lds, rs, acc);
     int* redi = (int*)pf_lds;            // ... and the index here (the stage buffers are free now): [wn - 1][MTL * 16]
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
 #pragma unroll
@@ -934,12 +935,12 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
     {
         PfHead e{partials, g.N};
         PfArgs a = pf_args(g, 8);
-        // (4 waves, two workgroups per CU: with ~1600 workgroups the shared CUs smooth the last round; 8 waves with
-        // one workgroup per CU measured 750 us against 640 us at 1024 rows)
-        constexpr size_t lds_b = pf_lds_bytes<8, 4, false>();
-        static hipError_t once = pf_set_lds(pf_head_kernel<8, 4>, lds_b);
+        // (8 waves, two workgroups per CU, two stages: 633 us at 1024 rows; 4 waves with two workgroups per CU measured
+        // 672 us, 8 waves with one workgroup per CU and four stages 750 us)
+        constexpr size_t lds_b = pf_lds_bytes<8, 8, true>();
+        static hipError_t once = pf_set_lds(pf_head_kernel<8, 8>, lds_b);
         if (once != hipSuccess) return once;
-        EE_LAUNCH_SM((pf_head_kernel<8, 4>), dim3(pf_grid<8>(a)), dim3(256), lds_b, s, a, e);
+        EE_LAUNCH_SM((pf_head_kernel<8, 8>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, e);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
