@@ -104,7 +104,7 @@ constexpr int pf_stages() {
     return NWAVE == 4 ? 2 : (WIDE ? (MTL == 8 ? 2 : 3) : 4);
 }
 template <int MTL, int NWAVE, bool WIDE>
-constexpr bool pf_pipe() {
+constexpr bool pf_pipe() {  // (the residual epilogue overrides this for its two-workgroups-per-CU variant)
     return NWAVE == 8 && MTL == 4;
 }
 
@@ -119,14 +119,13 @@ __device__ __forceinline__ void pf_wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int MTL, int NWAVE, bool WIDE>
+template <int MTL, int NWAVE, bool WIDE, bool PIPE = pf_pipe<MTL, NWAVE, WIDE>()>
 __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs,
                                             f32x4 (&acc)[32 / NWAVE][MTL / 2]) {
     constexpr int WNF = 32 / NWAVE;
     constexpr int NF = PF_NTL + 2 * MTL;  // fragments (1 KB each) per stage
     constexpr int FPW = NF / NWAVE;       // copied per wave
     constexpr int NST = pf_stages<MTL, NWAVE, WIDE>();
-    constexpr bool PIPE = pf_pipe<MTL, NWAVE, WIDE>();
     static_assert(NF % NWAVE == 0, "fragments must divide over the waves");
     static_assert((NST - 2) * FPW < 64, "vmcnt range");
     constexpr int STAGE = NF * 64;        // u32x4 per stage
@@ -376,17 +375,17 @@ struct PfResid {
     int ssq_n_out, d;
 };
 
-template <int MTL, int NWAVE>
-__global__ __launch_bounds__(NWAVE * 64, 2) void pf_resid_kernel(PfArgs a, PfResid e) {
+template <int MTL, int NWAVE, bool WIDE = false>
+__global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfArgs a, PfResid e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE, false>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, WIDE>(pf_lds);
     float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE, false>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, WIDE, (!WIDE && MTL == 4)>(a, t, pf_lds, rs, acc);  // (two operand sets need 152 registers here)
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
     float sq[MW];
@@ -923,6 +922,28 @@ hipError_t launch_pf_qkv(const PfGemm& g, void* q_hi, void* q_lo, const float* r
 hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, void* xgh_hi, void* xgh_lo, const float* g_next,
                            const float* g_head, float* ssq_out, int ssq_n_out, hipStream_t s) {
     PfResid e{x, (__bf16*)xg_hi, (__bf16*)xg_lo, (__bf16*)xgh_hi, (__bf16*)xgh_lo, g_next, g_head, ssq_out, ssq_n_out, g.N};
+    // Two workgroups per CU (four waves per SIMD) once the grid has more workgroups than CUs (30B widths at 2048
+    // rows: O 359 -> 332 us, down 922 -> 840 us); a grid of one workgroup per CU keeps the deeper ring and the
+    // second operand set.
+    const int mtl = pf_mtl(g);
+    const long n_wgs = (long)((g.N + 255) / 256) * ((g.M + mtl * 16 - 1) / (mtl * 16));
+    const bool wide = n_wgs > 256;
+    if (wide) {
+        if (mtl == 8) {
+            PfArgs a = pf_args(g, 8);
+            constexpr size_t lds_b = pf_lds_bytes<8, 8, true>();
+            static hipError_t once = pf_set_lds(pf_resid_kernel<8, 8, true>, lds_b);
+            if (once != hipSuccess) return once;
+            EE_LAUNCH_SM((pf_resid_kernel<8, 8, true>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, e);
+        } else {
+            PfArgs a = pf_args(g, 4);
+            constexpr size_t lds_b = pf_lds_bytes<4, 8, true>();
+            static hipError_t once = pf_set_lds(pf_resid_kernel<4, 8, true>, lds_b);
+            if (once != hipSuccess) return once;
+            EE_LAUNCH_SM((pf_resid_kernel<4, 8, true>), dim3(pf_grid<4>(a)), dim3(512), lds_b, s, a, e);
+        }
+        return hipGetLastError();
+    }
     PF_DISPATCH(pf_resid_kernel, false, e);
 }
 
