@@ -1005,8 +1005,10 @@ __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __re
                                                          const SegDesc* __restrict__ desc, int tag) {
     __shared__ float redm[512], reds[512];
     __shared__ int redi[512];
-    // thread t folds workgroups t, t+512, ... in ascending order, then a fixed tree over the threads
-    for (int m = 0; m < T; ++m) {
+    // one workgroup per row; thread t folds workgroups t, t+512, ... in ascending order, then a fixed tree over the threads
+    const int m = blockIdx.x;
+    if (m >= T) return;
+    {
         float mx = -INFINITY, s = 0.f;
         int ix = 0x7fffffff;
         for (int w = threadIdx.x; w < n_wg; w += 512) {
@@ -1273,7 +1275,7 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    EE_LAUNCH(head_merge_kernel, dim3(1), dim3(512), s, (const HeadPartial*)partials, c.N / 16, c.T, mode, threshold, results, c.desc, tag);
+    EE_LAUNCH(head_merge_kernel, dim3(c.T), dim3(512), s, (const HeadPartial*)partials, c.N / 16, c.T, mode, threshold, results, c.desc, tag);
     return hipGetLastError();
 }
 
