@@ -31,7 +31,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=15)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--threshold", type=float, default=0.8)
+    ap.add_argument("--threshold", type=float, default=None,
+                    help="exit threshold (default: 0.8 where the workload sweeps it, else the workload's own)")
     ap.add_argument("--max-pending", type=int, default=15)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel family (extra passes, stderr)")
@@ -225,6 +226,8 @@ def main():
 
     wl = CONFIGS[args.workload]
     shape = wl.shape
+    if args.threshold is None:
+        args.threshold = 0.8 if 0.8 in wl.thresholds else wl.thresholds[0]
     if args.exit_structure != "default":
         import dataclasses
         shape = dataclasses.replace(shape, exit_norm=args.exit_structure not in ("no_norm", "all"),
