@@ -20,8 +20,11 @@
  *     during the call.
  *   - A model is immutable once its tensors are set and may serve several caches.  A cache handle,
  *     and a model while a call is running on it, must not be used from two threads at once.
- *   - All work is enqueued on the given stream; calls that return tokens synchronise that stream
- *     before returning (the host needs the exit decision to know which layers to launch next).
+ *   - All work is enqueued on the given stream; calls that return tokens wait for the head results of
+ *     that work before returning (the host needs the exit decision to know which layers to launch
+ *     next): the results arrive in pinned host memory that the call polls, written by the last kernel
+ *     of the step, so nothing of the step is in flight when it returns.  ee_prefill, ee_kv_cache_flush
+ *     and the read-backs synchronise the stream.
  */
 #ifndef EE_H
 #define EE_H
