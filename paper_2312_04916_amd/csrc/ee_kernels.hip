@@ -471,7 +471,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_multi(const GemmArgs& a, int 
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[g][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int D = MT == 4 ? 2 : 4;
+    constexpr int D = (MT == 4 || MT * G >= 12) ? 2 : 4;  // ring slots: fewer where a slot already holds many KB
     u32x4 w[G][D], ah[MT][D], al[MT][D];
     const int n = kt1 - kt0;
     auto fill_w = [&](int u, int t) {
@@ -1114,6 +1114,12 @@ void set_gemm_min_wgs(int n) { g_min_wgs = n < 1 ? 1 : n; }
 static int gemm_min_wgs() { return g_min_wgs; }
 static int g_of(int mt, int n_tiles) {
     if (mt == 1 && n_tiles / 4 >= gemm_min_wgs()) return 4;
+    // up to two row tiles and a tile count that three divide into at least half that many workgroups (Q|K|V at the
+    // 7B width: 768 tiles = 256 workgroups of 3, one per CU, instead of three rounds of 256)
+    if (mt <= 2 && n_tiles % 3 == 0 && n_tiles / 3 >= gemm_min_wgs() / 2) return 3;
+    // ... or that six divide into a single round of workgroups (gate|up at the 7B width: 1376 tiles = 230 workgroups of
+    // 6 instead of three rounds of 2: the same makespan in tiles, a third of the row-operand traffic)
+    if (mt <= 2 && (n_tiles + 5) / 6 <= 256 && n_tiles / 6 >= gemm_min_wgs() * 2 / 5) return 6;
     if (n_tiles / 2 >= gemm_min_wgs()) return 2;
     return 1;
 }
@@ -1121,6 +1127,8 @@ static int g_of(int mt, int n_tiles) {
 #define EE_LAUNCH_G(ST, KERNEL, KS_, MT_, ...)                                                        \
     do {                                                                                              \
         if (_g == 4 && MT_ == 1) EE_LAUNCH((KERNEL<ST, KS_, 1, false, (KS_ == 16 ? 2 : 4)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 3 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, (MT_ <= 2 ? MT_ : 1), false, (KS_ == 16 ? 2 : 3)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 6 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, (MT_ <= 2 ? MT_ : 1), false, (KS_ == 16 ? 2 : 6)>), grid, block, s, __VA_ARGS__); \
         else if (_g >= 2) EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 2>), grid, block, s, __VA_ARGS__);   \
         else EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 1>), grid, block, s, __VA_ARGS__);                \
     } while (0)
@@ -1143,7 +1151,7 @@ static hipError_t lds_limit_once() {
         const int _ks = ks_of(c), _mt = mt_of(c.T), _nt = c.N / 16;                                                \
         const size_t _sm = a_lds_bytes(c);                                                                         \
         int _g = _sm ? 1 : g_of(_mt, _nt);                                                                         \
-        if (_ks == 16 && _g == 4) _g = 2; /* 1024 threads leave 128 registers per lane */                          \
+        if (_ks == 16 && _g >= 3) _g = 2; /* 1024 threads leave 128 registers per lane */                          \
         dim3 grid((_nt + _g - 1) / _g), block(_ks * 64);                                                           \
         if (_sm) {                                                                                                 \
             if (_ks == 4) EE_LAUNCH_LDS((KERNEL<ST, 4, 1, true, 1>), grid, block, _sm, s, __VA_ARGS__);            \
