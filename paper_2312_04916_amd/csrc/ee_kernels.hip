@@ -1114,21 +1114,25 @@ void set_gemm_min_wgs(int n) { g_min_wgs = n < 1 ? 1 : n; }
 static int gemm_min_wgs() { return g_min_wgs; }
 static int g_of(int mt, int n_tiles) {
     if (mt == 1 && n_tiles / 4 >= gemm_min_wgs()) return 4;
-    // up to two row tiles and a tile count that three divide into at least half that many workgroups (Q|K|V at the
-    // 7B width: 768 tiles = 256 workgroups of 3, one per CU, instead of three rounds of 256)
-    if (mt <= 2 && n_tiles % 3 == 0 && n_tiles / 3 >= gemm_min_wgs() / 2) return 3;
-    // ... or that six divide into a single round of workgroups (gate|up at the 7B width: 1376 tiles = 230 workgroups of
-    // 6 instead of three rounds of 2: the same makespan in tiles, a third of the row-operand traffic)
-    if (mt <= 2 && (n_tiles + 5) / 6 <= 256 && n_tiles / 6 >= gemm_min_wgs() * 2 / 5) return 6;
+    // Up to two row tiles: at these register counts one workgroup of 8 waves is resident per CU, so a launch runs in
+    // rounds of 256 workgroups.  Give a workgroup as many tiles as there would be rounds (2..6): one round, the same
+    // makespan in tiles, and the row operands and prologues are paid once instead of once per round (Q|K|V at the 7B
+    // width: 768 tiles = 256 x 3; gate|up: 1376 tiles = 230 x 6).  (The test hook scales the 256 with its threshold.)
+    const int cus = gemm_min_wgs() >= 512 ? 256 : (gemm_min_wgs() / 2 > 0 ? gemm_min_wgs() / 2 : 1);
+    const int rounds = (n_tiles + cus - 1) / cus;
+    if (mt <= 2 && rounds >= 2 && rounds <= 6) return rounds;
     if (n_tiles / 2 >= gemm_min_wgs()) return 2;
     return 1;
 }
 
 #define EE_LAUNCH_G(ST, KERNEL, KS_, MT_, ...)                                                        \
     do {                                                                                              \
+        constexpr int MTG = MT_ <= 2 ? MT_ : 1; /* 3..6 tiles: up to two row tiles */                 \
         if (_g == 4 && MT_ == 1) EE_LAUNCH((KERNEL<ST, KS_, 1, false, (KS_ == 16 ? 2 : 4)>), grid, block, s, __VA_ARGS__); \
-        else if (_g == 3 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, (MT_ <= 2 ? MT_ : 1), false, (KS_ == 16 ? 2 : 3)>), grid, block, s, __VA_ARGS__); \
-        else if (_g == 6 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, (MT_ <= 2 ? MT_ : 1), false, (KS_ == 16 ? 2 : 6)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 3 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, MTG, false, (KS_ == 16 ? 2 : 3)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 4 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, MTG, false, (KS_ == 16 ? 2 : 4)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 5 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, MTG, false, (KS_ == 16 ? 2 : 5)>), grid, block, s, __VA_ARGS__); \
+        else if (_g == 6 && MT_ <= 2) EE_LAUNCH((KERNEL<ST, KS_, MTG, false, (KS_ == 16 ? 2 : 6)>), grid, block, s, __VA_ARGS__); \
         else if (_g >= 2) EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 2>), grid, block, s, __VA_ARGS__);   \
         else EE_LAUNCH((KERNEL<ST, KS_, MT_, false, 1>), grid, block, s, __VA_ARGS__);                \
     } while (0)
@@ -1148,10 +1152,13 @@ static hipError_t lds_limit_once() {
 
 #define EE_DISPATCH(ST, KERNEL, ...)                                                                               \
     do {                                                                                                           \
-        const int _ks = ks_of(c), _mt = mt_of(c.T), _nt = c.N / 16;                                                \
+        int _ks = ks_of(c);                                                                                        \
+        const int _mt = mt_of(c.T), _nt = c.N / 16;                                                                \
         const size_t _sm = a_lds_bytes(c);                                                                         \
         int _g = _sm ? 1 : g_of(_mt, _nt);                                                                         \
-        if (_ks == 16 && _g >= 3) _g = 2; /* 1024 threads leave 128 registers per lane */                          \
+        /* 1024 threads leave 128 registers per lane: 3..6 tiles need the 8-wave variants (each wave then */       \
+        /* streams K/8, still >= 8 k-tiles here); otherwise 16 waves stay at two tiles */                          \
+        if (_ks == 16 && _g >= 3) { if (_g <= 6 && _mt <= 2) _ks = 8; else _g = 2; }                               \
         dim3 grid((_nt + _g - 1) / _g), block(_ks * 64);                                                           \
         if (_sm) {                                                                                                 \
             if (_ks == 4) EE_LAUNCH_LDS((KERNEL<ST, 4, 1, true, 1>), grid, block, _sm, s, __VA_ARGS__);            \

@@ -349,12 +349,13 @@ def test_workload_generator_is_device_independent():
 def test_ragged_batch_with_several_tiles_per_workgroup():
     """The same ragged batch with the GEMMs forced to give every workgroup several column tiles (the variants that
     the 7B shapes take when a step has many rows), including a head over more rows than LDS holds."""
-    ee.set_gemm_min_workgroups(1)
-    try:
-        test_ragged_batch_with_more_than_64_rows("bf16")
-        test_other_head_dims_with_split_kv(64, 256, 4)
-    finally:
-        ee.set_gemm_min_workgroups(512)
+    for min_wgs in (1, 16):  # 1: two or four tiles; 16: as many tiles as there would be rounds of 8 workgroups (3..6)
+        ee.set_gemm_min_workgroups(min_wgs)
+        try:
+            test_ragged_batch_with_more_than_64_rows("bf16")
+            test_other_head_dims_with_split_kv(64, 256, 4)
+        finally:
+            ee.set_gemm_min_workgroups(512)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
