@@ -791,12 +791,22 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
         }
         float pv[8];
         float tmax = -INFINITY;
+        if (tb + 31 <= pos0) {
+            // every key of the tile lies at or before the first query of this wave: no causal mask (rows past the end of
+            // the prompt then carry finite numbers that are never stored)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int pa = tb + lg * 8 + e;
-            const float val = (qvalid && pa <= pos0 + li) ? sacc[e >> 2][e & 3] * scale : -INFINITY;
-            pv[e] = val;
-            tmax = fmaxf(tmax, val);
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = sacc[e >> 2][e & 3] * scale;
+                tmax = fmaxf(tmax, pv[e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int pa = tb + lg * 8 + e;
+                const float val = (qvalid && pa <= pos0 + li) ? sacc[e >> 2][e & 3] * scale : -INFINITY;
+                pv[e] = val;
+                tmax = fmaxf(tmax, val);
+            }
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -806,10 +816,11 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
 #pragma unroll
             for (int e = 0; e < 8; ++e) pv[e] = 0.f;
         } else {
-            corr = expf(m_run - m_new);
+            // (hardware exponential: relative error about 1e-6 over the range that matters, far inside the bf16 contract)
+            corr = __expf(m_run - m_new);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                pv[e] = expf(pv[e] - m_new);
+                pv[e] = __expf(pv[e] - m_new);
                 psum += pv[e];
             }
         }
@@ -824,6 +835,9 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
             ph[e] = hi;
             pl[e] = (__bf16)(pv[e] - (float)hi);
         }
+        // the running maximum seldom moves once a few tiles have been seen: the accumulator is rescaled only when some
+        // query of this wave needs it
+        const bool rescale = __builtin_amdgcn_ballot_w64(corr != 1.f) != 0;
         const bool ragged = tb + 32 > ctx;  // positions beyond this wave's context may hold unknown bits: zero them
 #pragma unroll
         for (int c = 0; c < CG; ++c) {
@@ -833,7 +847,7 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
                 for (int e = 0; e < 8; ++e)
                     if (tb + lg * 8 + e >= ctx) vf[e] = (__bf16)0.f;
             }
-            o[c] = o[c] * corr;
+            if (rescale) o[c] = o[c] * corr;
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
             o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
         }
