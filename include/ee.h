@@ -227,14 +227,18 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
  * token each exit would emit after each prefix, and how confident it is).  pos_token / pos_conf are host
  * arrays [n_exits+1][n_tokens] (row i < n_exits: exit i, last row: final head), filled whatever the
  * threshold: pos_token = arg max of the head's logits at that position (ties: lowest id), pos_conf = its
- * soft-max probability.  Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
+ * soft-max probability.  pos_nll (host, same shape, may be NULL): the negative log-likelihood each head gives
+ * to the prompt's own next token, pos_nll[i][t] = log sum_v exp(z_v) - z[tokens[t+1]] for t < n_tokens-1 and 0 in
+ * the last column: the per-token cross-entropy terms of the early-exit training objective (Section 3, Eq. (1):
+ * a weighted sum of the exits' losses), computed from the same logits without storing them.
+ * Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
  * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
  * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
  * min(max_positions, EE_PREFILL_ROWS) rows, rounded up to 128 (environment variable read when the model is
  * sized and created; default 2048; 0 switches the path off), each projection one matrix-core GEMM. */
 int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                       int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf,
-                      void* stream);
+                      float* pos_nll, void* stream);
 
 /* One decode step for n_seqs sequences.
  *   seq_ids      [n_seqs]   distinct sequence ids

@@ -84,7 +84,7 @@ def lib():
         L.ee_kv_cache_free.argtypes = [vp]
         L.ee_debug_read_hidden.argtypes = [vp, vp, C.c_int, fp, vp]
         L.ee_prefill.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, vp]
-        L.ee_prefill_scored.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, i32p, fp, vp]
+        L.ee_prefill_scored.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, i32p, fp, fp, vp]
         L.ee_decode_step.argtypes = [vp, vp, C.c_int, i32p, i32p, i32p, C.POINTER(C.c_uint8), C.c_float, i32p, i32p,
                                      fp, vp]
         _lib = L
@@ -287,16 +287,20 @@ def prefill(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], thres
     return nt.value, ex.value, conf
 
 
-def prefill_scored(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], threshold: float, stream=None):
-    """ee_prefill_scored -> (next_token, exit_layer, conf[n_exits+1], pos_token[n_exits+1][n], pos_conf[n_exits+1][n])."""
+def prefill_scored(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], threshold: float, stream=None, nll: bool = False):
+    """ee_prefill_scored -> (next_token, exit_layer, conf[n_exits+1], pos_token[n_exits+1][n], pos_conf[n_exits+1][n])
+    and, with nll=True, pos_nll[n_exits+1][n] as a sixth element."""
     t = _i32(tokens)
     nt, ex = C.c_int32(), C.c_int32()
     nh = model.cfg.n_exits + 1
     conf = np.zeros(nh, np.float32)
     ptok = np.zeros((nh, len(t)), np.int32)
     pconf = np.zeros((nh, len(t)), np.float32)
+    pnll = np.zeros((nh, len(t)), np.float32) if nll else None
     _chk(lib().ee_prefill_scored(model.h, cache.h, seq, _ip(t), len(t), threshold, C.byref(nt), C.byref(ex), _fp(conf),
-                                 _ip(ptok), _fp(pconf), _stream_ptr(stream)), "ee_prefill_scored")
+                                 _ip(ptok), _fp(pconf), _fp(pnll) if nll else None, _stream_ptr(stream)), "ee_prefill_scored")
+    if nll:
+        return nt.value, ex.value, conf, ptok, pconf, pnll
     return nt.value, ex.value, conf, ptok, pconf
 
 

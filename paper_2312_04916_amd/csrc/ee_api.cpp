@@ -101,7 +101,7 @@ struct WorkspaceLayout {
     int max_blocks_per_seq;
     // prompt phase (bf16 model): buffers for pf_rows positions at a time, activations in the packed operand layout
     int pf_rows;  // 0: the prompt phase runs through the decode kernels in chunks
-    size_t pf_begin, pf_tokens, pf_x, pf_xg, pf_xgh, pf_q, pf_attn, pf_act, pf_ssq, pf_ssqe, pf_partials, pf_tok, pf_conf;
+    size_t pf_begin, pf_tokens, pf_x, pf_xg, pf_xgh, pf_q, pf_attn, pf_act, pf_ssq, pf_ssqe, pf_partials, pf_tok, pf_conf, pf_tgt, pf_zt, pf_nll;
 };
 
 // Rows per pass of the prompt-phase GEMM path; 0 when the model does not qualify (fp32, or widths the
@@ -164,6 +164,9 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
         w.pf_partials = take(Mp * (((size_t)c.vocab + 255) / 256) * sizeof(HeadPartial));
         w.pf_tok = take(Mp * 4);
         w.pf_conf = take(Mp * 4);
+        w.pf_tgt = take(Mp * 4);   // per row: the next token of the prompt (scoring its log-likelihood)
+        w.pf_zt = take(Mp * 4);    // its logit
+        w.pf_nll = take(Mp * 4);
     }
     w.total = off;
     return w;
@@ -684,7 +687,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
 // decide the first token.  score_tok / score_conf (host, [n_seg][n_tokens], optional): every head on
 // every position.
 int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* score_tok,
-                  float* score_conf, hipStream_t st) {
+                  float* score_conf, float* score_nll, hipStream_t st) {
     const ee_config& cf = m->cfg;
     const WorkspaceLayout& w = m->wsl;
     const int d = cf.d_model, F = cf.d_ff, V = cf.vocab, n_seg = m->n_seg();
@@ -722,6 +725,11 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
         g.M = M;
         std::memcpy(m->pf_host_tokens, tokens + p0, (size_t)M * 4);
         HIPCHK(hipMemcpyAsync(ws + w.pf_tokens, m->pf_host_tokens, (size_t)M * 4, hipMemcpyHostToDevice, st));
+        if (score_nll) {  // the token that follows each position (none after the last one of the prompt)
+            int32_t* tg = m->pf_host_tokens + Mp;
+            for (int r = 0; r < M; ++r) tg[r] = p0 + r + 1 < n_tokens ? tokens[p0 + r + 1] : -1;
+            HIPCHK(hipMemcpyAsync(ws + w.pf_tgt, tg, (size_t)M * 4, hipMemcpyHostToDevice, st));
+        }
         HIPCHK(launch_pf_embed(m->wbase + m->wl.embed, (const int32_t*)(ws + w.pf_tokens), M, d, m->gain(m->wl.g1[0]), x, xg_hi, xg_lo, ssq,
                                ssq_n, st));
         for (int sgi = 0; sgi < n_seg; ++sgi) {
@@ -773,7 +781,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                                            ssq_n, st));
                 }
             }
-            if (score_tok || score_conf) {  // this segment's head on every position of the pass
+            if (score_tok || score_conf || score_nll) {  // this segment's head on every position of the pass
                 const float* head_ssq = ssq;
                 const char *ha_hi = fin ? xg_hi : xgh_hi, *ha_lo = fin ? xg_lo : xgh_lo;
                 if (!fin && m->exit_mlp()) {
@@ -814,12 +822,16 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                 g.ssq = (fin || m->exit_norm()) ? head_ssq : nullptr;  // an exit without a norm reads x as it is
                 {
                     Timed t(m, EE_K_HEAD, st);
-                    HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf), st));
+                    HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf),
+                                          (const int32_t*)(ws + w.pf_tgt), (float*)(ws + w.pf_zt), score_nll ? (float*)(ws + w.pf_nll) : nullptr,
+                                          st));
                 }
                 if (score_tok)
                     HIPCHK(hipMemcpyAsync(score_tok + (size_t)sgi * n_tokens + p0, ws + w.pf_tok, (size_t)M * 4, hipMemcpyDeviceToHost, st));
                 if (score_conf)
                     HIPCHK(hipMemcpyAsync(score_conf + (size_t)sgi * n_tokens + p0, ws + w.pf_conf, (size_t)M * 4, hipMemcpyDeviceToHost, st));
+                if (score_nll)
+                    HIPCHK(hipMemcpyAsync(score_nll + (size_t)sgi * n_tokens + p0, ws + w.pf_nll, (size_t)M * 4, hipMemcpyDeviceToHost, st));
             }
             if (last && (fin || threshold < 1.0f)) {
                 const int l_end = m->seg_end(sgi);
@@ -891,7 +903,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
         }
     m->dbg_logits = nullptr;
     m->dbg_rows = 0;
-    size_t res_bytes = align_up(sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1)) + (size_t)m->wsl.pf_rows * 4;
+    size_t res_bytes = align_up(sizeof(HeadResult) * EE_MAX_SEQS * (EE_MAX_EXITS + 1)) + (size_t)m->wsl.pf_rows * 8;  // tokens and next-token targets of a pass
     hipError_t e = hipHostMalloc((void**)&m->pinned, align_up(m->wsl.upload_bytes) + res_bytes, hipHostMallocMapped);
     if (e != hipSuccess) {
         g_last_hip = (int)e;
@@ -1284,24 +1296,25 @@ int ee_kv_cache_free(ee_kv_cache* c) {
 
 namespace {
 int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* next_token,
-                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, void* stream);
+                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, float* score_nll, void* stream);
 }
 
 int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                int32_t* next_token, int32_t* exit_layer, float* conf, void* stream) {
-    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, nullptr, nullptr, stream);
+    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, nullptr, nullptr, nullptr, stream);
 }
 
 int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
-                      int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, void* stream) {
+                      int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, float* pos_nll,
+                      void* stream) {
     if (!pos_token || !pos_conf) return EE_ERR_ARG;
     if (m && m->wsl.pf_rows == 0) return EE_ERR_CONFIG;
-    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, stream);
+    return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, pos_nll, stream);
 }
 
 namespace {
 int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold, int32_t* next_token,
-                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, void* stream) {
+                 int32_t* exit_layer, float* conf, int32_t* score_tok, float* score_conf, float* score_nll, void* stream) {
     if (!m || !c || !tokens || !next_token || !exit_layer || c->m != m) return EE_ERR_ARG;
     if (m->n_missing) return EE_ERR_STATE;
     if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
@@ -1316,7 +1329,7 @@ int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, in
     const int n_seg = m->n_seg();
     const int CH = std::min(m->max_rows, 64);
     const bool large = m->wsl.pf_rows > 0 && (score_tok != nullptr || n_tokens >= PF_MIN_TOKENS);
-    if (large) EECHK(prefill_large(m, c, seq, tokens, n_tokens, threshold, score_tok, score_conf, st));
+    if (large) EECHK(prefill_large(m, c, seq, tokens, n_tokens, threshold, score_tok, score_conf, score_nll, st));
     put_btab(m, c, 0, s);
     for (int p0 = 0; p0 < n_tokens && !large; p0 += CH) {
         int n = std::min(CH, n_tokens - p0);

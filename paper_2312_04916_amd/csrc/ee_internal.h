@@ -137,7 +137,9 @@ hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, 
                            const float* g_head, float* ssq_out, int ssq_n_out, hipStream_t s);
 hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, hipStream_t s);
 // head on every row: (arg max, confidence) per row into tok / conf
-hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, hipStream_t s);
+// ... and, if nll != NULL, nll[row] = log sum exp(z) - z[target[row]] (0 where target[row] < 0)
+hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, const int32_t* target,
+                          float* target_logit, float* nll, hipStream_t s);
 // one fp32 row of the residual stream -> decode-side residual store entry (row-major two-term operands)
 hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
                                 size_t lo_off, float* dssq, int ssq_stride, hipStream_t s);

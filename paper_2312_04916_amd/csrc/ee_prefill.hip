@@ -480,6 +480,8 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_swiglu_kern
 struct PfHead {
     HeadPartial* partials;  // [rows][n_wgN]
     int V;
+    const int32_t* target;  // per row: the token whose logit is wanted (negative: none), or NULL
+    float* target_logit;    // per row: that logit
 };
 
 __device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, float s2, int i2) {
@@ -512,6 +514,8 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
         const float r = rs[ml];
         float mx = -INFINITY, sm = 0.f;
         int ix = 0x7fffffff;
+        const int m_row = t.mt0 * 16 + ml;
+        const int tgt = (e.target != nullptr && m_row < a.M) ? e.target[m_row] : -1;
 #pragma unroll
         for (int i = 0; i < WNF; ++i) {
             const int n = (t.nt0 + t.wn * WNF + i) * 16 + rg * 4;
@@ -523,6 +527,7 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
                     mx = z;
                     ix = n + q;
                 }
+                if (n + q == tgt) e.target_logit[m_row] = z;  // (exactly one lane of one workgroup holds it)
             }
         }
 #pragma unroll
@@ -574,8 +579,11 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
 }
 
 // one wave per row: merges the row's partials in workgroup order; token = arg max, confidence = 1 / sum exp(z - max)
+// and, where a target token is given, nll = log sum exp(z) - z[target]
 __global__ __launch_bounds__(64) void pf_head_merge_kernel(const HeadPartial* __restrict__ partials, int n_wg, int M,
-                                                           int32_t* __restrict__ tok, float* __restrict__ conf) {
+                                                           int32_t* __restrict__ tok, float* __restrict__ conf,
+                                                           const int32_t* __restrict__ target, const float* __restrict__ target_logit,
+                                                           float* __restrict__ nll) {
     const int m = blockIdx.x, lane = threadIdx.x;
     if (m >= M) return;
     float mx = -INFINITY, sm = 0.f;
@@ -602,6 +610,7 @@ __global__ __launch_bounds__(64) void pf_head_merge_kernel(const HeadPartial* __
     if (lane == 0) {
         tok[m] = ix;
         conf[m] = 1.0f / sm;
+        if (nll != nullptr) nll[m] = (target != nullptr && target[m] >= 0) ? (logf(sm) + mx) - target_logit[m] : 0.f;
     }
 }
 
@@ -965,10 +974,11 @@ hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, 
     PF_DISPATCH(pf_swiglu_kernel, true, (__bf16*)act_hi, (__bf16*)act_lo, F);
 }
 
-hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, hipStream_t s) {
+hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, const int32_t* target,
+                          float* target_logit, float* nll, hipStream_t s) {
     const int n_wg = (g.N + 255) / 256;
     {
-        PfHead e{partials, g.N};
+        PfHead e{partials, g.N, nll ? target : nullptr, target_logit};
         PfArgs a = pf_args(g, 8);
         // (8 waves, two workgroups per CU, two stages: 633 us at 1024 rows; 4 waves with two workgroups per CU measured
         // 672 us, 8 waves with one workgroup per CU and four stages 750 us)
@@ -979,7 +989,8 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    EE_LAUNCH(pf_head_merge_kernel, dim3(g.M), dim3(64), s, (const HeadPartial*)partials, n_wg, g.M, tok, conf);
+    EE_LAUNCH(pf_head_merge_kernel, dim3(g.M), dim3(64), s, (const HeadPartial*)partials, n_wg, g.M, tok, conf,
+              nll ? target : (const int32_t*)nullptr, (const float*)target_logit, nll);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@ import os
 
 import numpy as np
 import pytest
+import scipy.special
 
 import paper_2312_04916_amd as ee
 from oracle.from_workload import build_model
@@ -132,5 +133,47 @@ def test_scored_short_prompt_and_path_switched_off():
     assert e.value.code == -1
     tok, ex, conf = ee.prefill(gm, cache, 0, p, 0.5)
     assert cache.filled(0, shape.n_layers - 1) == 50
+    cache.close()
+    gm.close()
+
+
+@pytest.mark.parametrize("name,n,rows_env", [("hd64", 210, None), ("hd32", 300, 128)])
+def test_scored_negative_log_likelihood_of_the_prompt(name, n, rows_env):
+    """pos_nll[i][t] = -log p_i(tokens[t+1] | tokens[..t]) of every head: the per-token cross-entropy terms of the
+    early-exit training objective (Section 3, Eq. (1)), against log-sum-exp (scipy, fp64) of the oracle's logits.
+    With rows_env the prompt spans several passes: the target of a pass's last row is the next pass's first token."""
+    print(f"case: scored nll {name} n={n} rows_env={rows_env}", flush=True)
+    shape = SHAPES[name]
+    old = os.environ.get("EE_PREFILL_ROWS")
+    if rows_env is not None:
+        os.environ["EE_PREFILL_ROWS"] = str(rows_env)
+    try:
+        om = build_model(shape, 5, gain_jitter=0.1)
+        gm = load_gpu_model(shape, 5, gain_jitter=0.1, max_positions=512, max_rows=64, max_seqs=1)
+    finally:
+        if rows_env is not None:
+            if old is None:
+                del os.environ["EE_PREFILL_ROWS"]
+            else:
+                os.environ["EE_PREFILL_ROWS"] = old
+    p = prompt_tokens(shape.vocab, n, 45).numpy()
+    cache = ee.KvCache(gm, 1, 512, 64, 8)
+    hid, _, _ = om.forward_sequence(p)
+    out = ee.prefill_scored(gm, cache, 0, p, 0.5, nll=True)
+    pnll, pconf = out[5], out[4]
+    heads = list(shape.exit_layers) + [shape.n_layers]
+    worst = 0.0
+    for hi, layer in enumerate(heads):
+        for pos in range(n - 1):
+            z, dg = om.head_row(hi, hid[layer][pos])
+            ref = float(scipy.special.logsumexp(z.astype(np.float64)) - float(z[p[pos + 1]]))
+            got = float(pnll[hi, pos])
+            worst = max(worst, abs(got - ref))
+            assert abs(got - ref) <= 2e-2 * max(1.0, abs(ref)), (hi, pos, got, ref)
+            # consistency with the confidence of the same head: -log(conf) = log-sum-exp - max logit
+            assert abs(-np.log(float(pconf[hi, pos])) - (scipy.special.logsumexp(z.astype(np.float64)) - dg["top1"])) <= 2e-2
+        assert pnll[hi, n - 1] == 0.0  # no token follows the last position
+    assert float(np.mean(pnll[:, :-1])) > 1.0  # random weights: the mean loss is of the order of log(vocab)
+    print(f"  worst |nll - oracle| = {worst:.2e}, mean nll {np.mean(pnll[:, :-1]):.3f}", flush=True)
     cache.close()
     gm.close()
