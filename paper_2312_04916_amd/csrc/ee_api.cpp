@@ -598,7 +598,6 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
             d->qt_nq[nqt] = std::min(16, T - r);
             d->qt_pos0[nqt] = d->pos[r];
             d->qt_seq[nqt] = (int)b;
-            for (int q = 0; q < d->qt_nq[nqt]; ++q) d->row_qt[r + q] = nqt * 16 + q;
             ++nqt;
         }
         bool is_final = seg == m->n_seg() - 1;
@@ -608,6 +607,24 @@ void build_desc(const ee_model* m, const ee_kv_cache* c, SegDesc* d, const std::
             ++nh;
         }
     }
+    // Query tiles in order of falling context length: the attention workgroups of a launch are handed out in tile
+    // order, and the longest ones must not be the last to start (the rows themselves stay where they are).
+    {
+        struct Tile {
+            int32_t row0, nq, pos0, seq;
+        };
+        Tile tiles[EE_MAX_ROWS];
+        for (int i = 0; i < nqt; ++i) tiles[i] = Tile{d->qt_row0[i], d->qt_nq[i], d->qt_pos0[i], d->qt_seq[i]};
+        std::stable_sort(tiles, tiles + nqt, [](const Tile& a, const Tile& b) { return a.pos0 + a.nq > b.pos0 + b.nq; });
+        for (int i = 0; i < nqt; ++i) {
+            d->qt_row0[i] = tiles[i].row0;
+            d->qt_nq[i] = tiles[i].nq;
+            d->qt_pos0[i] = tiles[i].pos0;
+            d->qt_seq[i] = tiles[i].seq;
+        }
+    }
+    for (int i = 0; i < nqt; ++i)
+        for (int q = 0; q < d->qt_nq[i]; ++q) d->row_qt[d->qt_row0[i] + q] = i * 16 + q;
     d->T = T;
     d->n_qt = nqt;
     d->n_head = nh;

@@ -1413,7 +1413,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
     constexpr int KK = HD / 32, CG = HD / 16;
     __shared__ float wO[NW * 16 * (HD + 1)];
     __shared__ float wm[NW * 16], wl[NW * 16];
-    const int qt = blockIdx.x / kv.H, h = blockIdx.x % kv.H, split = blockIdx.y;
+    // workgroups are handed out in index order: tile-major (the host lists the tiles longest context first), so that all
+    // splits of a long context start before any short one
+    const int split = blockIdx.x % NS, qh_ = blockIdx.x / NS, qt = qh_ / kv.H, h = qh_ % kv.H;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: block-table reads become scalar loads
     const int lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
     const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
@@ -1622,7 +1624,7 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     if (NS > by_len) NS = by_len;
     if (NS > ATT_MAX_SPLITS) NS = ATT_MAX_SPLITS;
     if (NS < 1) NS = 1;
-    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs, NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc, btab, kv,
+    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs * NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc, btab, kv,
               lb, d, NS, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
