@@ -1396,7 +1396,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
 // attention, bf16 model: ragged multi-query decode attention over the paged cache with MFMA.
 // One workgroup = (query tile of <= 16 consecutive rows of one sequence, head, KV split); its 4 waves
 // take the split's 32-position tiles round-robin.  Per tile a wave computes S^T = K Q^T (K rows come
-// straight from the cache as MFMA A operands: 64 contiguous bytes per lane), applies the causal mask
+// straight from the cache as MFMA A operands: a load covers 16 rows x 64 contiguous bytes), applies the causal mask
 // (only the last rows of the context differ between the queries of a tile), keeps an online soft-max
 // per query, stages the V tile through LDS (coalesced 16-byte loads in, transposed 2-byte reads out)
 // and accumulates O^T += V^T P^T, where P^T is already in B-operand layout in the S^T registers.
@@ -1444,9 +1444,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
         const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * (HD / 4);
+            const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * 8;  // one load: 16 rows x 64 contiguous bytes
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 8);
+            for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 32);
         }
 #pragma unroll
         for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (size_t)(c * 16 + li) * kv.BT + lg * 8);
@@ -1454,11 +1454,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
 
     bf16x8 qh[KK], ql[KK];
     {
-        const __bf16* qp = q + (size_t)(row0 + (qvalid ? li : 0)) * d + h * HD + lg * (HD / 4);
+        const __bf16* qp = q + (size_t)(row0 + (qvalid ? li : 0)) * d + h * HD + lg * 8;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            qh[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + kk * 8));
-            ql[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + q_lo + kk * 8));
+            qh[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + kk * 32));
+            ql[kk] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + q_lo + kk * 32));
         }
     }
     const float scale = 1.0f / sqrtf((float)HD);
