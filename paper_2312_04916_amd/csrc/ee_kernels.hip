@@ -1619,13 +1619,20 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
     // KV splits: enough workgroups to cover the chip, at least ~4 tiles (one per wave) per split.  A
     // wave works through its tiles one after another, so short splits keep the dependent chain short.
-    int NS = 1024 / wgs;
-    int by_len = (tiles + 3) / 4;
+    // Few query tiles (a step of one or two rows per sequence, small batches): workgroups of 8 waves and
+    // about 6 tiles per split, i.e. fewer splits for the consumer to merge at the same number of waves.
+    const bool few = wgs <= 64;
+    int NS = (few ? 256 : 1024) / wgs;
+    int by_len = few ? (tiles + 5) / 6 : (tiles + 3) / 4;
     if (NS > by_len) NS = by_len;
     if (NS > ATT_MAX_SPLITS) NS = ATT_MAX_SPLITS;
     if (NS < 1) NS = 1;
-    EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs * NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc, btab, kv,
-              lb, d, NS, part);
+    if (few)
+        EE_LAUNCH((attn_mfma_kernel<HD, 8>), dim3(wgs * NS), dim3(8 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc,
+                  btab, kv, lb, d, NS, part);
+    else
+        EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs * NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc,
+                  btab, kv, lb, d, NS, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
     if (defer_ns != nullptr) {  // the consumer merges the splits itself
