@@ -272,6 +272,111 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
     __syncthreads();  // (also makes rs[] visible)
 }
 
+constexpr int PFK_NF = 2 * (PF_NTL + 8);  // fragments per stage: two k-tiles of 16 weight and 4 + 4 activation fragments
+constexpr int PFK_NST = 3;
+constexpr size_t pfk_lds_bytes() { return (size_t)PFK_NST * PFK_NF * 1024 + 64 * 4 * 8; }
+__device__ __forceinline__ float* pfk_rs_ptr(u32x4* lds) { return (float*)(lds + PFK_NST * PFK_NF * 64); }
+
+// ---------------------------------------------------------------------------------------------------
+// Main loop for a 64-row tile on a grid of one workgroup per CU: 16 waves, i.e. four per SIMD like the wide
+// kernels, as 4 (features) x 2 (rows) x 2 (halves of K).  A stage holds two k-tiles; wave group kh works on k-tile
+// 2s + kh with the wave tile of the plain main loop (4 weight tiles x 2 row tiles).  At the end the upper group
+// hands its accumulators to the lower one through LDS (fixed order: lower half of K first); only waves 0..7 leave
+// with sums, in the layout of the plain main loop with 8 waves.  KT must be even.
+// ---------------------------------------------------------------------------------------------------
+constexpr int PF16_FPW = PFK_NF / 16;
+
+__device__ __forceinline__ void pf_mainloop_k16(const PfArgs& a, const PfTile<4>& t, int kh, u32x4* lds, float* rs, f32x4 (&acc)[4][2]) {
+    constexpr int MTL = 4, NST = PFK_NST, FPW = PF16_FPW, HALF = PFK_NF / 2;
+    constexpr int STAGE = PFK_NF * 64;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int KT = a.KT, KS = KT >> 1;
+    const u32x4* src[FPW];
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) {
+        const int f = wave * FPW + i, fh = f / HALF, g = f % HALF;
+        if (g < PF_NTL) {
+            int tt = t.nt0 + g;
+            if (tt >= a.n_tiles) tt = a.n_tiles - 1;
+            src[i] = a.W + ((size_t)tt * KT + fh) * 64 + lane;
+        } else {
+            const int r = g - PF_NTL;
+            int mt = t.mt0 + (r < MTL ? r : r - MTL);
+            if (mt >= a.m_tiles) mt = a.m_tiles - 1;
+            src[i] = (r < MTL ? a.Xh : a.Xl) + ((size_t)mt * KT + fh) * 64 + lane;
+        }
+    }
+    auto issue = [&](int st, int s) {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i)
+            __builtin_amdgcn_global_load_lds(EE_GLB_PTR(src[i] + (size_t)s * 128), EE_LDS_PTR(lds + st * STAGE + (wave * FPW + i) * 64), 16,
+                                             0, 0);
+    };
+    for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
+        const int m = t.mt0 * 16 + ml;
+        float r = 1.f;
+        if (a.ssq != nullptr && m < a.M) {
+            const float* p = a.ssq + (size_t)m * a.ssq_n;
+            float sum = 0.f;
+            for (int i = 0; i < a.ssq_n; ++i) sum += p[i];
+            r = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+        }
+        rs[ml] = r;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) issue(p, p < KS ? p : KS - 1);
+    const unsigned lds0 = (unsigned)(size_t)EE_LDS_PTR(lds) + lane * 16;
+    const unsigned woff = (kh * HALF + t.wn * 4) * 1024, xoff = (kh * HALF + PF_NTL + t.wm * 2) * 1024;
+    int st_r = 0, st_w = NST - 1;
+    for (int s = 0; s < KS; ++s) {
+        u32x4 wf[4], xh[2], xl[2];
+        pf_wait_vm<(NST - 2) * FPW>();
+        __builtin_amdgcn_s_barrier();
+        const unsigned wb = lds0 + st_r * (STAGE * 16) + woff, xb = lds0 + st_r * (STAGE * 16) + xoff;
+        PF_DSR(wf[0], wb, 0); PF_DSR(wf[1], wb, 1024); PF_DSR(wf[2], wb, 2048); PF_DSR(wf[3], wb, 3072);
+        PF_DSR(xh[0], xb, 0); PF_DSR(xh[1], xb, 1024);
+        PF_DSR(xl[0], xb, 4096); PF_DSR(xl[1], xb, 5120);
+        issue(st_w, s + NST - 1 < KS ? s + NST - 1 : KS - 1);
+        st_r = st_r + 1 == NST ? 0 : st_r + 1;
+        st_w = st_w + 1 == NST ? 0 : st_w + 1;
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xl[0]),
+                     "+v"(xl[1]));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xl[j]),
+                                                                    acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, xh[j]),
+                                                                    acc[i][j], 0, 0, 0);
+    }
+    pf_wait_vm<0>();
+    __syncthreads();  // every copy has landed and every operand read is done: the stage buffers are free (rs[] is visible)
+    f32x4* xch = (f32x4*)lds;  // [wave 0..7][8][64 lanes]
+    if (kh == 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) xch[(((wave & 7) * 8) + i * 2 + j) * 64 + lane] = acc[i][j];
+    }
+    __syncthreads();
+    if (kh == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] += xch[((wave * 8) + i * 2 + j) * 64 + lane];
+    }
+    __syncthreads();  // before the epilogue reuses the buffers
+}
+
 template <int MTL, int NWAVE, bool WIDE>
 constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to seven reduction rows
     return pf_stages<MTL, NWAVE, WIDE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
@@ -375,17 +480,12 @@ struct PfResid {
     int ssq_n_out, d;
 };
 
-template <int MTL, int NWAVE, bool WIDE = false>
-__global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfArgs a, PfResid e) {
-    extern __shared__ u32x4 pf_lds[];
-    PfTile<MTL> t;
-    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+// (waves with active == false hold no sums: they only keep the barriers company)
+template <int MTL, int NWAVE>
+__device__ __forceinline__ void pf_resid_epilogue(const PfArgs& a, const PfResid& e, const PfTile<MTL>& t, const float* rs, float* red,
+                                                  const f32x4 (&acc)[32 / NWAVE][MTL / 2], bool active = true) {
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE, WIDE>(pf_lds);
-    float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
-    f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE, WIDE, (!WIDE && MTL == 4)>(a, t, pf_lds, rs, acc);  // (two operand sets need 152 registers here)
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
     float sq[MW];
@@ -394,7 +494,7 @@ __global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfAr
 #pragma unroll
     for (int i = 0; i < WNF; ++i) {
         const int T = t.nt0 + t.wn * WNF + i;
-        if (T >= a.n_tiles) continue;
+        if (T >= a.n_tiles || !active) continue;
         const int n = T * 16 + rg * 4;
         const f32x4 gn = *(const f32x4*)(e.g_next + n);
         f32x4 gh = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -428,7 +528,7 @@ __global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfAr
         float s = sq[j];
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
-        if (rg == 0) red[t.wn * (MTL * 16) + (t.wm * MW + j) * 16 + li] = s;
+        if (rg == 0 && active) red[t.wn * (MTL * 16) + (t.wm * MW + j) * 16 + li] = s;
     }
     __syncthreads();
     for (int ml = threadIdx.x; ml < MTL * 16; ml += blockDim.x) {
@@ -440,6 +540,34 @@ __global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfAr
             e.ssq_out[(size_t)m * e.ssq_n_out + t.n_wg] = sum;
         }
     }
+}
+
+template <int MTL, int NWAVE, bool WIDE = false>
+__global__ __launch_bounds__(NWAVE * 64, WIDE ? 4 : 2) void pf_resid_kernel(PfArgs a, PfResid e) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<MTL> t;
+    if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
+    float* rs = pf_rs_ptr<MTL, NWAVE, WIDE>(pf_lds);
+    float* red = rs + MTL * 16;  // [NWAVE/2][MTL*16]
+    f32x4 acc[32 / NWAVE][MTL / 2];
+    pf_mainloop<MTL, NWAVE, WIDE, (!WIDE && MTL == 4)>(a, t, pf_lds, rs, acc);  // (two operand sets need 152 registers here)
+    pf_resid_epilogue<MTL, NWAVE>(a, e, t, rs, red, acc);
+}
+
+// 64-row tile, one workgroup of 16 waves per CU, the contraction split over two wave groups
+__global__ __launch_bounds__(1024, 4) void pf_resid_k16_kernel(PfArgs a, PfResid e) {
+    extern __shared__ u32x4 pf_lds[];
+    PfTile<4> t;
+    if (!pf_tile_of<4, 8>(a, t)) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kh = wave >> 3;
+    t.wn = (wave & 7) % 4;
+    t.wm = (wave & 7) / 4;
+    float* rs = pfk_rs_ptr(pf_lds);
+    float* red = rs + 64;
+    f32x4 acc[4][2];
+    pf_mainloop_k16(a, t, kh, pf_lds, rs, acc);
+    pf_resid_epilogue<4, 8>(a, e, t, rs, red, acc, kh == 0);
 }
 
 // ---- epilogue 3: SwiGLU.  Tile j of the packed gate|up matrix: rows 0-7 gate features 8j.., rows 8-15 the up features
@@ -965,6 +1093,16 @@ hipError_t launch_pf_resid(const PfGemm& g, float* x, void* xg_hi, void* xg_lo, 
             if (once != hipSuccess) return once;
             EE_LAUNCH_SM((pf_resid_kernel<4, 8, true>), dim3(pf_grid<4>(a)), dim3(512), lds_b, s, a, e);
         }
+        return hipGetLastError();
+    }
+    // ... and, when the contraction has an even number of k-tiles, 16 waves with K split over two wave groups
+    // (O 68 -> 64 us, down 159 -> 152 us at the 7B width and 1024 rows)
+    if (mtl == 4 && (g.K / 32) % 2 == 0 && g.K / 32 >= 2 * PFK_NST) {
+        PfArgs a = pf_args(g, 4);
+        constexpr size_t lds_b = pfk_lds_bytes();
+        static hipError_t once = pf_set_lds(pf_resid_k16_kernel, lds_b);
+        if (once != hipSuccess) return once;
+        EE_LAUNCH_SM(pf_resid_k16_kernel, dim3(pf_grid<4>(a)), dim3(1024), lds_b, s, a, e);
         return hipGetLastError();
     }
     PF_DISPATCH(pf_resid_kernel, false, e);
