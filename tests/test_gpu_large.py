@@ -13,7 +13,7 @@ import torch
 
 import paper_2312_04916_amd as ee
 from oracle import oracle as O
-from workload import CONFIGS, prompt_tokens
+from workload import ModelShape, CONFIGS, prompt_tokens
 
 from common import build_pair, load_gpu_model, lockstep, rel_err
 
@@ -59,6 +59,14 @@ def test_c3_shape_two_layers_long_context():
     """7B-shaped layers and heads (every kernel in its benchmark launch shape), 2 layers, context 333+."""
     shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
     _lockstep_case(shape, 333, 20, (0.2,))
+
+
+def test_context_of_4200_positions_small_model():
+    """A prompt of 4200 tokens (three passes of the prompt phase, the later ones attending to what the earlier ones
+    cached; 66 cache blocks) and decode steps over that context: head_dim 128, two heads, so a step's attention runs
+    with the largest number of KV splits and the O projection merges all of them."""
+    shape = ModelShape(2, 256, 2, 128, 544, 2080, (1,), "bf16", 0.02, 0.3 / 2 ** 0.5)
+    _lockstep_case(shape, 4200, 12, (0.5,))
 
 
 def test_c5_shape_two_layers():
