@@ -824,8 +824,10 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
     static_assert(NCH % 4 == 0, "chunks must divide over the four waves");
     extern __shared__ u32x4 pfa_lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
-    // heavier blocks (later positions) first
-    const int qb = (int)(gridDim.x - 1 - blockIdx.x), h = blockIdx.y;
+    // Heavier blocks (later positions) first, and heads along x: workgroup ids go round-robin to the XCDs, so every XCD
+    // gets blocks of every length (with the blocks of one head along x, one XCD held the longest block of every head
+    // and another the shortest), and all blocks of a head share an XCD's L2 when the head count is a multiple of 8.
+    const int qb = (int)(gridDim.y - 1 - blockIdx.y), h = blockIdx.x;
     const int qt = qb * 4 + wave;
     const int r0 = qt * 16;
     const int nq = max(0, min(16, M - r0));
@@ -1148,7 +1150,7 @@ hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, con
 hipError_t launch_pf_attention(const void* q_hi, const void* q_lo, void* out_hi, void* out_lo, const KvGeom& kv, int layer,
                                const int32_t* bt, int p0, int M, int d, hipStream_t s) {
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
-    dim3 grid((M + 63) / 64, kv.H), block(256);
+    dim3 grid(kv.H, (M + 63) / 64), block(256);
     const size_t lds = (size_t)PFA_STAGES * (2 * (kv.hd / 32) + kv.hd / 16) * 1024;  // at most 64 KB
     switch (kv.hd) {
         case 32:
