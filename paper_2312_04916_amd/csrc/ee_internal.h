@@ -42,7 +42,7 @@ struct HeadPartial {
 
 // Geometry of the paged cache as the kernels see it.
 struct KvGeom {
-    void* pool;           // [L][n_blocks]{ K: [H][BT][hd], V transposed: [H][hd][BT] }
+    void* pool;           // [L][n_blocks]{ K: [H][BT][hd], V transposed in groups of 32 positions: [H][BT/32][hd][32] }
     size_t layer_stride;  // elements
     size_t blk_stride;    // elements: 2*H*BT*hd
     int32_t H, hd, BT, max_blocks_per_seq;

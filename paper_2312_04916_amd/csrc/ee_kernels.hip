@@ -823,11 +823,13 @@ __global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_q
                 ST* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + c * 8 + i;
                 kp[0] = cvt_st<ST>(lo);
                 kp[half] = cvt_st<ST>(hi);
-            } else {  // V block, transposed: [head][feature][position], so that attention reads P.V operands directly
-                ST* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd +
-                         ((size_t)h * e.hd + c * 8 + i) * e.BT + (pos % e.BT);
+            } else {  // V block, transposed in groups of 32 positions: [head][position / 32][feature][position % 32], so
+                      // that attention reads the P.V operands of a 32-position tile directly and as one contiguous piece
+                const int pin = pos % e.BT;
+                ST* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + (size_t)h * e.hd * e.BT +
+                         (size_t)(pin >> 5) * (e.hd * 32) + (c * 8 + i) * 32 + (pin & 31);
                 vp[0] = cvt_st<ST>(lo);
-                vp[(size_t)half * e.BT] = cvt_st<ST>(hi);
+                vp[half * 32] = cvt_st<ST>(hi);
             }
         }
     }
@@ -1315,7 +1317,7 @@ hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t*
 // were written by the QKV kernel).  Online soft-max over chunks of 1024 positions.
 // ------------------------------------------------------------------------------------------------
 // K of (head, position): pointer to its hd contiguous features.  V of (head, position, feature): one
-// element of the transposed V block [head][feature][position].
+// element of the transposed V block [head][position / 32][feature][position % 32].
 template <typename ST>
 __device__ __forceinline__ const ST* k_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int h, int pos) {
     int blk = bt[pos / kv.BT];
@@ -1324,8 +1326,9 @@ __device__ __forceinline__ const ST* k_ptr(const ST* layer_base, const KvGeom& k
 template <typename ST>
 __device__ __forceinline__ const ST* v_ptr(const ST* layer_base, const KvGeom& kv, const int32_t* bt, int h, int pos, int c) {
     int blk = bt[pos / kv.BT];
-    return layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * kv.hd + ((size_t)h * kv.hd + c) * kv.BT +
-           (pos % kv.BT);
+    const int pin = pos % kv.BT;
+    return layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * kv.hd + (size_t)h * kv.hd * kv.BT +
+           (size_t)(pin >> 5) * (kv.hd * 32) + c * 32 + (pin & 31);
 }
 
 __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
@@ -1441,7 +1444,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
         const int blk = bt[tb / kv.BT];
         const int tin = tb % kv.BT;
         const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + tin) * HD;
-        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
+        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT +
+                              (size_t)(tin >> 5) * (HD * 32);  // the tile's V: HD x 32, contiguous
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const __bf16* kp = kbase + (size_t)(krow0 + sub * 4) * HD + lg * 8;  // one load: 16 rows x 64 contiguous bytes
@@ -1449,7 +1453,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
             for (int kk = 0; kk < KK; ++kk) r.k[sub * KK + kk] = *(const u32x4*)(kp + kk * 32);
         }
 #pragma unroll
-        for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (size_t)(c * 16 + li) * kv.BT + lg * 8);
+        for (int c = 0; c < CG; ++c) r.v[c] = *(const u32x4*)(vbase + (c * 16 + li) * 32 + lg * 8);
     };
 
     bf16x8 qh[KK], ql[KK];

@@ -453,18 +453,19 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_qkv_kernel(
                     }
                 }
             } else {
-                // V block, transposed [head][feature][position]: four 2-byte stores per lane; the 16 lanes of a
-                // group cover 16 consecutive positions of one feature
+                // V block, transposed [head][position / 32][feature][position % 32]: four 2-byte stores per lane; the
+                // 16 lanes of a group cover 16 consecutive positions of one feature
                 const int ml = ml0 + li, m = t.mt0 * 16 + ml;
                 if (m < a.M) {
                     const float r = rs[ml];
                     const int pos = e.p0 + m;
                     const int blk = e.bt[pos / e.BT];
                     const int f = c * 8 + (rg & 1) * 4 + (rg >= 2 ? half : 0);
-                    __bf16* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + ((size_t)h * e.hd + f) * e.BT +
-                                 (pos % e.BT);
+                    const int pin = pos % e.BT;
+                    __bf16* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + (size_t)h * e.hd * e.BT +
+                                 (size_t)(pin >> 5) * (e.hd * 32) + f * 32 + (pin & 31);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) vp[(size_t)q * e.BT] = (__bf16)(acc[i][j][q] * r);
+                    for (int q = 0; q < 4; ++q) vp[q * 32] = (__bf16)(acc[i][j][q] * r);
                 }
             }
         }
@@ -851,7 +852,8 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
         const int blk = bt[tb / kv.BT];
         const int tin = tb % kv.BT;
         const __bf16* kbase = layer_base + (size_t)blk * kv.blk_stride + ((size_t)h * kv.BT + tin) * HD;
-        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT + tin;
+        const __bf16* vbase = layer_base + (size_t)blk * kv.blk_stride + (size_t)kv.H * kv.BT * HD + (size_t)h * HD * kv.BT +
+                              (size_t)(tin >> 5) * (HD * 32);
 #pragma unroll
         for (int i = 0; i < FPW; ++i) {
             const int c = wave * FPW + i;
@@ -860,7 +862,7 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
                 const int sub = c / KK, kk = c % KK;
                 src = kbase + (size_t)(krow0 + sub * 4) * HD + kk * 32 + lg * 8;
             } else {
-                src = vbase + (size_t)((c - 2 * KK) * 16 + li) * kv.BT + lg * 8;
+                src = vbase + ((c - 2 * KK) * 16 + li) * 32 + lg * 8;
             }
             __builtin_amdgcn_global_load_lds(EE_GLB_PTR(src), EE_LDS_PTR(pfa_lds + st * STAGE + c * 64), 16, 0, 0);
         }
