@@ -173,6 +173,10 @@ int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);
 enum { EE_K_QKV = 0, EE_K_ATTN = 1, EE_K_OPROJ = 2, EE_K_SWIGLU = 3, EE_K_DOWN = 4, EE_K_HEAD = 5, EE_K_KINDS = 6 };
 int ee_profile_begin(ee_model* m, int kernel, int max_launches);
 int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms);
+/* Sampling for the hook above: from the next ee_profile_begin on, only every `every`-th launch (>= 1; 1 = all, the
+ * default) of the family carries an event pair.  An event pair costs a launch about 5 us of queue time, which a
+ * throughput figure taken in the same region should not pay 32 times a step.  EE_ERR_ARG while a measurement runs. */
+int ee_profile_every(ee_model* m, int every);
 
 /* Measurement hook: a kernel that only reads (16 bytes per lane and load, eight loads in flight per wave) is run
  * n_launches times (1..1000) back to back over `bytes` bytes of the model's own weight buffer (0, or more than the

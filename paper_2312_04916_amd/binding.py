@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
@@ -72,6 +72,7 @@ def lib():
         L.ee_debug_plan.argtypes = [C.c_int, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
+        L.ee_profile_every.argtypes = [vp, C.c_int]
         L.ee_measure_stream_read.argtypes = [vp, sz, C.c_int, fp, vp]
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
@@ -154,7 +155,8 @@ class Model:
         _chk(lib().ee_debug_set_logits(self.h, self._logits.data_ptr(), rows), "ee_debug_set_logits")
         return self._logits
 
-    def profile_begin(self, kernel: int, max_launches: int = 65536) -> None:
+    def profile_begin(self, kernel: int, max_launches: int = 16384, every: int = 1) -> None:
+        _chk(lib().ee_profile_every(self.h, every), "ee_profile_every")
         _chk(lib().ee_profile_begin(self.h, kernel, max_launches), "ee_profile_begin")
 
     def profile_end(self) -> Tuple[int, float]:

@@ -192,6 +192,7 @@ struct ee_model {
     float* dbg_logits;
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
+    int prof_every = 1, prof_seen = 0;  // every prof_every-th launch of the family is timed
     std::vector<hipEvent_t> prof_ev;    // event pairs
     size_t prof_used = 0;               // events recorded so far
     size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? rows_padded(max_rows) * ld : 0; }  // hi -> lo distance
@@ -319,7 +320,7 @@ int check_cache_args(const ee_model* m, int max_seqs, int64_t max_tokens_total, 
 // Attaches an event pair to the next launch when its kernel family is being timed.
 struct Timed {
     Timed(ee_model* m, int kernel, hipStream_t) {
-        if (m->prof_kernel == kernel && m->prof_used + 2 <= m->prof_ev.size()) {
+        if (m->prof_kernel == kernel && m->prof_seen++ % m->prof_every == 0 && m->prof_used + 2 <= m->prof_ev.size()) {
             set_launch_events(m->prof_ev[m->prof_used], m->prof_ev[m->prof_used + 1]);
             m->prof_used += 2;
         }
@@ -1088,13 +1089,26 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
 
 int ee_profile_begin(ee_model* m, int kernel, int max_launches) {
     if (!m || kernel < 0 || kernel >= EE_K_KINDS || max_launches < 1 || max_launches > (1 << 20)) return EE_ERR_ARG;
+    // A fresh event costs several microseconds the first time it is recorded: new events are recorded once here, so
+    // that the launches they are attached to later are not slowed down by it.
+    bool fresh = false;
     while (m->prof_ev.size() < (size_t)max_launches * 2) {
         hipEvent_t e;
         HIPCHK(hipEventCreate(&e));
         m->prof_ev.push_back(e);
+        HIPCHK(hipEventRecord(e, nullptr));
+        fresh = true;
     }
+    if (fresh) HIPCHK(hipStreamSynchronize(nullptr));
     m->prof_used = 0;
+    m->prof_seen = 0;
     m->prof_kernel = kernel;
+    return EE_OK;
+}
+
+int ee_profile_every(ee_model* m, int every) {
+    if (!m || every < 1 || m->prof_kernel >= 0) return EE_ERR_ARG;
+    m->prof_every = every;
     return EE_OK;
 }
 
