@@ -78,6 +78,7 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
     exits, nbytes, forced = [], 0, 0
     prof = None
     t0 = None
+    log = []  # (row offsets, exit layers) per step: the bytes model is worked out after the clock has stopped
     for i in range(warmup + steps):
         if i == warmup:
             torch.cuda.synchronize()
@@ -87,6 +88,12 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
         ro, tk, pm = seqs.rows(ids)
         nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
         seqs.update(ids, nt, exl)
+        log.append((ro, exl))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if profile_kernel is not None:
+        prof = gm.profile_end()
+    for i, (ro, exl) in enumerate(log):
         deepest, heads = 0, set()
         for sq in ids:
             p, e = len(prompts[sq]) + i, int(exl[sq])
@@ -106,10 +113,6 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
                     fl[sq][k] = p + 1
         if i >= warmup:
             nbytes += deepest * w_layer + sum(w_head if h == L else w_exit for h in heads)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    if profile_kernel is not None:
-        prof = gm.profile_end()
     return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof, tokens=B * steps)
 
 
