@@ -402,3 +402,41 @@ def test_ragged_batch_with_more_than_64_rows(dtype):
     assert all(cache.pending(s) == 0 for s in ids)
     cache.close()
     gm.close()
+
+
+def test_measurement_hook_counts_and_samples_launches():
+    """ee_profile_begin / ee_profile_every / ee_profile_end: every launch of the chosen kernel family carries an event
+    pair, or every n-th one; the counts follow from the number of layers and steps, the durations are positive, and
+    the tokens are those of an unmeasured run."""
+    print("case: measurement hook", flush=True)
+    shape = TINY_BF16
+    gm = load_gpu_model(shape, 0, gain_jitter=0.1, max_positions=64, max_rows=16, max_seqs=1)
+    prompt = prompt_tokens(shape.vocab, 9, 2).numpy()
+
+    def run(kernel=None, every=1):
+        cache = ee.KvCache(gm, 1, 64, 32, 4)
+        seqs = ee.Sequences(shape.n_layers)
+        tok, _, _ = ee.prefill(gm, cache, 0, prompt, 1.0)
+        seqs.start(0, tok)
+        toks = [int(tok)]
+        if kernel is not None:
+            gm.profile_begin(kernel, max_launches=256, every=every)
+        for _ in range(6):
+            ro, tk, pm = seqs.rows([0])
+            nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, 1.0)
+            seqs.update([0], nt, exl)
+            toks.append(int(nt[0]))
+        prof = gm.profile_end() if kernel is not None else None
+        cache.close()
+        return toks, prof
+
+    ref, _ = run()
+    launches = 6 * shape.n_layers  # one gate|up launch per layer and step at full depth
+    for every in (1, 4, 5):
+        toks, (n, ms) = run(ee.EE_K_SWIGLU, every)
+        assert toks == ref
+        assert n == (launches + every - 1) // every, (every, n)
+        assert ms > 0.0
+    toks, (n, ms) = run(ee.EE_K_HEAD)  # the final head, once per step
+    assert toks == ref and n == 6 and ms > 0.0
+    gm.close()
