@@ -48,44 +48,36 @@ inline float rnd(int dtype, float v) { return dtype == EO_BF16 ? bf16_round(v) :
 inline float wload(const float* w, size_t i) { return w[i]; }
 inline float wload(const uint16_t* w, size_t i) { return bf16_to_f32(w[i]); }
 
-// dot product in fp64, four interleaved partial sums in a fixed order
+// dot product: one running fp64 sum, terms added in index order
 template <typename T>
 double dotd(const T* w, const float* h, int K) {
-    double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
-    int k = 0;
-    for (; k + 4 <= K; k += 4) {
-        s0 += (double)wload(w, k) * (double)h[k];
-        s1 += (double)wload(w, k + 1) * (double)h[k + 1];
-        s2 += (double)wload(w, k + 2) * (double)h[k + 2];
-        s3 += (double)wload(w, k + 3) * (double)h[k + 3];
-    }
-    for (; k < K; ++k) s0 += (double)wload(w, k) * (double)h[k];
-    return (s0 + s1) + (s2 + s3);
+    double s = 0;
+    for (int k = 0; k < K; ++k) s += (double)wload(w, k) * (double)h[k];
+    return s;
 }
 
+// y = W h, each output one dot product rounded once to fp32
 template <typename T>
-void matvec_t(const T* W, int N, int K, const float* h, double r, float* y) {
+void matvec_t(const T* W, int N, int K, const float* h, float* y) {
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static) num_threads(g_threads) if (g_threads > 1 && (size_t)N * K > 262144)
 #endif
-    for (int n = 0; n < N; ++n) y[n] = (float)(r * dotd(W + (size_t)n * K, h, K));
+    for (int n = 0; n < N; ++n) y[n] = (float)dotd(W + (size_t)n * K, h, K);
 }
 
-void matvec(int dtype, const void* W, int N, int K, const float* h, double r, float* y) {
+void matvec(int dtype, const void* W, int N, int K, const float* h, float* y) {
     if (dtype == EO_BF16)
-        matvec_t((const uint16_t*)W, N, K, h, r, y);
+        matvec_t((const uint16_t*)W, N, K, h, y);
     else
-        matvec_t((const float*)W, N, K, h, r, y);
+        matvec_t((const float*)W, N, K, h, y);
 }
 
-// r = 1/sqrt(mean(x^2)+eps);  h[k] = x[k]*g[k].  rmsnorm(x;g) = r*h (the scale r is applied to the
-// matrix product, which is the same number up to the last rounding).
-double norm_input(const float* x, const float* g, int K, float eps, float* h) {
+// rmsnorm(x; g)[k] = g[k] * x[k] / sqrt(mean(x^2) + eps), formed in fp64 and rounded once to fp32
+void rmsnorm(const float* x, const float* g, int K, float eps, float* h) {
     double ss = 0;
     for (int k = 0; k < K; ++k) ss += (double)x[k] * (double)x[k];
-    for (int k = 0; k < K; ++k) h[k] = x[k] * g[k];
-    float r = (float)(1.0 / std::sqrt(ss / K + (double)eps));
-    return (double)r;
+    const double root = std::sqrt(ss / K + (double)eps);
+    for (int k = 0; k < K; ++k) h[k] = (float)((double)g[k] * (double)x[k] / root);
 }
 
 // RoPE, half-split pairing: (i, i+hd/2), angle pos * base^(-2i/hd), positions from 0.
@@ -190,10 +182,10 @@ void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) 
     std::vector<float> h(d > F ? d : F), q(d), a(d), gate(F), up(F), y(d);
     float* k = K + (size_t)pos * d;
     float* v = V + (size_t)pos * d;
-    double r = norm_input(x, m->g1[l], d, c.rms_eps, h.data());
-    matvec(dt, m->wq[l], d, d, h.data(), r, q.data());
-    matvec(dt, m->wk[l], d, d, h.data(), r, k);
-    matvec(dt, m->wv[l], d, d, h.data(), r, v);
+    rmsnorm(x, m->g1[l], d, c.rms_eps, h.data());
+    matvec(dt, m->wq[l], d, d, h.data(), q.data());
+    matvec(dt, m->wk[l], d, d, h.data(), k);
+    matvec(dt, m->wv[l], d, d, h.data(), v);
     rope(q.data(), c.n_heads, c.head_dim, pos, c.rope_base);
     rope(k, c.n_heads, c.head_dim, pos, c.rope_base);
     for (int i = 0; i < d; ++i) {  // the cache stores K and V in the model's storage type
@@ -201,13 +193,13 @@ void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) 
         v[i] = rnd(dt, v[i]);
     }
     attention_row(q.data(), K, V, pos + 1, c.n_heads, c.head_dim, a.data());
-    matvec(dt, m->wo[l], d, d, a.data(), 1.0, y.data());
+    matvec(dt, m->wo[l], d, d, a.data(), y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
-    r = norm_input(x, m->g2[l], d, c.rms_eps, h.data());
-    matvec(dt, m->wg[l], F, d, h.data(), r, gate.data());
-    matvec(dt, m->wu[l], F, d, h.data(), r, up.data());
+    rmsnorm(x, m->g2[l], d, c.rms_eps, h.data());
+    matvec(dt, m->wg[l], F, d, h.data(), gate.data());
+    matvec(dt, m->wu[l], F, d, h.data(), up.data());
     swiglu(gate.data(), up.data(), F, h.data());
-    matvec(dt, m->wd[l], d, F, h.data(), 1.0, y.data());
+    matvec(dt, m->wd[l], d, F, h.data(), y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
 }
 
@@ -221,19 +213,18 @@ void head_row(const eo_model* m, int head, const float* x, float* z, eo_diag* di
     std::vector<float> xe(x, x + d), h(d > F ? d : F);
     if (!fin && (c.exit_flags & EO_EXIT_MLP)) {
         std::vector<float> gate(F), up(F), y(d);
-        double rm = norm_input(xe.data(), m->gm[head], d, c.rms_eps, h.data());
-        matvec(dt, m->ewg[head], F, d, h.data(), rm, gate.data());
-        matvec(dt, m->ewu[head], F, d, h.data(), rm, up.data());
+        rmsnorm(xe.data(), m->gm[head], d, c.rms_eps, h.data());
+        matvec(dt, m->ewg[head], F, d, h.data(), gate.data());
+        matvec(dt, m->ewu[head], F, d, h.data(), up.data());
         swiglu(gate.data(), up.data(), F, h.data());
-        matvec(dt, m->ewd[head], d, F, h.data(), 1.0, y.data());
+        matvec(dt, m->ewd[head], d, F, h.data(), y.data());
         for (int i = 0; i < d; ++i) xe[i] += y[i];
     }
-    double r = 1.0;
     if (!fin && (c.exit_flags & EO_EXIT_NO_NORM))
         for (int i = 0; i < d; ++i) h[i] = xe[i];
     else
-        r = norm_input(xe.data(), fin ? m->gf : m->ge[head], d, c.rms_eps, h.data());
-    matvec(dt, W, c.vocab, d, h.data(), r, z);
+        rmsnorm(xe.data(), fin ? m->gf : m->ge[head], d, c.rms_eps, h.data());
+    matvec(dt, W, c.vocab, d, h.data(), z);
     if (diag) {
         softmax_max(z, c.vocab, diag);
         diag->layer = fin ? c.n_layers : c.exit_layers[head];
@@ -563,12 +554,11 @@ int eo_last_logits(const eo_state* s, float* z_out) {
 void eo_norm_matvec(int dtype, const void* W, int N, int K, const float* x, const float* g, float eps,
                     float* y) {
     std::vector<float> h(K);
-    double r = 1.0;
     if (g)
-        r = norm_input(x, g, K, eps, h.data());
+        rmsnorm(x, g, K, eps, h.data());
     else
         for (int k = 0; k < K; ++k) h[k] = x[k];
-    matvec(dtype, W, N, K, h.data(), r, y);
+    matvec(dtype, W, N, K, h.data(), y);
 }
 
 void eo_rope(float* vec, int n_heads, int head_dim, int pos, float base) {

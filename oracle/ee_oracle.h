@@ -18,7 +18,8 @@
  *     their KV is recomputed; a full-depth pass is forced when the list
  *     reaches max_pending.
  * Arithmetic: values are fp32; every reduction (dot product, mean square,
- * softmax sum) is accumulated in fp64 and rounded once to fp32.  With
+ * softmax sum) is one running fp64 sum in index order, rounded once to fp32;
+ * a normalised vector is formed in fp64 (gain * x / root) and rounded once.  With
  * dtype = EO_BF16 the stored tensors are bf16: the weight matrices and the
  * embedding (given as bf16 bit patterns) and the cached K (after RoPE) and V,
  * which are rounded to bf16 (nearest even) when written.  Nothing else is
@@ -128,7 +129,7 @@ int eo_last_logits(const eo_state*, float* z_out); /* logits of the last head ev
 
 /* ---- single operations, exported for pins and real-shape spot checks ---- */
 float eo_bf16_round(float v);
-/* y[n] = r * sum_k W[n][k] * (x[k]*g[k]),  r = 1/sqrt(mean(x^2)+eps); g == NULL: no norm (r = 1, g = 1) */
+/* y = W rmsnorm(x; g), rmsnorm(x; g)[k] = g[k] x[k] / sqrt(mean(x^2)+eps); g == NULL: no norm, y = W x */
 void eo_norm_matvec(int dtype, const void* W, int N, int K, const float* x, const float* g, float eps,
                     float* y);
 void eo_rope(float* vec, int n_heads, int head_dim, int pos, float base);

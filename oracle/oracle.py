@@ -40,7 +40,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # EE_ORACLE_LIB: another build of the same source (the sanitizer build of oracle/build.py)
+        path = os.environ.get("EE_ORACLE_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         vp, i32p, fp = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float)
         L.eo_model_create.restype = vp
