@@ -20,7 +20,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
@@ -224,9 +223,7 @@ def main():
     import torch
 
     import paper_2312_04916_amd as ee
-    from common import ee_config_of
-    from oracle.from_workload import to_numpy
-    from workload import CONFIGS, model_tensor, model_tensor_list, prompt_lengths, prompt_tokens
+    from workload import CONFIGS, model_tensor, model_tensor_list, prompt_lengths, prompt_tokens, to_numpy
 
     wl = CONFIGS[args.workload]
     shape = wl.shape
@@ -244,7 +241,7 @@ def main():
     n_prompt = lens[0] if B == 1 else f"{min(lens)}..{max(lens)}"
     max_pos = max(lens) + args.warmup + args.steps + 48
     t_setup = time.perf_counter()
-    gm = ee.Model(ee_config_of(shape, max_pos), max_rows=min(256, 16 * B + 48), max_seqs=B)
+    gm = ee.Model(ee.config_of_shape(shape, max_pos), max_rows=min(256, 16 * B + 48), max_seqs=B)
     keep_host = not args.no_cpu_baseline
     tensors_host = {}
     for kind, idx in model_tensor_list(shape):

@@ -79,6 +79,12 @@ typedef struct {
     int32_t max_positions;                      /* longest sequence (prompt + generated) */
     float rms_eps, rope_base;
     int32_t exit_flags;                         /* EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP; 0 = default */
+    /* Tuning, not part of the model (and not stored in weight files); 0 = default for both. */
+    int32_t prefill_rows;        /* rows per pass of the prompt-phase GEMM path: 0 = 2048, n > 0 = min(n, 8192) rounded to
+                                    128 (at least 128), n < 0 = path off (prompts then go through the decode kernels) */
+    int32_t gemm_min_workgroups; /* a decode GEMM over many rows gives a workgroup several 16-column tiles as long as
+                                    this many workgroups remain: 0 = 512; tests lower it so that small models reach
+                                    those kernel variants */
 } ee_config;
 
 enum { EE_EXIT_NO_NORM = 1, EE_TIE_EMBEDDINGS = 2, EE_EXIT_MLP = 4 };
@@ -144,10 +150,6 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
 
 int ee_model_free(ee_model* m);
 
-/* Test hook: the GEMMs of a step with many rows give a workgroup several 16-column tiles as long as at least
- * n workgroups remain (default 512); tests lower it so that small models reach those kernel variants.
- * Process-wide. */
-int ee_debug_set_gemm_min_workgroups(int n);
 /* Test hook, host only (no GPU is touched): the step plan that ee_decode_step and ee_kv_cache_flush apply to one
  * sequence (Section 4: the deferred tokens join the current token's pass; Appendix D.3: a full-depth pass is forced
  * once the list has reached the cap).  filled[n_segments] (host, in/out) are the sequence's fill watermarks:
@@ -192,25 +194,41 @@ int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_
  * each resumes from the residual row saved at the depth it reached and joins only the layers it still lacks.
  * on = 1: the paper's wording taken literally, the deferred tokens are fed again from the embedding, so
  * every layer of the step sees them and rewrites their (identical) shallow KV entries.  Results are the same;
- * the second does more work per step.  May be switched at any time. */
+ * the second does more work per step.  The mode can change only while no sequence of the cache has a deferred
+ * token (right after creation, a flush or a full-depth step of every sequence): a saved residual row means
+ * different things in the two modes.  EE_ERR_STATE otherwise; setting the mode it already has always succeeds. */
 int ee_kv_cache_set_refeed(ee_kv_cache* c, int on);
-/* The cache is paged: a pool of blocks of block_tokens positions (a multiple of 32), shared by up to
+/* KV cache with per-sequence lists of deferred tokens (Section 4, "KV recomputation"; Appendix D.3).
+ * The cache is paged: a pool of blocks of block_tokens positions (a multiple of 32), shared by up to
  * max_seqs sequences, max_tokens_total positions in all.  Besides K and V it holds, per sequence, the
  * residual rows of the deferred tokens (max_pending + 1 rows) so that a deferred token resumes above
  * the depth it reached instead of starting again from layer 1 -- the KV entries it produces are the
- * same.  max_pending in [0, 63]: the forced-full-depth limit (0: every step runs full depth). */
+ * same.
+ * max_pending is the cap on a sequence's list of deferred tokens (Appendix D.3: once the list has reached a
+ * pre-set length, a full pass is forced): a step that starts with max_pending deferred tokens runs to full depth
+ * with the exits switched off.  1..EE_MAX_ROWS-1; <= 0 means no cap: no step is ever forced, the store holds
+ * max_rows rows per sequence, and a step whose rows (deferred + current, over all its sequences) exceed the
+ * model's max_rows fails with EE_ERR_NOMEM before anything is changed -- ee_kv_cache_flush the sequences and
+ * call again.  The same EE_ERR_NOMEM applies with a cap when the batch's lists together outgrow max_rows. */
 int ee_kv_cache_bytes(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens,
                       int max_pending, size_t* bytes);
 int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens,
                        int max_pending, void* dev_pool, size_t pool_bytes, ee_kv_cache** out);
 int ee_kv_cache_reset(ee_kv_cache* c, int seq); /* frees the sequence's blocks, clears its pending list */
-/* Number of positions whose K,V are present in `layer` (0-based). */
+/* Number of positions whose K,V are present in `layer` (0-based).  After an early exit the layers above the exit
+ * lag behind the shallow ones (Section 4, "KV recomputation": the KV caches of the deep layers are missing for a
+ * token that left early); the difference is what later steps, or a flush, fill in. */
 int ee_kv_cache_filled(const ee_kv_cache* c, int seq, int layer, int32_t* n_positions);
+/* Length of the sequence's list of deferred tokens (Section 4: the most recent tokens whose deep KV is missing). */
 int ee_kv_cache_pending(const ee_kv_cache* c, int seq, int32_t* n_pending);
-/* Copies K and V of positions [pos0, pos0+n) of one layer to host arrays [n][d_model] fp32. */
+/* Copies K (after the rotary embedding) and V of positions [pos0, pos0+n) of one layer to host arrays
+ * [n][d_model] fp32: the check that, after generation and a flush, the cache equals that of a full-depth pass over
+ * the same tokens (Section 4: recomputation leaves no KV entry missing).  Blocks until the copy is done. */
 int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int pos0, int n, float* k_host,
                      float* v_host, void* stream);
-/* Runs every deferred token of the given sequences through its missing layers; emits nothing. */
+/* Runs every deferred token of the given sequences through its missing layers; emits nothing (Section 4,
+ * "KV recomputation": the deferred tokens go through a forward pass that fills their missing entries; here without
+ * a current token, e.g. at the end of generation or before a step that would not fit).  Blocks until done. */
 int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, void* stream);
 int ee_kv_cache_free(ee_kv_cache* c);
 /* Test hook: residual stream (fp32 [d_model]) of the sequence's newest processed position, at the
@@ -238,13 +256,16 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
  * Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
  * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
  * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
- * min(max_positions, EE_PREFILL_ROWS) rows, rounded up to 128 (environment variable read when the model is
- * sized and created; default 2048; 0 switches the path off), each projection one matrix-core GEMM. */
+ * min(max_positions, prefill_rows) rows, rounded up to 128 (ee_config::prefill_rows), each projection one
+ * matrix-core GEMM. */
 int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int n_tokens, float threshold,
                       int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf,
                       float* pos_nll, void* stream);
 
-/* One decode step for n_seqs sequences.
+/* One decode step for n_seqs sequences: early-exit inference with KV recomputation (Section 4, "KV
+ * recomputation": the current token's pass also carries the recent tokens whose deep KV is missing; Section 5.2:
+ * the confidence rule, tested at each exit in depth order; Appendix D.3: the list of deferred tokens and the forced
+ * full pass once it has reached max_pending).  Blocks until the step's tokens are known.
  *   seq_ids      [n_seqs]   distinct sequence ids
  *   row_offsets  [n_seqs+1] rows of sequence i are tokens[row_offsets[i] .. row_offsets[i+1])
  *   tokens       per sequence: the ids of its deferred tokens, oldest first, then the current token
@@ -254,7 +275,11 @@ int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* token
  *                it (EE_ERR_STATE on mismatch).
  *   threshold    exit iff confidence >= threshold and threshold < 1
  * Outputs, [n_seqs] each: next_token, exit_layer (an exit layer, or n_layers for a full or forced
- * step) and conf (confidence at the head that emitted). */
+ * step) and conf (confidence at the head that emitted).
+ * Errors leave every sequence as it was: EE_ERR_STATE (rows disagree with the lists), EE_ERR_RANGE (token id,
+ * position beyond max_positions), EE_ERR_NOMEM (no free cache block, or more rows than max_rows).  After an
+ * EE_ERR_HIP (a launch failed, or the step's results did not arrive within two minutes) the handles must not be
+ * used again. */
 int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
                    const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
                    int32_t* exit_layer, float* conf, void* stream);

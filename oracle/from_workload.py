@@ -1,20 +1,9 @@
 """Builds an oracle model from the seeded workload generator (test infrastructure only)."""
 from __future__ import annotations
 
-import numpy as np
-import torch
-
-from workload import ModelShape, TensorKind, model_tensor, model_tensor_list
+from workload import ModelShape, TensorKind, model_tensor, model_tensor_list, to_numpy  # noqa: F401
 
 from . import oracle as O
-
-
-def to_numpy(t: torch.Tensor) -> np.ndarray:
-    """float32 -> float32 array; bfloat16 -> uint16 array of the same bit patterns."""
-    t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
 
 
 def config_of(shape: ModelShape) -> O.EoConfig:

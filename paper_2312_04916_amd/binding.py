@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_debug_set_gemm_min_workgroups", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step"]
@@ -30,7 +30,8 @@ class ee_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("n_exits", C.c_int32),
                 ("exit_layers", C.c_int32 * EE_MAX_EXITS), ("dtype", C.c_int32), ("max_positions", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32),
+                ("prefill_rows", C.c_int32), ("gemm_min_workgroups", C.c_int32)]
 
 
 EE_EXIT_NO_NORM, EE_TIE_EMBEDDINGS, EE_EXIT_MLP = 1, 2, 4
@@ -68,7 +69,6 @@ def lib():
                                     C.POINTER(vp)]
         L.ee_model_free.argtypes = [vp]
         L.ee_debug_set_logits.argtypes = [vp, vp, C.c_int]
-        L.ee_debug_set_gemm_min_workgroups.argtypes = [C.c_int]
         L.ee_debug_plan.argtypes = [C.c_int, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
@@ -98,7 +98,7 @@ def _chk(code: int, where: str) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, dtype, max_positions,
-                rms_eps=1e-5, rope_base=10000.0, exit_flags=0) -> ee_config:
+                rms_eps=1e-5, rope_base=10000.0, exit_flags=0, prefill_rows=0, gemm_min_workgroups=0) -> ee_config:
     c = ee_config()
     c.n_layers, c.d_model, c.n_heads, c.head_dim, c.d_ff, c.vocab = n_layers, d_model, n_heads, head_dim, d_ff, vocab
     c.n_exits = len(exit_layers)
@@ -108,7 +108,16 @@ def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, 
     c.max_positions = max_positions
     c.rms_eps, c.rope_base = rms_eps, rope_base
     c.exit_flags = exit_flags
+    c.prefill_rows, c.gemm_min_workgroups = prefill_rows, gemm_min_workgroups
     return c
+
+
+def config_of_shape(shape, max_positions: int, prefill_rows: int = 0, gemm_min_workgroups: int = 0) -> ee_config:
+    """ee_config of an object with the model-shape fields (n_layers, d_model, n_heads, head_dim, d_ff, vocab,
+    exit_layers, dtype, rms_eps, rope_base, exit_flags), e.g. workload.ModelShape."""
+    return make_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
+                       shape.exit_layers, shape.dtype, max_positions, shape.rms_eps, shape.rope_base, shape.exit_flags,
+                       prefill_rows, gemm_min_workgroups)
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> C.c_void_p:
@@ -274,11 +283,6 @@ def plan(filled: Sequence[int], position: int, max_pending: int, refeed: bool = 
     return bool(forced.value), [(lo[i], hi[i]) for i in range(n)], [f[i] for i in range(n)]
 
 
-def set_gemm_min_workgroups(n: int) -> None:
-    """ee_debug_set_gemm_min_workgroups (test hook, process-wide)."""
-    _chk(lib().ee_debug_set_gemm_min_workgroups(int(n)), "ee_debug_set_gemm_min_workgroups")
-
-
 def prefill(model: Model, cache: KvCache, seq: int, tokens: Sequence[int], threshold: float, stream=None):
     """ee_prefill -> (next_token, exit_layer, conf[n_exits+1])."""
     t = _i32(tokens)
@@ -313,8 +317,9 @@ def decode_step(model: Model, cache: KvCache, seq_ids: Sequence[int], row_offset
     pm = np.ascontiguousarray(np.asarray(pending_mask, dtype=np.uint8))
     n = len(s)
     nt, ex, cf = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float32)
-    _chk(lib().ee_decode_step(model.h, cache.h, n, _ip(s), _ip(ro), _ip(tk), pm.ctypes.data_as(C.POINTER(C.c_uint8)),
-                              threshold, _ip(nt), _ip(ex), _fp(cf), _stream_ptr(stream)), "ee_decode_step")
+    fn = lib().ee_decode_step
+    _chk(fn(model.h, cache.h, n, _ip(s), _ip(ro), _ip(tk), pm.ctypes.data_as(C.POINTER(C.c_uint8)),
+            threshold, _ip(nt), _ip(ex), _fp(cf), _stream_ptr(stream)), "ee_decode_step")
     return nt, ex, cf
 
 

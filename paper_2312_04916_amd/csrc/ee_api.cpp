@@ -3,6 +3,7 @@
 // segment of layers at a time and reads the exit decision back before launching the next
 // (Section 4 "KV recomputation", Section 5.2 exit rule, Appendix D.3 forced full pass).
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -49,6 +50,7 @@ int check_config(const ee_config& c) {
     if (c.max_positions < 1 || c.max_positions > (1 << 20)) return EE_ERR_CONFIG;
     if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return EE_ERR_CONFIG;
     if (c.exit_flags & ~(EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP)) return EE_ERR_CONFIG;
+    if (c.gemm_min_workgroups < 0) return EE_ERR_CONFIG;
     return EE_OK;
 }
 
@@ -105,17 +107,12 @@ struct WorkspaceLayout {
 };
 
 // Rows per pass of the prompt-phase GEMM path; 0 when the model does not qualify (fp32, or widths the
-// 256-column tiles do not divide evenly into the q|k|v parts).  EE_PREFILL_ROWS caps it (default 2048).
+// 256-column tiles do not divide evenly into the q|k|v parts).  ee_config::prefill_rows caps it (default 2048).
 constexpr int PF_MIN_TOKENS = 32;  // shorter prompts go through the decode kernels
 
 int pf_rows_of(const ee_config& c) {
-    if (c.dtype != EE_BF16 || c.d_model % 128) return 0;
-    int cap = 2048;
-    if (const char* e = std::getenv("EE_PREFILL_ROWS")) {
-        int v = std::atoi(e);
-        if (v <= 0) return 0;
-        cap = std::max(128, std::min(v, 8192));
-    }
+    if (c.dtype != EE_BF16 || c.d_model % 128 || c.prefill_rows < 0) return 0;
+    const int cap = c.prefill_rows == 0 ? 2048 : std::max(128, std::min(c.prefill_rows, 8192));
     int r = std::min((c.max_positions + 127) / 128 * 128, cap);
     return r / 128 * 128;
 }
@@ -189,6 +186,7 @@ struct ee_model {
     HeadResult* results_dev; // device view of the same memory
     int32_t* pf_host_tokens; // pinned staging of one prompt pass's token ids
     int head_tag = 0;        // tag of the latest head evaluation (see HeadResult::pad)
+    int head_wait_limit_s = 120;  // wall-clock bound of one wait for head results
     float* dbg_logits;
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
@@ -284,8 +282,12 @@ namespace {
 
 // rows of the residual store: one per position a sequence may have deferred plus its current one, the transient rows
 // of a prompt chunk, and the copies that exits with an MLP work on
+// Residual rows kept per sequence: its deferred tokens and the current one.  Without a cap (max_pending <= 0) the
+// list is bounded by what one step can carry: max_rows rows.
+int slots_per_seq(const ee_model* m, int max_pending) { return max_pending > 0 ? max_pending + 1 : m->max_rows; }
+
 size_t store_slots(const ee_model* m, int max_seqs, int max_pending) {
-    return (size_t)max_seqs * (max_pending + 1) + m->max_rows + (m->exit_mlp() ? m->max_seqs : 0);
+    return (size_t)max_seqs * slots_per_seq(m, max_pending) + m->max_rows + (m->exit_mlp() ? m->max_seqs : 0);
 }
 
 size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending, int* n_blocks,
@@ -313,7 +315,7 @@ size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total,
 int check_cache_args(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending) {
     if (!m) return EE_ERR_ARG;
     if (max_seqs < 1 || max_seqs > 4096 || max_tokens_total < 1 || BT < 32 || BT % 32 || BT > 1024) return EE_ERR_CONFIG;
-    if (max_pending < 0 || max_pending > 63) return EE_ERR_CONFIG;
+    if (max_pending > EE_MAX_ROWS - 1) return EE_ERR_CONFIG;
     return EE_OK;
 }
 
@@ -385,6 +387,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         GemmCommon g{};
         g.dtype = dt;
         g.T = T;
+        g.min_wgs = cf.gemm_min_workgroups;
         g.desc = dd;
         g.desc_host = m->host_desc(di);
         g.inv_d = 1.0f / (float)d;
@@ -471,6 +474,7 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     SegDesc* dd = m->dev_desc(di);
     GemmCommon g{};
     g.dtype = dt;
+    g.min_wgs = cf.gemm_min_workgroups;
     g.inv_d = 1.0f / (float)d;
     g.eps = cf.rms_eps;
     g.ssq_stride = c->ssq_stride;
@@ -531,6 +535,7 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
 // every so often, so that a failed launch (or a drained stream) ends the wait.
 int wait_head_results(ee_model* m, const SegDesc* hd, hipStream_t st) {
     const int tag = m->head_tag;
+    const auto t0 = std::chrono::steady_clock::now();
     for (unsigned spins = 1;; ++spins) {
         bool all = true;
         for (int i = 0; i < hd->n_head && all; ++i)
@@ -543,6 +548,11 @@ int wait_head_results(ee_model* m, const SegDesc* hd, hipStream_t st) {
                 return EE_OK;
             }
             if (q != hipErrorNotReady) HIPCHK(q);
+            // A step takes milliseconds; a stream that is still busy after this long will not finish.
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(m->head_wait_limit_s)) {
+                g_last_hip = (int)hipErrorNotReady;
+                return EE_ERR_HIP;
+            }
         }
 #if defined(__x86_64__)
         __builtin_ia32_pause();
@@ -1018,7 +1028,7 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
     // "EEWT0001": the config without exit_flags (the default exit structure); "EEWT0002": with it
     const bool v2 = ok && std::memcmp(magic, "EEWT0002", 8) == 0;
     ok = ok && (v2 || std::memcmp(magic, "EEWT0001", 8) == 0);
-    ok = ok && std::fread(&fc, v2 ? sizeof fc : offsetof(ee_config, exit_flags), 1, f) == 1;
+    ok = ok && std::fread(&fc, v2 ? offsetof(ee_config, prefill_rows) : offsetof(ee_config, exit_flags), 1, f) == 1;
     if (!ok || fc.exit_flags != cfg->exit_flags) {
         std::fclose(f);
         return EE_ERR_IO;
@@ -1161,14 +1171,9 @@ int ee_model_free(ee_model* m) {
     return EE_OK;
 }
 
-int ee_debug_set_gemm_min_workgroups(int n) {
-    set_gemm_min_wgs(n);
-    return EE_OK;
-}
-
 int ee_debug_plan(int n_segments, int32_t* filled, int position, int max_pending, int refeed, int reached, int32_t* forced,
                   int32_t* row_lo, int32_t* row_hi) {
-    if (n_segments < 1 || n_segments > EE_MAX_EXITS + 1 || !filled || max_pending < 0 || reached >= n_segments) return EE_ERR_ARG;
+    if (n_segments < 1 || n_segments > EE_MAX_EXITS + 1 || !filled || reached >= n_segments) return EE_ERR_ARG;
     for (int k = 0; k < n_segments; ++k)
         if (filled[k] < 0 || (k && filled[k] > filled[k - 1])) return EE_ERR_STATE;
     if (forced) *forced = plan::forced(filled, n_segments, max_pending) ? 1 : 0;
@@ -1213,8 +1218,8 @@ int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total
     c->m = m;
     c->max_seqs = max_seqs;
     c->BT = block_tokens;
-    c->S = max_pending + 1;
-    c->max_pending = max_pending;
+    c->S = slots_per_seq(m, max_pending);
+    c->max_pending = max_pending > 0 ? max_pending : 0;
     c->pool = (char*)dev_pool;
     c->ssq_stride = cf.d_model / (16 * gemm_resid_tiles_per_wg());
     c->xs_lo = cf.dtype == EE_BF16 ? store_slots(m, max_seqs, max_pending) * cf.d_model : 0;
@@ -1237,7 +1242,14 @@ int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total
 
 int ee_kv_cache_set_refeed(ee_kv_cache* c, int on) {
     if (!c) return EE_ERR_ARG;
-    c->refeed = on ? 1 : 0;
+    const int want = on ? 1 : 0;
+    if (want == c->refeed) return EE_OK;
+    // While a token is deferred its saved residual row means different things in the two modes (re-feeding rewrites
+    // the row at whatever depth the step reached, resuming relies on it standing at the depth the watermarks say):
+    // the mode may only change while no list holds a token.
+    for (const SeqState& s : c->seqs)
+        if (c->n_pending(s) > 0) return EE_ERR_STATE;
+    c->refeed = want;
     return EE_OK;
 }
 
@@ -1437,6 +1449,8 @@ int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_i
     std::vector<StepSeq> ss;
     size_t blocks_needed = 0;
     // pass 1: validate everything before touching any state
+    // (the deepest segment of the step carries every row the caller lists: they must fit one launch)
+    if (row_offsets[0] != 0 || row_offsets[n_seqs] > m->max_rows) return row_offsets[0] != 0 ? EE_ERR_ARG : EE_ERR_NOMEM;
     for (int b = 0; b < n_seqs; ++b) {
         int sid = seq_ids[b];
         if (sid < 0 || sid >= c->max_seqs) return EE_ERR_RANGE;

@@ -85,6 +85,7 @@ struct GemmCommon {
     int ssq_stride, ssq_n;
     float inv_d, eps;
     int T;  // rows
+    int min_wgs;  // workgroups a launch keeps when it gives a workgroup several column tiles (0: 512)
     const SegDesc* desc;
     const SegDesc* desc_host;  // host copy of *desc, or NULL: launches of up to 16 rows then carry the row indices by value
     // O projection only: A still lies as the attention kernel's split partials (att_ns splits), to be merged
@@ -144,7 +145,6 @@ hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, 
 hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
                                 size_t lo_off, float* dssq, int ssq_stride, hipStream_t s);
 
-void set_gemm_min_wgs(int n);  // workgroups a GEMM launch keeps when it gives a workgroup several column tiles
 int gemm_resid_tiles_per_wg();  // G of the residual epilogue: ssq partials per row = d / (16*G)
 size_t attention_part_floats(int max_rows, int H, int hd);  // scratch the attention kernel needs
 

@@ -1110,11 +1110,10 @@ static size_t a_lds_bytes(const GemmCommon& c) {
 
 // Column tiles per workgroup for the register path: as many (4 for one row tile, else 2) as still leave
 // gemm_min_wgs() workgroups, so that the rows' operands are re-read from L2 by fewer workgroups without
-// starving the chip of weight streams.  (512 unless a test lowers it to reach these variants on small models.)
-static int g_min_wgs = 512;
-void set_gemm_min_wgs(int n) { g_min_wgs = n < 1 ? 1 : n; }
-static int gemm_min_wgs() { return g_min_wgs; }
-static int g_of(int mt, int n_tiles) {
+// starving the chip of weight streams.  (GemmCommon::min_wgs: 512 unless the model's configuration lowers it, which
+// tests do to reach these variants on small models.)
+static int g_of(int mt, int n_tiles, int min_wgs) {
+    auto gemm_min_wgs = [min_wgs]() { return min_wgs >= 1 ? min_wgs : 512; };
     if (mt == 1 && n_tiles / 4 >= gemm_min_wgs()) return 4;
     // Up to two row tiles: at these register counts one workgroup of 8 waves is resident per CU, so a launch runs in
     // rounds of 256 workgroups.  Give a workgroup as many tiles as there would be rounds (2..6): one round, the same
@@ -1157,7 +1156,7 @@ static hipError_t lds_limit_once() {
         int _ks = ks_of(c);                                                                                        \
         const int _mt = mt_of(c.T), _nt = c.N / 16;                                                                \
         const size_t _sm = a_lds_bytes(c);                                                                         \
-        int _g = _sm ? 1 : g_of(_mt, _nt);                                                                         \
+        int _g = _sm ? 1 : g_of(_mt, _nt, c.min_wgs);                                                                        \
         /* 1024 threads leave 128 registers per lane: 3..6 tiles need the 8-wave variants (each wave then */       \
         /* streams K/8, still >= 8 k-tiles here); otherwise 16 waves stay at two tiles */                          \
         if (_ks == 16 && _g >= 3) { if (_g <= 6 && _mt <= 2) _ks = 8; else _g = 2; }                               \

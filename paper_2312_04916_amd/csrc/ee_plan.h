@@ -12,8 +12,11 @@ namespace plan {
 
 inline int pending(const int32_t* filled, int n_seg) { return filled[0] - filled[n_seg - 1]; }
 
-// A step starts at full depth with the exits switched off once the deferred list has reached the cap.
-inline bool forced(const int32_t* filled, int n_seg, int max_pending) { return pending(filled, n_seg) >= max_pending; }
+// A step starts at full depth with the exits switched off once the deferred list has reached the cap
+// (max_pending <= 0: there is no cap and no step is ever forced).
+inline bool forced(const int32_t* filled, int n_seg, int max_pending) {
+    return max_pending > 0 && pending(filled, n_seg) >= max_pending;
+}
 
 // Positions that pass through segment `seg` in a step whose current token sits at position p (p < 0: a flush,
 // which has no current token): [lo, hi] inclusive.  Resumed rows enter where their KV is missing; re-fed rows

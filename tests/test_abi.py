@@ -116,7 +116,7 @@ def _oracle_run(tau, cap, n_new=40):
         pos += 1
 
 
-@pytest.mark.parametrize("tau,cap", [(0.0, 3), (0.0, 15), (0.2, 6), (0.35, 40), (0.5, 2), (1.0, 5)])
+@pytest.mark.parametrize("tau,cap", [(0.0, 3), (0.0, 15), (0.2, 6), (0.35, 40), (0.5, 2), (1.0, 5), (0.0, 0), (0.2, -1)])
 def test_step_plan_follows_the_oracle_state(tau, cap):
     """The library's host-side plan (forced full pass at the cap, rows per segment, watermark updates) against the
     oracle's state step by step: rows of segment s must be exactly the positions whose KV the oracle lacks there."""
@@ -127,7 +127,7 @@ def test_step_plan_follows_the_oracle_state(tau, cap):
             filled = list(before)
         assert filled == before
         g_forced, rows, _ = ee.plan(filled, pos, cap)
-        assert g_forced == forced == (pend >= cap)
+        assert g_forced == forced == (cap > 0 and pend >= cap)   # a cap <= 0 means none: no step is ever forced
         n_forced += int(forced)
         for s, (lo, hi) in enumerate(rows):
             assert (lo, hi) == (before[s], pos)                  # resume: from where segment s lacks KV up to the current token
@@ -137,7 +137,7 @@ def test_step_plan_follows_the_oracle_state(tau, cap):
         _, _, filled = ee.plan(filled, pos, cap, reached=reached)
         assert filled == after
     if tau == 0.0:
-        assert n_forced > 0
+        assert (n_forced > 0) == (cap > 0)
     # a flush leaves nothing pending
     _, rows, flushed = ee.plan(filled, -1, cap, reached=len(filled) - 1)
     assert all(hi == filled[0] - 1 for _, hi in rows) and flushed == [filled[0]] * len(filled)

@@ -1,7 +1,7 @@
 """GPU parity of the exit structures of Section 2 ("Model architectures": exits without a normalisation, tied
 input/output embeddings, an MLP in front of the exit's output embedding), through the C ABI, against the CPU
 oracle: generation in lockstep (tokens and exit layers exact outside the guard band, hidden states, head logits
-and confidences within 1e-4 for fp32 and 2e-2 for bf16), batches against each sequence alone, the weight file,
+and confidences within 1e-4 for fp32 and 2e-3 for bf16), batches against each sequence alone, the weight file,
 and the prompt-phase GEMM path with the heads scored on every position."""
 import dataclasses
 import os
@@ -14,12 +14,11 @@ import paper_2312_04916_amd as ee
 from oracle.from_workload import build_model
 from workload import ModelShape, TensorKind, model_tensor, prompt_tokens, write_weight_file
 
-from common import GUARD, ee_config_of, load_gpu_model, lockstep, rel_err
+from common import GUARD, TOL, TOL_CONF, ee_config_of, kv_check, load_gpu_model, lockstep, rel_err
 
 pytestmark = pytest.mark.gpu
 
 BASE = ModelShape(4, 128, 4, 32, 352, 1024, (1, 2), "f32", 0.02, 0.3)
-TOL = {"f32": 1e-4, "bf16": 2e-2}
 VARIANTS = {
     "no_norm": dict(exit_norm=False),
     "tied": dict(tie_embeddings=True, head_sigma=0.5),
@@ -48,7 +47,7 @@ def test_lockstep_generation_with_other_exit_structures(name, dtype):
         assert not rep.mismatches, rep.mismatches[:5]
         assert rep.max_hidden_err <= TOL[dtype], rep.max_hidden_err
         assert rep.max_logit_err <= TOL[dtype], rep.max_logit_err
-        assert rep.max_conf_err <= TOL[dtype], rep.max_conf_err
+        assert rep.max_conf_err <= TOL_CONF[dtype], rep.max_conf_err
         exits_seen.update(rep.exit_layers)
         if tau == 0.0:
             assert rep.forced_full > 0  # the cap of 6 forces full-depth steps: the deferred rows pass the exits untouched
@@ -58,7 +57,7 @@ def test_lockstep_generation_with_other_exit_structures(name, dtype):
         _, ko, vo = om.forward_sequence(seq)
         for l in range(shape.n_layers):
             k, v = cache.read(0, l, 0, len(seq))
-            assert rel_err(k, ko[l]) <= TOL[dtype] and rel_err(v, vo[l]) <= TOL[dtype], (l, tau)
+            kv_check(k, ko[l], dtype, "K", l), kv_check(v, vo[l], dtype, "V", l)
         cache.close()
     assert len(exits_seen) >= 2, exits_seen
     gm.close()
@@ -151,14 +150,14 @@ def test_scored_prompt_phase_with_other_exit_structures(name):
     tok, ex, conf, ptok, pconf = ee.prefill_scored(gm, cache, 0, p, 0.3)
     for l in range(shape.n_layers):
         k, v = cache.read(0, l, 0, n)
-        assert rel_err(k, ko[l]) <= 2e-2 and rel_err(v, vo[l]) <= 2e-2
+        kv_check(k, ko[l], "bf16", "K", l), kv_check(v, vo[l], "bf16", "V", l)
     heads = list(shape.exit_layers) + [shape.n_layers]
     for hi, layer in enumerate(heads):
         for pos in range(n):
             _, dg = om.head_row(hi, hid[layer][pos])
             if int(ptok[hi, pos]) != dg["argmax"]:
                 assert dg["top1"] - dg["top2"] < GUARD and int(ptok[hi, pos]) == dg["arg2"], (hi, pos)
-            assert abs(float(pconf[hi, pos]) - dg["conf"]) <= 2e-2, (hi, pos, float(pconf[hi, pos]), dg["conf"])
+            assert abs(float(pconf[hi, pos]) - dg["conf"]) <= TOL_CONF["bf16"], (hi, pos, float(pconf[hi, pos]), dg["conf"])
     cache.close()
     gm.close()
 
@@ -176,7 +175,7 @@ def test_plain_prompt_phase_runs_the_exit_mlps_on_the_last_position():
     hid, _, _ = om.forward_sequence(p)
     for hi, layer in enumerate(list(shape.exit_layers) + [shape.n_layers]):
         _, dg = om.head_row(hi, hid[layer][-1])
-        assert abs(float(conf[hi]) - dg["conf"]) <= 2e-2, (hi, float(conf[hi]), dg["conf"])
-    assert rel_err(cache.read_hidden(0), hid[shape.n_layers][-1]) <= 2e-2
+        assert abs(float(conf[hi]) - dg["conf"]) <= TOL_CONF["bf16"], (hi, float(conf[hi]), dg["conf"])
+    assert rel_err(cache.read_hidden(0), hid[shape.n_layers][-1]) <= TOL["bf16"]
     cache.close()
     gm.close()

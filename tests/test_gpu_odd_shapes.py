@@ -1,7 +1,7 @@
 """GPU parity on shapes off the beaten track, through the C ABI, against the CPU oracle: widths that are not a
 power of two (three heads), feed-forward and vocabulary sizes that leave ragged tile groups, a model without
 exits, a model with an exit after every layer, a single head of 128.  Generation in lockstep (tokens and exit
-layers exact outside the guard band; hidden states, logits and confidences within 1e-4 for fp32 and 2e-2 for
+layers exact outside the guard band; hidden states, logits and confidences within 1e-4 for fp32 and 2e-3 for
 bf16), then the flushed cache against a full-depth forward of the whole sequence (Section 5.2: KV recomputation
 leaves the cache a full-depth pass would have written)."""
 import numpy as np
@@ -11,11 +11,10 @@ import paper_2312_04916_amd as ee
 from oracle.from_workload import build_model
 from workload import ModelShape, prompt_tokens
 
-from common import load_gpu_model, lockstep, rel_err
+from common import TOL, TOL_CONF, kv_check, load_gpu_model, lockstep, rel_err
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
 SHAPES = {
     # 3 heads of 32: d = 96 (3 k-tiles), 5 tiles of gate and up, 34 vocabulary tiles
     "d96": ModelShape(3, 96, 3, 32, 160, 544, (1,), "f32", 0.02, 0.35),
@@ -48,14 +47,14 @@ def test_lockstep_generation_on_odd_shapes(name, dtype):
         assert not rep.mismatches, rep.mismatches[:5]
         assert rep.max_hidden_err <= TOL[dtype], rep.max_hidden_err
         assert rep.max_logit_err <= TOL[dtype], rep.max_logit_err
-        assert rep.max_conf_err <= TOL[dtype], rep.max_conf_err
+        assert rep.max_conf_err <= TOL_CONF[dtype], rep.max_conf_err
         exits_seen.update(rep.exit_layers)
         cache.flush([0])
         seq = np.concatenate([prompt, np.array(rep.tokens[:-1], np.int32)])
         _, ko, vo = om.forward_sequence(seq)
         for l in range(shape.n_layers):
             k, v = cache.read(0, l, 0, len(seq))
-            assert rel_err(k, ko[l]) <= TOL[dtype] and rel_err(v, vo[l]) <= TOL[dtype], (l, tau)
+            kv_check(k, ko[l], dtype, "K", l), kv_check(v, vo[l], dtype, "V", l)
         cache.close()
     if shape.exit_layers:
         assert len(exits_seen) >= 2, exits_seen

@@ -13,5 +13,6 @@ from .gen import (  # noqa: F401
     model_tensor_list,
     prompt_tokens,
     prompt_lengths,
+    to_numpy,
     write_weight_file,
 )

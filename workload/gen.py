@@ -94,6 +94,16 @@ def gaussian_tensor(seed: int, tid: int, numel: int, sigma: float, mean: float =
     return out
 
 
+def to_numpy(t: torch.Tensor):
+    """float32 -> float32 array; bfloat16 -> uint16 array of the same bit patterns (numpy has no bfloat16)."""
+    import numpy as np
+
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
 def uniform_ints(seed: int, tid: int, numel: int, lo: int, hi: int, device="cpu") -> torch.Tensor:
     """int64[numel], uniform in [lo, hi) (modulo bias < 2^-40, irrelevant here)."""
     base = _stream_base(seed, tid)
