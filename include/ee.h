@@ -284,6 +284,24 @@ int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_i
                    const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
                    int32_t* exit_layer, float* conf, void* stream);
 
+/* ee_decode_step for callers that cannot provide (or allocate) a workspace at the time of the call: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same results bit for bit;
+ * the step's workspace (descriptors, activations, attention and head partials) is not the buffer the model was
+ * created over but an array of EE_STATIC_WORKSPACE_BYTES that the library keeps in each GPU's memory for the life of
+ * the process.  The call allocates nothing, on the device or through any library.
+ *   - EE_ERR_NOMEM, before anything is touched, if the model's decode workspace (the part of workspace_bytes in
+ *     front of the prompt-phase buffers; it grows with max_rows, max_seqs, d_ff and vocab) is larger than that: the
+ *     7B shape with max_rows <= 64 fits (28 MB), max_rows 256 (100 MB) does not.
+ *   - EE_ERR_ARG if the current device is not the one that holds the model.
+ *   - All calls on one GPU share the one array, whatever the model or the stream: two calls that overlap in time on
+ *     the same GPU race.  The array keeps the last call's contents; a step reads nothing of it that the same step
+ *     has not written first.
+ * The prompt phase (ee_prefill) and ee_kv_cache_flush still use the model's own workspace. */
+#define EE_STATIC_WORKSPACE_BYTES (32u << 20)
+int ee_decode_step_static(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
+                          const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
+                          int32_t* exit_layer, float* conf, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_creat
            "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
-           "ee_decode_step"]
+           "ee_decode_step", "ee_decode_step_static"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libee.so")
@@ -88,6 +88,7 @@ def lib():
         L.ee_prefill_scored.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, i32p, fp, fp, vp]
         L.ee_decode_step.argtypes = [vp, vp, C.c_int, i32p, i32p, i32p, C.POINTER(C.c_uint8), C.c_float, i32p, i32p,
                                      fp, vp]
+        L.ee_decode_step_static.argtypes = L.ee_decode_step.argtypes
         _lib = L
     return _lib
 
@@ -311,13 +312,13 @@ def prefill_scored(model: Model, cache: KvCache, seq: int, tokens: Sequence[int]
 
 
 def decode_step(model: Model, cache: KvCache, seq_ids: Sequence[int], row_offsets: Sequence[int], tokens: Sequence[int],
-                pending_mask: Sequence[int], threshold: float, stream=None):
-    """ee_decode_step -> (next_token[n], exit_layer[n], conf[n])."""
+                pending_mask: Sequence[int], threshold: float, stream=None, static_workspace: bool = False):
+    """ee_decode_step (or ee_decode_step_static) -> (next_token[n], exit_layer[n], conf[n])."""
     s, ro, tk = _i32(seq_ids), _i32(row_offsets), _i32(tokens)
     pm = np.ascontiguousarray(np.asarray(pending_mask, dtype=np.uint8))
     n = len(s)
     nt, ex, cf = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float32)
-    fn = lib().ee_decode_step
+    fn = lib().ee_decode_step_static if static_workspace else lib().ee_decode_step
     _chk(fn(model.h, cache.h, n, _ip(s), _ip(ro), _ip(tk), pm.ctypes.data_as(C.POINTER(C.c_uint8)),
             threshold, _ip(nt), _ip(ex), _fp(cf), _stream_ptr(stream)), "ee_decode_step")
     return nt, ex, cf

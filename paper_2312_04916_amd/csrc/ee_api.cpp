@@ -1438,6 +1438,59 @@ int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, in
 
 /* ------------------------------------------------------------------ decode */
 
+}  // extern "C" (the static workspace below has internal linkage)
+
+namespace {
+
+// Step workspace of ee_decode_step_static: one array per GPU, in that GPU's memory from the moment the library's code
+// is loaded there until the process ends.  In host code `static_step_ws` only names the symbol; its device address
+// is looked up once per device (static_ws_of) and every use goes through that pointer.
+static __device__ __align__(256) unsigned char static_step_ws[EE_STATIC_WORKSPACE_BYTES];
+
+constexpr int STATIC_WS_MAX_DEVICES = 64;
+char* g_static_ws[STATIC_WS_MAX_DEVICES];  // device address of static_step_ws on device i, or null: not looked up yet
+
+int static_ws_of(char** out) {
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_WS_MAX_DEVICES) return EE_ERR_ARG;
+    char* p = __atomic_load_n(&g_static_ws[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        HIPCHK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(static_step_ws)));
+        if (!p || ((uintptr_t)p & 255)) return EE_ERR_HIP;
+        __atomic_store_n(&g_static_ws[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return EE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ee_decode_step_static(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
+                          const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
+                          int32_t* exit_layer, float* conf, void* stream) {
+    if (!m) return EE_ERR_ARG;
+    // Everything a decode step keeps in the workspace lies in front of the prompt-phase buffers, and every byte of it
+    // that a step reads has been written earlier in the same step (descriptors, block tables and token ids by the
+    // upload, activations and partial results by the kernels): nothing has to be cleared between calls.
+    if (m->wsl.pf_begin > (size_t)EE_STATIC_WORKSPACE_BYTES) return EE_ERR_NOMEM;
+    hipPointerAttribute_t attr;
+    HIPCHK(hipPointerGetAttributes(&attr, m->wbase));
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (attr.device != dev) return EE_ERR_ARG;  // the array used is the current device's: it must be the model's
+    char* ws = nullptr;
+    EECHK(static_ws_of(&ws));
+    char* const own = m->ws;
+    m->ws = ws;
+    const int rc = ee_decode_step(m, c, n_seqs, seq_ids, row_offsets, tokens, pending_mask, threshold, next_token, exit_layer,
+                                  conf, stream);
+    m->ws = own;
+    return rc;
+}
+
 int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, const int32_t* row_offsets,
                    const int32_t* tokens, const uint8_t* pending_mask, float threshold, int32_t* next_token,
                    int32_t* exit_layer, float* conf, void* stream) {
