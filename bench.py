@@ -49,14 +49,18 @@ def parse():
     return ap.parse_args()
 
 
-def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending, profile_kernel=None, profile_every=1):
+def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending, profile_kernel=None, profile_every=1,
+             pipeline=False, confidences=False):
     """Prefill every sequence, then (warmup + steps) decode steps over the whole batch; returns the timing of
     the last `steps` and the algorithmic-bytes model of exactly those steps.
 
     Bytes of one step (what the method itself must move): the weights of every layer some sequence runs, once;
     the heads that are evaluated (an exit head if some sequence tests it, the final head if some sequence
     reaches it), once each; per sequence K and V of its context in every layer it runs, K and V of its active
-    rows written, one embedding row."""
+    rows written, one embedding row.  pipeline: the cache is in pipeline mode (nothing is deferred; the timed region
+    ends when the fill stream has caught up).  confidences: also collect every evaluated head's confidence per step
+    (one small host call per step, so not in the passes whose time is reported as the headline)."""
+    import numpy as np
     import torch
 
     B = len(prompts)
@@ -66,7 +70,8 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
     w_exit = w_head + (3 * d * F * es if shape.exit_mlp else 0)  # an exit with an MLP also streams that MLP
     seg_ends = list(shape.exit_layers) + [L]
     seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(L)]
-    seqs = ee.Sequences(L)
+    seqs = ee.Sequences(L, pipeline=pipeline)
+    confs = []
     fl = []  # host mirror of the fill watermarks, for the bytes model only
     for sq in ids:
         cache.reset(sq)
@@ -88,6 +93,8 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
         nt, exl, _ = ee.decode_step(gm, cache, ids, ro, tk, pm, tau)
         seqs.update(ids, nt, exl)
         log.append((ro, exl))
+        if confidences and i >= warmup:
+            confs.append(gm.step_confidences(B))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if profile_kernel is not None:
@@ -112,7 +119,18 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
                     fl[sq][k] = p + 1
         if i >= warmup:
             nbytes += deepest * w_layer + sum(w_head if h == L else w_exit for h in heads)
-    return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof, tokens=B * steps)
+    quant = None
+    if confs:
+        cf = np.stack(confs)  # [steps][B][n_exits+1]
+        quant = {}
+        for k, layer in enumerate(seg_ends):
+            v = cf[:, :, k].ravel()
+            v = v[v >= 0]
+            if v.size:
+                quant[str(layer)] = {"evaluated": int(v.size), "frac_ge_threshold": float(np.mean(v >= tau)),
+                                     **{f"q{int(q * 100)}": float(np.quantile(v, q)) for q in (0.1, 0.5, 0.9, 0.99)},
+                                     "max": float(v.max())}
+    return dict(seconds=dt, exits=exits, bytes=nbytes, forced=forced, prof=prof, tokens=B * steps, confidences=quant)
 
 
 PROFILE_EVERY = 8  # launches of the roofline kernel per timed one in the throughput pass
@@ -312,6 +330,37 @@ def main():
                                "bytes_model_speedup": full["bytes"] / r["bytes"], "forced_full_steps": r["forced"],
                                "exit_histogram": {str(e): r["exits"].count(e) for e in sorted(set(r["exits"]))}}
 
+    # confidence distribution at each head over the same steps as the headline (an untimed extra pass: one host call
+    # per step), so that the reader sees what the exit mix is made of
+    conf_quant = None
+    if not args.no_sweep:
+        conf_quant = generate(ee, gm, cache, prompts, args.threshold, args.warmup, args.steps, shape, es, args.max_pending,
+                              confidences=True)["confidences"]
+    # the smallest threshold tried at which early exit is measured faster than full depth
+    first_win = None
+    tried = sorted([(float(t), v["speedup_vs_full_depth"], v["bytes_model_speedup"]) for t, v in sweep.items()]
+                   + [(args.threshold, tps / tps_full, ideal_speedup)])
+    wins = [t for t in tried if t[1] > 1.0]
+    if wins:
+        t = max(wins, key=lambda x: x[0])
+        first_win = {"largest_threshold_with_speedup_above_1": t[0], "speedup_vs_full_depth": t[1], "bytes_model_speedup": t[2]}
+
+    # pipeline-based early exit on one GPU (second stream fills the KV of exited tokens) against KV recomputation,
+    # same thresholds (the comparison of the paper's Appendix B.1, there across 4 pipeline stages)
+    pipe_cmp = {}
+    if not args.no_sweep and not args.refeed and args.max_pending >= 5:
+        for tau in [t for t in (0.2, 0.4) if t in wl.thresholds]:
+            cache.flush(list(range(B)))
+            cache.set_pipeline(True)
+            r = generate(ee, gm, cache, prompts, tau, args.warmup, args.steps, shape, es, args.max_pending, pipeline=True)
+            cache.flush(list(range(B)))
+            cache.set_pipeline(False)
+            rec = sweep.get(str(tau))
+            pipe_cmp[str(tau)] = {"pipeline_tokens_per_s": r["tokens"] / r["seconds"],
+                                  "pipeline_speedup_vs_full_depth": full["seconds"] / r["seconds"],
+                                  "kv_recomputation_tokens_per_s": rec["tokens_per_s"] if rec else None,
+                                  "exit_histogram": {str(e): r["exits"].count(e) for e in sorted(set(r["exits"]))}}
+
     # cap on the deferred-token list (Appendix D.3) x how the deferred tokens are carried (resume / re-feed), at the
     # workload's lowest threshold: where carrying more rows stops being free
     pending_sweep = {}
@@ -350,6 +399,7 @@ def main():
         "full_depth_tokens_per_s": tps_full, "full_depth_ms_per_step": full["seconds"] / args.steps * 1e3,
         "speedup_vs_full_depth": tps / tps_full, "bytes_model_speedup": ideal_speedup,
         "exit_histogram": hist, "forced_full_steps": early["forced"], "threshold_sweep": sweep,
+        "head_confidences": conf_quant, "speedup_crossover": first_win, "pipeline_vs_kv_recomputation": pipe_cmp,
         "max_pending_sweep": pending_sweep, "deferred_tokens": "refeed" if args.refeed else "resume",
         "hbm_gbps": early["bytes"] / early["seconds"] / 1e9, "hbm_frac": early["bytes"] / early["seconds"] / 1e9 / HBM_PEAK_GBPS,
         "full_depth_hbm_gbps": full["bytes"] / full["seconds"] / 1e9,

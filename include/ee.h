@@ -163,6 +163,12 @@ int ee_model_free(ee_model* m);
  * non-increasing, EE_ERR_ARG on bad counts. */
 int ee_debug_plan(int n_segments, int32_t* filled, int position, int max_pending, int refeed, int reached,
                   int32_t* forced, int32_t* row_lo, int32_t* row_hi);
+/* Measurement hook: the confidence every head reported in the latest ee_decode_step, conf[n_seqs][n_exits+1] (host;
+ * row b = the b-th sequence of that call, column i = exit i, last column = final head); -1 where the head was not
+ * evaluated for that sequence in that step (the token had left at a shallower exit, exits disabled or step forced).
+ * The benchmark uses it to report the confidence distribution at each exit (Section 5.2: the rule compares exactly
+ * this number with the threshold). */
+int ee_debug_step_confidences(const ee_model* m, int n_seqs, float* conf);
 /* Test hook: if dev_logits != NULL, every head evaluation also stores its fp32 logits there,
  * [row][vocab] for the rows it evaluates (capacity_rows rows).  NULL switches it off. */
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows);
@@ -231,6 +237,24 @@ int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int 
  * a current token, e.g. at the end of generation or before a step that would not fit).  Blocks until done. */
 int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_ids, void* stream);
 int ee_kv_cache_free(ee_kv_cache* c);
+
+/* Pipeline-based early-exit inference on one GPU (Section 4, "Pipeline-based inference"; Appendix D.3; Appendix B.1:
+ * both inference methods generate the same output).  With a second workspace and a second stream, the cache stops
+ * deferring tokens: when a token leaves at an exit, ee_decode_step returns it at once and hands the token to
+ * fill_stream, which carries it through the segments above the exit (the later pipeline stages) so that their KV
+ * entries get filled, while the caller's stream already runs the next token's shallow segment.  A pass over a
+ * segment on either stream waits (HIP events) for the latest pass over that segment on the other one, so a token
+ * always finds the K and V of every earlier token.  The caller's lists stay empty: each sequence passes exactly
+ * one row (its current token) per step, ee_kv_cache_pending reports 0 and no step is ever forced.
+ *   dev_workspace   a second step workspace on the model's device, 256-byte aligned; workspace_bytes as reported by
+ *                   ee_model_bytes is always enough (EE_ERR_NOMEM if too small).  NULL switches the mode off again.
+ *   fill_stream     a HIP stream of the same priority as the one the steps are given, not the same stream.
+ * Every token still passes every layer (on one stream or the other), so on one GPU this trades no work for the
+ * early emission of tokens; ee_kv_cache_flush waits until the fill stream has caught up, and the read-backs and
+ * ee_kv_cache_reset do so on their own.  At most four tokens are in flight on the fill stream; a step that would add
+ * a fifth waits for the oldest.  EE_ERR_STATE while any token is deferred, EE_ERR_CONFIG in re-feed mode or when
+ * the cache keeps fewer than 6 residual rows per sequence (max_pending < 5). */
+int ee_kv_cache_set_pipeline(ee_model* m, ee_kv_cache* c, void* dev_workspace, size_t workspace_bytes, void* fill_stream);
 /* Test hook: residual stream (fp32 [d_model]) of the sequence's newest processed position, at the
  * depth it reached. */
 int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_host, void* stream);

@@ -17,8 +17,8 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
-           "ee_kv_cache_set_refeed", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_step_confidences", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_kv_cache_set_refeed", "ee_kv_cache_set_pipeline", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step", "ee_decode_step_static"]
 
@@ -69,6 +69,7 @@ def lib():
                                     C.POINTER(vp)]
         L.ee_model_free.argtypes = [vp]
         L.ee_debug_set_logits.argtypes = [vp, vp, C.c_int]
+        L.ee_debug_step_confidences.argtypes = [vp, C.c_int, fp]
         L.ee_debug_plan.argtypes = [C.c_int, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p]
         L.ee_profile_begin.argtypes = [vp, C.c_int, C.c_int]
         L.ee_profile_end.argtypes = [vp, i32p, fp]
@@ -78,6 +79,7 @@ def lib():
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
         L.ee_kv_cache_reset.argtypes = [vp, C.c_int]
         L.ee_kv_cache_set_refeed.argtypes = [vp, C.c_int]
+        L.ee_kv_cache_set_pipeline.argtypes = [vp, vp, vp, sz, vp]
         L.ee_kv_cache_filled.argtypes = [vp, C.c_int, C.c_int, i32p]
         L.ee_kv_cache_pending.argtypes = [vp, C.c_int, i32p]
         L.ee_kv_cache_read.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, fp, fp, vp]
@@ -165,6 +167,12 @@ class Model:
         _chk(lib().ee_debug_set_logits(self.h, self._logits.data_ptr(), rows), "ee_debug_set_logits")
         return self._logits
 
+    def step_confidences(self, n_seqs: int = 1) -> np.ndarray:
+        """ee_debug_step_confidences -> float32[n_seqs][n_exits+1], -1 where a head was not evaluated in the last step."""
+        out = np.zeros((n_seqs, self.cfg.n_exits + 1), np.float32)
+        _chk(lib().ee_debug_step_confidences(self.h, n_seqs, _fp(out)), "ee_debug_step_confidences")
+        return out
+
     def profile_begin(self, kernel: int, max_launches: int = 16384, every: int = 1) -> None:
         _chk(lib().ee_profile_every(self.h, every), "ee_profile_every")
         _chk(lib().ee_profile_begin(self.h, kernel, max_launches), "ee_profile_begin")
@@ -232,6 +240,19 @@ class KvCache:
 
     def set_refeed(self, on: bool) -> None:
         _chk(lib().ee_kv_cache_set_refeed(self.h, 1 if on else 0), "ee_kv_cache_set_refeed")
+
+    def set_pipeline(self, on: bool = True) -> None:
+        """ee_kv_cache_set_pipeline: pipeline-based early exit, with a second workspace and a second stream (both owned
+        here); on=False returns to KV recomputation."""
+        if not on:
+            _chk(lib().ee_kv_cache_set_pipeline(self.model.h, self.h, None, 0, None), "ee_kv_cache_set_pipeline")
+            self._fill_ws = self._fill_stream = None
+            return
+        self._fill_ws = torch.zeros(self.model.workspace_bytes, dtype=torch.uint8, device=self.model.device)
+        self._fill_stream = torch.cuda.Stream(device=self.model.device)
+        torch.cuda.synchronize()
+        _chk(lib().ee_kv_cache_set_pipeline(self.model.h, self.h, self._fill_ws.data_ptr(), self.model.workspace_bytes,
+                                            C.c_void_p(self._fill_stream.cuda_stream)), "ee_kv_cache_set_pipeline")
 
     def filled(self, seq: int, layer: int) -> int:
         n = C.c_int32()
@@ -328,8 +349,9 @@ class Sequences:
     """Caller-side bookkeeping of the deferred-token lists that ee_decode_step expects: every token
     emitted since the last step that ran to full depth, oldest first, then the current token."""
 
-    def __init__(self, n_layers: int):
+    def __init__(self, n_layers: int, pipeline: bool = False):
         self.n_layers = n_layers
+        self.pipeline = pipeline  # pipeline-based early exit: the library defers nothing, the lists stay empty
         self.pending: dict = {}
         self.current: dict = {}
 
@@ -347,7 +369,7 @@ class Sequences:
 
     def update(self, seq_ids: Sequence[int], next_token, exit_layer) -> None:
         for i, s in enumerate(seq_ids):
-            if int(exit_layer[i]) == self.n_layers:
+            if int(exit_layer[i]) == self.n_layers or self.pipeline:
                 self.pending[s] = []
             else:
                 self.pending[s].append(self.current[s])

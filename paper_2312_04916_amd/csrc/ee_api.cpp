@@ -187,6 +187,7 @@ struct ee_model {
     int32_t* pf_host_tokens; // pinned staging of one prompt pass's token ids
     int head_tag = 0;        // tag of the latest head evaluation (see HeadResult::pad)
     int head_wait_limit_s = 120;  // wall-clock bound of one wait for head results
+    int step_tag0 = 0;            // head_tag when the latest decode step began: later tags belong to that step
     float* dbg_logits;
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
@@ -257,10 +258,34 @@ struct SeqState {
     std::vector<int32_t> tokring;  // token id of position p at p % S
 };
 
+// Pipeline-based early exit on one GPU (Section 4, "Pipeline-based inference"; Appendix D.3): a token that leaves at an
+// exit is handed to a second stream, which runs it through its remaining segments (stages) to fill their KV
+// entries while the caller's stream already works on the next token.  A pass over segment k on one stream waits for
+// the latest pass over segment k on the other (the stage's earlier token), so every token finds the KV of its
+// predecessors.  The second stream has its own step workspace and a ring of host staging areas for its descriptors.
+struct Pipeline {
+    static constexpr int RING = 4, POOL = 256;
+    bool on = false;
+    hipStream_t stream = nullptr;   // the fill stream
+    char* ws = nullptr;             // its step workspace (device)
+    char* pinned = nullptr;         // RING staging areas (host, mapped)
+    char* pinned_dev = nullptr;
+    size_t slot_bytes = 0;
+    int next_slot = 0;
+    bool slot_used[RING] = {};
+    hipEvent_t slot_done[RING] = {};  // the fill that read staging area i has run
+    hipEvent_t pool[POOL] = {};       // pass-finished events, handed out round-robin
+    int next_ev = 0;
+    int last_ev[EE_MAX_EXITS + 1];    // per segment: pool index of its latest pass, or -1
+    hipStream_t last_stream[EE_MAX_EXITS + 1];
+    bool events_made = false;
+};
+
 struct ee_kv_cache {
     const ee_model* m;
     int max_seqs, BT, S, max_pending, n_blocks;
     int refeed = 0;  // deferred tokens re-enter at layer 1 (the paper's wording) instead of resuming where they stopped
+    Pipeline pipe;
     char* pool;
     size_t off_x, off_xg, off_xgh, off_ssq;
     size_t xs_lo;    // element distance from the hi to the lo term in xg / xgh (0 for fp32)
@@ -654,6 +679,7 @@ int max_ctx_of(const ee_kv_cache* c, const std::vector<StepSeq>& ss) {
 int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float threshold, bool decode, int32_t* next_token,
              int32_t* exit_layer, float* conf, hipStream_t st) {
     const int n_seg = m->n_seg();
+    if (decode) m->step_tag0 = m->head_tag;
     for (size_t b = 0; b < ss.size(); ++b) put_btab(m, c, (int)b, c->seqs[ss[b].seq]);
     int max_ctx = max_ctx_of(c, ss);
     std::vector<int> rows(n_seg, 0);
@@ -666,13 +692,23 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     };
     EECHK(rebuild(0));
     int n_active = (int)ss.size();
+    Pipeline& pp = c->pipe;
     for (int s = 0; s < n_seg && n_active > 0; ++s) {
         const SegDesc* hd = m->host_desc(s);
         if (hd->T > 0) {
             if (s == 0 && (decode || c->refeed))
                 HIPCHK(launch_embed(m->cfg.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), hd->T, m->cfg.d_model,
                                     m->gain(m->wl.g1[0]), c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
+            // pipeline mode: the stage's previous token may still be on the other stream (segment 0 only ever runs here)
+            if (pp.on && s > 0 && pp.last_ev[s] >= 0 && pp.last_stream[s] != st)
+                HIPCHK(hipStreamWaitEvent(st, pp.pool[pp.last_ev[s]], 0));
             EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
+            if (pp.on && s > 0) {
+                const int e = pp.next_ev++ % Pipeline::POOL;
+                HIPCHK(hipEventRecord(pp.pool[e], st));
+                pp.last_ev[s] = e;
+                pp.last_stream[s] = st;
+            }
         }
         bool is_final = s == n_seg - 1;
         if (decode && hd->n_head > 0) {
@@ -702,10 +738,41 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
                     SeqState& sq = c->seqs[q.seq];
                     plan::flushed(sq.filled.data(), n_seg);
                 }
-                HIPCHK(hipStreamSynchronize(st));
+                if (!pp.on) HIPCHK(hipStreamSynchronize(st));  // (a pipelined fill is waited for through its events)
             }
         }
     }
+    return EE_OK;
+}
+
+// Pipeline mode, after a decode step: the tokens that left at an exit go through their remaining segments on the
+// fill stream (no head, nothing emitted), in that stream's own workspace; the call only enqueues.  Their watermarks
+// advance now: every later pass over those segments is ordered behind this one by the per-segment events.
+int pipeline_fill(ee_model* m, ee_kv_cache* c, const std::vector<StepSeq>& step) {
+    Pipeline& pp = c->pipe;
+    std::vector<StepSeq> fs;
+    for (const StepSeq& q : step)
+        if (c->n_pending(c->seqs[q.seq]) > 0) fs.push_back(StepSeq{q.seq, -1, true, true});
+    if (fs.empty()) return EE_OK;
+    const int slot = pp.next_slot;
+    pp.next_slot = (slot + 1) % Pipeline::RING;
+    if (pp.slot_used[slot]) HIPCHK(hipEventSynchronize(pp.slot_done[slot]));  // its descriptors have been read
+    char *ws = m->ws, *pin = m->pinned, *pin_dev = m->pinned_dev;
+    m->ws = pp.ws;
+    m->pinned = pp.pinned + (size_t)slot * pp.slot_bytes;
+    m->pinned_dev = pp.pinned_dev + (size_t)slot * pp.slot_bytes;
+    int rc = run_step(m, c, fs, 1.0f, false, nullptr, nullptr, nullptr, pp.stream);
+    m->ws = ws;
+    m->pinned = pin;
+    m->pinned_dev = pin_dev;
+    EECHK(rc);
+    HIPCHK(hipEventRecord(pp.slot_done[slot], pp.stream));
+    pp.slot_used[slot] = true;
+    return EE_OK;
+}
+
+int pipeline_drain(ee_kv_cache* c) {
+    if (c->pipe.on) HIPCHK(hipStreamSynchronize(c->pipe.stream));
     return EE_OK;
 }
 
@@ -1186,6 +1253,18 @@ int ee_debug_plan(int n_segments, int32_t* filled, int position, int max_pending
     return EE_OK;
 }
 
+int ee_debug_step_confidences(const ee_model* m, int n_seqs, float* conf) {
+    if (!m || !conf || n_seqs < 1 || n_seqs > EE_MAX_SEQS) return EE_ERR_ARG;
+    const int n_seg = m->n_seg();
+    for (int b = 0; b < n_seqs; ++b)
+        for (int s = 0; s < n_seg; ++s) {
+            const HeadResult& r = m->results[s * EE_MAX_SEQS + b];
+            const bool fresh = m->head_tag >= m->step_tag0 ? (r.pad > m->step_tag0 && r.pad <= m->head_tag) : false;
+            conf[(size_t)b * n_seg + s] = fresh ? r.conf : -1.f;
+        }
+    return EE_OK;
+}
+
 int ee_debug_set_logits(ee_model* m, void* dev_logits, int capacity_rows) {
     if (!m) return EE_ERR_ARG;
     m->dbg_logits = (float*)dev_logits;
@@ -1244,6 +1323,7 @@ int ee_kv_cache_set_refeed(ee_kv_cache* c, int on) {
     if (!c) return EE_ERR_ARG;
     const int want = on ? 1 : 0;
     if (want == c->refeed) return EE_OK;
+    if (want && c->pipe.on) return EE_ERR_CONFIG;  // the fill stream resumes tokens from their saved rows
     // While a token is deferred its saved residual row means different things in the two modes (re-feeding rewrites
     // the row at whatever depth the step reached, resuming relies on it standing at the depth the watermarks say):
     // the mode may only change while no list holds a token.
@@ -1256,6 +1336,7 @@ int ee_kv_cache_set_refeed(ee_kv_cache* c, int on) {
 int ee_kv_cache_reset(ee_kv_cache* c, int seq) {
     if (!c) return EE_ERR_ARG;
     if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
+    EECHK(pipeline_drain(c));  // a fill in flight may still write to the blocks given back here
     SeqState& s = c->seqs[seq];
     for (int32_t b : s.blocks) c->free_blocks.push_back(b);
     s.blocks.clear();
@@ -1285,6 +1366,7 @@ int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int 
     const SeqState& s = c->seqs[seq];
     if (pos0 + n > (int)s.blocks.size() * c->BT) return EE_ERR_RANGE;
     if (n == 0) return EE_OK;
+    EECHK(pipeline_drain(const_cast<ee_kv_cache*>(c)));
     hipStream_t st = (hipStream_t)stream;
     put_btab(m, c, 0, s);
     EECHK(upload(m, st));
@@ -1306,6 +1388,7 @@ int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_ho
     if (seq < 0 || seq >= c->max_seqs) return EE_ERR_RANGE;
     const SeqState& s = c->seqs[seq];
     if (s.filled[0] < 1) return EE_ERR_STATE;
+    EECHK(pipeline_drain(const_cast<ee_kv_cache*>(c)));
     hipStream_t st = (hipStream_t)stream;
     size_t d = m->cfg.d_model;
     HIPCHK(hipMemcpyAsync(x_host, c->x() + (size_t)c->slot_of(seq, s.filled[0] - 1) * d, d * 4, hipMemcpyDeviceToHost, st));
@@ -1326,11 +1409,18 @@ int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* se
         if (c->seqs[sid].filled[0] < 1) return EE_ERR_STATE;
         ss.push_back(StepSeq{sid, -1, true, true});
     }
+    if (c->pipe.on) return pipeline_drain(c);  // nothing is ever deferred there: wait for the fills in flight
     return run_step(m, c, ss, 1.0f, false, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int ee_kv_cache_free(ee_kv_cache* c) {
     if (!c) return EE_ERR_ARG;
+    if (c->pipe.events_made) {
+        if (c->pipe.on) (void)hipStreamSynchronize(c->pipe.stream);
+        for (auto& e : c->pipe.slot_done) (void)hipEventDestroy(e);
+        for (auto& e : c->pipe.pool) (void)hipEventDestroy(e);
+        (void)hipHostFree(c->pipe.pinned);
+    }
     delete c;
     return EE_OK;
 }
@@ -1535,7 +1625,42 @@ int ee_decode_step(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* seq_i
         int tok = tokens[row_offsets[b + 1] - 1];
         s.tokring[ss[b].p % c->S] = tok;
     }
-    return run_step(m, c, ss, threshold, true, next_token, exit_layer, conf, (hipStream_t)stream);
+    EECHK(run_step(m, c, ss, threshold, true, next_token, exit_layer, conf, (hipStream_t)stream));
+    return c->pipe.on ? pipeline_fill(m, c, ss) : EE_OK;
+}
+
+int ee_kv_cache_set_pipeline(ee_model* m, ee_kv_cache* c, void* dev_workspace, size_t workspace_bytes, void* fill_stream) {
+    if (!m || !c || c->m != m) return EE_ERR_ARG;
+    Pipeline& pp = c->pipe;
+    EECHK(pipeline_drain(c));
+    if (!dev_workspace) {  // back to KV recomputation (nothing is deferred in pipeline mode, so any time is fine)
+        pp.on = false;
+        return EE_OK;
+    }
+    if (((uintptr_t)dev_workspace & 255) || !fill_stream) return EE_ERR_ARG;
+    if (workspace_bytes < m->wsl.pf_begin) return EE_ERR_NOMEM;
+    if (c->refeed || c->S < Pipeline::RING + 2) return EE_ERR_CONFIG;  // a token's residual row must outlive its fill
+    for (const SeqState& s : c->seqs)
+        if (c->n_pending(s) > 0) return EE_ERR_STATE;
+    if (!pp.events_made) {
+        for (auto& e : pp.slot_done) HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        for (auto& e : pp.pool) HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        pp.slot_bytes = align_up(m->wsl.upload_bytes);
+        HIPCHK(hipHostMalloc((void**)&pp.pinned, pp.slot_bytes * Pipeline::RING, hipHostMallocMapped));
+        std::memset(pp.pinned, 0, pp.slot_bytes * Pipeline::RING);
+        HIPCHK(hipHostGetDevicePointer((void**)&pp.pinned_dev, pp.pinned, 0));
+        pp.events_made = true;
+    }
+    pp.stream = (hipStream_t)fill_stream;
+    pp.ws = (char*)dev_workspace;
+    pp.next_slot = 0;
+    for (bool& u : pp.slot_used) u = false;
+    for (int k = 0; k <= EE_MAX_EXITS; ++k) {
+        pp.last_ev[k] = -1;
+        pp.last_stream[k] = nullptr;
+    }
+    pp.on = true;
+    return EE_OK;
 }
 
 }  // extern "C"

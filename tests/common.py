@@ -129,8 +129,11 @@ def _judge(rep: LockstepReport, step: int, diag: dict, tau: float, gpu_exits_her
 
 def lockstep(gm: ee.Model, cache: ee.KvCache, om: O.Model, prompt, n_new: int, tau: float, max_pending: int,
              seq: int = 0, check_hidden: bool = True, logits: Optional[torch.Tensor] = None,
-             max_positions: Optional[int] = None) -> LockstepReport:
-    """Generates n_new tokens on the GPU and drives the oracle through the same decisions."""
+             max_positions: Optional[int] = None, pipeline: bool = False) -> LockstepReport:
+    """Generates n_new tokens on the GPU and drives the oracle through the same decisions.  pipeline: the cache is
+    in pipeline mode (no deferred lists on the GPU side; the oracle still generates by KV recomputation, the two
+    methods give the same output); the hidden state is then not compared, a second stream is moving it on."""
+    check_hidden = check_hidden and not pipeline
     sh = om.cfg
     L, n_exits = sh.n_layers, sh.n_exits
     rep = LockstepReport()
@@ -155,7 +158,7 @@ def lockstep(gm: ee.Model, cache: ee.KvCache, om: O.Model, prompt, n_new: int, t
     if check_hidden:  # after prefill both hold the last prompt position at full depth
         rep.max_hidden_err = max(rep.max_hidden_err, rel_err(cache.read_hidden(seq), st.last_hidden()))
 
-    seqs = ee.Sequences(L)
+    seqs = ee.Sequences(L, pipeline=pipeline)
     seqs.start(seq, tok)
     for step in range(1, n_new):
         ro, tk, pm = seqs.rows([seq])
@@ -182,7 +185,7 @@ def lockstep(gm: ee.Model, cache: ee.KvCache, om: O.Model, prompt, n_new: int, t
         seqs.update([seq], nt, exl)
         rep.tokens.append(g_tok)
         rep.exit_layers.append(g_ex)
-        if cache.pending(seq) != st.n_pending():
+        if not pipeline and cache.pending(seq) != st.n_pending():
             rep.mismatches.append(f"step {step}: pending {cache.pending(seq)} vs oracle {st.n_pending()}")
     rep.state = st
     rep.seqs = seqs
