@@ -11,6 +11,9 @@
 //                  a = softmax_{j<=pos}(q.k_j / sqrt(hd)) v_j  per head;   x <- x + Wo a
 //                  h = rmsnorm(x; g2_l);  x <- x + Wd (silu(Wg h) * (Wu h))
 //   exit i (after layer e_i):  z = We_i rmsnorm(x; ge_i);  conf = max softmax(z)   (Sections 2, 5.2)
+//   an exit may first pass x through modules of its own (Section 2): an MLP block, or a complete Transformer layer
+//   (same block as above with the exit's weights; its attention runs over the K and V that the same exit layer
+//   produced at the earlier positions); the backbone's x is not changed
 //   rmsnorm(x; g) = g * x / sqrt(mean(x^2) + eps)
 #include "ee_oracle.h"
 
@@ -154,11 +157,15 @@ struct eo_model {
     std::vector<const void*> wq, wk, wv, wo, wg, wu, wd;
     std::vector<const float*> ge;
     std::vector<const void*> we;
-    std::vector<const float*> gm;           // exit MLP: norm gain
-    std::vector<const void*> ewg, ewu, ewd; // exit MLP: gate, up, down
+    std::vector<const float*> gm;           // exit MLP (alone, or second half of the exit's layer): norm gain
+    std::vector<const void*> ewg, ewu, ewd; // ... gate, up, down
+    std::vector<const float*> ga;           // exit layer, attention half: norm gain
+    std::vector<const void*> ewq, ewk, ewv, ewo;
     const float* gf = nullptr;
     const void* wf = nullptr;
     int n_seg() const { return c.n_exits + 1; }
+    bool exit_layer() const { return c.exit_flags & EO_EXIT_LAYER; }
+    int n_kv_layers() const { return c.n_layers + (exit_layer() ? c.n_exits : 0); }  // exit i's layer caches as layer L+i
     int seg_end(int s) const { return s < c.n_exits ? c.exit_layers[s] : c.n_layers; }
     int seg_begin(int s) const { return s == 0 ? 0 : c.exit_layers[s - 1]; }
 };
@@ -175,36 +182,61 @@ void embed_row(const eo_model* m, int tok, float* x) {
     }
 }
 
-// One layer on one row.  K, V: [>= pos+1][d]; row pos is written, rows 0..pos are read.
-void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) {
+// The weights of one Transformer block: a backbone layer, or the layer an exit may contain.
+struct BlockW {
+    const float *g1, *g2;
+    const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+};
+BlockW layer_weights(const eo_model* m, int l) {
+    return BlockW{m->g1[l], m->g2[l], m->wq[l], m->wk[l], m->wv[l], m->wo[l], m->wg[l], m->wu[l], m->wd[l]};
+}
+BlockW exit_layer_weights(const eo_model* m, int i) {
+    return BlockW{m->ga[i], m->gm[i], m->ewq[i], m->ewk[i], m->ewv[i], m->ewo[i], m->ewg[i], m->ewu[i], m->ewd[i]};
+}
+
+// K and V of one row: k, v = Wk h, Wv h with h = rmsnorm(x; g1), k rotated to the row's position, both rounded to the
+// storage type of the cache.  Written to row `pos` of K, V ([>= pos+1][d]); h is returned for the caller's q.
+void block_kv_row(const eo_model* m, const BlockW& w, const float* x, int pos, float* K, float* V, float* h) {
     const eo_config& c = m->c;
-    int d = c.d_model, F = c.d_ff, dt = c.dtype;
-    std::vector<float> h(d > F ? d : F), q(d), a(d), gate(F), up(F), y(d);
+    int d = c.d_model, dt = c.dtype;
     float* k = K + (size_t)pos * d;
     float* v = V + (size_t)pos * d;
-    rmsnorm(x, m->g1[l], d, c.rms_eps, h.data());
-    matvec(dt, m->wq[l], d, d, h.data(), q.data());
-    matvec(dt, m->wk[l], d, d, h.data(), k);
-    matvec(dt, m->wv[l], d, d, h.data(), v);
-    rope(q.data(), c.n_heads, c.head_dim, pos, c.rope_base);
+    rmsnorm(x, w.g1, d, c.rms_eps, h);
+    matvec(dt, w.wk, d, d, h, k);
+    matvec(dt, w.wv, d, d, h, v);
     rope(k, c.n_heads, c.head_dim, pos, c.rope_base);
     for (int i = 0; i < d; ++i) {  // the cache stores K and V in the model's storage type
         k[i] = rnd(dt, k[i]);
         v[i] = rnd(dt, v[i]);
     }
+}
+
+// One block on one row.  K, V: [>= pos+1][d]; row pos is written, rows 0..pos are read.
+void block_row(const eo_model* m, const BlockW& w, float* x, int pos, float* K, float* V) {
+    const eo_config& c = m->c;
+    int d = c.d_model, F = c.d_ff, dt = c.dtype;
+    std::vector<float> h(d > F ? d : F), q(d), a(d), gate(F), up(F), y(d);
+    block_kv_row(m, w, x, pos, K, V, h.data());
+    matvec(dt, w.wq, d, d, h.data(), q.data());
+    rope(q.data(), c.n_heads, c.head_dim, pos, c.rope_base);
     attention_row(q.data(), K, V, pos + 1, c.n_heads, c.head_dim, a.data());
-    matvec(dt, m->wo[l], d, d, a.data(), y.data());
+    matvec(dt, w.wo, d, d, a.data(), y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
-    rmsnorm(x, m->g2[l], d, c.rms_eps, h.data());
-    matvec(dt, m->wg[l], F, d, h.data(), gate.data());
-    matvec(dt, m->wu[l], F, d, h.data(), up.data());
+    rmsnorm(x, w.g2, d, c.rms_eps, h.data());
+    matvec(dt, w.wg, F, d, h.data(), gate.data());
+    matvec(dt, w.wu, F, d, h.data(), up.data());
     swiglu(gate.data(), up.data(), F, h.data());
-    matvec(dt, m->wd[l], d, F, h.data(), y.data());
+    matvec(dt, w.wd, d, F, h.data(), y.data());
     for (int i = 0; i < d; ++i) x[i] += y[i];
 }
 
+void layer_row(const eo_model* m, int l, float* x, int pos, float* K, float* V) {
+    block_row(m, layer_weights(m, l), x, pos, K, V);
+}
+
 // Head `head` on one row (Section 2, "Model architectures"): an exit is, in this order, an optional MLP block,
-// an optional normalisation, and an output embedding matrix that is its own or the input embedding.
+// an optional normalisation, and an output embedding matrix that is its own or the input embedding.  (An exit that
+// contains a complete Transformer layer applies that layer first, see exit_layer_row; x is then its output.)
 void head_row(const eo_model* m, int head, const float* x, float* z, eo_diag* diag) {
     const eo_config& c = m->c;
     const int d = c.d_model, F = c.d_ff, dt = c.dtype;
@@ -248,7 +280,45 @@ struct eo_state {
     int n_rows() const { return cur_pos - row_pos0 + 1; }
 };
 
+namespace {
+
+// Exit `i` on the row x at position pos of the state's sequence.  If the exit contains a Transformer layer, the row's
+// K and V in that layer are written (cache layer L+i) whether or not the head is read; with_head: the exit's layer
+// (on a copy of x), then the head, into last_logits and *diag.
+void exit_row(eo_state* s, int i, const float* x, int pos, bool with_head, eo_diag* diag) {
+    const eo_model* m = s->m;
+    const int d = m->c.d_model, L = m->c.n_layers;
+    std::vector<float> xe(x, x + d);
+    if (m->exit_layer()) {
+        BlockW w = exit_layer_weights(m, i);
+        if (with_head) {
+            block_row(m, w, xe.data(), pos, s->Kl(L + i), s->Vl(L + i));
+        } else {
+            std::vector<float> h(d);
+            block_kv_row(m, w, x, pos, s->Kl(L + i), s->Vl(L + i), h.data());
+        }
+    }
+    if (with_head) head_row(m, i, xe.data(), s->last_logits.data(), diag);
+}
+
+}  // namespace
+
 extern "C" {
+
+int eo_exit_layer_sequence(const eo_model* m, int exit, const float* hidden, int n, float* x_out, float* k_out, float* v_out) {
+    if (!m->exit_layer() || exit < 0 || exit >= m->c.n_exits || n < 1) return -1;
+    const int d = m->c.d_model;
+    std::vector<float> K((size_t)n * d), V((size_t)n * d);
+    BlockW w = exit_layer_weights(m, exit);
+    for (int t = 0; t < n; ++t) {
+        std::vector<float> x(hidden + (size_t)t * d, hidden + (size_t)(t + 1) * d);
+        block_row(m, w, x.data(), t, K.data(), V.data());
+        if (x_out) std::memcpy(x_out + (size_t)t * d, x.data(), sizeof(float) * d);
+    }
+    if (k_out) std::memcpy(k_out, K.data(), sizeof(float) * n * d);
+    if (v_out) std::memcpy(v_out, V.data(), sizeof(float) * n * d);
+    return 0;
+}
 
 void eo_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
 int eo_get_threads(void) { return g_threads; }
@@ -258,7 +328,8 @@ eo_model* eo_model_create(const eo_config* cfg) {
     const eo_config& c = *cfg;
     if (c.n_layers < 1 || c.d_model < 1 || c.n_heads < 1 || c.head_dim < 2 || (c.head_dim & 1) ||
         c.n_heads * c.head_dim != c.d_model || c.d_ff < 1 || c.vocab < 2 || c.n_exits < 0 || c.n_exits > 8 ||
-        (c.exit_flags & ~(EO_EXIT_NO_NORM | EO_TIE_EMBEDDINGS | EO_EXIT_MLP)))
+        (c.exit_flags & ~(EO_EXIT_NO_NORM | EO_TIE_EMBEDDINGS | EO_EXIT_MLP | EO_EXIT_LAYER)) ||
+        ((c.exit_flags & EO_EXIT_MLP) && (c.exit_flags & EO_EXIT_LAYER)))
         return nullptr;
     for (int i = 0; i < c.n_exits; ++i) {
         if (c.exit_layers[i] < 1 || c.exit_layers[i] >= c.n_layers) return nullptr;
@@ -273,7 +344,8 @@ eo_model* eo_model_create(const eo_config* cfg) {
     m->ge.assign(c.n_exits, nullptr);
     m->we.assign(c.n_exits, nullptr);
     m->gm.assign(c.n_exits, nullptr);
-    for (auto* v : {&m->ewg, &m->ewu, &m->ewd}) v->assign(c.n_exits, nullptr);
+    m->ga.assign(c.n_exits, nullptr);
+    for (auto* v : {&m->ewg, &m->ewu, &m->ewd, &m->ewq, &m->ewk, &m->ewv, &m->ewo}) v->assign(c.n_exits, nullptr);
     return m;
 }
 
@@ -299,6 +371,11 @@ int eo_model_set_tensor(eo_model* m, int kind, int index, const void* data) {
         case EO_EXIT_WG: if (!lay(E)) return -1; m->ewg[index] = data; return 0;
         case EO_EXIT_WU: if (!lay(E)) return -1; m->ewu[index] = data; return 0;
         case EO_EXIT_WD: if (!lay(E)) return -1; m->ewd[index] = data; return 0;
+        case EO_EXIT_ATTN_NORM: if (!lay(E)) return -1; m->ga[index] = (const float*)data; return 0;
+        case EO_EXIT_WQ: if (!lay(E)) return -1; m->ewq[index] = data; return 0;
+        case EO_EXIT_WK: if (!lay(E)) return -1; m->ewk[index] = data; return 0;
+        case EO_EXIT_WV: if (!lay(E)) return -1; m->ewv[index] = data; return 0;
+        case EO_EXIT_WO: if (!lay(E)) return -1; m->ewo[index] = data; return 0;
     }
     return -1;
 }
@@ -346,6 +423,13 @@ static int generate_g0(const eo_model* m, const int32_t* prompt, int n_prompt, i
             for (int i = 0; i < c.n_exits && tok < 0; ++i) {
                 const float* x = hid.data() + ((size_t)c.exit_layers[i] * n + (n - 1)) * d;
                 eo_diag dg;
+                std::vector<float> xe;
+                if (m->exit_layer()) {  // the exit's own layer over the whole sequence of hidden states at this depth
+                    xe.resize((size_t)n * d);
+                    if (eo_exit_layer_sequence(m, i, hid.data() + (size_t)c.exit_layers[i] * n * d, n, xe.data(), nullptr, nullptr))
+                        return -1;
+                    x = xe.data() + (size_t)(n - 1) * d;
+                }
                 head_row(m, i, x, z.data(), &dg);
                 if (dg.conf >= threshold) {
                     tok = dg.argmax;
@@ -409,7 +493,7 @@ eo_state* eo_state_create(const eo_model* m, int max_positions, int max_pending)
     s->max_pending = max_pending;
     s->tok.assign(max_positions, -1);
     s->filled.assign(m->n_seg(), 0);
-    size_t n = (size_t)m->c.n_layers * max_positions * m->c.d_model;
+    size_t n = (size_t)m->n_kv_layers() * max_positions * m->c.d_model;
     s->K.assign(n, 0.f);
     s->V.assign(n, 0.f);
     s->last_hidden.assign(m->c.d_model, 0.f);
@@ -432,8 +516,12 @@ int eo_prefill(eo_state* s, const int32_t* tokens, int n, eo_diag* diag_out) {
         int next_exit = 0;
         for (int l = 0; l < c.n_layers; ++l) {
             layer_row(m, l, x.data(), t, s->Kl(l), s->Vl(l));
-            if (t == n - 1 && next_exit < c.n_exits && c.exit_layers[next_exit] == l + 1) {
-                head_row(m, next_exit, x.data(), s->last_logits.data(), &diag_out[next_exit]);
+            if (next_exit < c.n_exits && c.exit_layers[next_exit] == l + 1) {
+                // every position leaves its K and V in the exit's own layer; the head is read at the last one
+                if (t == n - 1)
+                    exit_row(s, next_exit, x.data(), t, true, &diag_out[next_exit]);
+                else if (m->exit_layer())
+                    exit_row(s, next_exit, x.data(), t, false, nullptr);
                 ++next_exit;
             }
         }
@@ -476,10 +564,16 @@ int eo_step_advance(eo_state* s, int eval_head, eo_diag* diag) {
     const float* xc = s->rows.data() + (size_t)(s->n_rows() - 1) * d;
     std::memcpy(s->last_hidden.data(), xc, sizeof(float) * d);
     int depth = m->seg_end(seg);
-    if (depth == m->c.n_layers)
+    if (depth == m->c.n_layers) {
         head_row(m, m->c.n_exits, xc, s->last_logits.data(), diag);
-    else if (eval_head)
-        head_row(m, seg, xc, s->last_logits.data(), diag);
+    } else {
+        // the deferred rows (oldest first) leave their K and V in the exit's own layer, if it has one; the current
+        // row does too, and is the only one whose head is read (and only if the exits are on in this step)
+        if (m->exit_layer())
+            for (int i = 0; i + 1 < s->n_rows(); ++i)
+                exit_row(s, seg, s->rows.data() + (size_t)i * d, s->row_pos0 + i, false, nullptr);
+        if (eval_head || m->exit_layer()) exit_row(s, seg, xc, s->cur_pos, eval_head != 0, diag);
+    }
     return depth;
 }
 
@@ -517,7 +611,14 @@ int eo_flush(eo_state* s) {
     std::vector<float> x(d);
     for (int t = p0; t < p1; ++t) {
         embed_row(m, s->tok[t], x.data());
-        for (int l = 0; l < m->c.n_layers; ++l) layer_row(m, l, x.data(), t, s->Kl(l), s->Vl(l));
+        int next_exit = 0;
+        for (int l = 0; l < m->c.n_layers; ++l) {
+            layer_row(m, l, x.data(), t, s->Kl(l), s->Vl(l));
+            if (next_exit < m->c.n_exits && m->c.exit_layers[next_exit] == l + 1) {
+                if (m->exit_layer()) exit_row(s, next_exit, x.data(), t, false, nullptr);
+                ++next_exit;
+            }
+        }
     }
     for (auto& f : s->filled) f = p1;
     return 0;
@@ -532,7 +633,7 @@ int eo_n_pending(const eo_state* s) { return s->filled[0] - s->filled[s->m->n_se
 
 int eo_kv_read(const eo_state* s, int layer, int pos0, int n, float* k_out, float* v_out) {
     const eo_config& c = s->m->c;
-    if (layer < 0 || layer >= c.n_layers || pos0 < 0 || n < 0 || pos0 + n > s->max_pos) return -1;
+    if (layer < 0 || layer >= s->m->n_kv_layers() || pos0 < 0 || n < 0 || pos0 + n > s->max_pos) return -1;
     size_t off = ((size_t)layer * s->max_pos + pos0) * c.d_model;
     std::memcpy(k_out, s->K.data() + off, sizeof(float) * n * c.d_model);
     std::memcpy(v_out, s->V.data() + off, sizeof(float) * n * c.d_model);

@@ -55,13 +55,21 @@ typedef struct {
  *   EO_TIE_EMBEDDINGS  every exit and the final head use the input embedding matrix [vocab][d];
  *   EO_EXIT_MLP        exit i first applies an MLP block of its own, of the same form as a layer's:
  *                      x' = x + W_d (silu(W_g h) * (W_u h)), h = rmsnorm(x; g_mlp), and its (norm and)
- *                      output embedding read x'.  The backbone's x is not changed. */
-enum { EO_EXIT_NO_NORM = 1, EO_TIE_EMBEDDINGS = 2, EO_EXIT_MLP = 4 };
+ *                      output embedding read x'.  The backbone's x is not changed.
+ *   EO_EXIT_LAYER      exit i first applies a complete Transformer layer of its own (the same block as a backbone
+ *                      layer, own weights) to the hidden states at its depth: its attention at position t runs over
+ *                      the K and V that this exit layer produced at positions 0..t.  Its output feeds the exit's
+ *                      (norm and) output embedding; the backbone's x is not changed.  In generation with a KV cache,
+ *                      every position that passes depth e_i leaves its K and V in the exit's layer (cache layer
+ *                      n_layers + i), whether or not the exit is evaluated for it.  Not together with EO_EXIT_MLP. */
+enum { EO_EXIT_NO_NORM = 1, EO_TIE_EMBEDDINGS = 2, EO_EXIT_MLP = 4, EO_EXIT_LAYER = 8 };
 
 /* tensor kinds, same numbering as the workload generator's TensorKind */
 enum { EO_EMBED = 0, EO_ATTN_NORM = 1, EO_WQ = 2, EO_WK = 3, EO_WV = 4, EO_WO = 5, EO_MLP_NORM = 6,
        EO_WG = 7, EO_WU = 8, EO_WD = 9, EO_EXIT_NORM = 10, EO_EXIT_HEAD = 11, EO_FINAL_NORM = 12,
-       EO_FINAL_HEAD = 13, EO_EXIT_MLP_NORM = 14, EO_EXIT_WG = 15, EO_EXIT_WU = 16, EO_EXIT_WD = 17 };
+       EO_FINAL_HEAD = 13, EO_EXIT_MLP_NORM = 14, EO_EXIT_WG = 15, EO_EXIT_WU = 16, EO_EXIT_WD = 17,
+       /* attention half of an exit's Transformer layer; kinds 14..17 are its MLP half */
+       EO_EXIT_ATTN_NORM = 18, EO_EXIT_WQ = 19, EO_EXIT_WK = 20, EO_EXIT_WV = 21, EO_EXIT_WO = 22 };
 
 typedef struct eo_model eo_model;
 typedef struct eo_state eo_state;
@@ -99,6 +107,11 @@ int eo_generate_plain(const eo_model*, const int32_t* prompt, int n_prompt, int 
 int eo_forward_sequence(const eo_model*, const int32_t* tokens, int n, float* hidden_out, float* k_out,
                         float* v_out);
 
+/* The Transformer layer of exit `exit` (EO_EXIT_LAYER) applied to a whole sequence of hidden states [n][d] (the
+ * residual stream after layer e_i at positions 0..n-1), causally.  x_out: [n][d] its output; k_out / v_out: [n][d]
+ * its keys (after RoPE) and values.  Any output may be NULL. */
+int eo_exit_layer_sequence(const eo_model*, int exit, const float* hidden, int n, float* x_out, float* k_out, float* v_out);
+
 /* ---- G1: KV cache + pending list + recomputation ---- */
 eo_state* eo_state_create(const eo_model*, int max_positions, int max_pending);
 void eo_state_free(eo_state*);
@@ -123,7 +136,7 @@ int eo_decode_step(eo_state*, int32_t token, float threshold, int32_t* next_toke
 int eo_flush(eo_state*);
 int eo_filled(const eo_state*, int segment); /* positions whose KV is present in every layer of the segment */
 int eo_n_pending(const eo_state*);
-int eo_kv_read(const eo_state*, int layer, int pos0, int n, float* k_out, float* v_out); /* [n][d] */
+int eo_kv_read(const eo_state*, int layer, int pos0, int n, float* k_out, float* v_out); /* [n][d]; layer n_layers + i: exit i's own layer */
 int eo_last_hidden(const eo_state*, float* x_out); /* current row's residual stream at the depth reached */
 int eo_last_logits(const eo_state*, float* z_out); /* logits of the last head evaluated, [vocab] */
 
@@ -140,7 +153,8 @@ void eo_swiglu(const float* gate, const float* up, int n, float* out);
 void eo_softmax_max(const float* z, int n, eo_diag* out);
 /* one layer on one row: x in/out [d]; K,V: [>=pos+1][d], row `pos` is written, rows 0..pos are read */
 int eo_layer_row(const eo_model*, int layer, float* x, int pos, float* K, float* V);
-/* head i (0..n_exits-1 exits, n_exits = final) on one row; z_out may be NULL */
+/* head i (0..n_exits-1 exits, n_exits = final) on one row; z_out may be NULL.  For a model with EO_EXIT_LAYER, x is
+ * the output of the exit's layer at that row (eo_exit_layer_sequence): this call applies what comes after it. */
 int eo_head_row(const eo_model*, int head, const float* x, float* z_out, eo_diag* diag);
 
 #ifdef __cplusplus

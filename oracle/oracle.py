@@ -22,7 +22,7 @@ class EoConfig(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32)]
 
 
-EO_EXIT_NO_NORM, EO_TIE_EMBEDDINGS, EO_EXIT_MLP = 1, 2, 4
+EO_EXIT_NO_NORM, EO_TIE_EMBEDDINGS, EO_EXIT_MLP, EO_EXIT_LAYER = 1, 2, 4, 8
 
 
 class EoDiag(C.Structure):
@@ -52,6 +52,7 @@ def lib():
         L.eo_generate_g0_capped.argtypes = [vp, i32p, C.c_int, C.c_int, C.c_float, C.c_int, i32p, i32p]
         L.eo_generate_plain.argtypes = [vp, i32p, C.c_int, C.c_int, i32p]
         L.eo_forward_sequence.argtypes = [vp, i32p, C.c_int, fp, fp, fp]
+        L.eo_exit_layer_sequence.argtypes = [vp, C.c_int, fp, C.c_int, fp, fp, fp]
         L.eo_state_create.restype = vp
         L.eo_state_create.argtypes = [vp, C.c_int, C.c_int]
         L.eo_state_free.argtypes = [vp]
@@ -173,6 +174,15 @@ class Model:
         if lib().eo_forward_sequence(self.h, _ip(t), n, _fp(hid), _fp(k), _fp(v)):
             raise RuntimeError("eo_forward_sequence failed")
         return hid, k, v
+
+    def exit_layer_sequence(self, exit_index: int, hidden: np.ndarray):
+        """The exit's own Transformer layer over hidden states [n][d] -> (x_out, k, v), each [n][d]."""
+        hidden = np.ascontiguousarray(hidden, dtype=np.float32)
+        n, d = hidden.shape
+        x, k, v = (np.zeros((n, d), np.float32) for _ in range(3))
+        if lib().eo_exit_layer_sequence(self.h, exit_index, _fp(hidden), n, _fp(x), _fp(k), _fp(v)):
+            raise RuntimeError("eo_exit_layer_sequence failed")
+        return x, k, v
 
     def layer_row(self, layer: int, x: np.ndarray, pos: int, K: np.ndarray, V: np.ndarray) -> None:
         if lib().eo_layer_row(self.h, layer, _fp(x), pos, _fp(K), _fp(V)):

@@ -161,3 +161,153 @@ def test_kv_recomputation_equals_the_plain_definition_for_every_exit_structure(k
         assert np.array_equal(t0, toks) and np.array_equal(e0, exits)
         mixes.update(exits)
     assert len(mixes) >= 2, "the thresholds must exercise exits and the final head"
+
+
+# ---------------------------------------------------------------- a complete Transformer layer in the exit
+
+def _np_block(x, K, V, w, H, hd, eps, base):
+    """One pre-norm block on one row in numpy fp64 (K, V: rows of the earlier positions, this row appended)."""
+    pos = len(K)
+    d = len(x)
+    h = rms(x.astype(np.float32), w["g1"], eps)
+    q, k, v = w["wq"] @ h, w["wk"] @ h, w["wv"] @ h
+
+    def rot(vec):
+        out = vec.copy()
+        half = hd // 2
+        for hh in range(H):
+            for i in range(half):
+                ang = pos * base ** (-2.0 * i / hd)
+                a, b = vec[hh * hd + i], vec[hh * hd + i + half]
+                out[hh * hd + i] = a * np.cos(ang) - b * np.sin(ang)
+                out[hh * hd + i + half] = b * np.cos(ang) + a * np.sin(ang)
+        return out
+
+    q, k = rot(q), rot(k)
+    K.append(k)
+    V.append(v)
+    Ka, Va = np.array(K), np.array(V)
+    a = np.zeros(d)
+    for hh in range(H):
+        sl = slice(hh * hd, (hh + 1) * hd)
+        p = scipy.special.softmax(Ka[:, sl] @ q[sl] / np.sqrt(hd))
+        a[sl] = p @ Va[:, sl]
+    x1 = x + w["wo"] @ a
+    h2 = rms(x1.astype(np.float32), w["g2"], eps)
+    gate, up = w["wg"] @ h2, w["wu"] @ h2
+    return x1 + w["wd"] @ (gate / (1.0 + np.exp(-gate)) * up)
+
+
+def _exit_w(m, e):
+    names = dict(g1=TensorKind.EXIT_ATTN_NORM, wq=TensorKind.EXIT_WQ, wk=TensorKind.EXIT_WK, wv=TensorKind.EXIT_WV,
+                 wo=TensorKind.EXIT_WO, g2=TensorKind.EXIT_MLP_NORM, wg=TensorKind.EXIT_WG, wu=TensorKind.EXIT_WU,
+                 wd=TensorKind.EXIT_WD)
+    return {k: m.tensor(v, e).astype(np.float64) for k, v in names.items()}
+
+
+def test_exit_layer_flags_and_tensor_list():
+    sh = variant(exit_layer=True)
+    assert sh.exit_flags == 8
+    kinds = [k for k, _ in model_tensor_list(sh)]
+    for k in (TensorKind.EXIT_ATTN_NORM, TensorKind.EXIT_WQ, TensorKind.EXIT_WK, TensorKind.EXIT_WV, TensorKind.EXIT_WO,
+              TensorKind.EXIT_MLP_NORM, TensorKind.EXIT_WG, TensorKind.EXIT_WU, TensorKind.EXIT_WD):
+        assert kinds.count(k) == 2
+    # an exit cannot have both an MLP of its own and a layer of its own (the layer already ends in an MLP)
+    with pytest.raises(ValueError):
+        O.Model(O.make_config(4, 128, 4, 32, 352, 1024, (1, 2), "f32", exit_flags=4 | 8))
+
+
+def test_exit_layer_matches_a_numpy_fp64_block_over_the_sequence():
+    """The exit's layer is an ordinary causal Transformer block over the hidden states at the exit's depth: against a
+    block written out in numpy fp64 (its own attention over its own keys and values), then the exit's norm and head."""
+    sh = variant(exit_layer=True)
+    m = build_model(sh, 11, gain_jitter=0.1)
+    n = 7
+    hid = np.ascontiguousarray(RNG.standard_normal((n, sh.d_model)), dtype=np.float32)
+    for e in range(2):
+        xo, ko, vo = m.exit_layer_sequence(e, hid)
+        w = _exit_w(m, e)
+        K, V = [], []
+        for t in range(n):
+            ref = _np_block(hid[t].astype(np.float64), K, V, w, sh.n_heads, sh.head_dim, sh.rms_eps, sh.rope_base)
+            assert np.max(np.abs(xo[t] - ref)) <= 2e-5 * np.max(np.abs(ref)), (e, t)
+        assert np.max(np.abs(ko - np.array(K))) <= 1e-5 * np.max(np.abs(K))
+        assert np.max(np.abs(vo - np.array(V))) <= 1e-5 * np.max(np.abs(V))
+        # the last position really attends to the earlier ones: changing position 0 changes it
+        hid2 = hid.copy()
+        hid2[0] += 1.0
+        xo2, _, _ = m.exit_layer_sequence(e, hid2)
+        assert np.max(np.abs(xo2[-1] - xo[-1])) > 1e-4
+        # ... and never to later ones (causal)
+        hid3 = hid.copy()
+        hid3[-1] += 1.0
+        xo3, _, _ = m.exit_layer_sequence(e, hid3)
+        assert np.array_equal(xo3[:-1], xo[:-1])
+        # what follows the layer is the exit's norm and output embedding
+        z, _ = m.head_row(e, xo[-1])
+        refz = m.tensor(TensorKind.EXIT_HEAD, e).astype(np.float64) @ rms(xo[-1], m.tensor(TensorKind.EXIT_NORM, e), sh.rms_eps)
+        assert np.max(np.abs(z - refz)) <= 1e-5 * np.max(np.abs(refz))
+
+
+def test_exit_layer_with_zero_output_projections_is_the_default_exit():
+    """W_o = 0 and W_d = 0 in the exit's layer: the layer adds nothing to x, so tokens, exit layers and the backbone's
+    cache are those of the model with the minimalistic exit, for both generators."""
+    sh = variant(exit_layer=True)
+    m = build_model(sh, 12, gain_jitter=0.1)
+    base = build_model(BASE, 12, gain_jitter=0.1)
+    for e in range(2):
+        m.set_tensor(TensorKind.EXIT_WO, e, np.zeros((sh.d_model, sh.d_model), np.float32))
+        m.set_tensor(TensorKind.EXIT_WD, e, np.zeros((sh.d_model, sh.d_ff), np.float32))
+    p = prompt_tokens(sh.vocab, 12, 9).numpy()
+    for tau in (0.0, 0.15, 0.4, 1.0):
+        assert all(np.array_equal(a, b) for a, b in zip(m.generate_g0(p, 14, tau), base.generate_g0(p, 14, tau)))
+        outs = []
+        for mod in (m, base):
+            st = O.State(mod, 64, 3)
+            diags = st.prefill(p)
+            tok = next((dg["argmax"] for dg in diags[:-1] if tau < 1.0 and dg["conf"] >= tau), diags[-1]["argmax"])
+            seq = [tok]
+            for _ in range(13):
+                tok, ex, _ = st.decode_step(tok, tau)
+                seq.append((tok, ex))
+            st.flush()
+            outs.append((seq, st.kv_read(3, 0, 12 + 13)))
+        assert outs[0][0] == outs[1][0]
+        assert np.array_equal(outs[0][1][0], outs[1][1][0]) and np.array_equal(outs[0][1][1], outs[1][1][1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cap", [0, 3])
+def test_exit_layer_kv_recomputation_equals_the_plain_definition(dtype, cap):
+    """G1 (cache, deferred tokens, the exit layers' own caches filled as positions pass their depth) against G0 (every
+    token from a cache-free forward, the exit's layer run over the whole sequence), bit for bit; and after a flush the
+    exit layers' caches equal the exit layer applied to the full-depth hidden states of everything generated."""
+    sh = variant(dtype=dtype, exit_layer=True)
+    m = build_model(sh, 13, gain_jitter=0.1)
+    p = prompt_tokens(sh.vocab, 14, 8).numpy()
+    mixes = set()
+    for tau in (0.0, 0.08, 0.25, 1.0):
+        t0, e0 = m.generate_g0(p, 18, tau, max_pending=cap)
+        st = O.State(m, 64, cap)
+        diags = st.prefill(p)
+        tok, ex = diags[-1]["argmax"], diags[-1]["layer"]
+        if tau < 1.0:
+            for dg in diags[:-1]:
+                if dg["conf"] >= tau:
+                    tok, ex = dg["argmax"], dg["layer"]
+                    break
+        toks, exits = [tok], [ex]
+        for _ in range(17):
+            tok, ex, _ = st.decode_step(tok, tau)
+            toks.append(tok)
+            exits.append(ex)
+        assert np.array_equal(t0, toks) and np.array_equal(e0, exits), (tau, t0, toks, e0, exits)
+        mixes.update(exits)
+        st.flush()
+        seq = np.concatenate([p, np.array(toks[:-1], np.int32)])
+        hid, _, _ = m.forward_sequence(seq)
+        for e, layer in enumerate(sh.exit_layers):
+            _, ke, ve = m.exit_layer_sequence(e, hid[layer])
+            kc, vc = st.kv_read(sh.n_layers + e, 0, len(seq))
+            assert np.array_equal(kc, ke) and np.array_equal(vc, ve), (tau, e)
+    assert len(mixes) >= 2

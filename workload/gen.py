@@ -130,9 +130,16 @@ class TensorKind(enum.IntEnum):
     EXIT_WG = 15        # [d_ff][d]  per exit
     EXIT_WU = 16        # [d_ff][d]
     EXIT_WD = 17        # [d][d_ff]
+    # a complete Transformer layer in the exit: the four kinds above are its MLP half, these its attention half
+    EXIT_ATTN_NORM = 18  # [d]     per exit
+    EXIT_WQ = 19         # [d][d]  per exit
+    EXIT_WK = 20
+    EXIT_WV = 21
+    EXIT_WO = 22
 
 
-_NORMS = (TensorKind.ATTN_NORM, TensorKind.MLP_NORM, TensorKind.EXIT_NORM, TensorKind.FINAL_NORM, TensorKind.EXIT_MLP_NORM)
+_NORMS = (TensorKind.ATTN_NORM, TensorKind.MLP_NORM, TensorKind.EXIT_NORM, TensorKind.FINAL_NORM, TensorKind.EXIT_MLP_NORM,
+          TensorKind.EXIT_ATTN_NORM)
 _HEADS = (TensorKind.EXIT_HEAD, TensorKind.FINAL_HEAD)
 
 
@@ -155,10 +162,12 @@ class ModelShape:
     exit_norm: bool = True                # RMSNorm in front of each exit's output embedding
     tie_embeddings: bool = False          # every exit and the final head use the input embedding matrix
     exit_mlp: bool = False                # each exit starts with an MLP block of its own (same form as a layer's)
+    exit_layer: bool = False              # each exit starts with a complete Transformer layer of its own (not with exit_mlp)
 
     @property
     def exit_flags(self) -> int:
-        return (0 if self.exit_norm else 1) | (2 if self.tie_embeddings else 0) | (4 if self.exit_mlp else 0)
+        return ((0 if self.exit_norm else 1) | (2 if self.tie_embeddings else 0) | (4 if self.exit_mlp else 0)
+                | (8 if self.exit_layer else 0))
 
     def tensor_shape(self, kind: TensorKind) -> Tuple[int, ...]:
         d, f, v = self.d_model, self.d_ff, self.vocab
@@ -169,7 +178,8 @@ class ModelShape:
             TensorKind.WD: (d, f), TensorKind.EXIT_NORM: (d,), TensorKind.EXIT_HEAD: (v, d),
             TensorKind.FINAL_NORM: (d,), TensorKind.FINAL_HEAD: (v, d),
             TensorKind.EXIT_MLP_NORM: (d,), TensorKind.EXIT_WG: (f, d), TensorKind.EXIT_WU: (f, d),
-            TensorKind.EXIT_WD: (d, f),
+            TensorKind.EXIT_WD: (d, f), TensorKind.EXIT_ATTN_NORM: (d,), TensorKind.EXIT_WQ: (d, d),
+            TensorKind.EXIT_WK: (d, d), TensorKind.EXIT_WV: (d, d), TensorKind.EXIT_WO: (d, d),
         }[TensorKind(kind)]
 
     def n_params(self) -> int:
@@ -218,7 +228,10 @@ def model_tensor_list(shape: ModelShape) -> List[Tuple[TensorKind, int]]:
                   TensorKind.MLP_NORM, TensorKind.WG, TensorKind.WU, TensorKind.WD):
             out.append((k, l))
     for i in range(len(shape.exit_layers)):
-        if shape.exit_mlp:
+        if shape.exit_layer:
+            for k in (TensorKind.EXIT_ATTN_NORM, TensorKind.EXIT_WQ, TensorKind.EXIT_WK, TensorKind.EXIT_WV, TensorKind.EXIT_WO):
+                out.append((k, i))
+        if shape.exit_mlp or shape.exit_layer:
             for k in (TensorKind.EXIT_MLP_NORM, TensorKind.EXIT_WG, TensorKind.EXIT_WU, TensorKind.EXIT_WD):
                 out.append((k, i))
         if shape.exit_norm:
@@ -243,7 +256,12 @@ def model_tensor(shape: ModelShape, kind: TensorKind, index: int, seed: int = 0,
     kind = TensorKind(kind)
     dims = shape.tensor_shape(kind)
     numel = math.prod(dims)
-    tid = int(kind) + 16 * index if kind < TensorKind.EXIT_MLP_NORM else 100000 + (int(kind) - 14) + 4 * index
+    if kind < TensorKind.EXIT_MLP_NORM:
+        tid = int(kind) + 16 * index
+    elif kind < TensorKind.EXIT_ATTN_NORM:
+        tid = 100000 + (int(kind) - 14) + 4 * index
+    else:
+        tid = 200000 + (int(kind) - 18) + 8 * index
     if kind in _NORMS:
         if gain_jitter == 0.0:
             return torch.ones(dims, dtype=torch.float32, device=device)
@@ -271,7 +289,9 @@ def write_weight_file(path: str, shape: ModelShape, seed: int = 0, max_positions
     (19 little-endian 32-bit fields: n_layers, d_model, n_heads, head_dim, d_ff, vocab, n_exits,
     exit_layers[8], dtype, max_positions, rms_eps, rope_base), then every tensor in canonical order as
     raw elements (matrices in the storage dtype, gains fp32).  A model whose exits are not the default
-    structure is written as "EEWT0002": the same with a 20th field, exit_flags, after rope_base."""
+    structure is written as "EEWT0002": the same with a 20th field, exit_flags, after rope_base.  Per exit the
+    canonical order is: the attention half of its Transformer layer (if any), its MLP (if any, alone or as the
+    layer's second half), its norm (if any), its output embedding (unless tied)."""
     import struct
 
     ex = list(shape.exit_layers) + [0] * (8 - len(shape.exit_layers))
