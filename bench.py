@@ -39,9 +39,9 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true", help="skip the threshold sweep of the workload")
     ap.add_argument("--refeed", action="store_true",
                     help="deferred tokens are fed again from the embedding (paper-literal) instead of resuming")
-    ap.add_argument("--exit-structure", default="default", choices=["default", "no_norm", "tied", "mlp", "all"],
+    ap.add_argument("--exit-structure", default="default", choices=["default", "no_norm", "tied", "mlp", "all", "layer"],
                     help="structure of the exits (Section 2): RMSNorm + own matrix (default), no norm, embeddings tied, "
-                         "an MLP in front of each exit, or all three")
+                         "an MLP in front of each exit, all three, or a complete Transformer layer in each exit")
     ap.add_argument("--no-prefill-bench", action="store_true", help="skip the timing of the prompt phase")
     ap.add_argument("--prefill-only", action="store_true", help="time the prompt phase only and print its figures")
     ap.add_argument("--pmc-run", action="store_true",
@@ -67,7 +67,10 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
     ids = list(range(B))
     d, F, V, L = shape.d_model, shape.d_ff, shape.vocab, shape.n_layers
     w_layer, w_head = (4 * d * d + 3 * d * F) * es, d * V * es
-    w_exit = w_head + (3 * d * F * es if shape.exit_mlp else 0)  # an exit with an MLP also streams that MLP
+    # an exit with an MLP also streams that MLP; one with a layer of its own streams that layer, and its q|k|v matrix
+    # even when the exit is not evaluated (every row that passes leaves its K and V there)
+    w_exit = w_head + (3 * d * F * es if shape.exit_mlp else 0) + (w_layer if shape.exit_layer else 0)
+    w_exit_kv_only = 3 * d * d * es if shape.exit_layer else 0
     seg_ends = list(shape.exit_layers) + [L]
     seg_of_layer = [next(k for k, se in enumerate(seg_ends) if l < se) for l in range(L)]
     seqs = ee.Sequences(L, pipeline=pipeline)
@@ -119,6 +122,7 @@ def generate(ee, gm, cache, prompts, tau, warmup, steps, shape, es, max_pending,
                     fl[sq][k] = p + 1
         if i >= warmup:
             nbytes += deepest * w_layer + sum(w_head if h == L else w_exit for h in heads)
+            nbytes += w_exit_kv_only * sum(1 for x in shape.exit_layers if x <= deepest and x not in heads)
     quant = None
     if confs:
         cf = np.stack(confs)  # [steps][B][n_exits+1]
@@ -251,7 +255,7 @@ def main():
         import dataclasses
         shape = dataclasses.replace(shape, exit_norm=args.exit_structure not in ("no_norm", "all"),
                                     tie_embeddings=args.exit_structure in ("tied", "all"),
-                                    exit_mlp=args.exit_structure in ("mlp", "all"))
+                                    exit_mlp=args.exit_structure in ("mlp", "all"), exit_layer=args.exit_structure == "layer")
     es = 2 if shape.dtype == "bf16" else 4
     B = wl.batch
     lens = [wl.prompt_len[0]] * B if wl.prompt_len[0] == wl.prompt_len[1] else \

@@ -68,6 +68,16 @@ enum {
  *                      x' = x + W_d (silu(W_g h) * (W_u h)), h = rmsnorm(x; g_mlp); its (norm and) output
  *                      embedding read x', the backbone's x is unchanged.  Tensors EE_T_EXIT_MLP_NORM,
  *                      EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD per exit, hidden width d_ff.
+ *   EE_EXIT_LAYER      exit i starts with a complete Transformer layer of its own (Section 2 and Appendix D.1 name it
+ *                      next to the MLP), the same block as a backbone layer with the exit's weights, applied to the
+ *                      hidden states at the exit's depth: its attention at position t runs over the K and V this
+ *                      layer produced at positions 0..t.  Its output feeds the exit's (norm and) output embedding;
+ *                      the backbone's x is unchanged.  Every position that passes the exit's depth leaves its K and
+ *                      V in that layer, whether or not the exit is evaluated for it (exits disabled, forced step,
+ *                      deferred row): the cache holds them as layer n_layers + i, filled together with the segment
+ *                      that ends at the exit.  Tensors EE_T_EXIT_ATTN_NORM, EE_T_EXIT_WQ/WK/WV/WO and, for its MLP
+ *                      half, EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG/WU/WD.  Not together with EE_EXIT_MLP (EE_ERR_CONFIG);
+ *                      ee_prefill_scored does not support it (EE_ERR_CONFIG).
  * Setting a tensor that the configured structure does not have returns EE_ERR_CONFIG.
  * Supported: d_model = n_heads*head_dim; head_dim in {32, 64, 128}; d_model, d_ff multiples of 32;
  * vocab a multiple of 32.
@@ -78,7 +88,7 @@ typedef struct {
     int32_t dtype;                              /* EE_F32 | EE_BF16: storage of matrices, embedding, KV */
     int32_t max_positions;                      /* longest sequence (prompt + generated) */
     float rms_eps, rope_base;
-    int32_t exit_flags;                         /* EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP; 0 = default */
+    int32_t exit_flags;                         /* EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP | EE_EXIT_LAYER; 0 = default */
     /* Tuning, not part of the model (and not stored in weight files); 0 = default for both. */
     int32_t prefill_rows;        /* rows per pass of the prompt-phase GEMM path: 0 = 2048, n > 0 = min(n, 8192) rounded to
                                     128 (at least 128), n < 0 = path off (prompts then go through the decode kernels) */
@@ -87,7 +97,7 @@ typedef struct {
                                     those kernel variants */
 } ee_config;
 
-enum { EE_EXIT_NO_NORM = 1, EE_TIE_EMBEDDINGS = 2, EE_EXIT_MLP = 4 };
+enum { EE_EXIT_NO_NORM = 1, EE_TIE_EMBEDDINGS = 2, EE_EXIT_MLP = 4, EE_EXIT_LAYER = 8 };
 
 /* Tensor kinds for ee_model_set_tensor (index = layer for per-layer kinds, exit number for EXIT_*). */
 enum {
@@ -109,7 +119,12 @@ enum {
     EE_T_EXIT_WG = 15,       /* [d_ff][d_model], per exit                           */
     EE_T_EXIT_WU = 16,       /* [d_ff][d_model]                                     */
     EE_T_EXIT_WD = 17,       /* [d_model][d_ff]                                     */
-    EE_T_KINDS = 18
+    EE_T_EXIT_ATTN_NORM = 18, /* [d_model] fp32 gain, per exit (EE_EXIT_LAYER only; 14..17 are that layer's MLP half) */
+    EE_T_EXIT_WQ = 19,        /* [d_model][d_model], per exit                        */
+    EE_T_EXIT_WK = 20,
+    EE_T_EXIT_WV = 21,
+    EE_T_EXIT_WO = 22,
+    EE_T_KINDS = 23
 };
 
 typedef struct ee_model ee_model;
@@ -141,7 +156,8 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
  * then every tensor in the order EMBED, per layer {ATTN_NORM, WQ, WK, WV, WO, MLP_NORM, WG, WU, WD},
  * per exit {EXIT_NORM, EXIT_HEAD}, FINAL_NORM, FINAL_HEAD, each as raw little-endian elements.
  * A model with exit_flags != 0 is stored as "EEWT0002": exit_flags follows rope_base in the config, and
- * the per-exit group is {EXIT_MLP_NORM, EXIT_WG, EXIT_WU, EXIT_WD (with EE_EXIT_MLP)}, {EXIT_NORM (unless
+ * the per-exit group is {EXIT_ATTN_NORM, EXIT_WQ, EXIT_WK, EXIT_WV, EXIT_WO (with EE_EXIT_LAYER)}, {EXIT_MLP_NORM,
+ * EXIT_WG, EXIT_WU, EXIT_WD (with EE_EXIT_MLP or EE_EXIT_LAYER)}, {EXIT_NORM (unless
  * EE_EXIT_NO_NORM)}, {EXIT_HEAD (unless tied)}; FINAL_HEAD is absent when tied.
  * dev_staging is a device scratch buffer of at least staging_bytes = the largest tensor. */
 int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weights, size_t weight_bytes,
@@ -221,7 +237,7 @@ int ee_kv_cache_bytes(const ee_model* m, int max_seqs, int64_t max_tokens_total,
 int ee_kv_cache_create(const ee_model* m, int max_seqs, int64_t max_tokens_total, int block_tokens,
                        int max_pending, void* dev_pool, size_t pool_bytes, ee_kv_cache** out);
 int ee_kv_cache_reset(ee_kv_cache* c, int seq); /* frees the sequence's blocks, clears its pending list */
-/* Number of positions whose K,V are present in `layer` (0-based).  After an early exit the layers above the exit
+/* Number of positions whose K,V are present in `layer` (0-based; n_layers + i: the layer inside exit i).  After an early exit the layers above the exit
  * lag behind the shallow ones (Section 4, "KV recomputation": the KV caches of the deep layers are missing for a
  * token that left early); the difference is what later steps, or a flush, fill in. */
 int ee_kv_cache_filled(const ee_kv_cache* c, int seq, int layer, int32_t* n_positions);

@@ -34,8 +34,9 @@ class ee_config(C.Structure):
                 ("prefill_rows", C.c_int32), ("gemm_min_workgroups", C.c_int32)]
 
 
-EE_EXIT_NO_NORM, EE_TIE_EMBEDDINGS, EE_EXIT_MLP = 1, 2, 4
-(EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD) = range(14, 18)
+EE_EXIT_NO_NORM, EE_TIE_EMBEDDINGS, EE_EXIT_MLP, EE_EXIT_LAYER = 1, 2, 4, 8
+(EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD, EE_T_EXIT_ATTN_NORM, EE_T_EXIT_WQ, EE_T_EXIT_WK, EE_T_EXIT_WV,
+ EE_T_EXIT_WO) = range(14, 23)
 
 
 class EeError(RuntimeError):

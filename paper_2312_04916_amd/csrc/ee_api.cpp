@@ -49,7 +49,8 @@ int check_config(const ee_config& c) {
     }
     if (c.max_positions < 1 || c.max_positions > (1 << 20)) return EE_ERR_CONFIG;
     if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return EE_ERR_CONFIG;
-    if (c.exit_flags & ~(EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP)) return EE_ERR_CONFIG;
+    if (c.exit_flags & ~(EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP | EE_EXIT_LAYER)) return EE_ERR_CONFIG;
+    if ((c.exit_flags & EE_EXIT_MLP) && (c.exit_flags & EE_EXIT_LAYER)) return EE_ERR_CONFIG;
     if (c.gemm_min_workgroups < 0) return EE_ERR_CONFIG;
     return EE_OK;
 }
@@ -57,7 +58,8 @@ int check_config(const ee_config& c) {
 struct WeightLayout {
     size_t embed, rope, gf, wf, ones, total;
     std::vector<size_t> g1, qkv, wo, g2, gu, wd, ge, we;
-    std::vector<size_t> gm, egu, ewd;  // exits with an MLP: its norm gain, gate|up, down
+    std::vector<size_t> gm, egu, ewd;  // exits with an MLP (or a whole layer): its norm gain, gate|up, down
+    std::vector<size_t> ga, eqkv, ewo; // exits with a whole layer: attention norm gain, q|k|v, o
 };
 
 WeightLayout weight_layout(const ee_config& c) {
@@ -79,7 +81,12 @@ WeightLayout weight_layout(const ee_config& c) {
     }
     const bool tied = c.exit_flags & EE_TIE_EMBEDDINGS;
     for (int i = 0; i < c.n_exits; ++i) {
-        if (c.exit_flags & EE_EXIT_MLP) {
+        if (c.exit_flags & EE_EXIT_LAYER) {
+            w.ga.push_back(take(d * 4));
+            w.eqkv.push_back(take(3 * d * d * es));
+            w.ewo.push_back(take(d * d * es));
+        }
+        if (c.exit_flags & (EE_EXIT_MLP | EE_EXIT_LAYER)) {
             w.gm.push_back(take(d * 4));
             w.egu.push_back(take(2 * F * d * es));
             w.ewd.push_back(take(d * F * es));
@@ -129,8 +136,8 @@ WorkspaceLayout workspace_layout(const ee_config& c, int max_rows, int max_seqs)
     };
     w.max_blocks_per_seq = c.max_positions / 32 + 1;
     w.upload = off;
-    // one descriptor per segment; with an MLP in the exits, one more per segment for the rows that MLP works on
-    w.descs = take(sizeof(SegDesc) * (EE_MAX_EXITS + 1) * ((c.exit_flags & EE_EXIT_MLP) ? 2 : 1));
+    // one descriptor per segment; with an MLP or a layer in the exits, one more per segment for the rows that works on
+    w.descs = take(sizeof(SegDesc) * (EE_MAX_EXITS + 1) * ((c.exit_flags & (EE_EXIT_MLP | EE_EXIT_LAYER)) ? 2 : 1));
     w.btab = take((size_t)max_seqs * w.max_blocks_per_seq * 4);
     w.tokens = take(EE_MAX_ROWS * 4);
     w.upload_bytes = off - w.upload;
@@ -223,13 +230,17 @@ struct ee_model {
         static const int per_layer[] = {EE_T_ATTN_NORM, EE_T_WQ, EE_T_WK, EE_T_WV, EE_T_WO, EE_T_MLP_NORM, EE_T_WG, EE_T_WU, EE_T_WD};
         for (int j = 0; j < 9; ++j)
             if (per_layer[j] == kind) return index >= 0 && index < L ? 3 + 2 * E + index * 9 + j : -1;
-        static const int per_exit[] = {EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD};
-        for (int j = 0; j < 4; ++j)
-            if (per_exit[j] == kind) return index >= 0 && index < E ? 3 + 2 * E + 9 * L + index * 4 + j : -1;
+        static const int per_exit[] = {EE_T_EXIT_MLP_NORM, EE_T_EXIT_WG, EE_T_EXIT_WU, EE_T_EXIT_WD, EE_T_EXIT_ATTN_NORM,
+                                       EE_T_EXIT_WQ,       EE_T_EXIT_WK, EE_T_EXIT_WV,       EE_T_EXIT_WO};
+        for (int j = 0; j < 9; ++j)
+            if (per_exit[j] == kind) return index >= 0 && index < E ? 3 + 2 * E + 9 * L + index * 9 + j : -1;
         return -1;
     }
-    int n_tensors() const { return 3 + 2 * cfg.n_exits + 9 * cfg.n_layers + 4 * cfg.n_exits; }
+    int n_tensors() const { return 3 + 2 * cfg.n_exits + 9 * cfg.n_layers + 9 * cfg.n_exits; }
     bool exit_mlp() const { return cfg.exit_flags & EE_EXIT_MLP; }
+    bool exit_layer() const { return cfg.exit_flags & EE_EXIT_LAYER; }
+    bool exit_block() const { return exit_mlp() || exit_layer(); }  // the exit works on copies of its rows
+    int n_kv_layers() const { return cfg.n_layers + (exit_layer() ? cfg.n_exits : 0); }  // exit i's layer caches as layer L+i
     int mlp_desc(int seg) const { return EE_MAX_EXITS + 1 + seg; }  // descriptor of the rows exit `seg`'s MLP works on
     bool exit_norm() const { return !(cfg.exit_flags & EE_EXIT_NO_NORM); }
     bool tied() const { return cfg.exit_flags & EE_TIE_EMBEDDINGS; }
@@ -242,12 +253,19 @@ struct ee_model {
             case EE_T_EXIT_MLP_NORM:
             case EE_T_EXIT_WG:
             case EE_T_EXIT_WU:
-            case EE_T_EXIT_WD: return exit_mlp();
+            case EE_T_EXIT_WD: return exit_block();
+            case EE_T_EXIT_ATTN_NORM:
+            case EE_T_EXIT_WQ:
+            case EE_T_EXIT_WK:
+            case EE_T_EXIT_WV:
+            case EE_T_EXIT_WO: return exit_layer();
             default: return true;
         }
     }
-    // gain folded into the operand that exit i reads first (its MLP's norm, else its own norm, else none)
-    const float* exit_in_gain(int i) const { return gain(exit_mlp() ? wl.gm[i] : (exit_norm() ? wl.ge[i] : wl.ones)); }
+    // gain folded into the operand that exit i reads first (its layer's or MLP's first norm, else its own norm, else none)
+    const float* exit_in_gain(int i) const {
+        return gain(exit_layer() ? wl.ga[i] : exit_mlp() ? wl.gm[i] : (exit_norm() ? wl.ge[i] : wl.ones));
+    }
     // gain in front of exit i's output embedding
     const float* exit_out_gain(int i) const { return gain(exit_norm() ? wl.ge[i] : wl.ones); }
 };
@@ -299,7 +317,7 @@ struct ee_kv_cache {
     float* ssq() const { return (float*)(pool + off_ssq); }
     int slot_of(int seq, int pos) const { return seq * S + pos % S; }
     int transient_slot(int r) const { return max_seqs * S + r; }
-    int exit_slot(int r) const { return max_seqs * S + m->max_rows + r; }  // copies an exit's MLP works on
+    int exit_slot(int r) const { return max_seqs * S + m->max_rows + r; }  // copies an exit's MLP or layer works on
     int n_pending(const SeqState& s) const { return plan::pending(s.filled.data(), (int)s.filled.size()); }
 };
 
@@ -312,7 +330,8 @@ namespace {
 int slots_per_seq(const ee_model* m, int max_pending) { return max_pending > 0 ? max_pending + 1 : m->max_rows; }
 
 size_t store_slots(const ee_model* m, int max_seqs, int max_pending) {
-    return (size_t)max_seqs * slots_per_seq(m, max_pending) + m->max_rows + (m->exit_mlp() ? m->max_seqs : 0);
+    // (an exit's MLP works on copies of the head rows, an exit's layer on copies of all the rows of the launch)
+    return (size_t)max_seqs * slots_per_seq(m, max_pending) + m->max_rows + (m->exit_layer() ? m->max_rows : m->exit_mlp() ? m->max_seqs : 0);
 }
 
 size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total, int BT, int max_pending, int* n_blocks,
@@ -321,7 +340,7 @@ size_t kv_pool_layout(const ee_model* m, int max_seqs, int64_t max_tokens_total,
     size_t es = esize(c.dtype), d = c.d_model;
     int nb = (int)((max_tokens_total + BT - 1) / BT) + max_seqs;
     size_t blk = 2 * (size_t)c.n_heads * BT * c.head_dim;
-    size_t off = align_up((size_t)c.n_layers * nb * blk * es);
+    size_t off = align_up((size_t)m->n_kv_layers() * nb * blk * es);
     size_t slots = store_slots(m, max_seqs, max_pending);
     size_t P = d / (16 * gemm_resid_tiles_per_wg());
     if (n_blocks) *n_blocks = nb;
@@ -394,88 +413,114 @@ int run_mlp(ee_model* m, ee_kv_cache* c, GemmCommon g, const char* w_gu, const c
     return EE_OK;
 }
 
+// The weights of one Transformer block: a backbone layer, or the layer an exit may contain.
+struct BlockW {
+    const char *qkv, *wo, *gu, *wd;
+    const float* g2;  // gain of the norm in front of the MLP half
+};
+
+// One block over the rows described by dev_desc(di): q,k,v = W_qkv rmsnorm(x; g1) with rotary embedding and the KV
+// write into cache layer kv_layer, attention, x += W_o a, the MLP half.  The rows' x.g1 operand is read from `a_first`
+// (a row-major operand store, indexed by the rows' slots), or from the packed copy when the rows are too many for LDS
+// (the caller has packed it).  kv_only: stop after the KV write (the rows only have to leave their K and V here).
+int run_block(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int kv_layer, const BlockW& w, void* a_first, bool kv_only,
+              const float* g_next, const float* g_head, bool pack_next, int max_ctx, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    const int d = cf.d_model, F = cf.d_ff, dt = cf.dtype;
+    SegDesc* dd = m->dev_desc(di);
+    const int32_t* xrow = (const int32_t*)((char*)dd + offsetof(SegDesc, xrow));
+    const bool pk_d = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, d);
+    const bool pk_F = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, F);
+    char* xg_pk = m->ws + m->wsl.xg_pk;
+    GemmCommon g{};
+    g.dtype = dt;
+    g.T = T;
+    g.min_wgs = cf.gemm_min_workgroups;
+    g.desc = dd;
+    g.desc_host = m->host_desc(di);
+    g.inv_d = 1.0f / (float)d;
+    g.eps = cf.rms_eps;
+    g.ssq_stride = c->ssq_stride;
+    g.ssq_n = c->ssq_stride;
+    // q,k,v = W_qkv rmsnorm(x; g1); rotary; KV write
+    g.W = w.qkv;
+    g.N = 3 * d;
+    g.K = d;
+    g.A = pk_d ? (void*)xg_pk : a_first;
+    g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
+    g.a_packed = pk_d;
+    g.lda = d;
+    g.arow = xrow;
+    g.ssq = c->ssq();
+    {
+        Timed t(m, EE_K_QKV, st);
+        HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, kv_layer, st));
+    }
+    if (kv_only) return EE_OK;
+    int att_ns = 0;
+    {
+        Timed t(m, EE_K_ATTN, st);
+        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, kv_layer, d,
+                                (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
+                                gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, pk_d, st));
+    }
+    // x += W_o a ; operand for the MLP norm
+    g.W = w.wo;
+    g.N = d;
+    g.K = d;
+    g.A = m->ws + m->wsl.attn;
+    g.a_lo = m->lo_rows(d);
+    g.a_packed = pk_d;
+    g.arow = nullptr;
+    g.ssq = nullptr;
+    if (att_ns > 0) {
+        g.att_part = (const float*)(m->ws + m->wsl.attn_part);
+        g.att_ns = att_ns;
+        g.att_H = cf.n_heads;
+        g.att_hd = cf.head_dim;
+    }
+    {
+        Timed t(m, EE_K_OPROJ, st);
+        HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), w.g2, nullptr, d, pk_d ? xg_pk : nullptr,
+                                 m->lo_rows(d), st));
+    }
+    g.att_part = nullptr;
+    // (the next block of this call reads the packed copy; across calls the residual store is the interface)
+    return run_mlp(m, c, g, w.gu, w.wd, c->xg(), xrow, pk_d, pk_F, g_next, g_head, pk_d && pack_next, st);
+}
+
 // ---- the per-layer launch sequence over the rows described by dev_desc(di)
 int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st) {
     const ee_config& cf = m->cfg;
-    const int d = cf.d_model, F = cf.d_ff, dt = cf.dtype;
+    const int d = cf.d_model, dt = cf.dtype;
     SegDesc* dd = m->dev_desc(di);
     const int32_t* xrow = (const int32_t*)((char*)dd + offsetof(SegDesc, xrow));
     // More rows than a workgroup can stage in LDS: the GEMMs then take their row operands from packed arrays
     // (dense rows of this launch in MFMA operand order) that the producing epilogues write, and the segment
     // starts by packing the rows' x.g operands out of the residual store.
     const bool pk_d = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, d);
-    const bool pk_F = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, F);
-    char* xg_pk = m->ws + m->wsl.xg_pk;
     if (pk_d && l0 < l1)
-        HIPCHK(launch_pack_rows(c->xg(), c->xs_lo, d, xrow, T, d, xg_pk, m->lo_rows(d), st));
+        HIPCHK(launch_pack_rows(c->xg(), c->xs_lo, d, xrow, T, d, m->ws + m->wsl.xg_pk, m->lo_rows(d), st));
     for (int l = l0; l < l1; ++l) {
-        GemmCommon g{};
-        g.dtype = dt;
-        g.T = T;
-        g.min_wgs = cf.gemm_min_workgroups;
-        g.desc = dd;
-        g.desc_host = m->host_desc(di);
-        g.inv_d = 1.0f / (float)d;
-        g.eps = cf.rms_eps;
-        g.ssq_stride = c->ssq_stride;
-        g.ssq_n = c->ssq_stride;
-        // q,k,v = W_qkv rmsnorm(x; g1); rotary; KV write
-        g.W = m->wbase + m->wl.qkv[l];
-        g.N = 3 * d;
-        g.K = d;
-        g.A = pk_d ? (void*)xg_pk : c->xg();
-        g.a_lo = pk_d ? m->lo_rows(d) : c->xs_lo;
-        g.a_packed = pk_d;
-        g.lda = d;
-        g.arow = xrow;
-        g.ssq = c->ssq();
-        {
-            Timed t(m, EE_K_QKV, st);
-            HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, l, st));
-        }
-        int att_ns = 0;
-        {
-            Timed t(m, EE_K_ATTN, st);
-            HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, l, d,
-                                (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
-                                gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, pk_d, st));
-        }
-        // x += W_o a ; operand for the MLP norm
-        g.W = m->wbase + m->wl.wo[l];
-        g.N = d;
-        g.K = d;
-        g.A = m->ws + m->wsl.attn;
-        g.a_lo = m->lo_rows(d);
-        g.a_packed = pk_d;
-        g.arow = nullptr;
-        g.ssq = nullptr;
-        if (att_ns > 0) {
-            g.att_part = (const float*)(m->ws + m->wsl.attn_part);
-            g.att_ns = att_ns;
-            g.att_H = cf.n_heads;
-            g.att_hd = cf.head_dim;
-        }
-        {
-            Timed t(m, EE_K_OPROJ, st);
-            HIPCHK(launch_gemm_resid(g, c->x(), c->xg(), nullptr, c->xs_lo, c->ssq(), m->gain(m->wl.g2[l]), nullptr, d,
-                                     pk_d ? xg_pk : nullptr, m->lo_rows(d), st));
-        }
-        g.att_part = nullptr;
+        const BlockW w{m->wbase + m->wl.qkv[l], m->wbase + m->wl.wo[l], m->wbase + m->wl.gu[l], m->wbase + m->wl.wd[l],
+                       m->gain(m->wl.g2[l])};
         const float* g_next = (l + 1 < cf.n_layers) ? m->gain(m->wl.g1[l + 1]) : m->gain(m->wl.gf);
         const float* g_head = nullptr;
         for (int i = 0; i < cf.n_exits; ++i)
             if (cf.exit_layers[i] == l + 1) g_head = m->exit_in_gain(i);
-        // (the next layer of this call reads the packed copy; across calls the residual store is the interface)
-        EECHK(run_mlp(m, c, g, m->wbase + m->wl.gu[l], m->wbase + m->wl.wd[l], c->xg(), xrow, pk_d, pk_F, g_next, g_head,
-                      pk_d && l + 1 < l1, st));
+        EECHK(run_block(m, c, di, T, n_qt, l, w, c->xg(), false, g_next, g_head, l + 1 < l1, max_ctx, st));
     }
     return EE_OK;
 }
 
 // Rows that exit `seg`'s MLP works on: copies, in slots of their own, of the head rows listed in host_desc(seg).
 // Call after the head rows of host_desc(seg) are set and before the descriptors are uploaded.
+void fill_exit_layer_desc(const ee_model* m, const ee_kv_cache* c, int seg, const SegDesc* d);
+
 void fill_mlp_desc(const ee_model* m, const ee_kv_cache* c, int seg) {
-    if (!m->exit_mlp() || seg >= m->cfg.n_exits) return;
+    if (seg >= m->cfg.n_exits) return;
+    if (m->exit_layer()) fill_exit_layer_desc(m, c, seg, m->host_desc(seg));
+    if (!m->exit_mlp()) return;
     const SegDesc* d = m->host_desc(seg);
     SegDesc* e = m->host_desc(m->mlp_desc(seg));
     e->T = d->n_head;
@@ -489,6 +534,39 @@ void fill_mlp_desc(const ee_model* m, const ee_kv_cache* c, int seg) {
         e->head_xrow[r] = c->exit_slot(r);
         e->head_slot[r] = d->head_slot[r];
     }
+}
+
+// Rows that exit `seg`'s own Transformer layer works on: copies, in slots of their own, of ALL the rows of `d` (each
+// leaves its K and V in the exit's layer), at the same positions; the head rows are the copies of d's head rows.
+void fill_exit_layer_desc(const ee_model* m, const ee_kv_cache* c, int seg, const SegDesc* d) {
+    SegDesc* e = m->host_desc(m->mlp_desc(seg));
+    if (e != d) *e = *d;  // positions, cache blocks, sequences and query tiles are those of the rows copied
+    for (int r = 0; r < d->T; ++r) e->xrow[r] = c->exit_slot(r);
+    for (int j = 0; j < d->n_head; ++j) {
+        int r = 0;
+        while (r < d->T && d->xrow[r] != d->head_xrow[j]) ++r;
+        e->head_xrow[j] = c->exit_slot(r < d->T ? r : 0);
+    }
+}
+
+// The Transformer layer inside exit `seg` over the rows whose residual-store slots are listed in the device array
+// `src` (host_desc(mlp_desc(seg)) lists their copies): the rows' x, first operand and sum-of-squares partials are copied to the exit's slots, every copy leaves
+// its K and V in the exit's cache layer, and, with_head, the whole layer runs on the copies so that the head rows'
+// x'.g (g: the exit's norm gain, or 1) stands in the first operand store at the copies' slots.
+int run_exit_layer(ee_model* m, ee_kv_cache* c, int seg, const int32_t* src, bool with_head, int max_ctx, hipStream_t st) {
+    const ee_config& cf = m->cfg;
+    const int d = cf.d_model, dt = cf.dtype, me = m->mlp_desc(seg);
+    const SegDesc* eh = m->host_desc(me);
+    const int T = eh->T;
+    if (T <= 0) return EE_OK;
+    const int32_t* dst = (const int32_t*)((char*)m->dev_desc(me) + offsetof(SegDesc, xrow));
+    HIPCHK(launch_copy_slots(dt, src, dst, T, d, c->x(), c->xgh(), c->xs_lo, c->ssq(), c->ssq_stride, st));
+    if (dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, d))
+        HIPCHK(launch_pack_rows(c->xgh(), c->xs_lo, d, dst, T, d, m->ws + m->wsl.xg_pk, m->lo_rows(d), st));
+    const BlockW w{m->wbase + m->wl.eqkv[seg], m->wbase + m->wl.ewo[seg], m->wbase + m->wl.egu[seg], m->wbase + m->wl.ewd[seg],
+                   m->gain(m->wl.gm[seg])};
+    return run_block(m, c, me, T, eh->n_qt, cf.n_layers + seg, w, c->xgh(), !with_head, m->exit_out_gain(seg), nullptr, false, max_ctx,
+                     st);
 }
 
 // head `hi` (exit number, or n_exits for the final head) on the rows listed in dev_desc(di).head_*
@@ -507,6 +585,11 @@ int run_head(ee_model* m, ee_kv_cache* c, int di, int hi, int n_head, int mode, 
     g.T = n_head;
     void* a_rows = fin ? c->xg() : c->xgh();  // x.g of the gain this head reads first
     const SegDesc* hd = m->host_desc(di);
+    if (!fin && m->exit_layer()) {  // run_exit_layer has left x'.g at the copies' slots
+        dd = m->dev_desc(m->mlp_desc(di));
+        hd = m->host_desc(m->mlp_desc(di));
+        a_rows = c->xg();
+    }
     if (!fin && m->exit_mlp()) {
         // The exit's MLP works on copies of the head rows, so that the backbone's rows stay as they are; its down
         // projection leaves x'.g (g: the exit's norm gain, or 1) in the first operand store at the copies' slots.
@@ -703,6 +786,9 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
             if (pp.on && s > 0 && pp.last_ev[s] >= 0 && pp.last_stream[s] != st)
                 HIPCHK(hipStreamWaitEvent(st, pp.pool[pp.last_ev[s]], 0));
             EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
+            if (m->exit_layer() && s < m->cfg.n_exits)
+                EECHK(run_exit_layer(m, c, s, (const int32_t*)((char*)m->dev_desc(s) + offsetof(SegDesc, xrow)), decode && hd->n_head > 0,
+                                     max_ctx, st));
             if (pp.on && s > 0) {
                 const int e = pp.next_ev++ % Pipeline::POOL;
                 HIPCHK(hipEventRecord(pp.pool[e], st));
@@ -807,6 +893,17 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
         di->head_xrow[0] = slot;
         di->head_slot[0] = i * EE_MAX_SEQS;
         fill_mlp_desc(m, c, i);
+        if (m->exit_layer() && i < cf.n_exits) {  // the exit's layer runs on a copy of the last position's row
+            SegDesc* e = m->host_desc(m->mlp_desc(i));
+            e->T = e->n_qt = e->n_head = 1;
+            e->pad = 0;
+            e->xrow[0] = e->head_xrow[0] = c->exit_slot(0);
+            e->pos[0] = e->qt_pos0[0] = n_tokens - 1;
+            e->kvblk[0] = s.blocks[(n_tokens - 1) / c->BT];
+            e->rseq[0] = e->row_qt[0] = e->qt_row0[0] = e->qt_seq[0] = 0;
+            e->qt_nq[0] = 1;
+            e->head_slot[0] = i * EE_MAX_SEQS;
+        }
     }
     EECHK(upload(m, st));
     const int32_t* bt = m->dev_btab();
@@ -876,6 +973,17 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                                            ssq_n, st));
                 }
             }
+            if (!fin && m->exit_layer()) {
+                // every position of the pass leaves its K and V in the exit's own layer (the q it also forms is not used)
+                g.W = m->wbase + m->wl.eqkv[sgi];
+                g.N = 3 * d;
+                g.K = d;
+                g.A_hi = xgh_hi;
+                g.A_lo = xgh_lo;
+                g.ssq = ssq;
+                Timed t(m, EE_K_QKV, st);
+                HIPCHK(launch_pf_qkv(g, q_hi, q_lo, (const float*)(m->wbase + m->wl.rope), c->geom, cf.n_layers + sgi, bt, p0, st));
+            }
             if (score_tok || score_conf || score_nll) {  // this segment's head on every position of the pass
                 const float* head_ssq = ssq;
                 const char *ha_hi = fin ? xg_hi : xgh_hi, *ha_lo = fin ? xg_lo : xgh_lo;
@@ -936,6 +1044,9 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                 HIPCHK(launch_pf_export_row(x + (size_t)(M - 1) * d, d, g_a, g_b, c->x() + (size_t)slot * d,
                                             (char*)c->xg() + (size_t)slot * d * es, (char*)c->xgh() + (size_t)slot * d * es, c->xs_lo,
                                             c->ssq() + (size_t)slot * c->ssq_stride, c->ssq_stride, st));
+                if (!fin && m->exit_layer())
+                    EECHK(run_exit_layer(m, c, sgi, (const int32_t*)((char*)m->dev_desc(sgi) + offsetof(SegDesc, head_xrow)), true,
+                                         n_tokens, st));
                 EECHK(run_head(m, c, sgi, sgi, 1, fin ? HEAD_EMIT : HEAD_RULE, threshold, st));
             }
         }
@@ -1072,6 +1183,11 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
         case EE_T_EXIT_WG: rc = mat(m->wl.egu[index], F, d, PACK_GATE); break;
         case EE_T_EXIT_WU: rc = mat(m->wl.egu[index], F, d, PACK_UP); break;
         case EE_T_EXIT_WD: rc = mat(m->wl.ewd[index], d, F, PACK_PLAIN); break;
+        case EE_T_EXIT_ATTN_NORM: rc = gain(m->wl.ga[index]); break;
+        case EE_T_EXIT_WQ: rc = mat(m->wl.eqkv[index], d, d, PACK_ROTARY); break;
+        case EE_T_EXIT_WK: rc = mat(m->wl.eqkv[index] + d * d * es, d, d, PACK_ROTARY); break;
+        case EE_T_EXIT_WV: rc = mat(m->wl.eqkv[index] + 2 * d * d * es, d, d, PACK_ROTARY); break;
+        case EE_T_EXIT_WO: rc = mat(m->wl.ewo[index], d, d, PACK_PLAIN); break;
         default: return EE_ERR_RANGE;
     }
     if (rc != EE_OK) return rc;
@@ -1143,7 +1259,12 @@ int ee_model_load(const ee_config* cfg, const char* weights_path, void* dev_weig
             rc = one(kinds[j], l, ns[j], (kinds[j] == EE_T_ATTN_NORM || kinds[j] == EE_T_MLP_NORM) ? 4 : es);
     }
     for (int i = 0; rc == EE_OK && i < cfg->n_exits; ++i) {
-        if (m->exit_mlp()) {
+        if (m->exit_layer()) {
+            rc = one(EE_T_EXIT_ATTN_NORM, i, d, 4);
+            for (int k : {EE_T_EXIT_WQ, EE_T_EXIT_WK, EE_T_EXIT_WV, EE_T_EXIT_WO})
+                if (rc == EE_OK) rc = one(k, i, d * d, es);
+        }
+        if (rc == EE_OK && m->exit_block()) {
             rc = one(EE_T_EXIT_MLP_NORM, i, d, 4);
             if (rc == EE_OK) rc = one(EE_T_EXIT_WG, i, F * d, es);
             if (rc == EE_OK) rc = one(EE_T_EXIT_WU, i, F * d, es);
@@ -1347,8 +1468,10 @@ int ee_kv_cache_reset(ee_kv_cache* c, int seq) {
 
 int ee_kv_cache_filled(const ee_kv_cache* c, int seq, int layer, int32_t* n_positions) {
     if (!c || !n_positions) return EE_ERR_ARG;
-    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= c->m->cfg.n_layers) return EE_ERR_RANGE;
-    *n_positions = c->seqs[seq].filled[c->m->seg_of_layer(layer)];
+    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= c->m->n_kv_layers()) return EE_ERR_RANGE;
+    // (the layer inside exit i is filled together with the segment that ends at that exit)
+    const int L = c->m->cfg.n_layers;
+    *n_positions = c->seqs[seq].filled[layer < L ? c->m->seg_of_layer(layer) : layer - L];
     return EE_OK;
 }
 
@@ -1362,7 +1485,7 @@ int ee_kv_cache_pending(const ee_kv_cache* c, int seq, int32_t* n_pending) {
 int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int pos0, int n, float* k_host, float* v_host,
                      void* stream) {
     if (!m || !c || !k_host || !v_host || c->m != m) return EE_ERR_ARG;
-    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= m->cfg.n_layers || pos0 < 0 || n < 0) return EE_ERR_RANGE;
+    if (seq < 0 || seq >= c->max_seqs || layer < 0 || layer >= m->n_kv_layers() || pos0 < 0 || n < 0) return EE_ERR_RANGE;
     const SeqState& s = c->seqs[seq];
     if (pos0 + n > (int)s.blocks.size() * c->BT) return EE_ERR_RANGE;
     if (n == 0) return EE_OK;
@@ -1441,7 +1564,7 @@ int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* token
                       int32_t* next_token, int32_t* exit_layer, float* conf, int32_t* pos_token, float* pos_conf, float* pos_nll,
                       void* stream) {
     if (!pos_token || !pos_conf) return EE_ERR_ARG;
-    if (m && m->wsl.pf_rows == 0) return EE_ERR_CONFIG;
+    if (m && (m->wsl.pf_rows == 0 || m->exit_layer())) return EE_ERR_CONFIG;
     return prefill_impl(m, c, seq, tokens, n_tokens, threshold, next_token, exit_layer, conf, pos_token, pos_conf, pos_nll, stream);
 }
 
@@ -1498,12 +1621,22 @@ int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, in
             di->head_slot[0] = i * EE_MAX_SEQS;
         }
         for (int i = 0; i < n_seg; ++i) fill_mlp_desc(m, c, i);
+        for (int i = 0; m->exit_layer() && i < cf.n_exits; ++i) {  // each exit's layer works on copies of the chunk's rows
+            fill_exit_layer_desc(m, c, i, d);
+            SegDesc* e = m->host_desc(m->mlp_desc(i));
+            e->n_head = 1;
+            e->head_xrow[0] = c->exit_slot(n - 1);
+            e->head_slot[0] = i * EE_MAX_SEQS;
+        }
         EECHK(upload(m, st));
         HIPCHK(launch_embed(cf.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), n, cf.d_model, m->gain(m->wl.g1[0]),
                             c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
         for (int sgi = 0; sgi < n_seg; ++sgi) {
             EECHK(run_layers(m, c, 0, n, d->n_qt, m->seg_begin(sgi), m->seg_end(sgi), p0 + n, st));
             bool fin = sgi == n_seg - 1;
+            if (!fin && m->exit_layer())
+                EECHK(run_exit_layer(m, c, sgi, (const int32_t*)((char*)m->dev_desc(0) + offsetof(SegDesc, xrow)),
+                                     last && threshold < 1.0f, p0 + n, st));
             if (last && (fin || threshold < 1.0f)) EECHK(run_head(m, c, sgi, sgi, 1, fin ? HEAD_EMIT : HEAD_RULE, threshold, st));
         }
         HIPCHK(hipStreamSynchronize(st));  // the pinned staging is rewritten by the next chunk
