@@ -684,8 +684,29 @@ void put_btab(const ee_model* m, const ee_kv_cache* c, int row, const SeqState& 
     std::copy(s.blocks.begin(), s.blocks.end(), bt);
 }
 
-int upload(ee_model* m, hipStream_t st) {
-    HIPCHK(launch_copy16(m->pinned_dev, m->ws + m->wsl.upload, m->wsl.upload_bytes, st));
+// What of the upload region a step needs: the descriptors of the model's segments, those of the exits' own rows (if
+// the exits work on copies), and the block tables and token ids behind them.
+void upload_ranges(const ee_model* m, uint32_t off16[3], uint32_t n16[3]) {
+    const WorkspaceLayout& w = m->wsl;
+    off16[0] = (uint32_t)((w.descs - w.upload) / 16);
+    n16[0] = (uint32_t)((sizeof(SegDesc) * m->n_seg() + 15) / 16);
+    off16[1] = (uint32_t)((w.descs - w.upload + sizeof(SegDesc) * (EE_MAX_EXITS + 1)) / 16);
+    n16[1] = m->exit_block() ? (uint32_t)((sizeof(SegDesc) * m->cfg.n_exits + 15) / 16) : 0;
+    off16[2] = (uint32_t)((w.btab - w.upload) / 16);
+    n16[2] = (uint32_t)((w.upload + w.upload_bytes - w.btab + 15) / 16);
+}
+
+// Descriptors, block tables and token ids of the step: staging area -> workspace; with embed_rows > 0 the same launch
+// looks up the rows of host_desc(0) in the embedding.
+int upload(ee_model* m, hipStream_t st, int embed_rows = 0, ee_kv_cache* c = nullptr) {
+    uint32_t off16[3], n16[3];
+    upload_ranges(m, off16, n16);
+    const SegDesc* d0 = m->host_desc(0);
+    const SegDesc* d0_dev = (const SegDesc*)(m->pinned_dev + (m->wsl.descs - m->wsl.upload));
+    HIPCHK(launch_step_begin(m->cfg.dtype, m->pinned_dev, m->ws + m->wsl.upload, off16, n16, embed_rows, m->host_tokens(), d0->xrow,
+                             (const int32_t*)(m->pinned_dev + (m->wsl.tokens - m->wsl.upload)), d0_dev->xrow,
+                             m->wbase + m->wl.embed, m->cfg.d_model, m->gain(m->wl.g1[0]), c ? c->x() : nullptr, c ? c->xg() : nullptr,
+                             c ? c->xs_lo : 0, c ? c->ssq() : nullptr, c ? c->ssq_stride : 0, st));
     return EE_OK;
 }
 
@@ -771,7 +792,9 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
             build_desc(m, c, m->host_desc(s), ss, s, decode, threshold, &rows[s]);
             if (rows[s] > m->max_rows) return EE_ERR_NOMEM;
         }
-        return upload(m, st);
+        // (the first upload of a step also looks up the rows that start at the embedding)
+        const bool embed = from == 0 && (decode || c->refeed) && m->host_desc(0)->T > 0;
+        return upload(m, st, embed ? m->host_desc(0)->T : 0, c);
     };
     EECHK(rebuild(0));
     int n_active = (int)ss.size();
@@ -779,9 +802,6 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     for (int s = 0; s < n_seg && n_active > 0; ++s) {
         const SegDesc* hd = m->host_desc(s);
         if (hd->T > 0) {
-            if (s == 0 && (decode || c->refeed))
-                HIPCHK(launch_embed(m->cfg.dtype, m->wbase + m->wl.embed, m->dev_tokens(), m->dev_desc(0), hd->T, m->cfg.d_model,
-                                    m->gain(m->wl.g1[0]), c->x(), c->xg(), c->xs_lo, c->ssq(), c->ssq_stride, st));
             // pipeline mode: the stage's previous token may still be on the other stream (segment 0 only ever runs here)
             if (pp.on && s > 0 && pp.last_ev[s] >= 0 && pp.last_stream[s] != st)
                 HIPCHK(hipStreamWaitEvent(st, pp.pool[pp.last_ev[s]], 0));

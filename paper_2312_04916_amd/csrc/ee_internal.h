@@ -55,12 +55,10 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
 // ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
 
-// bytes (rounded up to 16; both buffers are sized and aligned for that) from host-mapped pinned memory to the device
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
 hipError_t launch_copy_slots(int dtype, const int32_t* dev_src, const int32_t* dev_dst, int n, int d, float* x, void* xgh, size_t lo,
                              float* ssq, int ssq_stride, hipStream_t s);
-hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s);
 
 hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStream_t s);
 
@@ -68,6 +66,14 @@ hipError_t launch_rope_table(float* cs, int max_pos, int hd, float base, hipStre
 enum PackMode { PACK_PLAIN = 0, PACK_ROTARY = 1, PACK_GATE = 2, PACK_UP = 3 };
 hipError_t launch_pack(int dtype, const void* src, void* dst, int n_rows, int K, int mode, int hd, hipStream_t s);
 
+// The start of a decode step in one launch: up to three ranges (16-byte units from the start of the upload region) copied
+// from the host-mapped staging area to the workspace, and T rows looked up in the embedding (T = 0: the copy alone).
+// tok_host / slot_host: the rows' token ids and residual-store slots for the by-value path (T <= 16);
+// tok_mapped / slot_mapped: device views of the same arrays in the staging area.
+hipError_t launch_step_begin(int dtype, const void* staging_mapped, void* ws_region, const uint32_t off16[3], const uint32_t n16[3],
+                             int T, const int32_t* tok_host, const int32_t* slot_host, const int32_t* tok_mapped,
+                             const int32_t* slot_mapped, const void* embed, int d, const float* g_next, float* x, void* xg, size_t xg_lo,
+                             float* ssq, int ssq_stride, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens, const SegDesc* desc, int T, int d,
                         const float* g_next, float* x, void* xg, size_t xg_lo, float* ssq, int ssq_stride, hipStream_t s);
 

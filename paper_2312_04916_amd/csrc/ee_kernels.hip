@@ -89,20 +89,6 @@ hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_
     return hipGetLastError();
 }
 
-// Copy from host-mapped pinned memory into the workspace by a kernel: the step's descriptors reach the device
-// in stream order without a hand-over to the copy engine (whose completion signal costs the next kernel some
-// twenty microseconds of waiting).
-__global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
-}
-
-hipError_t launch_copy16(const void* src_mapped, void* dst, size_t bytes, hipStream_t s) {
-    const size_t n16 = (bytes + 15) / 16;
-    const unsigned grid = (unsigned)((n16 + 255) / 256 < 64 ? (n16 + 255) / 256 : 64);
-    EE_LAUNCH(copy16_kernel, dim3(grid ? grid : 1), dim3(256), s, (const u32x4*)src_mapped, (u32x4*)dst, n16);
-    return hipGetLastError();
-}
-
 // Plain read of a buffer, one KB per wave and load, eight loads in flight per wave: what this GPU's memory delivers
 // to a kernel that only reads.  The benchmark quotes the decode step against it next to the nominal peak.
 __global__ __launch_bounds__(512) void stream_read_kernel(const u32x4* __restrict__ p, size_t n_kb, int kb_per_wave, uint32_t* sink) {
@@ -285,6 +271,104 @@ hipError_t launch_embed(int dtype, const void* embed, const int32_t* dev_tokens,
     else
         EE_LAUNCH(embed_kernel<float>, dim3(T), dim3(256), s, (const float*)embed, dev_tokens, desc, d, g_next, x,
                            (float*)xg, xg_lo, ssq, ssq_stride);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// start of a decode step in one launch: the step's descriptors, block tables and token ids go from the host-mapped
+// staging area to the workspace (up to three ranges of it: the descriptors in use, those of the exits' own rows, the
+// tables), and the rows that start at the embedding are looked up.  The embedding workgroups take their token ids and
+// residual-store slots by value (up to 16 rows) or straight from the staging area, so they do not wait for the copy.
+// ------------------------------------------------------------------------------------------------
+struct StepBegin {
+    const u32x4* src;  // staging area (host memory, mapped)
+    u32x4* dst;        // the same region in the workspace
+    uint32_t off16[3], n16[3];  // ranges to copy, in 16-byte units from the start of the region
+    int n_copy_wgs;
+    int T;  // rows to embed
+    int has_v;
+    int32_t tok_v[16], slot_v[16];
+    const int32_t* tok_h;   // host-mapped token ids and slots of the rows (more than 16 rows)
+    const int32_t* slot_h;
+};
+
+template <typename ST>
+__global__ __launch_bounds__(256) void step_begin_kernel(StepBegin b, const ST* __restrict__ embed, int d, const float* __restrict__ g_next,
+                                                         float* __restrict__ x, ST* __restrict__ xg, size_t xg_lo, float* __restrict__ ssq,
+                                                         int ssq_stride) {
+    if ((int)blockIdx.x < b.n_copy_wgs) {
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < b.n16[r]; i += (uint32_t)b.n_copy_wgs * 256)
+                b.dst[b.off16[r] + i] = b.src[b.off16[r] + i];
+        return;
+    }
+    __shared__ float red[4];
+    const int r = (int)blockIdx.x - b.n_copy_wgs;
+    const int slot = b.has_v ? b.slot_v[r] : b.slot_h[r];
+    const int tok = b.has_v ? b.tok_v[r] : b.tok_h[r];
+    float s = 0.f;
+    for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {  // d is a multiple of 32
+        float v[8];
+        if constexpr (sizeof(ST) == 2) {
+            const bf16x8 e = *(const bf16x8*)(embed + (size_t)tok * d + i);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (float)e[j];
+        } else {
+            const f32x4 e0 = *(const f32x4*)(embed + (size_t)tok * d + i), e1 = *(const f32x4*)(embed + (size_t)tok * d + i + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[j] = e0[j];
+                v[4 + j] = e1[j];
+            }
+        }
+        const f32x4 g0 = *(const f32x4*)(g_next + i), g1 = *(const f32x4*)(g_next + i + 4);
+        *(f32x4*)(x + (size_t)slot * d + i) = f32x4{v[0], v[1], v[2], v[3]};
+        *(f32x4*)(x + (size_t)slot * d + i + 4) = f32x4{v[4], v[5], v[6], v[7]};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            store_split<ST>(xg + (size_t)slot * d + i + j, xg_lo, v[j] * (j < 4 ? g0[j] : g1[j - 4]));
+            s += v[j] * v[j];
+        }
+    }
+    // sum of squares: lanes of a wave through a fixed butterfly, then the four waves in order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    const float tot = ((red[0] + red[1]) + red[2]) + red[3];
+    for (int i = threadIdx.x; i < ssq_stride; i += 256) ssq[(size_t)slot * ssq_stride + i] = (i == 0) ? tot : 0.f;
+}
+
+hipError_t launch_step_begin(int dtype, const void* staging_mapped, void* ws_region, const uint32_t off16[3], const uint32_t n16[3],
+                             int T, const int32_t* tok_host, const int32_t* slot_host, const int32_t* tok_mapped,
+                             const int32_t* slot_mapped, const void* embed, int d, const float* g_next, float* x, void* xg, size_t xg_lo,
+                             float* ssq, int ssq_stride, hipStream_t s) {
+    StepBegin b{};
+    b.src = (const u32x4*)staging_mapped;
+    b.dst = (u32x4*)ws_region;
+    uint32_t total = 0;
+    for (int r = 0; r < 3; ++r) {
+        b.off16[r] = off16[r];
+        b.n16[r] = n16[r];
+        total += n16[r];
+    }
+    b.n_copy_wgs = (int)((total + 255) / 256 < 32 ? (total + 255) / 256 : 32);
+    if (b.n_copy_wgs < 1) b.n_copy_wgs = 1;
+    b.T = T;
+    b.has_v = T <= 16;
+    for (int r = 0; r < T && r < 16; ++r) {
+        b.tok_v[r] = tok_host[r];
+        b.slot_v[r] = slot_host[r];
+    }
+    b.tok_h = tok_mapped;
+    b.slot_h = slot_mapped;
+    if (dtype == EE_BF16)
+        EE_LAUNCH(step_begin_kernel<__bf16>, dim3(b.n_copy_wgs + T), dim3(256), s, b, (const __bf16*)embed, d, g_next, x, (__bf16*)xg, xg_lo, ssq,
+                  ssq_stride);
+    else
+        EE_LAUNCH(step_begin_kernel<float>, dim3(b.n_copy_wgs + T), dim3(256), s, b, (const float*)embed, d, g_next, x, (float*)xg, (size_t)0, ssq,
+                  ssq_stride);
     return hipGetLastError();
 }
 
@@ -574,7 +658,7 @@ __host__ __device__ inline int a_lds_row_stride(int K) { return 2 * K + 32; }  /
 constexpr int ATT_MAX_SPLITS = 16;
 __host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
 
-template <int KS, bool ATT, typename Pre>
+template <int KS, int ATT, typename Pre>
 __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int tile, GemmSmem<KS, 1>& sm, Pre pre) {
     extern __shared__ __attribute__((aligned(16))) unsigned char ee_dyn_smem[];
     __bf16* abuf = (__bf16*)ee_dyn_smem;
@@ -618,10 +702,11 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
             const int qt = rq >> 4, qq = rq & 15;
             const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * NS * pstride;
             // every load of every split goes out before the first is used: one memory round trip in all
-            float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
-            f32x4 o0[ATT_MAX_SPLITS], o1[ATT_MAX_SPLITS];
+            constexpr int MAXS = ATT > 0 ? ATT : 1;
+            float ms[MAXS], ls[MAXS];
+            f32x4 o0[MAXS], o1[MAXS];
 #pragma unroll
-            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp) {
+            for (int sp = 0; sp < MAXS; ++sp) {
                 if (sp < NS) {  // (uniform over the workgroup)
                     const float* ps = pb + (size_t)sp * pstride;
                     ms[sp] = ps[qq];
@@ -632,13 +717,13 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
             }
             float M = -INFINITY;
 #pragma unroll
-            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp)
+            for (int sp = 0; sp < MAXS; ++sp)
                 if (sp < NS) M = fmaxf(M, ms[sp]);
             float O[8], L = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) O[e] = 0.f;
 #pragma unroll
-            for (int sp = 0; sp < ATT_MAX_SPLITS; ++sp) {
+            for (int sp = 0; sp < MAXS; ++sp) {
                 if (sp >= NS || ms[sp] == -INFINITY) continue;
                 const float f = expf(ms[sp] - M);
 #pragma unroll
@@ -743,7 +828,7 @@ __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile, G
 
 // `pre` runs once the first weight loads are in flight: the place to fetch what the epilogue needs.
 // Leaves tile g of the workgroup (g < G, tile index tile0 + g) in sm.out[g].
-template <typename ST, int KS, int MT, bool ALDS, int G, typename Pre, bool ATT = false>
+template <typename ST, int KS, int MT, bool ALDS, int G, typename Pre, int ATT = 0>
 __device__ __forceinline__ void gemm_mainloop(const GemmArgs& a, int tile0, GemmSmem<KS, MT, G>& sm, Pre pre) {
     if constexpr (G > 1) {
         static_assert(sizeof(ST) == 2 && !ALDS, "several tiles per workgroup: bf16 register path only");
@@ -859,7 +944,7 @@ __device__ __forceinline__ int resid_slot(const ResidArgs<ST>& e, int m) {
     return e.has_v ? e.xrow_v[m] : e.xrow[m];
 }
 
-template <typename ST, int KS, int MT, bool ALDS, bool ATT, int G>
+template <typename ST, int KS, int MT, bool ALDS, int ATT, int G>
 __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidArgs<ST>& e) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int tile0 = blockIdx.x * G;
@@ -913,13 +998,13 @@ __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidAr
 
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_resid_kernel(GemmArgs a, ResidArgs<ST> e) {
-    gemm_resid_body<ST, KS, MT, ALDS, false, G>(a, e);
+    gemm_resid_body<ST, KS, MT, ALDS, 0, G>(a, e);
 }
 
 // O projection whose input rows are merged from the attention kernel's split partials while being staged
-template <int KS>
+template <int KS, int MAXS>
 __global__ __launch_bounds__(KS * 64) void gemm_resid_att_kernel(GemmArgs a, ResidArgs<__bf16> e) {
-    gemm_resid_body<__bf16, KS, 1, true, true, 1>(a, e);
+    gemm_resid_body<__bf16, KS, 1, true, MAXS, 1>(a, e);
 }
 
 // ---- epilogue 3: SwiGLU.  Tile j: columns 0..7 = gate features 8j.., columns 8..15 = the matching up features
@@ -1257,8 +1342,9 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
             // (at most 8 waves: the merge holds every split's partials in registers at once)
             const int ks = ks_of(c) == 4 ? 4 : 8;
             dim3 grid(c.N / 16), block(ks * 64);
-            if (ks == 4) EE_LAUNCH_LDS(gemm_resid_att_kernel<4>, grid, block, sm, s, a, e);
-            else EE_LAUNCH_LDS(gemm_resid_att_kernel<8>, grid, block, sm, s, a, e);
+            if (ks == 4) EE_LAUNCH_LDS((gemm_resid_att_kernel<4, ATT_MAX_SPLITS>), grid, block, sm, s, a, e);
+            else if (c.att_ns <= 8) EE_LAUNCH_LDS((gemm_resid_att_kernel<8, 8>), grid, block, sm, s, a, e);
+            else EE_LAUNCH_LDS((gemm_resid_att_kernel<8, ATT_MAX_SPLITS>), grid, block, sm, s, a, e);
         } else if (c.dtype == EE_BF16) {
             // (the packed copy of a later pass starts r0/16 row groups further on)
             __bf16* pk = xg_pk ? (__bf16*)xg_pk + (size_t)(r0 / 16) * (d / 32) * 512 : nullptr;
