@@ -7,6 +7,7 @@ into numbers.  See ``gen.py``.
 from .gen import (  # noqa: F401
     CONFIGS,
     ModelShape,
+    TABLE4_EXIT_HEAD_SCALE,
     TensorKind,
     gaussian_tensor,
     model_tensor,
