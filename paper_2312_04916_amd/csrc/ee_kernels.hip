@@ -1094,21 +1094,31 @@ __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __re
                                                          const SegDesc* __restrict__ desc, int tag) {
     __shared__ float redm[512], reds[512];
     __shared__ int redi[512];
-    // one workgroup per row; thread t folds workgroups t, t+512, ... in ascending order, then a fixed tree over the threads
+    // one workgroup per row; thread t folds workgroups t, t+512, ... in ascending order (eight loads in flight at a
+    // time: the partials come from the other XCDs, so each load is a trip to memory), then a fixed tree over the
+    // threads: through LDS down to one wave, by lane shuffles inside it (the same pairs either way)
     const int m = blockIdx.x;
     if (m >= T) return;
+    const int out_slot = desc->head_slot[m];  // (requested now, used at the very end)
     {
         float mx = -INFINITY, s = 0.f;
         int ix = 0x7fffffff;
-        for (int w = threadIdx.x; w < n_wg; w += 512) {
-            HeadPartial p = partials[(size_t)w * EE_MAX_SEQS + m];
-            merge_partial(mx, s, ix, p.max, p.sum, p.idx);
+        for (int w0 = threadIdx.x; w0 < n_wg; w0 += 8 * 512) {
+            HeadPartial p[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int w = w0 + j * 512;
+                if (w < n_wg) p[j] = partials[(size_t)w * EE_MAX_SEQS + m];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (w0 + j * 512 < n_wg) merge_partial(mx, s, ix, p[j].max, p[j].sum, p[j].idx);
         }
         redm[threadIdx.x] = mx;
         reds[threadIdx.x] = s;
         redi[threadIdx.x] = ix;
         __syncthreads();
-        for (int o = 256; o > 0; o >>= 1) {
+        for (int o = 256; o >= 64; o >>= 1) {
             if ((int)threadIdx.x < o) {
                 float m1 = redm[threadIdx.x], s1 = reds[threadIdx.x];
                 int i1 = redi[threadIdx.x];
@@ -1121,6 +1131,20 @@ __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __re
             }
             __syncthreads();
         }
+        if (threadIdx.x < 64) {
+            float m1 = redm[threadIdx.x], s1 = reds[threadIdx.x];
+            int i1 = redi[threadIdx.x];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float m2 = __shfl_down(m1, o), s2 = __shfl_down(s1, o);
+                const int i2 = __shfl_down(i1, o);
+                if ((int)threadIdx.x < o && (s2 > 0.f || m2 > -INFINITY)) merge_partial(m1, s1, i1, m2, s2, i2);
+            }
+            if (threadIdx.x == 0) {
+                reds[0] = s1;
+                redi[0] = i1;
+            }
+        }
         if (threadIdx.x == 0) {
             float conf = 1.0f / reds[0];
             HeadResult r;
@@ -1130,7 +1154,7 @@ __global__ __launch_bounds__(512) void head_merge_kernel(const HeadPartial* __re
             r.pad = 0;
             // The results live in host memory that the host polls: the tag goes last, after a system-wide
             // fence, so that a host that sees the tag sees the rest.
-            HeadResult* dst = results + desc->head_slot[m];
+            HeadResult* dst = results + out_slot;
             dst->token = r.token;
             dst->conf = r.conf;
             dst->fired = r.fired;
