@@ -13,6 +13,7 @@
 #include "ee_launch.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace ee {
 
@@ -498,7 +499,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16(const GemmArgs& a, int tile, 
     for (int u = 0; u < D; ++u)
         if (u < n) fill_a(u, u);
     rms_scales<MT>(a, sm.rs);
-    pre();
+    pre(std::false_type{});
     const int full = n / D, rem = n - full * D;
     for (int gI = 0; gI + 1 < full; ++gI) {  // steady state: every refill is in range
 #pragma unroll
@@ -602,7 +603,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_multi(const GemmArgs& a, int 
     for (int u = 0; u < D; ++u)
         if (u < n) fill_a(u, u);
     rms_scales<MT>(a, sm.rs);
-    pre();
+    pre(std::false_type{});
     const int full = n / D, rem = n - full * D;
     for (int gI = 0; gI + 1 < full; ++gI) {
 #pragma unroll
@@ -655,6 +656,11 @@ __device__ __forceinline__ void gemm_mainloop_bf16_multi(const GemmArgs& a, int 
 constexpr int A_LDS_MAX_BYTES = 72 * 1024;
 __host__ __device__ inline int a_lds_row_stride(int K) { return 2 * K + 32; }  // elements; +64 B staggers the banks of two rows
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global load of
+// the wave (its release fence covers vector memory as a whole), which is not wanted where a ring of weight loads is
+// meant to stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 constexpr int ATT_MAX_SPLITS = 16;
 __host__ __device__ inline int att_part_stride(int hd) { return 32 + 16 * hd; }
 
@@ -667,54 +673,97 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
     const int KT = a.KT, K = a.K;
     const int kt0 = (int)(((long)ks * KT) / KS), kt1 = (int)(((long)(ks + 1) * KT) / KS);
     const u32x4* wp = (const u32x4*)a.W + ((size_t)tile * KT + kt0) * 64 + lane;
-    constexpr int D = 12;
+    // (8 waves: the single-row path below keeps a row chunk next to the ring inside 80 registers per lane)
+    constexpr int D = (KS == 8 && ATT == 0) ? 11 : 12;
     u32x4 w[D];
     const int n = kt1 - kt0;
     auto fill = [&](int u, int t) { w[u] = __builtin_nontemporal_load(wp + (size_t)t * 64); };
-    // Sum-of-squares partials of the rows: wave w takes rows w, w + KS.  The loads go out first, ahead of the
-    // weight stream, and are reduced after the rows have been staged.
-    constexpr int RPW = (16 + KS - 1) / KS;  // rows per wave
-    float ssq_part[RPW];
-#pragma unroll
-    for (int j = 0; j < RPW; ++j) {
-        const int m = ks + j * KS;
-        float sp = 0.f;
-        if (a.ssq != nullptr && m < a.T) {
-            const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
-            for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
-        }
-        ssq_part[j] = sp;
-    }
-#pragma unroll
-    for (int u = 0; u < D; ++u)
-        if (u < n) fill(u, u);
     const int rstride = a_lds_row_stride(K);
     const int cpr = K / 8;  // 16-byte chunks per row and term
-    if constexpr (ATT) {
-        // The rows are attention outputs that still lie as per-split partials (max, sum, unnormalised
-        // output): merge the splits here, in split order, exactly as attn_merge_kernel does, and split the
-        // result into its two bf16 terms.  Saves a launch between attention and this projection.
-        const int pstride = att_part_stride(a.att_hd), NS = a.att_ns;
-        for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
-            const int m = c / cpr, k8 = c - m * cpr;
+    constexpr int RC = KS == 16 ? 2 : 1;  // 16-byte chunks of a row that a thread of the single-row path holds
+    constexpr int MAXS = ATT > 0 ? ATT : 1;
+    // ---- single row whose indices all travel in the kernel arguments (the batch-1 decode step).
+    // Everything the workgroup needs before its first MFMA (sum-of-squares partials, the row or the attention
+    // partials it is merged from, the epilogue's operands) is requested FIRST, then the ring, and nothing waits in
+    // between: loads return in issue order, so the small loads are back after one memory latency and the ring
+    // streams behind them.  For the compiler to place exactly those waits the path has no load in a loop, none that
+    // hangs off another load and none through a pointer it cannot prove global (after such loads it waits for
+    // everything outstanding), the ring is filled unconditionally (a surplus slot repeats a tile), and the barrier
+    // that publishes the staged row orders LDS traffic only.  Per-workgroup time stamps had shown the ring going out
+    // 2-4 us after kernel entry and every wave sitting at the barrier until its whole burst had arrived.
+    const bool one_row = a.has_row_v && a.T == 1 && a.ssq_n <= 512 && cpr <= RC * KS * 64 && (ATT == 0 || (ATT <= 8 && a.att_ns <= MAXS));
+    if (one_row) {
+        const int slot = a.arow_v[0];
+        // sum-of-squares partials of the row: wave 0, eight per lane (indices clamped, surplus values dropped)
+        float sv[8];
+        const bool do_ssq = a.ssq != nullptr && ks == 0;
+        if (do_ssq) {
+            const float* p = a.ssq + (size_t)slot * a.ssq_stride;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = lane + 64 * j;
+                sv[j] = p[i < a.ssq_n ? i : a.ssq_n - 1];
+            }
+        }
+        u32x4 rh[RC], rl[RC];
+        float ms[MAXS], ls[MAXS];
+        f32x4 o0[MAXS], o1[MAXS];
+        if constexpr (ATT == 0) {
+            const __bf16* srow = (const __bf16*)a.A + (size_t)slot * a.lda;
+#pragma unroll
+            for (int j = 0; j < RC; ++j) {
+                int k8 = threadIdx.x + j * KS * 64;
+                if (k8 >= cpr) k8 = cpr - 1;
+                rh[j] = *(const u32x4*)(srow + k8 * 8);
+                rl[j] = *(const u32x4*)(srow + a.a_lo + k8 * 8);
+            }
+        } else {
+            // the row still lies as the attention kernel's per-split partials: this thread's chunk of every split
+            int k8 = threadIdx.x;
+            if (k8 >= cpr) k8 = cpr - 1;
             const int h = (k8 * 8) / a.att_hd, cc = (k8 * 8) % a.att_hd;
-            const int rq = a.has_row_v ? a.rq_v[m] : a.att_desc->row_qt[m];
+            const int rq = a.rq_v[0];
             const int qt = rq >> 4, qq = rq & 15;
-            const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * NS * pstride;
-            // every load of every split goes out before the first is used: one memory round trip in all
-            constexpr int MAXS = ATT > 0 ? ATT : 1;
-            float ms[MAXS], ls[MAXS];
-            f32x4 o0[MAXS], o1[MAXS];
+            const int pstride = att_part_stride(a.att_hd);
+            const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * a.att_ns * pstride;
 #pragma unroll
             for (int sp = 0; sp < MAXS; ++sp) {
-                if (sp < NS) {  // (uniform over the workgroup)
-                    const float* ps = pb + (size_t)sp * pstride;
-                    ms[sp] = ps[qq];
-                    ls[sp] = ps[16 + qq];
-                    o0[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc);
-                    o1[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc + 4);
+                const float* ps = pb + (size_t)(sp < a.att_ns ? sp : a.att_ns - 1) * pstride;
+                ms[sp] = ps[qq];
+                ls[sp] = ps[16 + qq];
+                o0[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc);
+                o1[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc + 4);
+            }
+        }
+        pre(std::true_type{});
+#pragma unroll
+        for (int u = 0; u < D; ++u) fill(u, u < n ? u : (n > 0 ? n - 1 : 0));
+        // r = 1/sqrt(mean(x^2)+eps): lane sums in index order, a fixed butterfly
+        if (ks == 0) {
+            float r = 1.f;
+            if (do_ssq) {
+                float sp = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (lane + 64 * j < a.ssq_n) sp += sv[j];
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+                r = 1.0f / sqrtf(sp * a.inv_d + a.eps);
+            }
+            if (lane < 16) sm.rs[lane] = lane == 0 ? r : 1.f;
+        }
+        if constexpr (ATT == 0) {
+#pragma unroll
+            for (int j = 0; j < RC; ++j) {
+                const int k8 = threadIdx.x + j * KS * 64;
+                if (k8 < cpr) {
+                    *(u32x4*)(abuf + k8 * 8) = rh[j];
+                    *(u32x4*)(abuf + K + k8 * 8) = rl[j];
                 }
             }
+        } else {
+            // merge of the splits, in split order, exactly as attn_merge_kernel does; two bf16 terms
+            const int NS = a.att_ns;
             float M = -INFINITY;
 #pragma unroll
             for (int sp = 0; sp < MAXS; ++sp)
@@ -741,31 +790,108 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
                 hv[e] = hi;
                 lv[e] = (__bf16)(v - (float)hi);
             }
-            *(bf16x8*)(abuf + (size_t)m * rstride + k8 * 8) = hv;
-            *(bf16x8*)(abuf + (size_t)m * rstride + K + k8 * 8) = lv;
-        }
-    } else {
-        for (int m = 0; m < a.T; ++m) {  // (row by row: the row's slot is uniform, a scalar load at most)
-            const __bf16* srow = (const __bf16*)a.A + (size_t)gemm_slot(a, m) * a.lda;
-            for (int k8 = threadIdx.x; k8 < cpr; k8 += blockDim.x) {
-                u32x4 h = *(const u32x4*)(srow + k8 * 8);
-                u32x4 l = *(const u32x4*)(srow + a.a_lo + k8 * 8);
-                *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
-                *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+            if ((int)threadIdx.x < cpr) {
+                *(bf16x8*)(abuf + threadIdx.x * 8) = hv;
+                *(bf16x8*)(abuf + K + threadIdx.x * 8) = lv;
             }
         }
+        lds_barrier();
+    } else {
+        // ---- general prologue: the ring first, then whatever has to be looked up
+        // Sum-of-squares partials of the rows: wave w takes rows w, w + KS.  The loads go out first, ahead of the
+        // weight stream, and are reduced after the rows have been staged.
+        constexpr int RPW = (16 + KS - 1) / KS;  // rows per wave
+        float ssq_part[RPW];
+    #pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int m = ks + j * KS;
+            float sp = 0.f;
+            if (a.ssq != nullptr && m < a.T) {
+                const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
+                for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
+            }
+            ssq_part[j] = sp;
+        }
+    #pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (u < n) fill(u, u);
+        if constexpr (ATT) {
+            // The rows are attention outputs that still lie as per-split partials (max, sum, unnormalised
+            // output): merge the splits here, in split order, exactly as attn_merge_kernel does, and split the
+            // result into its two bf16 terms.  Saves a launch between attention and this projection.
+            const int pstride = att_part_stride(a.att_hd), NS = a.att_ns;
+            for (int c = threadIdx.x; c < a.T * cpr; c += blockDim.x) {
+                const int m = c / cpr, k8 = c - m * cpr;
+                const int h = (k8 * 8) / a.att_hd, cc = (k8 * 8) % a.att_hd;
+                const int rq = a.has_row_v ? a.rq_v[m] : a.att_desc->row_qt[m];
+                const int qt = rq >> 4, qq = rq & 15;
+                const float* pb = a.att_part + (size_t)(qt * a.att_H + h) * NS * pstride;
+                // every load of every split goes out before the first is used: one memory round trip in all
+                constexpr int MAXS = ATT > 0 ? ATT : 1;
+                float ms[MAXS], ls[MAXS];
+                f32x4 o0[MAXS], o1[MAXS];
+    #pragma unroll
+                for (int sp = 0; sp < MAXS; ++sp) {
+                    if (sp < NS) {  // (uniform over the workgroup)
+                        const float* ps = pb + (size_t)sp * pstride;
+                        ms[sp] = ps[qq];
+                        ls[sp] = ps[16 + qq];
+                        o0[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc);
+                        o1[sp] = *(const f32x4*)(ps + 32 + qq * a.att_hd + cc + 4);
+                    }
+                }
+                float M = -INFINITY;
+    #pragma unroll
+                for (int sp = 0; sp < MAXS; ++sp)
+                    if (sp < NS) M = fmaxf(M, ms[sp]);
+                float O[8], L = 0.f;
+    #pragma unroll
+                for (int e = 0; e < 8; ++e) O[e] = 0.f;
+    #pragma unroll
+                for (int sp = 0; sp < MAXS; ++sp) {
+                    if (sp >= NS || ms[sp] == -INFINITY) continue;
+                    const float f = expf(ms[sp] - M);
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        O[e] += f * o0[sp][e];
+                        O[4 + e] += f * o1[sp][e];
+                    }
+                    L += f * ls[sp];
+                }
+                bf16x8 hv, lv;
+    #pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float v = O[e] / L;
+                    const __bf16 hi = (__bf16)v;
+                    hv[e] = hi;
+                    lv[e] = (__bf16)(v - (float)hi);
+                }
+                *(bf16x8*)(abuf + (size_t)m * rstride + k8 * 8) = hv;
+                *(bf16x8*)(abuf + (size_t)m * rstride + K + k8 * 8) = lv;
+            }
+        } else {
+            for (int m = 0; m < a.T; ++m) {  // (row by row: the row's slot is uniform, a scalar load at most)
+                const __bf16* srow = (const __bf16*)a.A + (size_t)gemm_slot(a, m) * a.lda;
+                for (int k8 = threadIdx.x; k8 < cpr; k8 += blockDim.x) {
+                    u32x4 h = *(const u32x4*)(srow + k8 * 8);
+                    u32x4 l = *(const u32x4*)(srow + a.a_lo + k8 * 8);
+                    *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
+                    *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+                }
+            }
+        }
+        // r[m] = 1/sqrt(mean(x^2)+eps): lane partials (fetched at the top, long back by now) through a fixed butterfly
+    #pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int m = ks + j * KS;
+            float sp = ssq_part[j];
+    #pragma unroll
+            for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+            if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
+        }
+        pre(std::false_type{});
+        __syncthreads();
     }
-    // r[m] = 1/sqrt(mean(x^2)+eps): lane partials (fetched at the top, long back by now) through a fixed butterfly
-#pragma unroll
-    for (int j = 0; j < RPW; ++j) {
-        const int m = ks + j * KS;
-        float sp = ssq_part[j];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
-        if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
-    }
-    pre();
-    __syncthreads();
     const __bf16* ar = abuf + (size_t)(li < a.T ? li : 0) * rstride + (size_t)kt0 * 32 + lg * 8;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     auto use = [&](int u, int t) {
@@ -810,7 +936,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
 template <int KS, int MT, typename Pre>
 __device__ __forceinline__ void gemm_mainloop_f32(const GemmArgs& a, int tile, GemmSmem<KS, MT>& sm, Pre pre) {
     rms_scales<MT>(a, sm.rs);
-    pre();
+    pre(std::false_type{});
     __syncthreads();
     for (int idx = threadIdx.x; idx < MT * 256; idx += blockDim.x) {
         int m = idx >> 4, c = idx & 15;
@@ -856,6 +982,7 @@ struct QkvArgs {
     int H, hd, BT;
     const int32_t* pos;    // per row: position, physical KV block
     const int32_t* kvblk;
+    int32_t pos_v0, blk_v0;  // those of row 0 (a launch of one row reads them here)
 };
 
 template <typename ST, int KS, int MT, bool ALDS, int G = 1>
@@ -868,10 +995,15 @@ __global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_q
     const int m0 = threadIdx.x >> 3, i0 = threadIdx.x & 7;
     int pos0 = 0, blk0 = 0;
     float2 cs0 = make_float2(1.f, 0.f);
-    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, [&]() {
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, [&](auto one_row) {
         if (m0 < a.T) {
-            pos0 = e.pos[m0];
-            blk0 = e.kvblk[m0];
+            if constexpr (decltype(one_row)::value) {  // (the row's position and block sit in the kernel arguments)
+                pos0 = e.pos_v0;
+                blk0 = e.blk_v0;
+            } else {
+                pos0 = e.pos[m0];
+                blk0 = e.kvblk[m0];
+            }
             if (tile0 / per_part < 2) cs0 = e.rope_cs[(size_t)pos0 * half + (tile0 % per_head) * 8 + i0];
         }
     });
@@ -952,9 +1084,12 @@ __device__ __forceinline__ void gemm_resid_body(const GemmArgs& a, const ResidAr
     const int m0 = threadIdx.x >> 4, i0 = threadIdx.x & 15;
     size_t o0 = 0;
     float x0 = 0.f, gn0 = 0.f, gh0 = 0.f;
-    auto pre = [&]() {
+    auto pre = [&](auto one_row) {
         if (m0 < a.T) {
-            o0 = (size_t)resid_slot(e, m0) * e.d + tile0 * 16 + i0;
+            if constexpr (decltype(one_row)::value)
+                o0 = (size_t)e.xrow_v[0] * e.d + tile0 * 16 + i0;
+            else
+                o0 = (size_t)resid_slot(e, m0) * e.d + tile0 * 16 + i0;
             x0 = e.x[o0];
             gn0 = e.g_next[tile0 * 16 + i0];
             if (e.xgh) gh0 = e.g_head[tile0 * 16 + i0];
@@ -1012,7 +1147,7 @@ template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_swiglu_kernel(GemmArgs a, ST* act, size_t act_lo, int F, int act_pk) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int tile0 = blockIdx.x * G;
-    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, [](auto) {});
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int tile = tile0 + g;
@@ -1052,7 +1187,7 @@ template <typename ST, int KS, int MT, bool ALDS, int G = 1>
 __global__ __launch_bounds__(KS * 64, ALDS ? (KS == 16 ? 4 : 6) : 1) void gemm_head_kernel(GemmArgs a, HeadArgs e) {
     __shared__ GemmSmem<KS, MT, G> sm;
     const int tile0 = blockIdx.x * G;
-    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, []() {});
+    gemm_mainloop<ST, KS, MT, ALDS, G>(a, tile0, sm, [](auto) {});
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int tile = tile0 + g;
@@ -1331,11 +1466,12 @@ hipError_t launch_gemm_qkv(const GemmCommon& cc, void* q, size_t q_lo, const flo
         const int32_t* blk = desc_array(c.desc, offsetof(SegDesc, kvblk), r0);
         if (c.dtype == EE_BF16) {
             QkvArgs<__bf16> e{(__bf16*)q + (size_t)r0 * d, q_lo, d, (const float2*)rope_cs,
-                              (__bf16*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk};
+                              (__bf16*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk,
+                              c.desc_host ? c.desc_host->pos[r0] : 0, c.desc_host ? c.desc_host->kvblk[r0] : 0};
             EE_DISPATCH(__bf16, gemm_qkv_kernel, a, e);
         } else {
             QkvArgs<float> e{(float*)q + (size_t)r0 * d, q_lo, d, (const float2*)rope_cs,
-                             (float*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk};
+                             (float*)kv.pool + (size_t)layer * kv.layer_stride, kv.blk_stride, kv.H, kv.hd, kv.BT, pos, blk, 0, 0};
             EE_DISPATCH_F32(gemm_qkv_kernel, a, e);
         }
         hipError_t err = hipGetLastError();
