@@ -797,24 +797,46 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
         }
         lds_barrier();
     } else {
-        // ---- general prologue: the ring first, then whatever has to be looked up
-        // Sum-of-squares partials of the rows: wave w takes rows w, w + KS.  The loads go out first, ahead of the
-        // weight stream, and are reduced after the rows have been staged.
+        // ---- general prologue (several rows, or indices that have to be looked up): stage everything, then the ring.
+        // Behind the ring the staged data would be back only with the ring's whole first burst (loads return in
+        // order) and each dependent look-up would cost the wave another such wait; ahead of it the rows cost one
+        // memory latency per pair of rows before the weights start to stream.
+        // Sum-of-squares partials of the rows: wave w takes rows w, w + KS: lane-strided in order, a fixed butterfly.
         constexpr int RPW = (16 + KS - 1) / KS;  // rows per wave
-        float ssq_part[RPW];
-    #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int m = ks + j * KS;
-            float sp = 0.f;
-            if (a.ssq != nullptr && m < a.T) {
-                const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
-                for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
+        {
+            float sv[RPW][8];
+            const bool quick = a.ssq != nullptr && a.ssq_n <= 512;
+#pragma unroll
+            for (int j = 0; j < RPW; ++j) {
+                const int m = ks + j * KS;
+                if (quick && m < a.T) {
+                    const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj) {
+                        const int i = lane + 64 * jj;
+                        sv[j][jj] = p[i < a.ssq_n ? i : a.ssq_n - 1];
+                    }
+                }
             }
-            ssq_part[j] = sp;
+#pragma unroll
+            for (int j = 0; j < RPW; ++j) {
+                const int m = ks + j * KS;
+                float sp = 0.f;
+                if (a.ssq != nullptr && m < a.T) {
+                    if (quick) {
+#pragma unroll
+                        for (int jj = 0; jj < 8; ++jj)
+                            if (lane + 64 * jj < a.ssq_n) sp += sv[j][jj];
+                    } else {
+                        const float* p = a.ssq + (size_t)gemm_slot(a, m) * a.ssq_stride;
+                        for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
+                    }
+                }
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+                if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
+            }
         }
-    #pragma unroll
-        for (int u = 0; u < D; ++u)
-            if (u < n) fill(u, u);
         if constexpr (ATT) {
             // The rows are attention outputs that still lie as per-split partials (max, sum, unnormalised
             // output): merge the splits here, in split order, exactly as attn_merge_kernel does, and split the
@@ -870,27 +892,24 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
                 *(bf16x8*)(abuf + (size_t)m * rstride + K + k8 * 8) = lv;
             }
         } else {
-            for (int m = 0; m < a.T; ++m) {  // (row by row: the row's slot is uniform, a scalar load at most)
-                const __bf16* srow = (const __bf16*)a.A + (size_t)gemm_slot(a, m) * a.lda;
+            for (int m = 0; m < a.T; m += 2) {  // (two rows per memory round trip; a row's slot is uniform)
+                const int m1 = m + 1 < a.T ? m + 1 : m;
+                const __bf16* s0 = (const __bf16*)a.A + (size_t)gemm_slot(a, m) * a.lda;
+                const __bf16* s1 = (const __bf16*)a.A + (size_t)gemm_slot(a, m1) * a.lda;
                 for (int k8 = threadIdx.x; k8 < cpr; k8 += blockDim.x) {
-                    u32x4 h = *(const u32x4*)(srow + k8 * 8);
-                    u32x4 l = *(const u32x4*)(srow + a.a_lo + k8 * 8);
-                    *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h;
-                    *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l;
+                    const u32x4 h0 = *(const u32x4*)(s0 + k8 * 8), l0 = *(const u32x4*)(s0 + a.a_lo + k8 * 8);
+                    const u32x4 h1 = *(const u32x4*)(s1 + k8 * 8), l1 = *(const u32x4*)(s1 + a.a_lo + k8 * 8);
+                    *(u32x4*)(abuf + (size_t)m * rstride + k8 * 8) = h0;
+                    *(u32x4*)(abuf + (size_t)m * rstride + K + k8 * 8) = l0;
+                    *(u32x4*)(abuf + (size_t)m1 * rstride + k8 * 8) = h1;
+                    *(u32x4*)(abuf + (size_t)m1 * rstride + K + k8 * 8) = l1;
                 }
             }
         }
-        // r[m] = 1/sqrt(mean(x^2)+eps): lane partials (fetched at the top, long back by now) through a fixed butterfly
-    #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int m = ks + j * KS;
-            float sp = ssq_part[j];
-    #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
-            if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
-        }
         pre(std::false_type{});
-        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < D; ++u) fill(u, u < n ? u : (n > 0 ? n - 1 : 0));
+        lds_barrier();
     }
     const __bf16* ar = abuf + (size_t)(li < a.T ? li : 0) * rstride + (size_t)kt0 * 32 + lg * 8;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
