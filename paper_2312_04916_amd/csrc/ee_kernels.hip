@@ -1848,7 +1848,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
     }
 }
 
-template <int HD>
+template <int HD, int MAXS>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, int NS, __bf16* __restrict__ out,
                                                          size_t out_lo, int out_pk, const SegDesc* __restrict__ desc, int H, int d) {
     const int qt = blockIdx.x / H, h = blockIdx.x % H;
@@ -1856,16 +1856,27 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
     const float* pb = part + (size_t)(qt * H + h) * NS * att_part_stride(HD);
     for (int idx = threadIdx.x; idx < nq * HD; idx += 256) {
         int qq = idx / HD, cc = idx % HD;
+        // (all loads of all splits go out together, a surplus split repeating the last one: one memory round trip
+        // instead of one per split and pass)
+        float ms[MAXS], ls[MAXS], os[MAXS];
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            const float* ps = pb + (size_t)(s < NS ? s : NS - 1) * att_part_stride(HD);
+            ms[s] = ps[qq];
+            ls[s] = ps[16 + qq];
+            os[s] = ps[32 + qq * HD + cc];
+        }
         float M = -INFINITY;
-        for (int s = 0; s < NS; ++s) M = fmaxf(M, pb[(size_t)s * att_part_stride(HD) + qq]);
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s)
+            if (s < NS) M = fmaxf(M, ms[s]);
         float O = 0.f, L = 0.f;
-        for (int s = 0; s < NS; ++s) {
-            const float* ps = pb + (size_t)s * att_part_stride(HD);
-            float ms = ps[qq];
-            if (ms == -INFINITY) continue;
-            float f = expf(ms - M);
-            O += f * ps[32 + qq * HD + cc];
-            L += f * ps[16 + qq];
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            if (s >= NS || ms[s] == -INFINITY) continue;
+            float f = expf(ms[s] - M);
+            O += f * os[s];
+            L += f * ls[s];
         }
         store_split_at<__bf16>(out, out_lo, row0 + qq, h * HD + cc, d, out_pk, O / L);
     }
@@ -1908,7 +1919,14 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
         *defer_ns = NS;
         return e;
     }
-    EE_LAUNCH(attn_merge_kernel<HD>, dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
+    if (NS <= 2)
+        EE_LAUNCH((attn_merge_kernel<HD, 2>), dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
+    else if (NS <= 4)
+        EE_LAUNCH((attn_merge_kernel<HD, 4>), dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
+    else if (NS <= 8)
+        EE_LAUNCH((attn_merge_kernel<HD, 8>), dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
+    else
+        EE_LAUNCH((attn_merge_kernel<HD, ATT_MAX_SPLITS>), dim3(wgs), dim3(256), s, (const float*)part, NS, (__bf16*)out, io_lo, out_pk, desc, kv.H, d);
     return hipGetLastError();
 }
 
