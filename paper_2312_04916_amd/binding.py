@@ -89,8 +89,9 @@ def lib():
         L.ee_debug_read_hidden.argtypes = [vp, vp, C.c_int, fp, vp]
         L.ee_prefill.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, vp]
         L.ee_prefill_scored.argtypes = [vp, vp, C.c_int, i32p, C.c_int, C.c_float, i32p, i32p, fp, i32p, fp, fp, vp]
-        L.ee_decode_step.argtypes = [vp, vp, C.c_int, i32p, i32p, i32p, C.POINTER(C.c_uint8), C.c_float, i32p, i32p,
-                                     fp, vp]
+        # (the step's arrays go in as plain addresses: building a typed ctypes pointer per array and call cost the
+        # step 40 us of host time)
+        L.ee_decode_step.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
         L.ee_decode_step_static.argtypes = L.ee_decode_step.argtypes
         _lib = L
     return _lib
@@ -341,8 +342,10 @@ def decode_step(model: Model, cache: KvCache, seq_ids: Sequence[int], row_offset
     n = len(s)
     nt, ex, cf = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float32)
     fn = lib().ee_decode_step_static if static_workspace else lib().ee_decode_step
-    _chk(fn(model.h, cache.h, n, _ip(s), _ip(ro), _ip(tk), pm.ctypes.data_as(C.POINTER(C.c_uint8)),
-            threshold, _ip(nt), _ip(ex), _fp(cf), _stream_ptr(stream)), "ee_decode_step")
+    code = fn(model.h, cache.h, n, s.ctypes.data, ro.ctypes.data, tk.ctypes.data, pm.ctypes.data, threshold, nt.ctypes.data,
+              ex.ctypes.data, cf.ctypes.data, _stream_ptr(stream))
+    if code != 0:
+        _chk(code, "ee_decode_step")
     return nt, ex, cf
 
 
