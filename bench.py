@@ -145,7 +145,7 @@ def prefill_bench(ee, gm, cache, prompt, shape, breakdown, traffic=None):
     """Times the prompt phase (GEMM path) on one prompt: plain ee_prefill, the scored variant (every head on
     every position), and the gate|up GEMM alone (HIP events on its dispatches).  Algorithmic flops: 2*P*params
     of the layers + causal attention; every activation operand is two bf16 terms, so the matrix cores issue
-    twice that."""
+    twice that (except in the scored heads, which by default take the leading term of their input only)."""
     import torch
 
     P = len(prompt)
@@ -185,6 +185,8 @@ def prefill_bench(ee, gm, cache, prompt, shape, breakdown, traffic=None):
         "scored_ms": scored * 1e3, "scored_heads": n_heads,
         "scored_algorithmic_tflops": (L * layer_flops + n_heads * head_flops) / scored / 1e12,
         "head_gemm_algorithmic_tflops_from_difference": hd_tflops,
+        "head_gemm_frac_of_mfma_peak": hd_tflops / MFMA_PEAK_TFLOPS,
+        "scored_head_terms": int(gm.cfg.scored_head_terms) or 1,
         "roofline": {"bound": "mfma", "kernel": "pf_swiglu_kernel (gate|up GEMM over all prompt rows + SwiGLU)",
                      "achieved": sw_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sw_tflops / MFMA_PEAK_TFLOPS,
                      "mfma_issue_tflops": 2 * sw_tflops, "mfma_issue_frac": 2 * sw_tflops / MFMA_PEAK_TFLOPS,

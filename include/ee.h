@@ -89,12 +89,18 @@ typedef struct {
     int32_t max_positions;                      /* longest sequence (prompt + generated) */
     float rms_eps, rope_base;
     int32_t exit_flags;                         /* EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP | EE_EXIT_LAYER; 0 = default */
-    /* Tuning, not part of the model (and not stored in weight files); 0 = default for both. */
+    /* Tuning, not part of the model (and not stored in weight files); 0 = default for each. */
     int32_t prefill_rows;        /* rows per pass of the prompt-phase GEMM path: 0 = 2048, n > 0 = min(n, 8192) rounded to
                                     128 (at least 128), n < 0 = path off (prompts then go through the decode kernels) */
     int32_t gemm_min_workgroups; /* a decode GEMM over many rows gives a workgroup several 16-column tiles as long as
                                     this many workgroups remain: 0 = 512; tests lower it so that small models reach
                                     those kernel variants */
+    int32_t scored_head_terms;   /* bf16 terms of the activations in the heads that ee_prefill_scored evaluates on
+                                    every position: 0 or 1 = the leading term only (half the matrix-core work; the
+                                    logits then carry the rounding of the head's input to bf16, about 1e-3 of their
+                                    largest), 2 = both terms, as everywhere else.  Nothing but pos_token, pos_conf
+                                    and pos_nll depends on it: the prompt's own token and exit are decided by the
+                                    decode heads on the last row. */
 } ee_config;
 
 enum { EE_EXIT_NO_NORM = 1, EE_TIE_EMBEDDINGS = 2, EE_EXIT_MLP = 4, EE_EXIT_LAYER = 8 };
@@ -293,7 +299,9 @@ int ee_prefill(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, int 
  * to the prompt's own next token, pos_nll[i][t] = log sum_v exp(z_v) - z[tokens[t+1]] for t < n_tokens-1 and 0 in
  * the last column: the per-token cross-entropy terms of the early-exit training objective (Section 3, Eq. (1):
  * a weighted sum of the exits' losses), computed from the same logits without storing them.
- * Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw.
+ * Everything else is as ee_prefill; row [.][n_tokens-1] repeats what the rule saw (to the precision of
+ * ee_config::scored_head_terms: by default these heads read the leading bf16 term of their input only, which
+ * moves a confidence by up to about 4e-3; the rule's own heads always read both).
  * Needs the prompt-phase GEMM path: a bf16 model with d_model a multiple of 128 (EE_ERR_CONFIG otherwise).
  * Prompts of 32 tokens or more, and every scored prompt, take that path: whole passes of up to
  * min(max_positions, prefill_rows) rows, rounded up to 128 (ee_config::prefill_rows), each projection one

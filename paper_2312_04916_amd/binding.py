@@ -31,7 +31,7 @@ class ee_config(C.Structure):
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("n_exits", C.c_int32),
                 ("exit_layers", C.c_int32 * EE_MAX_EXITS), ("dtype", C.c_int32), ("max_positions", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("exit_flags", C.c_int32),
-                ("prefill_rows", C.c_int32), ("gemm_min_workgroups", C.c_int32)]
+                ("prefill_rows", C.c_int32), ("gemm_min_workgroups", C.c_int32), ("scored_head_terms", C.c_int32)]
 
 
 EE_EXIT_NO_NORM, EE_TIE_EMBEDDINGS, EE_EXIT_MLP, EE_EXIT_LAYER = 1, 2, 4, 8
@@ -103,7 +103,8 @@ def _chk(code: int, where: str) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, dtype, max_positions,
-                rms_eps=1e-5, rope_base=10000.0, exit_flags=0, prefill_rows=0, gemm_min_workgroups=0) -> ee_config:
+                rms_eps=1e-5, rope_base=10000.0, exit_flags=0, prefill_rows=0, gemm_min_workgroups=0,
+                scored_head_terms=0) -> ee_config:
     c = ee_config()
     c.n_layers, c.d_model, c.n_heads, c.head_dim, c.d_ff, c.vocab = n_layers, d_model, n_heads, head_dim, d_ff, vocab
     c.n_exits = len(exit_layers)
@@ -113,16 +114,17 @@ def make_config(n_layers, d_model, n_heads, head_dim, d_ff, vocab, exit_layers, 
     c.max_positions = max_positions
     c.rms_eps, c.rope_base = rms_eps, rope_base
     c.exit_flags = exit_flags
-    c.prefill_rows, c.gemm_min_workgroups = prefill_rows, gemm_min_workgroups
+    c.prefill_rows, c.gemm_min_workgroups, c.scored_head_terms = prefill_rows, gemm_min_workgroups, scored_head_terms
     return c
 
 
-def config_of_shape(shape, max_positions: int, prefill_rows: int = 0, gemm_min_workgroups: int = 0) -> ee_config:
+def config_of_shape(shape, max_positions: int, prefill_rows: int = 0, gemm_min_workgroups: int = 0,
+                    scored_head_terms: int = 0) -> ee_config:
     """ee_config of an object with the model-shape fields (n_layers, d_model, n_heads, head_dim, d_ff, vocab,
     exit_layers, dtype, rms_eps, rope_base, exit_flags), e.g. workload.ModelShape."""
     return make_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
                        shape.exit_layers, shape.dtype, max_positions, shape.rms_eps, shape.rope_base, shape.exit_flags,
-                       prefill_rows, gemm_min_workgroups)
+                       prefill_rows, gemm_min_workgroups, scored_head_terms)
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> C.c_void_p:

@@ -51,7 +51,7 @@ int check_config(const ee_config& c) {
     if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return EE_ERR_CONFIG;
     if (c.exit_flags & ~(EE_EXIT_NO_NORM | EE_TIE_EMBEDDINGS | EE_EXIT_MLP | EE_EXIT_LAYER)) return EE_ERR_CONFIG;
     if ((c.exit_flags & EE_EXIT_MLP) && (c.exit_flags & EE_EXIT_LAYER)) return EE_ERR_CONFIG;
-    if (c.gemm_min_workgroups < 0) return EE_ERR_CONFIG;
+    if (c.gemm_min_workgroups < 0 || c.scored_head_terms < 0 || c.scored_head_terms > 2) return EE_ERR_CONFIG;
     return EE_OK;
 }
 
@@ -1047,7 +1047,7 @@ int prefill_large(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, i
                     Timed t(m, EE_K_HEAD, st);
                     HIPCHK(launch_pf_head(g, (HeadPartial*)(ws + w.pf_partials), (int32_t*)(ws + w.pf_tok), (float*)(ws + w.pf_conf),
                                           (const int32_t*)(ws + w.pf_tgt), (float*)(ws + w.pf_zt), score_nll ? (float*)(ws + w.pf_nll) : nullptr,
-                                          st));
+                                          cf.scored_head_terms == 2, st));
                 }
                 if (score_tok)
                     HIPCHK(hipMemcpyAsync(score_tok + (size_t)sgi * n_tokens + p0, ws + w.pf_tok, (size_t)M * 4, hipMemcpyDeviceToHost, st));

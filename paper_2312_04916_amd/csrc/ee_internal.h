@@ -146,7 +146,7 @@ hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, 
 // head on every row: (arg max, confidence) per row into tok / conf
 // ... and, if nll != NULL, nll[row] = log sum exp(z) - z[target[row]] (0 where target[row] < 0)
 hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, const int32_t* target,
-                          float* target_logit, float* nll, hipStream_t s);
+                          float* target_logit, float* nll, bool two_terms, hipStream_t s);
 // one fp32 row of the residual stream -> decode-side residual store entry (row-major two-term operands)
 hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, const float* g_b, float* dx, void* dxg, void* dxgh,
                                 size_t lo_off, float* dssq, int ssq_stride, hipStream_t s);

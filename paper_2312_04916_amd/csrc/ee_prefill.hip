@@ -99,9 +99,10 @@ __device__ __forceinline__ bool pf_tile_of(const PfArgs& a, PfTile<MTL>& t) {
 //    for the 64-row tile, which also has room for a second operand set in registers);
 //  - otherwise one workgroup per CU with four stages and two operand sets (the residual epilogue needs the registers).
 // The head GEMM (4 waves, two workgroups per CU, 2 stages) is its own case.
-template <int MTL, int NWAVE, bool WIDE>
+// (LO = false: the activations' hi term only, 24 KB instead of 32 KB per stage of the 128-row tile, so three stages fit twice)
+template <int MTL, int NWAVE, bool WIDE, bool LO = true>
 constexpr int pf_stages() {
-    return NWAVE == 4 ? 2 : (WIDE ? (MTL == 8 ? 2 : 3) : 4);
+    return NWAVE == 4 ? 2 : (WIDE ? (MTL == 8 && LO ? 2 : 3) : 4);
 }
 template <int MTL, int NWAVE, bool WIDE>
 constexpr bool pf_pipe() {  // (the residual epilogue overrides this for its two-workgroups-per-CU variant)
@@ -119,13 +120,14 @@ __device__ __forceinline__ void pf_wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int MTL, int NWAVE, bool WIDE, bool PIPE = pf_pipe<MTL, NWAVE, WIDE>()>
+template <int MTL, int NWAVE, bool WIDE, bool PIPE = pf_pipe<MTL, NWAVE, WIDE>(), bool LO = true>
 __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& t, u32x4* lds, float* rs,
                                             f32x4 (&acc)[32 / NWAVE][MTL / 2]) {
     constexpr int WNF = 32 / NWAVE;
-    constexpr int NF = PF_NTL + 2 * MTL;  // fragments (1 KB each) per stage
-    constexpr int FPW = NF / NWAVE;       // copied per wave
-    constexpr int NST = pf_stages<MTL, NWAVE, WIDE>();
+    constexpr int NF = PF_NTL + (LO ? 2 : 1) * MTL;  // fragments (1 KB each) per stage
+    constexpr int FPW = NF / NWAVE;                  // copied per wave
+    constexpr int NST = pf_stages<MTL, NWAVE, WIDE, LO>();
+    static_assert(LO || !PIPE, "the single-term loop has one operand set");
     static_assert(NF % NWAVE == 0, "fragments must divide over the waves");
     static_assert((NST - 2) * FPW < 64, "vmcnt range");
     constexpr int STAGE = NF * 64;        // u32x4 per stage
@@ -142,7 +144,7 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             if (tt >= a.n_tiles) tt = a.n_tiles - 1;
             src[i] = a.W + (size_t)tt * KT * 64 + lane;
         } else {
-            const int g = f - PF_NTL;
+            const int g = f - PF_NTL;  // (g < MTL always in the single-term loop)
             int mt = t.mt0 + (g < MTL ? g : g - MTL);
             if (mt >= a.m_tiles) mt = a.m_tiles - 1;
             src[i] = (g < MTL ? a.Xh : a.Xl) + (size_t)mt * KT * 64 + lane;
@@ -191,10 +193,14 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             PF_DSR(f.wf[4], wb, 4096); PF_DSR(f.wf[5], wb, 5120); PF_DSR(f.wf[6], wb, 6144); PF_DSR(f.wf[7], wb, 7168);
         }
         PF_DSR(f.xh[0], xb, 0); PF_DSR(f.xh[1], xb, 1024);
-        PF_DSR(f.xl[0], xb, MTL * 1024); PF_DSR(f.xl[1], xb, MTL * 1024 + 1024);
         if constexpr (MW == 4) {
             PF_DSR(f.xh[2], xb, 2048); PF_DSR(f.xh[3], xb, 3072);
-            PF_DSR(f.xl[2], xb, MTL * 1024 + 2048); PF_DSR(f.xl[3], xb, MTL * 1024 + 3072);
+        }
+        if constexpr (LO) {
+            PF_DSR(f.xl[0], xb, MTL * 1024); PF_DSR(f.xl[1], xb, MTL * 1024 + 1024);
+            if constexpr (MW == 4) {
+                PF_DSR(f.xl[2], xb, MTL * 1024 + 2048); PF_DSR(f.xl[3], xb, MTL * 1024 + 3072);
+            }
         }
         issue(st_w, kt + NST - 1 < KT ? kt + NST - 1 : KT - 1);
         st_r = st_r + 1 == NST ? 0 : st_r + 1;
@@ -202,7 +208,11 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
     };
     // the operands are in registers after this (and the MFMAs that use them may not move above it)
     auto landed = [&](Frags& f) {
-        if constexpr (WNF == 8 && MW == 4)
+        if constexpr (!LO) {
+            static_assert(LO || (WNF == 4 && MW == 4), "single-term loop: 8 waves on the 128-row tile");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.xh[0]), "+v"(f.xh[1]),
+                         "+v"(f.xh[2]), "+v"(f.xh[3]));
+        } else if constexpr (WNF == 8 && MW == 4)
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.wf[4]), "+v"(f.wf[5]),
                          "+v"(f.wf[6]), "+v"(f.wf[7]), "+v"(f.xh[0]), "+v"(f.xh[1]), "+v"(f.xh[2]), "+v"(f.xh[3]), "+v"(f.xl[0]),
                          "+v"(f.xl[1]), "+v"(f.xl[2]), "+v"(f.xl[3]));
@@ -264,7 +274,7 @@ __device__ __forceinline__ void pf_mainloop(const PfArgs& a, const PfTile<MTL>& 
             Frags f;
             fetch(f, kt);
             landed(f);
-            multiply_lo(f);
+            if constexpr (LO) multiply_lo(f);
             multiply_hi(f);
         }
     }
@@ -377,14 +387,14 @@ __device__ __forceinline__ void pf_mainloop_k16(const PfArgs& a, const PfTile<4>
     __syncthreads();  // before the epilogue reuses the buffers
 }
 
-template <int MTL, int NWAVE, bool WIDE>
+template <int MTL, int NWAVE, bool WIDE, bool LO = true>
 constexpr size_t pf_lds_bytes() {  // the stages + rs[] + up to seven reduction rows
-    return pf_stages<MTL, NWAVE, WIDE>() * (size_t)(PF_NTL + 2 * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
+    return pf_stages<MTL, NWAVE, WIDE, LO>() * (size_t)(PF_NTL + (LO ? 2 : 1) * MTL) * 1024 + (size_t)MTL * 16 * 4 * 8;
 }
 
-template <int MTL, int NWAVE, bool WIDE>
+template <int MTL, int NWAVE, bool WIDE, bool LO = true>
 __device__ __forceinline__ float* pf_rs_ptr(u32x4* lds) {
-    return (float*)(lds + pf_stages<MTL, NWAVE, WIDE>() * (PF_NTL + 2 * MTL) * 64);
+    return (float*)(lds + pf_stages<MTL, NWAVE, WIDE, LO>() * (PF_NTL + (LO ? 2 : 1) * MTL) * 64);
 }
 
 // ---- epilogue 1: RMS scale, rotary embedding, q (packed), k and v into the paged cache
@@ -623,18 +633,18 @@ __device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, f
     }
 }
 
-template <int MTL, int NWAVE>
+template <int MTL, int NWAVE, bool LO>
 __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel(PfArgs a, PfHead e) {
     extern __shared__ u32x4 pf_lds[];
     PfTile<MTL> t;
     if (!pf_tile_of<MTL, NWAVE>(a, t)) return;
     constexpr int WNF = 32 / NWAVE;
     constexpr int MW = MTL / 2;
-    float* rs = pf_rs_ptr<MTL, NWAVE, (NWAVE == 8)>(pf_lds);
+    float* rs = pf_rs_ptr<MTL, NWAVE, (NWAVE == 8), LO>(pf_lds);
     constexpr int WN = NWAVE / 2;        // waves along the features
     float* red = rs + MTL * 16;          // waves wn > 0 hand (max, sum) over here: [2 * (wn - 1) + {0, 1}][MTL * 16]
     f32x4 acc[WNF][MW];
-    pf_mainloop<MTL, NWAVE, (NWAVE == 8)>(a, t, pf_lds, rs, acc);
+    pf_mainloop<MTL, NWAVE, (NWAVE == 8), false, LO>(a, t, pf_lds, rs, acc);
     int* redi = (int*)pf_lds;            // ... and the index here (the stage buffers are free now): [wn - 1][MTL * 16]
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
 #pragma unroll
@@ -1117,17 +1127,25 @@ hipError_t launch_pf_swiglu(const PfGemm& g, void* act_hi, void* act_lo, int F, 
 }
 
 hipError_t launch_pf_head(const PfGemm& g, HeadPartial* partials, int32_t* tok, float* conf, const int32_t* target,
-                          float* target_logit, float* nll, hipStream_t s) {
+                          float* target_logit, float* nll, bool two_terms, hipStream_t s) {
     const int n_wg = (g.N + 255) / 256;
-    {
-        PfHead e{partials, g.N, nll ? target : nullptr, target_logit};
-        PfArgs a = pf_args(g, 8);
+    PfHead e{partials, g.N, nll ? target : nullptr, target_logit};
+    PfArgs a = pf_args(g, 8);
+    if (two_terms) {
         // (8 waves, two workgroups per CU, two stages: 633 us at 1024 rows; 4 waves with two workgroups per CU measured
         // 672 us, 8 waves with one workgroup per CU and four stages 750 us)
         constexpr size_t lds_b = pf_lds_bytes<8, 8, true>();
-        static hipError_t once = pf_set_lds(pf_head_kernel<8, 8>, lds_b);
+        static hipError_t once = pf_set_lds(pf_head_kernel<8, 8, true>, lds_b);
         if (once != hipSuccess) return once;
-        EE_LAUNCH_SM((pf_head_kernel<8, 8>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, e);
+        EE_LAUNCH_SM((pf_head_kernel<8, 8, true>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, e);
+    } else {
+        // the leading term of the activations only: half the MFMAs, 24 KB per stage, three stages
+        constexpr size_t lds_b = pf_lds_bytes<8, 8, true, false>();
+        static hipError_t once = pf_set_lds(pf_head_kernel<8, 8, false>, lds_b);
+        if (once != hipSuccess) return once;
+        EE_LAUNCH_SM((pf_head_kernel<8, 8, false>), dim3(pf_grid<8>(a)), dim3(512), lds_b, s, a, e);
+    }
+    {
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }

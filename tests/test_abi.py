@@ -66,6 +66,7 @@ def test_bad_configs_are_rejected():
     assert code(d_ff=100) == -1             # not a multiple of 32
     assert code(dtype=7) == -1
     assert code(max_positions=0) == -1
+    assert code(scored_head_terms=2) == 0 and code(scored_head_terms=3) == -1 and code(scored_head_terms=-1) == -1
     cfg = ee_config_of(good, 256)
     cfg.exit_layers[0], cfg.exit_layers[1] = 2, 1  # not ascending
     assert L.ee_model_bytes(C.byref(cfg), 16, 1, C.byref(wb), None) == -1

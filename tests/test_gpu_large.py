@@ -273,16 +273,19 @@ def test_c5_full_size_invariants():
         gm.close()
 
 
-def test_c3_shape_prompt_phase_scored():
+@pytest.mark.parametrize("head_terms", [2, 1])
+def test_c3_shape_prompt_phase_scored(head_terms):
     """Prompt phase through the GEMM path at the 7B widths (2 layers, exit after the first): cached K/V of every
-    position and both heads scored on sampled positions against the oracle's cache-free forward."""
-    from common import GUARD
+    position and both heads scored on sampled positions against the oracle's cache-free forward; the scored heads
+    on both terms of their input and on the leading one only (the library's default)."""
+    from common import GUARD, TOL_CONF_ONE_TERM
     shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
     n = 200
     O.set_threads(16)
-    om, gm = build_pair(shape, 0, max_positions=256)
+    om, gm = build_pair(shape, 0, max_positions=256, scored_head_terms=head_terms)
+    tol_pos = TOL_CONF["bf16"] if head_terms == 2 else TOL_CONF_ONE_TERM
     try:
-        print("case: C3-shaped scored prompt phase", flush=True)
+        print(f"case: C3-shaped scored prompt phase, head terms {head_terms}", flush=True)
         p = prompt_tokens(shape.vocab, n, 5).numpy()
         cache = ee.KvCache(gm, 1, 256, 64, 15)
         tok, ex, conf, ptok, pconf = ee.prefill_scored(gm, cache, 0, p, 0.2)
@@ -298,9 +301,9 @@ def test_c3_shape_prompt_phase_scored():
                 if int(ptok[hi, pos]) != dg["argmax"]:
                     assert dg["top1"] - dg["top2"] < GUARD and int(ptok[hi, pos]) == dg["arg2"], (hi, pos, dg)
                     forced += 1
-                assert abs(float(pconf[hi, pos]) - dg["conf"]) <= TOL_CONF["bf16"], (hi, pos, float(pconf[hi, pos]), dg["conf"])
+                assert abs(float(pconf[hi, pos]) - dg["conf"]) <= tol_pos, (hi, pos, float(pconf[hi, pos]), dg["conf"])
         assert forced <= 3
-        assert abs(float(conf[1]) - float(pconf[1, n - 1])) <= 1e-4
+        assert abs(float(conf[1]) - float(pconf[1, n - 1])) <= (1e-4 if head_terms == 2 else tol_pos)
         cache.close()
     finally:
         gm.close()
