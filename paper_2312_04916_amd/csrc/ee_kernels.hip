@@ -10,6 +10,7 @@
 // of the kernel that produced it.  No float atomics: every reduction has a fixed order.
 #include "ee_internal.h"
 
+#include "ee_lanes.h"
 #include "ee_launch.h"
 
 #include <cstdlib>
@@ -333,8 +334,7 @@ __global__ __launch_bounds__(256) void step_begin_kernel(StepBegin b, const ST* 
         }
     }
     // sum of squares: lanes of a wave through a fixed butterfly, then the four waves in order
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
     const float tot = ((red[0] + red[1]) + red[2]) + red[3];
@@ -430,8 +430,7 @@ __device__ __forceinline__ void rms_scales(const GemmArgs& a, float* rs) {
             const float* p = a.ssq + (size_t)slot * a.ssq_stride;
             float s = 0.f;
             for (int i = lane; i < a.ssq_n; i += 64) s += p[i];
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+            s = wave_sum(s);
             r = 1.0f / sqrtf(s * a.inv_d + a.eps);
         }
         if (lane == 0) rs[m] = r;
@@ -746,8 +745,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
                     if (lane + 64 * j < a.ssq_n) sp += sv[j];
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+                sp = wave_sum(sp);
                 r = 1.0f / sqrtf(sp * a.inv_d + a.eps);
             }
             if (lane < 16) sm.rs[lane] = lane == 0 ? r : 1.f;
@@ -832,8 +830,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
                         for (int i = lane; i < a.ssq_n; i += 64) sp += p[i];
                     }
                 }
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) sp += __shfl_xor(sp, o);
+                sp = wave_sum(sp);
                 if (lane == 0 && m < 16) sm.rs[m] = (a.ssq != nullptr && m < a.T) ? 1.0f / sqrtf(sp * a.inv_d + a.eps) : 1.f;
             }
         }
@@ -1764,8 +1761,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
             pv[e] = val;
             tmax = fmaxf(tmax, val);
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = rows4_max(tmax);
         const float m_new = fmaxf(m_run, tmax);
         float corr = 1.f, psum = 0.f;
         if (m_new == -INFINITY) {
@@ -1781,8 +1777,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
                 psum += pv[e];
             }
         }
-        psum += __shfl_xor(psum, 16);
-        psum += __shfl_xor(psum, 32);
+        psum = rows4_sum(psum);
         l_run = l_run * corr + psum;
         m_run = m_new;
         bf16x8 ph, pl;
@@ -1793,6 +1788,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
             pl[e] = (__bf16)(pv[e] - (float)hi);
         }
         // positions beyond the context hold unknown bits (their probabilities are zero): zero them
+        // (splitting the score chains over four accumulators and the P.V product into one pass per term, as the
+        // prompt-phase kernel does, measured no faster at batch 1 and 2 % slower at batch 16: this kernel waits for
+        // memory, and the extra registers cost it waves)
         const bool ragged = tb + 32 > ctx;
 #pragma unroll
         for (int c = 0; c < CG; ++c) {

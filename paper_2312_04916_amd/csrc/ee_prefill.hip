@@ -14,6 +14,7 @@
 // activation operand, of a K-cache row, or of a packed q row.
 #include "ee_internal.h"
 
+#include "ee_lanes.h"
 #include "ee_launch.h"
 
 namespace ee {
@@ -537,8 +538,7 @@ __device__ __forceinline__ void pf_resid_epilogue(const PfArgs& a, const PfResid
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
         float s = sq[j];
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
+        s = rows4_sum(s);
         if (rg == 0 && active) red[t.wn * (MTL * 16) + (t.wm * MW + j) * 16 + li] = s;
     }
     __syncthreads();
@@ -774,8 +774,7 @@ __global__ __launch_bounds__(256) void pf_embed_kernel(const __bf16* __restrict_
             xg_lo[pi] = (__bf16)(o - (float)h);
         }
         float s = v * v;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        s = wave_sum(s);
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
         __syncthreads();
         if (threadIdx.x == 0) ssq[(size_t)m * ssq_n + part] = (red[0] + red[1]) + (red[2] + red[3]);
@@ -806,45 +805,49 @@ __global__ __launch_bounds__(256) void pf_export_row_kernel(const float* __restr
         }
         s += v * v;
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
     for (int i = threadIdx.x; i < ssq_stride; i += 256) dssq[i] = i == 0 ? (red[0] + red[1]) + (red[2] + red[3]) : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------------
-// causal attention over many query rows of one sequence.  A workgroup owns 64 consecutive query positions
-// of one head (16 per wave) and walks the keys 0 .. its last position in tiles of 32.  Each K / V^T tile
-// is copied once per workgroup from the paged cache into LDS, already permuted into MFMA operand order
-// by the copy's source addressing (so that the reads back are plain 1 KB wave reads without bank
-// conflicts), through a ring of stages that keeps several tiles in flight; the arithmetic is the decode
-// kernel's (S^T = K Q^T so that P^T is already a B operand; q and P as two bf16 terms).
+// causal attention over many query rows of one sequence.  A block of 64 consecutive query positions of one
+// head (16 per wave, four waves) walks the keys 0 .. its last position in tiles of 32.  The work of a block
+// grows with its position, so a workgroup takes two: waves 0-3 the j-th block from the end, waves 4-7 the
+// j-th from the start, which makes every workgroup (and, a wave of each block per SIMD, every SIMD) carry the
+// same number of key tiles; the lighter block's keys are a prefix of the heavier one's, so both read the
+// same tiles.  Each K / V^T tile is copied once per workgroup from the paged cache into LDS, already permuted
+// into MFMA operand order by the copy's source addressing (so that the reads back are plain 1 KB wave reads
+// without bank conflicts), through a ring of stages that keeps several tiles in flight; the arithmetic is the
+// decode kernel's (S^T = K Q^T so that P^T is already a B operand; q and P as two bf16 terms).
 // ---------------------------------------------------------------------------------------------------
 constexpr int PFA_STAGES = 4;
 
 template <int HD>
-__global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ q_hi, const u32x4* __restrict__ q_lo,
+__global__ __launch_bounds__(512) void pf_attn_kernel(const u32x4* __restrict__ q_hi, const u32x4* __restrict__ q_lo,
                                                       __bf16* __restrict__ out_hi, __bf16* __restrict__ out_lo,
                                                       const __bf16* __restrict__ layer_base, KvGeom kv,
                                                       const int32_t* __restrict__ bt, int p0, int M, int d) {
     constexpr int KK = HD / 32, CG = HD / 16;
-    constexpr int NCH = 2 * KK + CG;  // 1 KB chunks per tile: K score halves x k-steps, then V feature groups
-    constexpr int FPW = NCH / 4;      // copied per wave
-    constexpr int STAGE = NCH * 64;   // u32x4
-    static_assert(NCH % 4 == 0, "chunks must divide over the four waves");
+    constexpr int NCH = 2 * KK + CG;     // 1 KB chunks per tile: K score halves x k-steps, then V feature groups
+    constexpr int NCW = NCH >= 8 ? 8 : 4;  // waves that copy
+    constexpr int FPW = NCH / NCW;       // copied per such wave
+    constexpr int STAGE = NCH * 64;      // u32x4
+    static_assert(NCH % NCW == 0, "chunks must divide over the copying waves");
     extern __shared__ u32x4 pfa_lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
-    // Heavier blocks (later positions) first, and heads along x: workgroup ids go round-robin to the XCDs, so every XCD
-    // gets blocks of every length (with the blocks of one head along x, one XCD held the longest block of every head
-    // and another the shortest), and all blocks of a head share an XCD's L2 when the head count is a multiple of 8.
-    const int qb = (int)(gridDim.y - 1 - blockIdx.y), h = blockIdx.x;
-    const int qt = qb * 4 + wave;
+    // Heads along x: workgroup ids go round-robin to the XCDs, and all blocks of a head share an XCD's L2 when the head
+    // count is a multiple of 8.
+    const int nb = (M + 63) >> 6, h = blockIdx.x;
+    const int qb_far = nb - 1 - (int)blockIdx.y, qb_near = (int)blockIdx.y;  // (the middle block of an odd count has no partner)
+    const int qb = wave < 4 ? qb_far : qb_near;
+    const int qt = qb * 4 + (wave & 3);
     const int r0 = qt * 16;
-    const int nq = max(0, min(16, M - r0));
+    const int nq = (wave >= 4 && qb_near >= qb_far) ? 0 : max(0, min(16, M - r0));
     const int pos0 = p0 + r0, ctx = pos0 + nq;
     const int my_tiles = nq > 0 ? (ctx + 31) >> 5 : 0;
-    const int wg_last = min(M, qb * 64 + 64);                 // rows of this workgroup end here
+    const int wg_last = min(M, qb_far * 64 + 64);             // rows of this workgroup end here
     const int wg_tiles = (p0 + wg_last + 31) >> 5;            // >= my_tiles of every wave
     const int KTd = d / 32;
     const bool qvalid = li < nq;
@@ -858,6 +861,7 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
     }
     // copy of tile t into stage st: chunk c = wave*FPW + i; this lane's 16 bytes of it
     auto issue = [&](int st, int t) {
+        if (wave >= NCW) return;  // (head size 32: a tile is four chunks)
         const int tb = t << 5;
         const int blk = bt[tb / kv.BT];
         const int tin = tb % kv.BT;
@@ -929,17 +933,21 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(vf_[0]), "+v"(vf_[1]));
         if (t >= my_tiles) continue;  // (uniform over the wave) keys beyond this wave's rows
         const int tb = t << 5;
-        f32x4 sacc[2];
+        // four independent accumulation chains (score half x term of q), so that no MFMA waits for the one before it
+        f32x4 sacc[2], s_lo[2], s_hi[2];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            sacc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int sub = 0; sub < 2; ++sub) s_lo[sub] = s_hi[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
+        for (int kk = 0; kk < KK; ++kk) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
                 const bf16x8 kfr = __builtin_bit_cast(bf16x8, kf[sub * KK + kk]);
-                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, ql[kk], sacc[sub], 0, 0, 0);
-                sacc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, qh[kk], sacc[sub], 0, 0, 0);
+                s_lo[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, ql[kk], s_lo[sub], 0, 0, 0);
+                s_hi[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, qh[kk], s_hi[sub], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) sacc[sub] = s_lo[sub] + s_hi[sub];
         float pv[8];
         float tmax = -INFINITY;
         if (tb + 31 <= pos0) {
@@ -959,8 +967,7 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
                 tmax = fmaxf(tmax, val);
             }
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = rows4_max(tmax);
         const float m_new = fmaxf(m_run, tmax);
         float corr = 1.f, psum = 0.f;
         if (m_new == -INFINITY) {
@@ -975,8 +982,7 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
                 psum += pv[e];
             }
         }
-        psum += __shfl_xor(psum, 16);
-        psum += __shfl_xor(psum, 32);
+        psum = rows4_sum(psum);
         l_run = l_run * corr + psum;
         m_run = m_new;
         bf16x8 ph, pl;
@@ -990,18 +996,25 @@ __global__ __launch_bounds__(256) void pf_attn_kernel(const u32x4* __restrict__ 
         // query of this wave needs it
         const bool rescale = __builtin_amdgcn_ballot_w64(corr != 1.f) != 0;
         const bool ragged = tb + 32 > ctx;  // positions beyond this wave's context may hold unknown bits: zero them
+        if (ragged) {
 #pragma unroll
-        for (int c = 0; c < CG; ++c) {
-            bf16x8 vf = __builtin_bit_cast(bf16x8, vf_[c]);
-            if (ragged) {
+            for (int c = 0; c < CG; ++c) {
+                bf16x8 vf = __builtin_bit_cast(bf16x8, vf_[c]);
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     if (tb + lg * 8 + e >= ctx) vf[e] = (__bf16)0.f;
+                vf_[c] = __builtin_bit_cast(u32x4, vf);
             }
-            if (rescale) o[c] = o[c] * corr;
-            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[c], 0, 0, 0);
-            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, o[c], 0, 0, 0);
         }
+        if (rescale) {
+#pragma unroll
+            for (int c = 0; c < CG; ++c) o[c] = o[c] * corr;
+        }
+        // (one pass per term of P over all feature groups: the two MFMAs on an accumulator are CG instructions apart)
+#pragma unroll
+        for (int c = 0; c < CG; ++c) o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf_[c]), pl, o[c], 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < CG; ++c) o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf_[c]), ph, o[c], 0, 0, 0);
     }
     pf_wait_vm<0>();  // surplus copies of the ring
     // O^T: lane (query li, group lg) holds features c*16 + lg*4 .. +3
@@ -1170,7 +1183,7 @@ hipError_t launch_pf_export_row(const float* x_row, int d, const float* g_a, con
 hipError_t launch_pf_attention(const void* q_hi, const void* q_lo, void* out_hi, void* out_lo, const KvGeom& kv, int layer,
                                const int32_t* bt, int p0, int M, int d, hipStream_t s) {
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
-    dim3 grid(kv.H, (M + 63) / 64), block(256);
+    dim3 grid(kv.H, ((M + 63) / 64 + 1) / 2), block(512);
     const size_t lds = (size_t)PFA_STAGES * (2 * (kv.hd / 32) + kv.hd / 16) * 1024;  // at most 64 KB
     switch (kv.hd) {
         case 32:

@@ -57,6 +57,13 @@ TOL_CONF_ONE_TERM = 8e-3
 TOL_NLL_ONE_TERM = 1e-2
 
 
+def flip_guard(dg: dict, head_terms: int) -> float:
+    """Largest gap between the oracle's two best logits at which the other arg max is still accepted: the guard band,
+    and for one-term scored heads 4e-3 of the best logit if that is more (each of the two logits is off by up to
+    about 2e-3 of its size there)."""
+    return GUARD if head_terms == 2 else max(GUARD, 4e-3 * abs(dg["top1"]))
+
+
 def rel_err(a: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(a.astype(np.float64) - ref.astype(np.float64))) / max(np.max(np.abs(ref)), 1e-30))
 

@@ -142,7 +142,7 @@ def test_scored_prompt_phase_with_other_exit_structures(name):
     shape = dataclasses.replace(ModelShape(3, 256, 4, 64, 512, 2048, (1, 2), "bf16", 0.02, 0.3 / 2 ** 0.5), **VARIANTS[name])
     print(f"case: scored prompt phase {name}", flush=True)
     om = build_model(shape, 21, gain_jitter=0.1)
-    gm = load_gpu_model(shape, 21, gain_jitter=0.1, max_positions=512, max_rows=64, max_seqs=1)
+    gm = load_gpu_model(shape, 21, gain_jitter=0.1, max_positions=512, max_rows=64, max_seqs=1, scored_head_terms=2)
     n = 150
     p = prompt_tokens(shape.vocab, n, 22).numpy()
     cache = ee.KvCache(gm, 1, 512, 64, 8)

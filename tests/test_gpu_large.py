@@ -278,7 +278,7 @@ def test_c3_shape_prompt_phase_scored(head_terms):
     """Prompt phase through the GEMM path at the 7B widths (2 layers, exit after the first): cached K/V of every
     position and both heads scored on sampled positions against the oracle's cache-free forward; the scored heads
     on both terms of their input and on the leading one only (the library's default)."""
-    from common import GUARD, TOL_CONF_ONE_TERM
+    from common import TOL_CONF_ONE_TERM, flip_guard
     shape = dataclasses.replace(CONFIGS["C3"].shape, n_layers=2, exit_layers=(1,))
     n = 200
     O.set_threads(16)
@@ -299,7 +299,7 @@ def test_c3_shape_prompt_phase_scored(head_terms):
             for pos in list(range(0, n, 9)) + list(range(n - 6, n)):
                 _, dg = om.head_row(hi, hid[layer][pos])
                 if int(ptok[hi, pos]) != dg["argmax"]:
-                    assert dg["top1"] - dg["top2"] < GUARD and int(ptok[hi, pos]) == dg["arg2"], (hi, pos, dg)
+                    assert dg["top1"] - dg["top2"] < flip_guard(dg, head_terms) and int(ptok[hi, pos]) == dg["arg2"], (hi, pos, dg)
                     forced += 1
                 assert abs(float(pconf[hi, pos]) - dg["conf"]) <= tol_pos, (hi, pos, float(pconf[hi, pos]), dg["conf"])
         assert forced <= 3
