@@ -460,7 +460,8 @@ int run_block(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int kv_layer
     int att_ns = 0;
     {
         Timed t(m, EE_K_ATTN, st);
-        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, T, n_qt, m->dev_btab(), c->geom, kv_layer, d,
+        HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, g.desc_host, T, n_qt, m->dev_btab(), c->geom,
+                                kv_layer, d,
                                 (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
                                 gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, pk_d, st));
     }

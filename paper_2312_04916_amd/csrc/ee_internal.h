@@ -112,7 +112,8 @@ hipError_t launch_pack_rows(const void* src, size_t src_lo, int ld, const int32_
 hipError_t launch_gemm_head(const GemmCommon& c, HeadPartial* partials, int32_t* counter, float* logits, int mode,
                             float threshold, HeadResult* results, int tag, hipStream_t s);
 
-hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, const SegDesc* desc_host, int T, int n_qt,
+                            const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
                             bool out_packed, hipStream_t s);
 // defer_ns != NULL: when the KV range was split, leave the partials unmerged and report the number of splits

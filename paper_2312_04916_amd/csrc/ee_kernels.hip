@@ -1668,12 +1668,18 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const ST* __restrict__
 // Partials of the KV splits are merged by attn_merge_kernel in a fixed order.
 // ------------------------------------------------------------------------------------------------
 
+// A launch with a single query tile (one sequence, at most 16 rows: every step at batch 1) gets the tile by value, so
+// that the first K load is two dependent loads away from the kernel's start (block table, K) instead of three.
+struct AttTile0 {
+    int32_t one, row0, nq, pos0, seq;
+};
+
 template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __restrict__ q, size_t q_lo, __bf16* __restrict__ out,
                                                              size_t out_lo, int out_pk, const SegDesc* __restrict__ desc,
                                                              const int32_t* __restrict__ btab, KvGeom kv,
                                                              const __bf16* __restrict__ layer_base, int d, int NS,
-                                                             float* __restrict__ part) {
+                                                             float* __restrict__ part, AttTile0 t0) {
     constexpr int KK = HD / 32, CG = HD / 16;
     __shared__ float wO[NW * 16 * (HD + 1)];
     __shared__ float wm[NW * 16], wl[NW * 16];
@@ -1682,10 +1688,14 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
     const int split = blockIdx.x % NS, qh_ = blockIdx.x / NS, qt = qh_ / kv.H, h = qh_ % kv.H;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: block-table reads become scalar loads
     const int lane = threadIdx.x & 63, li = lane & 15, lg = lane >> 4;
-    const int row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt];
-    const int pos0 = desc->qt_pos0[qt];
+    int row0, nq, pos0, seq;
+    if (t0.one) {
+        row0 = t0.row0, nq = t0.nq, pos0 = t0.pos0, seq = t0.seq;
+    } else {
+        row0 = desc->qt_row0[qt], nq = desc->qt_nq[qt], pos0 = desc->qt_pos0[qt], seq = desc->qt_seq[qt];
+    }
     const int ctx = pos0 + nq;
-    const int32_t* bt = btab + (size_t)desc->qt_seq[qt] * kv.max_blocks_per_seq;
+    const int32_t* bt = btab + (size_t)seq * kv.max_blocks_per_seq;
     const int n_tiles = (ctx + 31) >> 5;
     const int tps = (n_tiles + NS - 1) / NS;
     const int t_lo = split * tps, t_hi = min(n_tiles, t_lo + tps);
@@ -1887,10 +1897,12 @@ size_t attention_part_floats(int max_rows, int H, int hd) {
 }
 
 template <int HD>
-static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, int n_qt, const int32_t* btab,
-                                        const KvGeom& kv, int layer, int d, float* part, int max_ctx, int* defer_ns, bool out_packed,
-                                        hipStream_t s) {
+static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, const SegDesc* desc, const SegDesc* desc_host, int n_qt,
+                                        const int32_t* btab, const KvGeom& kv, int layer, int d, float* part, int max_ctx, int* defer_ns,
+                                        bool out_packed, hipStream_t s) {
     const int out_pk = out_packed ? d / 32 : 0;
+    AttTile0 t0{0, 0, 0, 0, 0};
+    if (n_qt == 1 && desc_host != nullptr) t0 = AttTile0{1, desc_host->qt_row0[0], desc_host->qt_nq[0], desc_host->qt_pos0[0], desc_host->qt_seq[0]};
     const int wgs = n_qt * kv.H;
     const int tiles = (max_ctx + 31) / 32;
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
@@ -1907,10 +1919,10 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     if (NS < 1) NS = 1;
     if (few)
         EE_LAUNCH((attn_mfma_kernel<HD, 8>), dim3(wgs * NS), dim3(8 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc,
-                  btab, kv, lb, d, NS, part);
+                  btab, kv, lb, d, NS, part, t0);
     else
         EE_LAUNCH((attn_mfma_kernel<HD, 4>), dim3(wgs * NS), dim3(4 * 64), s, (const __bf16*)q, io_lo, (__bf16*)out, io_lo, out_pk, desc,
-                  btab, kv, lb, d, NS, part);
+                  btab, kv, lb, d, NS, part, t0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || NS == 1) return e;
     if (defer_ns != nullptr) {  // the consumer merges the splits itself
@@ -1928,7 +1940,8 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     return hipGetLastError();
 }
 
-hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, int T, int n_qt, const int32_t* btab,
+hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, const SegDesc* desc, const SegDesc* desc_host, int T, int n_qt,
+                            const int32_t* btab,
                             const KvGeom& kv, int layer, int d, float* part, int32_t* counters, int max_ctx, int* defer_ns,
                             bool out_packed, hipStream_t s) {
     (void)counters;
@@ -1936,9 +1949,9 @@ hipError_t launch_attention(int dtype, const void* q, void* out, size_t io_lo, c
     if (T <= 0) return hipSuccess;
     if (dtype == EE_BF16) {
         switch (kv.hd) {
-            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
-            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
-            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
+            case 32: return launch_attention_mfma<32>(q, out, io_lo, desc, desc_host, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
+            case 64: return launch_attention_mfma<64>(q, out, io_lo, desc, desc_host, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
+            case 128: return launch_attention_mfma<128>(q, out, io_lo, desc, desc_host, n_qt, btab, kv, layer, d, part, max_ctx, defer_ns, out_packed, s);
             default: return hipErrorInvalidValue;
         }
     }
