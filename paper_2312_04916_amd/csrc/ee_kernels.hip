@@ -1518,7 +1518,8 @@ hipError_t launch_gemm_resid(const GemmCommon& cc, float* x, void* xg, void* xgh
             // (at most 8 waves: the merge holds every split's partials in registers at once)
             const int ks = ks_of(c) == 4 ? 4 : 8;
             dim3 grid(c.N / 16), block(ks * 64);
-            if (ks == 4) EE_LAUNCH_LDS((gemm_resid_att_kernel<4, ATT_MAX_SPLITS>), grid, block, sm, s, a, e);
+            if (ks == 4 && c.att_ns <= 8) EE_LAUNCH_LDS((gemm_resid_att_kernel<4, 8>), grid, block, sm, s, a, e);
+            else if (ks == 4) EE_LAUNCH_LDS((gemm_resid_att_kernel<4, ATT_MAX_SPLITS>), grid, block, sm, s, a, e);
             else if (c.att_ns <= 8) EE_LAUNCH_LDS((gemm_resid_att_kernel<8, 8>), grid, block, sm, s, a, e);
             else EE_LAUNCH_LDS((gemm_resid_att_kernel<8, ATT_MAX_SPLITS>), grid, block, sm, s, a, e);
         } else if (c.dtype == EE_BF16) {
