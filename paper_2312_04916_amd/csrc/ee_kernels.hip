@@ -1909,10 +1909,12 @@ static hipError_t launch_attention_mfma(const void* q, void* out, size_t io_lo, 
     const __bf16* lb = (const __bf16*)kv.pool + (size_t)layer * kv.layer_stride;
     // KV splits: enough workgroups to cover the chip, at least ~4 tiles (one per wave) per split.  A
     // wave works through its tiles one after another, so short splits keep the dependent chain short.
-    // Up to 256 (query tile, head) pairs (steps of a few rows, small batches): workgroups of 8 waves, one per CU,
+    // Up to 512 (query tile, head) pairs (steps of a few rows, small and medium batches): workgroups of 8 waves
     // and about 6 tiles per split: fewer splits to merge at the same number of waves, none at all from 129
-    // pairs on (30B shape, 4 sequences x 52 heads: 51 us with 4 splits of 4 waves + merge -> 45.5 us).
-    const bool few = wgs <= 256;
+    // pairs on (30B shape, 4 sequences x 52 heads: 51 us with 4 splits of 4 waves + merge -> 45.5 us; 7B shape,
+    // 16 sequences x 32 heads: 2 splits of 4 waves + a merge launch -> one workgroup of 8 waves per pair, the same
+    // waves per CU and no merge, 5.48 -> 5.40 ms per step).
+    const bool few = wgs <= 512;
     int NS = (few ? 256 : 1024) / wgs;
     int by_len = few ? (tiles + 5) / 6 : (tiles + 3) / 4;
     if (NS > by_len) NS = by_len;
