@@ -216,6 +216,12 @@ int ee_profile_every(ee_model* m, int every);
  * beside the nominal 8 TB/s (Section 4 relies on weight streaming dominating a decode step).  Blocks until done. */
 int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_per_s, void* stream);
 
+/* Test hook: the kernels reduce over the lanes of a wave (sums of squares, the soft-max maxima and sums of the
+ * attention of Section 4's decode step) with lane swaps instead of shuffles through the LDS; this runs both forms on
+ * a million pseudo-random values (on the model's workspace, so not while a step is in flight) and stores in
+ * *mismatches (host) how many results differ in any bit: 0 is the contract.  Blocks until done. */
+int ee_debug_lane_reductions(ee_model* m, int32_t* mismatches, void* stream);
+
 /* ---------------------------------------------------------------- KV cache */
 
 /* How the deferred tokens of this cache are carried along (Section 4, "KV recomputation").  on = 0 (default):

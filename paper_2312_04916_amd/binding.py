@@ -17,7 +17,7 @@ KERNEL_NAMES = ["qkv", "attention", "oproj", "swiglu", "down", "head"]
  EE_T_EXIT_NORM, EE_T_EXIT_HEAD, EE_T_FINAL_NORM, EE_T_FINAL_HEAD) = range(14)
 
 EXPORTS = ["ee_strerror", "ee_last_hip_error", "ee_model_bytes", "ee_model_create", "ee_model_set_tensor",
-           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_step_confidences", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_kv_cache_bytes", "ee_kv_cache_create",
+           "ee_model_load", "ee_model_free", "ee_debug_set_logits", "ee_debug_step_confidences", "ee_debug_plan", "ee_profile_begin", "ee_profile_end", "ee_profile_every", "ee_measure_stream_read", "ee_debug_lane_reductions", "ee_kv_cache_bytes", "ee_kv_cache_create",
            "ee_kv_cache_set_refeed", "ee_kv_cache_set_pipeline", "ee_kv_cache_reset", "ee_kv_cache_filled", "ee_kv_cache_pending", "ee_kv_cache_read",
            "ee_kv_cache_flush", "ee_kv_cache_free", "ee_debug_read_hidden", "ee_prefill", "ee_prefill_scored",
            "ee_decode_step", "ee_decode_step_static"]
@@ -76,6 +76,7 @@ def lib():
         L.ee_profile_end.argtypes = [vp, i32p, fp]
         L.ee_profile_every.argtypes = [vp, C.c_int]
         L.ee_measure_stream_read.argtypes = [vp, sz, C.c_int, fp, vp]
+        L.ee_debug_lane_reductions.argtypes = [vp, i32p, vp]
         L.ee_kv_cache_bytes.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.POINTER(sz)]
         L.ee_kv_cache_create.argtypes = [vp, C.c_int, C.c_int64, C.c_int, C.c_int, vp, sz, C.POINTER(vp)]
         L.ee_kv_cache_reset.argtypes = [vp, C.c_int]
@@ -191,6 +192,12 @@ class Model:
         g = C.c_float()
         _chk(lib().ee_measure_stream_read(self.h, n_bytes, n_launches, C.byref(g), _stream_ptr(None)), "ee_measure_stream_read")
         return g.value
+
+    def lane_reduction_mismatches(self) -> int:
+        """ee_debug_lane_reductions: results of the kernels' lane reductions that differ from the shuffle butterflies."""
+        n = C.c_int32(-1)
+        _chk(lib().ee_debug_lane_reductions(self.h, C.byref(n), _stream_ptr(None)), "ee_debug_lane_reductions")
+        return n.value
 
     def close(self):
         if self.h:

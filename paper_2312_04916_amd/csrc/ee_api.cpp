@@ -1347,6 +1347,17 @@ int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms) {
     return EE_OK;
 }
 
+int ee_debug_lane_reductions(ee_model* m, int32_t* mismatches, void* stream) {
+    if (!m || !mismatches) return EE_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* dev = (int32_t*)(m->ws + m->wsl.attn_part);  // (idle between steps)
+    HIPCHK(hipMemsetAsync(dev, 0, 4, st));
+    HIPCHK(launch_lane_reduction_check(dev, st));
+    HIPCHK(hipMemcpyAsync(mismatches, dev, 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    return EE_OK;
+}
+
 int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_per_s, void* stream) {
     if (!m || !gb_per_s || n_launches < 1 || n_launches > 1000) return EE_ERR_ARG;
     if (bytes == 0 || bytes > m->wl.total) bytes = m->wl.total;

@@ -56,6 +56,7 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 // ---- launch wrappers (ee_kernels.hip).  dtype: EE_F32 | EE_BF16.  All return the launch status.
 
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_lane_reduction_check(int32_t* dev_mismatches, hipStream_t s);
 hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
 hipError_t launch_copy_slots(int dtype, const int32_t* dev_src, const int32_t* dev_dst, int n, int d, float* x, void* xgh, size_t lo,
                              float* ssq, int ssq_stride, hipStream_t s);

@@ -111,6 +111,38 @@ __global__ __launch_bounds__(512) void stream_read_kernel(const u32x4* __restric
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && sink) sink[0] = acc.x;  // keeps the loads alive
 }
 
+// Test hook: the lane reductions of ee_lanes.h against the xor butterflies over __shfl_xor that they replace, on
+// pseudo-random values of mixed sign and magnitude; counts the lanes whose results differ in any bit.
+__global__ __launch_bounds__(256) void lane_reduction_check_kernel(int32_t* __restrict__ mismatches, int rounds) {
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    int bad = 0;
+    for (int r = 0; r < rounds; ++r) {
+        h ^= h >> 15;
+        h *= 2246822519u;
+        h ^= h >> 13;
+        h *= 3266489917u;
+        h ^= h >> 16;
+        // sign, a small exponent range and 23 mantissa bits: sums that round at every step
+        const float v = __uint_as_float((h & 0x807fffffu) | ((118u + ((h >> 23) & 15u)) << 23));
+        float a = v, b = v, c = v;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+        b += __shfl_xor(b, 16);
+        b += __shfl_xor(b, 32);
+        c = fmaxf(c, __shfl_xor(c, 16));
+        c = fmaxf(c, __shfl_xor(c, 32));
+        bad += __float_as_uint(a) != __float_as_uint(wave_sum(v));
+        bad += __float_as_uint(b) != __float_as_uint(rows4_sum(v));
+        bad += __float_as_uint(c) != __float_as_uint(rows4_max(v));
+    }
+    if (bad) atomicAdd(mismatches, bad);
+}
+
+hipError_t launch_lane_reduction_check(int32_t* dev_mismatches, hipStream_t s) {
+    EE_LAUNCH(lane_reduction_check_kernel, dim3(64), dim3(256), s, dev_mismatches, 64);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s) {
     const size_t n_kb = bytes / 1024;
     if (n_kb == 0) return hipSuccess;

@@ -505,3 +505,13 @@ def test_measurement_hook_counts_and_samples_launches():
     toks, (n, ms) = run(ee.EE_K_HEAD)  # the final head, once per step
     assert toks == ref and n == 6 and ms > 0.0
     gm.close()
+
+
+def test_lane_reductions_equal_the_shuffle_butterflies():
+    """The wave-wide and four-row reductions the kernels use (lane swaps, row rotates) against the xor butterflies over
+    shuffles that they stand for: a million pseudo-random values, every result compared bit for bit on the device."""
+    gm = load_gpu_model(TINY_BF16, 0, max_positions=64, max_rows=16, max_seqs=1)
+    try:
+        assert gm.lane_reduction_mismatches() == 0
+    finally:
+        gm.close()
