@@ -330,6 +330,10 @@ int ee_prefill_scored(ee_model* m, ee_kv_cache* c, int seq, const int32_t* token
  *   threshold    exit iff confidence >= threshold and threshold < 1
  * Outputs, [n_seqs] each: next_token, exit_layer (an exit layer, or n_layers for a full or forced
  * step) and conf (confidence at the head that emitted).
+ * With one sequence the call enqueues, behind each exit's head, the KV write and the attention of the next layer
+ * before it knows the decision (they touch nothing a token that leaves depends on); when the token does leave, those
+ * two kernels may still be running on `stream` as the call returns.  Later calls on the same stream are ordered behind
+ * them; calls with this model on another stream wait for them first; ee_kv_cache_free and ee_model_free wait too.
  * Errors leave every sequence as it was: EE_ERR_STATE (rows disagree with the lists), EE_ERR_RANGE (token id,
  * position beyond max_positions), EE_ERR_NOMEM (no free cache block, or more rows than max_rows).  After an
  * EE_ERR_HIP (a launch failed, or the step's results did not arrive within two minutes) the handles must not be

@@ -199,6 +199,12 @@ struct ee_model {
     int dbg_rows;
     int prof_kernel = -1;               // kernel family being timed, or -1
     int prof_every = 1, prof_seen = 0;  // every prof_every-th launch of the family is timed
+    // A decode step at batch 1 enqueues the first two kernels of the next segment before it knows whether the token
+    // leaves at the exit (run_step); when it does leave, they are still running on `spec_stream` as the call returns.
+    // Work on the same stream is ordered behind them anyway; a call on another stream waits for `spec_ev` first.
+    hipEvent_t spec_ev = nullptr;
+    hipStream_t spec_stream = nullptr;
+    bool spec_recorded = false;
     std::vector<hipEvent_t> prof_ev;    // event pairs
     size_t prof_used = 0;               // events recorded so far
     size_t lo_rows(size_t ld) const { return cfg.dtype == EE_BF16 ? rows_padded(max_rows) * ld : 0; }  // hi -> lo distance
@@ -423,8 +429,11 @@ struct BlockW {
 // write into cache layer kv_layer, attention, x += W_o a, the MLP half.  The rows' x.g1 operand is read from `a_first`
 // (a row-major operand store, indexed by the rows' slots), or from the packed copy when the rows are too many for LDS
 // (the caller has packed it).  kv_only: stop after the KV write (the rows only have to leave their K and V here).
+enum { BLOCK_ALL = 0, BLOCK_FRONT = 1, BLOCK_REST = 2 };  // FRONT: the KV write and the attention; REST: what follows them
+
 int run_block(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int kv_layer, const BlockW& w, void* a_first, bool kv_only,
-              const float* g_next, const float* g_head, bool pack_next, int max_ctx, hipStream_t st) {
+              const float* g_next, const float* g_head, bool pack_next, int max_ctx, hipStream_t st, int phase = BLOCK_ALL,
+              int* att_ns_io = nullptr) {
     const ee_config& cf = m->cfg;
     const int d = cf.d_model, F = cf.d_ff, dt = cf.dtype;
     SegDesc* dd = m->dev_desc(di);
@@ -452,18 +461,22 @@ int run_block(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int kv_layer
     g.lda = d;
     g.arow = xrow;
     g.ssq = c->ssq();
-    {
+    if (phase != BLOCK_REST) {
         Timed t(m, EE_K_QKV, st);
         HIPCHK(launch_gemm_qkv(g, m->ws + m->wsl.q, m->lo_rows(d), (const float*)(m->wbase + m->wl.rope), c->geom, kv_layer, st));
     }
     if (kv_only) return EE_OK;
-    int att_ns = 0;
-    {
+    int att_ns = phase == BLOCK_REST ? *att_ns_io : 0;
+    if (phase != BLOCK_REST) {
         Timed t(m, EE_K_ATTN, st);
         HIPCHK(launch_attention(dt, m->ws + m->wsl.q, m->ws + m->wsl.attn, m->lo_rows(d), dd, g.desc_host, T, n_qt, m->dev_btab(), c->geom,
                                 kv_layer, d,
                                 (float*)(m->ws + m->wsl.attn_part), (int32_t*)(m->ws + m->wsl.counters) + 64, max_ctx,
                                 gemm_rows_fit_lds(dt, T, d) ? &att_ns : nullptr, pk_d, st));
+    }
+    if (phase == BLOCK_FRONT) {
+        *att_ns_io = att_ns;
+        return EE_OK;
     }
     // x += W_o a ; operand for the MLP norm
     g.W = w.wo;
@@ -491,7 +504,10 @@ int run_block(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int kv_layer
 }
 
 // ---- the per-layer launch sequence over the rows described by dev_desc(di)
-int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st) {
+// first_phase: BLOCK_FRONT stops after the attention of layer l0 (nothing of the rows' residual stream has changed
+// then); BLOCK_REST takes the pass up from there.  *att_ns_io carries the attention's split count between the two.
+int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int l1, int max_ctx, hipStream_t st,
+               int first_phase = BLOCK_ALL, int* att_ns_io = nullptr) {
     const ee_config& cf = m->cfg;
     const int d = cf.d_model, dt = cf.dtype;
     SegDesc* dd = m->dev_desc(di);
@@ -500,7 +516,7 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
     // (dense rows of this launch in MFMA operand order) that the producing epilogues write, and the segment
     // starts by packing the rows' x.g operands out of the residual store.
     const bool pk_d = dt == EE_BF16 && !gemm_rows_fit_lds(dt, T, d);
-    if (pk_d && l0 < l1)
+    if (pk_d && l0 < l1 && first_phase != BLOCK_REST)
         HIPCHK(launch_pack_rows(c->xg(), c->xs_lo, d, xrow, T, d, m->ws + m->wsl.xg_pk, m->lo_rows(d), st));
     for (int l = l0; l < l1; ++l) {
         const BlockW w{m->wbase + m->wl.qkv[l], m->wbase + m->wl.wo[l], m->wbase + m->wl.gu[l], m->wbase + m->wl.wd[l],
@@ -509,7 +525,9 @@ int run_layers(ee_model* m, ee_kv_cache* c, int di, int T, int n_qt, int l0, int
         const float* g_head = nullptr;
         for (int i = 0; i < cf.n_exits; ++i)
             if (cf.exit_layers[i] == l + 1) g_head = m->exit_in_gain(i);
-        EECHK(run_block(m, c, di, T, n_qt, l, w, c->xg(), false, g_next, g_head, l + 1 < l1, max_ctx, st));
+        EECHK(run_block(m, c, di, T, n_qt, l, w, c->xg(), false, g_next, g_head, l + 1 < l1, max_ctx, st,
+                        l == l0 ? first_phase : BLOCK_ALL, att_ns_io));
+        if (l == l0 && first_phase == BLOCK_FRONT) break;
     }
     return EE_OK;
 }
@@ -780,10 +798,17 @@ int max_ctx_of(const ee_kv_cache* c, const std::vector<StepSeq>& ss) {
     return mx;
 }
 
+// Work that an earlier decode step left running on another stream (see ee_model::spec_ev) is waited for first.
+int settle(ee_model* m, hipStream_t st) {
+    if (m->spec_recorded && st != m->spec_stream) HIPCHK(hipStreamWaitEvent(st, m->spec_ev, 0));
+    return EE_OK;
+}
+
 // Common engine of decode and flush.  For a flush p = -1 everywhere and no head runs.
 int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float threshold, bool decode, int32_t* next_token,
              int32_t* exit_layer, float* conf, hipStream_t st) {
     const int n_seg = m->n_seg();
+    EECHK(settle(m, st));
     if (decode) m->step_tag0 = m->head_tag;
     for (size_t b = 0; b < ss.size(); ++b) put_btab(m, c, (int)b, c->seqs[ss[b].seq]);
     int max_ctx = max_ctx_of(c, ss);
@@ -800,13 +825,15 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
     EECHK(rebuild(0));
     int n_active = (int)ss.size();
     Pipeline& pp = c->pipe;
+    int spec_seg = -1, spec_ns = 0;  // segment whose first layer's KV write and attention are already enqueued
     for (int s = 0; s < n_seg && n_active > 0; ++s) {
         const SegDesc* hd = m->host_desc(s);
         if (hd->T > 0) {
             // pipeline mode: the stage's previous token may still be on the other stream (segment 0 only ever runs here)
             if (pp.on && s > 0 && pp.last_ev[s] >= 0 && pp.last_stream[s] != st)
                 HIPCHK(hipStreamWaitEvent(st, pp.pool[pp.last_ev[s]], 0));
-            EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st));
+            EECHK(run_layers(m, c, s, hd->T, hd->n_qt, m->seg_begin(s), m->seg_end(s), max_ctx, st, spec_seg == s ? BLOCK_REST : BLOCK_ALL,
+                             &spec_ns));
             if (m->exit_layer() && s < m->cfg.n_exits)
                 EECHK(run_exit_layer(m, c, s, (const int32_t*)((char*)m->dev_desc(s) + offsetof(SegDesc, xrow)), decode && hd->n_head > 0,
                                      max_ctx, st));
@@ -820,6 +847,24 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
         bool is_final = s == n_seg - 1;
         if (decode && hd->n_head > 0) {
             EECHK(run_head(m, c, s, s, hd->n_head, is_final ? HEAD_EMIT : HEAD_RULE, threshold, st));
+            // One sequence: either it leaves here or the next segment runs on the rows already described.  Its first
+            // layer's KV write and attention are enqueued before the host knows which, so that the GPU does not stand
+            // idle while the result travels and the launches follow.  They change nothing a token that leaves depends
+            // on: K and V of rows whose watermark for that segment stays where it was (the pass that does advance it
+            // writes them again), and the q, attention and partial buffers of the workspace.  The residual stream is
+            // first touched by the O projection, which waits for the decision.
+            if (!is_final && ss.size() == 1 && !pp.on) {
+                const SegDesc* nd = m->host_desc(s + 1);
+                const int dt = m->cfg.dtype;
+                if (nd->T > 0 && (dt != EE_BF16 || gemm_rows_fit_lds(dt, nd->T, m->cfg.d_model))) {
+                    EECHK(run_layers(m, c, s + 1, nd->T, nd->n_qt, m->seg_begin(s + 1), m->seg_end(s + 1), max_ctx, st, BLOCK_FRONT, &spec_ns));
+                    spec_seg = s + 1;
+                    if (m->spec_ev == nullptr) HIPCHK(hipEventCreateWithFlags(&m->spec_ev, hipEventDisableTiming));
+                    HIPCHK(hipEventRecord(m->spec_ev, st));
+                    m->spec_stream = st;
+                    m->spec_recorded = true;
+                }
+            }
             EECHK(wait_head_results(m, hd, st));
             int fired_now = 0;
             for (int i = 0; i < hd->n_head; ++i) {
@@ -1170,6 +1215,7 @@ int ee_model_set_tensor(ee_model* m, int kind, int index, const void* dev_src, s
     const size_t d = c.d_model, F = c.d_ff, V = c.vocab, es = esize(c.dtype);
     const int dt = c.dtype, hd = c.head_dim;
     hipStream_t st = (hipStream_t)stream;
+    EECHK(settle(m, st));
     auto gain = [&](size_t off) -> int {
         if (n_elems != d) return EE_ERR_ARG;
         HIPCHK(hipMemcpyAsync(m->wbase + off, dev_src, d * 4, hipMemcpyDeviceToDevice, st));
@@ -1350,6 +1396,7 @@ int ee_profile_end(ee_model* m, int32_t* n_launches, float* total_ms) {
 int ee_debug_lane_reductions(ee_model* m, int32_t* mismatches, void* stream) {
     if (!m || !mismatches) return EE_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
+    EECHK(settle(m, st));
     int32_t* dev = (int32_t*)(m->ws + m->wsl.attn_part);  // (idle between steps)
     HIPCHK(hipMemsetAsync(dev, 0, 4, st));
     HIPCHK(launch_lane_reduction_check(dev, st));
@@ -1385,6 +1432,10 @@ int ee_measure_stream_read(ee_model* m, size_t bytes, int n_launches, float* gb_
 
 int ee_model_free(ee_model* m) {
     if (!m) return EE_ERR_ARG;
+    if (m->spec_ev) {
+        if (m->spec_recorded) (void)hipEventSynchronize(m->spec_ev);
+        (void)hipEventDestroy(m->spec_ev);
+    }
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     if (m->pinned) (void)hipHostFree(m->pinned);
     delete m;
@@ -1523,6 +1574,7 @@ int ee_kv_cache_read(ee_model* m, const ee_kv_cache* c, int seq, int layer, int 
     if (n == 0) return EE_OK;
     EECHK(pipeline_drain(const_cast<ee_kv_cache*>(c)));
     hipStream_t st = (hipStream_t)stream;
+    EECHK(settle(m, st));
     put_btab(m, c, 0, s);
     EECHK(upload(m, st));
     const size_t d = m->cfg.d_model;
@@ -1545,6 +1597,7 @@ int ee_debug_read_hidden(ee_model* m, const ee_kv_cache* c, int seq, float* x_ho
     if (s.filled[0] < 1) return EE_ERR_STATE;
     EECHK(pipeline_drain(const_cast<ee_kv_cache*>(c)));
     hipStream_t st = (hipStream_t)stream;
+    EECHK(settle(m, st));
     size_t d = m->cfg.d_model;
     HIPCHK(hipMemcpyAsync(x_host, c->x() + (size_t)c->slot_of(seq, s.filled[0] - 1) * d, d * 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
@@ -1570,6 +1623,7 @@ int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* se
 
 int ee_kv_cache_free(ee_kv_cache* c) {
     if (!c) return EE_ERR_ARG;
+    if (c->m->spec_recorded) (void)hipEventSynchronize(c->m->spec_ev);  // (kernels of the last step may still write K and V)
     if (c->pipe.events_made) {
         if (c->pipe.on) (void)hipStreamSynchronize(c->pipe.stream);
         for (auto& e : c->pipe.slot_done) (void)hipEventDestroy(e);
@@ -1613,6 +1667,7 @@ int prefill_impl(ee_model* m, ee_kv_cache* c, int seq, const int32_t* tokens, in
     if (s.filled[0] != 0) return EE_ERR_STATE;
     EECHK(ensure_blocks(c, s, n_tokens));
     hipStream_t st = (hipStream_t)stream;
+    EECHK(settle(m, st));
     const ee_config& cf = m->cfg;
     const int n_seg = m->n_seg();
     const int CH = std::min(m->max_rows, 64);
