@@ -79,3 +79,46 @@ def test_requests_share_slots_and_blocks(dtype, refeed):
     for j, (prompt, n_new) in enumerate(jobs):
         assert got[j] == _alone(gm, shape, prompt, n_new, tau, cap, refeed), j
     gm.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_steps_on_alternating_streams_equal_one_stream(dtype):
+    """A decode step with one sequence leaves two kernels of the next layer in flight when its token takes an exit;
+    the next call may come on another stream and must be ordered behind them.  Steps issued on two streams in turn
+    (with a cache read on a third in between) must give the tokens, exit layers and cache of the same steps on one
+    stream."""
+    import dataclasses
+    import torch
+    shape = dataclasses.replace(SHAPE, dtype=dtype)
+    gm = load_gpu_model(shape, 3, gain_jitter=0.1, max_positions=256, max_rows=64, max_seqs=1)
+    prompt = prompt_tokens(shape.vocab, 21, 8).numpy()
+    tau, n_new = 0.004, 40  # low threshold: most tokens leave at the first exit
+
+    def run(streams):
+        cache = ee.KvCache(gm, 1, 256, 32, 15)
+        seqs = ee.Sequences(shape.n_layers)
+        tok, ex, _ = ee.prefill(gm, cache, 0, prompt, tau, stream=streams[0])
+        seqs.start(0, tok)
+        out = [(int(tok), int(ex))]
+        for i in range(n_new - 1):
+            ro, tk, pm = seqs.rows([0])
+            nt, exl, _ = ee.decode_step(gm, cache, [0], ro, tk, pm, tau, stream=streams[i % len(streams)])
+            seqs.update([0], nt, exl)
+            out.append((int(nt[0]), int(exl[0])))
+            if i % 7 == 3:
+                cache.read(0, 0, 0, 5, stream=streams[-1])
+        cache.flush([0], stream=streams[0])
+        kv = [cache.read(0, l, 0, len(prompt) + n_new - 1, stream=streams[-1]) for l in range(shape.n_layers)]
+        cache.close()
+        return out, kv
+
+    try:
+        one = torch.cuda.Stream()
+        ref_out, ref_kv = run([one])
+        assert sum(1 for _, e in ref_out if e < shape.n_layers) >= n_new // 2, ref_out
+        out, kv = run([torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()])
+        assert out == ref_out
+        for (k, v), (k0, v0) in zip(kv, ref_kv):
+            assert np.array_equal(k, k0) and np.array_equal(v, v0)
+    finally:
+        gm.close()
