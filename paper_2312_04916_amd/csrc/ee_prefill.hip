@@ -625,11 +625,11 @@ struct PfHead {
 
 __device__ __forceinline__ void pf_merge(float& m, float& s, int& i, float m2, float s2, int i2) {
     if (m2 > m || (m2 == m && i2 < i)) {
-        s = s * expf(m - m2) + s2;
+        s = s * __expf(m - m2) + s2;
         m = m2;
         i = i2;
     } else if (m2 > -INFINITY) {
-        s = s + s2 * expf(m2 - m);
+        s = s + s2 * __expf(m2 - m);
     }
 }
 
@@ -647,6 +647,8 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
     pf_mainloop<MTL, NWAVE, (NWAVE == 8), false, LO>(a, t, pf_lds, rs, acc);
     int* redi = (int*)pf_lds;            // ... and the index here (the stage buffers are free now): [wn - 1][MTL * 16]
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
+    float mxs[MW], sms[MW];
+    int ixs[MW];
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
         const int ml = (t.wm * MW + j) * 16 + li;
@@ -659,46 +661,58 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
         for (int i = 0; i < WNF; ++i) {
             const int n = (t.nt0 + t.wn * WNF + i) * 16 + rg * 4;
             if (n >= e.V) continue;
+            acc[i][j] = acc[i][j] * r;  // the logits, in place
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float z = acc[i][j][q] * r;
+                const float z = acc[i][j][q];
                 if (z > mx) {
                     mx = z;
                     ix = n + q;
                 }
-                if (n + q == tgt) e.target_logit[m_row] = z;  // (exactly one lane of one workgroup holds it)
+            }
+            if ((unsigned)(tgt - n) < 4u) {  // (exactly one lane of one workgroup holds the wanted token's logit)
+                const int q = tgt - n;
+                e.target_logit[m_row] = q == 0 ? acc[i][j][0] : q == 1 ? acc[i][j][1] : q == 2 ? acc[i][j][2] : acc[i][j][3];
             }
         }
+        // (hardware exponential: relative error about 1e-6, far inside what the logits themselves carry; the library
+        // routine made this epilogue a ninth of the kernel)
 #pragma unroll
         for (int i = 0; i < WNF; ++i) {
             const int n = (t.nt0 + t.wn * WNF + i) * 16 + rg * 4;
             if (n >= e.V) continue;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) sm += expf(acc[i][j][q] * r - mx);
+            for (int q = 0; q < 4; ++q) sm += __expf(acc[i][j][q] - mx);
         }
-        // the four lane groups of a row, in a fixed order
-#pragma unroll
-        for (int o = 16; o <= 32; o <<= 1) {
-            const float m2 = __shfl_xor(mx, o), s2 = __shfl_xor(sm, o);
-            const int i2 = __shfl_xor(ix, o);
-            if (lane & o) {  // the upper partner takes (lower, upper) order as well, so both end up equal
-                float m1 = m2, s1 = s2;
-                int i1 = i2;
-                pf_merge(m1, s1, i1, mx, sm, ix);
-                mx = m1;
-                sm = s1;
-                ix = i1;
-            } else {
-                pf_merge(mx, sm, ix, m2, s2, i2);
-            }
+        // the four lane groups of a row, in a fixed order (even row then odd row, lower half then upper half: every
+        // lane forms the same merge, so all four groups end up equal)
+        {
+            float m0, m1, s0, s1, i0, i1;
+            row_pair_of(mx, m0, m1);
+            row_pair_of(sm, s0, s1);
+            row_pair_of(__int_as_float(ix), i0, i1);
+            int ia = __float_as_int(i0);
+            pf_merge(m0, s0, ia, m1, s1, __float_as_int(i1));
+            halves_of(m0, mx, m1);
+            halves_of(s0, sm, s1);
+            halves_of(__int_as_float(ia), i0, i1);
+            ix = __float_as_int(i0);
+            pf_merge(mx, sm, ix, m1, s1, __float_as_int(i1));
         }
         if (t.wn > 0 && rg == 0) {
             red[(2 * (t.wn - 1)) * (MTL * 16) + ml] = mx;
             red[(2 * (t.wn - 1) + 1) * (MTL * 16) + ml] = sm;
             redi[(t.wn - 1) * (MTL * 16) + ml] = ix;
         }
-        __syncthreads();
-        if (t.wn == 0 && rg == 0) {
+        mxs[j] = mx, sms[j] = sm, ixs[j] = ix;
+    }
+    __syncthreads();  // (one hand-over for all row tiles: their slots are disjoint)
+    if (t.wn == 0 && rg == 0) {
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            const int ml = (t.wm * MW + j) * 16 + li;
+            float mx = mxs[j], sm = sms[j];
+            int ix = ixs[j];
 #pragma unroll
             for (int wv = 1; wv < WN; ++wv)
                 pf_merge(mx, sm, ix, red[(2 * (wv - 1)) * (MTL * 16) + ml], red[(2 * (wv - 1) + 1) * (MTL * 16) + ml],
@@ -713,7 +727,6 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_head_kernel
                 e.partials[(size_t)m * a.n_wgN + t.n_wg] = p;
             }
         }
-        __syncthreads();
     }
 }
 
