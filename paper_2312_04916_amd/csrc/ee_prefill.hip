@@ -50,6 +50,20 @@ __device__ __forceinline__ void pk_store4(__bf16* hi, __bf16* lo, int m, int k, 
     *(bf16x4*)(lo + o) = l;
 }
 
+// ... and two consecutive features (k % 2 == 0)
+__device__ __forceinline__ void pk_store2(__bf16* hi, __bf16* lo, int m, int k, int KT, float v0, float v1) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const size_t o = pk_index(m, k, KT);
+    const __bf16 h0 = (__bf16)v0, h1 = (__bf16)v1;
+    bf16x2 h, l;
+    h[0] = h0;
+    h[1] = h1;
+    l[0] = (__bf16)(v0 - (float)h0);
+    l[1] = (__bf16)(v1 - (float)h1);
+    *(bf16x2*)(hi + o) = h;
+    *(bf16x2*)(lo + o) = l;
+}
+
 struct PfArgs {
     const u32x4* W;   // packed weights [n_tiles][KT][64]
     const u32x4* Xh;  // packed activations [m_tiles][KT][64], hi and lo terms
@@ -439,6 +453,8 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_qkv_kernel(
                 const float r = rs[ml];
                 f32x4 v = acc[i][j] * r;
                 f32x4 o;
+                // (a lane swap instead of this shuffle costs the kernel eight more live registers, which it does not have:
+                // 48 spilled, four times the run time)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) o[q] = __shfl_xor(v[q], 32);
                 const bool is_hi = rg >= 2;
@@ -602,15 +618,19 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_swiglu_kern
         for (int j = 0; j < MW; ++j) {
             const int ml = (t.wm * MW + j) * 16 + li, m = t.mt0 * 16 + ml;
             const f32x4 v = acc[i][j] * rs[ml];
-            f32x4 o;
+            // The gate features sit in the lower 32 lanes, their up partners in the upper 32.  Both halves get both
+            // (a lane swap each) and share the work: the lower half forms features 0 and 1 of its four, the upper
+            // half 2 and 3.  Hardware exponential and reciprocal (a few 1e-7 relative: the results are kept to 16
+            // mantissa bits); with the library routines and one half idle this epilogue was 8 % of the kernel.
+            float gq[4], uq[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) o[q] = __shfl_xor(v[q], 32);
-            if (rg < 2 && m < a.M) {
-                float res[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) res[q] = v[q] / (1.0f + expf(-v[q])) * o[q];
-                pk_store4(act_hi, act_lo, m, T * 8 + rg * 4, KTf, res);
-            }
+            for (int q = 0; q < 4; ++q) halves_of(v[q], gq[q], uq[q]);
+            const bool upper = rg >= 2;
+            const float g0 = upper ? gq[2] : gq[0], g1 = upper ? gq[3] : gq[1];
+            const float u0 = upper ? uq[2] : uq[0], u1 = upper ? uq[3] : uq[1];
+            if (m < a.M)
+                pk_store2(act_hi, act_lo, m, T * 8 + (rg & 1) * 4 + (upper ? 2 : 0), KTf, __fdividef(g0, 1.0f + __expf(-g0)) * u0,
+                          __fdividef(g1, 1.0f + __expf(-g1)) * u1);
         }
     }
 }
