@@ -437,63 +437,56 @@ __global__ __launch_bounds__(NWAVE * 64, NWAVE == 8 ? 4 : 2) void pf_qkv_kernel(
     pf_mainloop<MTL, NWAVE, true>(a, t, pf_lds, rs, acc);
     const int lane = threadIdx.x & 63, li = lane & 15, rg = lane >> 4;
     const int KTd = e.d / 32;
+    // (row tiles outside, weight tiles inside: what depends on the position alone, its cache block, its place in the
+    // block and its RMS scale, is formed once per row instead of once per tile)
 #pragma unroll
-    for (int i = 0; i < WNF; ++i) {
-        const int T = t.nt0 + t.wn * WNF + i;
-        if (T >= a.n_tiles) continue;  // (uniform over the wave)
-        const int part = T / tiles_per_part, rem = T % tiles_per_part;
-        const int h = rem / per_head, c = rem % per_head;
+    for (int j = 0; j < MW; ++j) {
+        const int ml = (t.wm * MW + j) * 16 + li, m = t.mt0 * 16 + ml;
+        if (m >= a.M) continue;
+        const float r = rs[ml];
+        const int pos = e.p0 + m;
+        const int blk = e.bt[pos / e.BT], pin = pos % e.BT;
+        const bool is_hi = rg >= 2;
 #pragma unroll
-        for (int j = 0; j < MW; ++j) {
-            const int ml0 = (t.wm * MW + j) * 16;
+        for (int i = 0; i < WNF; ++i) {
+            const int T = t.nt0 + t.wn * WNF + i;
+            if (T >= a.n_tiles) continue;  // (uniform over the wave)
+            const int part = T / tiles_per_part, rem = T % tiles_per_part;
+            const int h = rem / per_head, c = rem % per_head;
             if (part < 2) {
                 // lane: features rg*4..rg*4+3 of the tile (rows 0-7 = features c*8.., rows 8-15 = their rotary
                 // partners) for position m
-                const int ml = ml0 + li, m = t.mt0 * 16 + ml;
-                const float r = rs[ml];
                 f32x4 v = acc[i][j] * r;
                 f32x4 o;
                 // (a lane swap instead of this shuffle costs the kernel eight more live registers, which it does not have:
                 // 48 spilled, four times the run time)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) o[q] = __shfl_xor(v[q], 32);
-                const bool is_hi = rg >= 2;
                 const int fi = c * 8 + (rg & 1) * 4;
-                if (m < a.M) {
-                    const int pos = e.p0 + m;
-                    const f32x4 cs0 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi);
-                    const f32x4 cs1 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi + 2);
-                    const float cx[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sx[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
-                    float res[4];
+                const f32x4 cs0 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi);
+                const f32x4 cs1 = *(const f32x4*)(e.rope_cs + (size_t)pos * half + fi + 2);
+                const float cx[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sx[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+                float res[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) res[q] = is_hi ? v[q] * cx[q] + o[q] * sx[q] : v[q] * cx[q] - o[q] * sx[q];
-                    const int f = fi + (is_hi ? half : 0);
-                    if (part == 0) {
-                        pk_store4(e.q_hi, e.q_lo, m, h * e.hd + f, KTd, res);
-                    } else {
-                        const int blk = e.bt[pos / e.BT];
-                        __bf16* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + (pos % e.BT)) * e.hd + f;
-                        bf16x4 kb;
+                for (int q = 0; q < 4; ++q) res[q] = is_hi ? v[q] * cx[q] + o[q] * sx[q] : v[q] * cx[q] - o[q] * sx[q];
+                const int f = fi + (is_hi ? half : 0);
+                if (part == 0) {
+                    pk_store4(e.q_hi, e.q_lo, m, h * e.hd + f, KTd, res);
+                } else {
+                    __bf16* kp = e.kv_layer + (size_t)blk * e.blk_stride + ((size_t)h * e.BT + pin) * e.hd + f;
+                    bf16x4 kb;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) kb[q] = (__bf16)res[q];
-                        *(bf16x4*)kp = kb;
-                    }
+                    for (int q = 0; q < 4; ++q) kb[q] = (__bf16)res[q];
+                    *(bf16x4*)kp = kb;
                 }
             } else {
                 // V block, transposed [head][position / 32][feature][position % 32]: four 2-byte stores per lane; the
                 // 16 lanes of a group cover 16 consecutive positions of one feature
-                const int ml = ml0 + li, m = t.mt0 * 16 + ml;
-                if (m < a.M) {
-                    const float r = rs[ml];
-                    const int pos = e.p0 + m;
-                    const int blk = e.bt[pos / e.BT];
-                    const int f = c * 8 + (rg & 1) * 4 + (rg >= 2 ? half : 0);
-                    const int pin = pos % e.BT;
-                    __bf16* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + (size_t)h * e.hd * e.BT +
-                                 (size_t)(pin >> 5) * (e.hd * 32) + f * 32 + (pin & 31);
+                const int f = c * 8 + (rg & 1) * 4 + (is_hi ? half : 0);
+                __bf16* vp = e.kv_layer + (size_t)blk * e.blk_stride + (size_t)e.H * e.BT * e.hd + (size_t)h * e.hd * e.BT +
+                             (size_t)(pin >> 5) * (e.hd * 32) + f * 32 + (pin & 31);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) vp[q * 32] = (__bf16)(acc[i][j][q] * r);
-                }
+                for (int q = 0; q < 4; ++q) vp[q * 32] = (__bf16)(acc[i][j][q] * r);
             }
         }
     }
