@@ -804,7 +804,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
 #pragma unroll
             for (int sp = 0; sp < MAXS; ++sp) {
                 if (sp >= NS || ms[sp] == -INFINITY) continue;
-                const float f = expf(ms[sp] - M);
+                const float f = __expf(ms[sp] - M);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     O[e] += f * o0[sp][e];
@@ -901,7 +901,7 @@ __device__ __forceinline__ void gemm_mainloop_bf16_lds(const GemmArgs& a, int ti
     #pragma unroll
                 for (int sp = 0; sp < MAXS; ++sp) {
                     if (sp >= NS || ms[sp] == -INFINITY) continue;
-                    const float f = expf(ms[sp] - M);
+                    const float f = __expf(ms[sp] - M);
     #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         O[e] += f * o0[sp][e];
@@ -1872,7 +1872,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const __bf16* __rest
         if (M > -INFINITY) {
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
-                float f = expf(wm[w * 16 + qq] - M);
+                float f = __expf(wm[w * 16 + qq] - M);
                 O += f * wO[(w * 16 + qq) * (HD + 1) + cc];
                 L += f * wl[w * 16 + qq];
             }
@@ -1915,7 +1915,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 #pragma unroll
         for (int s = 0; s < MAXS; ++s) {
             if (s >= NS || ms[s] == -INFINITY) continue;
-            float f = expf(ms[s] - M);
+            float f = __expf(ms[s] - M);
             O += f * os[s];
             L += f * ls[s];
         }
