@@ -309,6 +309,7 @@ struct ee_kv_cache {
     const ee_model* m;
     int max_seqs, BT, S, max_pending, n_blocks;
     int refeed = 0;  // deferred tokens re-enter at layer 1 (the paper's wording) instead of resuming where they stopped
+    bool spec_used = false;  // a decode step on this cache has left kernels in flight at its return (see run_step)
     Pipeline pipe;
     char* pool;
     size_t off_x, off_xg, off_xgh, off_ssq;
@@ -863,6 +864,7 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
                     HIPCHK(hipEventRecord(m->spec_ev, st));
                     m->spec_stream = st;
                     m->spec_recorded = true;
+                    c->spec_used = true;
                 }
             }
             EECHK(wait_head_results(m, hd, st));
@@ -1623,7 +1625,9 @@ int ee_kv_cache_flush(ee_model* m, ee_kv_cache* c, int n_seqs, const int32_t* se
 
 int ee_kv_cache_free(ee_kv_cache* c) {
     if (!c) return EE_ERR_ARG;
-    if (c->m->spec_recorded) (void)hipEventSynchronize(c->m->spec_ev);  // (kernels of the last step may still write K and V)
+    // (kernels that a step enqueued ahead of an exit decision may still write K and V; the model, and with it their
+    // event, may already be gone)
+    if (c->spec_used) (void)hipDeviceSynchronize();
     if (c->pipe.events_made) {
         if (c->pipe.on) (void)hipStreamSynchronize(c->pipe.stream);
         for (auto& e : c->pipe.slot_done) (void)hipEventDestroy(e);
