@@ -860,7 +860,6 @@ int run_step(ee_model* m, ee_kv_cache* c, std::vector<StepSeq>& ss, float thresh
                 if (nd->T > 0 && (dt != EE_BF16 || gemm_rows_fit_lds(dt, nd->T, m->cfg.d_model))) {
                     EECHK(run_layers(m, c, s + 1, nd->T, nd->n_qt, m->seg_begin(s + 1), m->seg_end(s + 1), max_ctx, st, BLOCK_FRONT, &spec_ns));
                     spec_seg = s + 1;
-                    if (m->spec_ev == nullptr) HIPCHK(hipEventCreateWithFlags(&m->spec_ev, hipEventDisableTiming));
                     HIPCHK(hipEventRecord(m->spec_ev, st));
                     m->spec_stream = st;
                     m->spec_recorded = true;
@@ -1192,6 +1191,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     do {
         if ((e = hipHostGetDevicePointer((void**)&m->results_dev, m->results, 0)) != hipSuccess) break;
         if ((e = hipHostGetDevicePointer((void**)&m->pinned_dev, m->pinned, 0)) != hipSuccess) break;
+        if ((e = hipEventCreateWithFlags(&m->spec_ev, hipEventDisableTiming)) != hipSuccess) break;  // (no step creates anything)
         if ((e = hipMemsetAsync(m->ws + m->wsl.counters, 0, 256 * 4, st)) != hipSuccess) break;
         if ((e = launch_fill_f32((float*)(m->wbase + m->wl.ones), 1.0f, (size_t)cfg->d_model, st)) != hipSuccess) break;
         if (m->wsl.pf_rows && (e = hipMemsetAsync(m->ws + m->wsl.pf_begin, 0, m->wsl.total - m->wsl.pf_begin, st)) != hipSuccess) break;
@@ -1200,6 +1200,7 @@ int ee_model_create(const ee_config* cfg, void* dev_weights, size_t weight_bytes
     if (e != hipSuccess) {
         g_last_hip = (int)e;
         rc = EE_ERR_HIP;
+        if (m->spec_ev) (void)hipEventDestroy(m->spec_ev);
         (void)hipHostFree(m->pinned);
         delete m;
         return rc;
