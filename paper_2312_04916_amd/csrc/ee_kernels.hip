@@ -685,6 +685,11 @@ __device__ __forceinline__ void gemm_mainloop_bf16_multi(const GemmArgs& a, int 
 // K = 4096); with 112 KB (one workgroup per CU) the 30B-shaped steps of 4 rows were 5 % slower than on the register
 // path, while 2-4 rows at the 7B width gained 2-4 % over it.
 constexpr int A_LDS_MAX_BYTES = 72 * 1024;
+// The 16-wave variants (K beyond 4096) have the CU to themselves whatever their LDS use, so two or three of their
+// rows may take up to 140 KB (the down projection at the 7B width: 88 and 132 KB; 23.1 us on the register path,
+// which steps carrying a deferred row or two took until then, against 18 us; C3 at threshold 0.2: 2.262 -> 2.240 ms
+// per step).  Four rows stay on the register path: see the 30B-shaped steps above.
+constexpr int A_LDS_MAX_BYTES_16 = 140 * 1024;
 __host__ __device__ inline int a_lds_row_stride(int K) { return 2 * K + 32; }  // elements; +64 B staggers the banks of two rows
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global load of
@@ -1397,6 +1402,7 @@ static int ks_of(const GemmCommon& c) {
 static size_t a_lds_bytes(const GemmCommon& c) {
     if (c.dtype != EE_BF16 || c.T > 16) return 0;
     size_t b = (size_t)c.T * a_lds_row_stride(c.K) * 2;
+    if (ks_of(c) == 16 && c.T <= 3) return b <= (size_t)A_LDS_MAX_BYTES_16 ? b : 0;
     return b <= (size_t)A_LDS_MAX_BYTES ? b : 0;
 }
 
@@ -1433,7 +1439,7 @@ static int g_of(int mt, int n_tiles, int min_wgs) {
 // more dynamic LDS than the default limit has to be asked for once per kernel
 template <auto K>
 static hipError_t lds_limit_once() {
-    static hipError_t e = hipFuncSetAttribute((const void*)K, hipFuncAttributeMaxDynamicSharedMemorySize, A_LDS_MAX_BYTES);
+    static hipError_t e = hipFuncSetAttribute((const void*)K, hipFuncAttributeMaxDynamicSharedMemorySize, A_LDS_MAX_BYTES_16);
     return e;
 }
 #define EE_LAUNCH_LDS(KERNEL_INST, ...)                                         \
